@@ -1,0 +1,269 @@
+/*
+ * CPU oracle for batched single-token decode attention over a paged KV cache.
+ *
+ * TEST INFRASTRUCTURE, not a product path: only the tests, the smoke check and the
+ * benchmark's CPU-baseline leg may build or call this file.  It shares no code with
+ * the HIP library and knows nothing about tiles, splits or online softmax.
+ *
+ * What it computes is the plain definition of grouped-query attention for one new
+ * query token per sequence (the paper's Appendix A, Scenario A, describes the model
+ * family: grouped-query attention in which 32 query heads share 8 key/value heads,
+ * served from a paged KV cache).  For sequence b, query head h, KV head g = h / G
+ * with G = Hq / Hkv, and logical token t in [0, L_b):
+ *
+ *     phys  = block_tables[b][t / BS],   slot = t % BS
+ *     k_t   = deq(k_cache[phys][g][slot][:]),   v_t = deq(v_cache[phys][g][slot][:])
+ *     s_t   = scale * sum_d q[b][h][d] * k_t[d]
+ *     p_t   = exp(s_t - max_u s_u) / sum_u exp(s_u - max_u s_u)
+ *     out[b][h][:] = sum_t p_t * v_t[:]
+ *
+ * everything in float64, two passes over the scores, one final rounding of out to
+ * float32.  deq widens bf16 bit patterns exactly, or maps an OCP e4m3 byte through a
+ * 256-entry table (built here from the format's closed form) times the KV head's
+ * scale (k_scale for K, v_scale for V).  L_b = 0 gives a zero row.
+ *
+ * Every pin that ties this file to something other than itself lives in
+ * tests/test_oracle_pins.py (closed forms, invariants, dense library softmax, brute
+ * force); no function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define PA_ORACLE_KV_BF16 0
+#define PA_ORACLE_KV_FP8_E4M3 1
+
+/* OCP 8-bit floating point, E4M3 variant: 1 sign, 4 exponent (bias 7), 3 mantissa bits;
+ * no infinities; S.1111.111 is NaN; exponent field 0 is subnormal: (m/8) * 2^-6. */
+static double e4m3_value(unsigned byte)
+{
+    unsigned sign = (byte >> 7) & 1u;
+    unsigned expo = (byte >> 3) & 0xFu;
+    unsigned mant = byte & 0x7u;
+    double mag;
+    if (expo == 0xFu && mant == 0x7u)
+        return NAN;
+    if (expo == 0)
+        mag = ldexp((double)mant / 8.0, -6);
+    else
+        mag = ldexp(1.0 + (double)mant / 8.0, (int)expo - 7);
+    return sign ? -mag : mag;
+}
+
+void pa_oracle_e4m3_table(double *table256)
+{
+    for (unsigned i = 0; i < 256; ++i)
+        table256[i] = e4m3_value(i);
+}
+
+static double bf16_value(uint16_t bits)
+{
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+typedef struct {
+    const uint16_t *q;
+    const void *k_cache, *v_cache;
+    const int32_t *block_tables, *context_lens;
+    double scale;
+    int kv_dtype;
+    const float *k_scale, *v_scale;
+    int32_t B, Hq, Hkv, D, BS, MB, NB;
+    double e4m3[256];
+} problem;
+
+static double load_kv(const problem *p, const void *cache, const float *head_scale, int64_t phys, int g,
+                      int slot, int d)
+{
+    int64_t idx = ((phys * p->Hkv + g) * p->BS + slot) * (int64_t)p->D + d;
+    if (p->kv_dtype == PA_ORACLE_KV_BF16)
+        return bf16_value(((const uint16_t *)cache)[idx]);
+    return p->e4m3[((const uint8_t *)cache)[idx]] * (double)head_scale[g];
+}
+
+/* One output row.  scores has room for L doubles.  Returns 0, or -2 on a block id
+ * outside the pool for a valid token. */
+static int attend_row(const problem *p, int b, int h, double *scores, double *out_row, double *lse_out,
+                      double *probs_row)
+{
+    const int G = p->Hq / p->Hkv;
+    const int g = h / G;
+    const int L = p->context_lens[b];
+    const uint16_t *qrow = p->q + ((int64_t)b * p->Hq + h) * p->D;
+
+    for (int d = 0; d < p->D; ++d)
+        out_row[d] = 0.0;
+    if (L <= 0) {
+        if (lse_out)
+            *lse_out = -INFINITY;
+        return 0;
+    }
+    double smax = -INFINITY;
+    for (int t = 0; t < L; ++t) {
+        int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];
+        if (phys < 0 || phys >= p->NB)
+            return -2;
+        double acc = 0.0;
+        for (int d = 0; d < p->D; ++d)
+            acc += bf16_value(qrow[d]) * load_kv(p, p->k_cache, p->k_scale, phys, g, t % p->BS, d);
+        scores[t] = p->scale * acc;
+        if (scores[t] > smax)
+            smax = scores[t];
+    }
+    double denom = 0.0;
+    for (int t = 0; t < L; ++t) {
+        scores[t] = exp(scores[t] - smax);
+        denom += scores[t];
+    }
+    for (int t = 0; t < L; ++t) {
+        int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];
+        double w = scores[t] / denom;
+        if (probs_row)
+            probs_row[t] = w;
+        for (int d = 0; d < p->D; ++d)
+            out_row[d] += w * load_kv(p, p->v_cache, p->v_scale, phys, g, t % p->BS, d);
+    }
+    if (lse_out)
+        *lse_out = smax + log(denom);
+    return 0;
+}
+
+/*
+ * Attention rows for the whole batch (row_b == NULL: n_rows must be B*Hq, row r is
+ * b = r / Hq, h = r % Hq) or for a selection of (row_b[r], row_h[r]) pairs.
+ *
+ *   out_f32   [n_rows, D] float32, required
+ *   out_f64   [n_rows, D] float64, optional (NULL to skip)
+ *   lse       [n_rows]    float64 log-sum-exp of the scaled scores, optional
+ *   probs     [n_rows, probs_stride] float64 softmax weights per logical token, optional
+ *
+ * Returns 0; -1 bad shape/argument; -2 a valid token's block id is outside [0, NB);
+ * -3 out of memory.
+ */
+int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                     const int32_t *context_lens, float scale, int kv_dtype, const float *k_scale,
+                     const float *v_scale, int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t BS, int32_t MB,
+                     int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_h, float *out_f32,
+                     double *out_f64, double *lse, double *probs, int64_t probs_stride)
+{
+    if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !out_f32)
+        return -1;
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || BS <= 0 || MB <= 0 || NB <= 0 || Hq % Hkv != 0)
+        return -1;
+    if (kv_dtype != PA_ORACLE_KV_BF16 && kv_dtype != PA_ORACLE_KV_FP8_E4M3)
+        return -1;
+    if (kv_dtype == PA_ORACLE_KV_FP8_E4M3 && (!k_scale || !v_scale))
+        return -1;
+    if (!row_b != !row_h)
+        return -1;
+    if (!row_b && n_rows != (int64_t)B * Hq)
+        return -1;
+
+    problem p;
+    p.q = q; p.k_cache = k_cache; p.v_cache = v_cache;
+    p.block_tables = block_tables; p.context_lens = context_lens;
+    p.scale = (double)scale; p.kv_dtype = kv_dtype; p.k_scale = k_scale; p.v_scale = v_scale;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.D = D; p.BS = BS; p.MB = MB; p.NB = NB;
+    pa_oracle_e4m3_table(p.e4m3);
+
+    int64_t max_len = 1;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        int b = row_b ? row_b[r] : (int)(r / Hq);
+        int h = row_h ? row_h[r] : (int)(r % Hq);
+        if (b < 0 || b >= B || h < 0 || h >= Hq)
+            return -1;
+        int L = context_lens[b];
+        if ((int64_t)L > (int64_t)MB * BS)
+            return -1;
+        if (probs && L > probs_stride)
+            return -1;
+        if (L > max_len)
+            max_len = L;
+    }
+
+    int status = 0;
+#pragma omp parallel
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)max_len);
+        double *row = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!scores || !row) {
+#pragma omp atomic write
+            status = -3;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t r = 0; r < n_rows; ++r) {
+                int b = row_b ? row_b[r] : (int)(r / Hq);
+                int h = row_h ? row_h[r] : (int)(r % Hq);
+                int rc = attend_row(&p, b, h, scores, row, lse ? &lse[r] : NULL,
+                                    probs ? probs + r * probs_stride : NULL);
+                if (rc != 0) {
+#pragma omp atomic write
+                    status = rc;
+                }
+                for (int d = 0; d < D; ++d) {
+                    out_f32[r * D + d] = (float)row[d];
+                    if (out_f64)
+                        out_f64[r * D + d] = row[d];
+                }
+            }
+        }
+        free(scores);
+        free(row);
+    }
+    return status;
+}
+
+/*
+ * Where the walk goes, for the indexing checks: the physical block ids that sequence b's
+ * valid tokens live in, in logical order (block_tables[b][0 .. ceil(L_b/BS))).  Writes at
+ * most cap ids and returns how many the sequence has.
+ */
+int32_t pa_oracle_visited_blocks(const int32_t *block_tables, const int32_t *context_lens, int32_t MB, int32_t BS,
+                                 int32_t b, int32_t *ids, int32_t cap)
+{
+    int32_t L = context_lens[b];
+    int32_t n = L <= 0 ? 0 : (L + BS - 1) / BS;
+    for (int32_t i = 0; i < n && i < cap; ++i)
+        ids[i] = block_tables[(int64_t)b * MB + i];
+    return n;
+}
+
+/*
+ * The split-K partition of a context of L tokens into chunks of C tokens, written from
+ * its definition: n = ceil(L / C) chunks, chunk s covers tokens [s*C, min((s+1)*C, L)).
+ * Fills starts/ends (at most cap entries) and returns n (0 for L <= 0).
+ */
+int32_t pa_oracle_split_ranges(int32_t L, int32_t C, int32_t *starts, int32_t *ends, int32_t cap)
+{
+    if (L <= 0 || C <= 0)
+        return 0;
+    int32_t n = 0;
+    for (int32_t lo = 0; lo < L; lo += C) {
+        if (n < cap) {
+            starts[n] = lo;
+            ends[n] = lo + C < L ? lo + C : L;
+        }
+        ++n;
+    }
+    return n;
+}
+
+int pa_oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp single
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

@@ -1,0 +1,144 @@
+"""ctypes front end of the float64 CPU oracle in pa_oracle.c.
+
+TEST INFRASTRUCTURE: imported only by the tests, the smoke check and the benchmark's
+CPU-baseline leg.  It never imports the HIP binding and the HIP binding never imports it.
+Arrays go in as numpy (bf16 bit patterns as uint16, fp8 bytes as uint8) and come out as
+numpy; all arithmetic happens in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pa_oracle.c")
+_LIB = os.path.join(_HERE, "libpa_oracle.so")
+_lib = None
+
+KV_BF16 = 0
+KV_FP8_E4M3 = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile pa_oracle.c with gcc (-O2, OpenMP over output rows) into libpa_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        p = ctypes.c_void_p
+        i32, i64 = ctypes.c_int32, ctypes.c_int64
+        L.pa_oracle_decode.restype = ctypes.c_int
+        L.pa_oracle_decode.argtypes = [p, p, p, p, p, ctypes.c_float, ctypes.c_int, p, p,
+                                       i32, i32, i32, i32, i32, i32, i32, i64, p, p, p, p, p, p, i64]
+        L.pa_oracle_e4m3_table.restype = None
+        L.pa_oracle_e4m3_table.argtypes = [p]
+        L.pa_oracle_visited_blocks.restype = i32
+        L.pa_oracle_visited_blocks.argtypes = [p, p, i32, i32, i32, p, i32]
+        L.pa_oracle_split_ranges.restype = i32
+        L.pa_oracle_split_ranges.argtypes = [i32, i32, p, p, i32]
+        L.pa_oracle_num_threads.restype = ctypes.c_int
+        L.pa_oracle_num_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == dtype, (a.dtype, dtype)
+    return a
+
+
+def decode(q_bits: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_tables: np.ndarray,
+           context_lens: np.ndarray, scale, kv_dtype: int = KV_BF16, k_scale: Optional[np.ndarray] = None,
+           v_scale: Optional[np.ndarray] = None, rows: Optional[Sequence[Tuple[int, int]]] = None,
+           want_f64: bool = False, want_lse: bool = False, want_probs: bool = False):
+    """Run the oracle.  Returns a dict with 'out' float32 [B,Hq,D] (or [n_rows,D] when ``rows``
+    selects (b,h) pairs) and, on request, 'out_f64', 'lse' and 'probs' ([.., MB*BS], zero past L_b)."""
+    q_bits = _c(q_bits, np.uint16)
+    kv_np = np.uint16 if kv_dtype == KV_BF16 else np.uint8
+    k_cache = _c(k_cache, kv_np)
+    v_cache = _c(v_cache, kv_np)
+    block_tables = _c(block_tables, np.int32)
+    context_lens = _c(context_lens, np.int32)
+    B, Hq, D = q_bits.shape
+    NB, Hkv, BS, D2 = k_cache.shape
+    assert D2 == D and v_cache.shape == k_cache.shape and block_tables.shape[0] == B == context_lens.shape[0]
+    MB = block_tables.shape[1]
+    if kv_dtype == KV_FP8_E4M3:
+        k_scale = _c(k_scale, np.float32)
+        v_scale = _c(v_scale, np.float32)
+        assert k_scale.shape == (Hkv,) and v_scale.shape == (Hkv,)
+    if rows is None:
+        n_rows, rb, rh, shape = B * Hq, None, None, (B, Hq, D)
+    else:
+        rb = np.ascontiguousarray([r[0] for r in rows], dtype=np.int32)
+        rh = np.ascontiguousarray([r[1] for r in rows], dtype=np.int32)
+        n_rows, shape = len(rows), (len(rows), D)
+    out = np.zeros((n_rows, D), dtype=np.float32)
+    out64 = np.zeros((n_rows, D), dtype=np.float64) if want_f64 else None
+    lse = np.zeros(n_rows, dtype=np.float64) if want_lse else None
+    stride = MB * BS
+    probs = np.zeros((n_rows, stride), dtype=np.float64) if want_probs else None
+    rc = lib().pa_oracle_decode(_ptr(q_bits), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(context_lens),
+                                ctypes.c_float(float(np.float32(scale))), int(kv_dtype), _ptr(k_scale), _ptr(v_scale),
+                                B, Hq, Hkv, D, BS, MB, NB, n_rows, _ptr(rb), _ptr(rh), _ptr(out), _ptr(out64),
+                                _ptr(lse), _ptr(probs), stride)
+    if rc != 0:
+        raise RuntimeError(f"pa_oracle_decode failed with code {rc}")
+    res = {"out": out.reshape(shape)}
+    if want_f64:
+        res["out_f64"] = out64.reshape(shape)
+    if want_lse:
+        res["lse"] = lse.reshape(shape[:-1])
+    if want_probs:
+        res["probs"] = probs.reshape(shape[:-1] + (stride,))
+    return res
+
+
+def decode_batch(batch, **kw):
+    """Convenience: run on an object with the fields of workloads.DecodeBatch (duck-typed)."""
+    return decode(batch.q, batch.k_cache, batch.v_cache, batch.block_tables, batch.context_lens, batch.scale,
+                  batch.kv_dtype, batch.k_scale, batch.v_scale, **kw)
+
+
+def e4m3_table() -> np.ndarray:
+    t = np.zeros(256, dtype=np.float64)
+    lib().pa_oracle_e4m3_table(_ptr(t))
+    return t
+
+
+def visited_blocks(block_tables: np.ndarray, context_lens: np.ndarray, block_size: int, b: int) -> np.ndarray:
+    block_tables = _c(block_tables, np.int32)
+    context_lens = _c(context_lens, np.int32)
+    MB = block_tables.shape[1]
+    ids = np.zeros(MB, dtype=np.int32)
+    n = lib().pa_oracle_visited_blocks(_ptr(block_tables), _ptr(context_lens), MB, block_size, b, _ptr(ids), MB)
+    return ids[:n].copy()
+
+
+def split_ranges(context_len: int, split_tokens: int):
+    cap = 0 if context_len <= 0 or split_tokens <= 0 else (context_len + split_tokens - 1) // split_tokens
+    s = np.zeros(max(cap, 1), dtype=np.int32)
+    e = np.zeros(max(cap, 1), dtype=np.int32)
+    n = lib().pa_oracle_split_ranges(int(context_len), int(split_tokens), _ptr(s), _ptr(e), cap)
+    return s[:n].copy(), e[:n].copy()
+
+
+def num_threads() -> int:
+    return int(lib().pa_oracle_num_threads())

@@ -1,0 +1,43 @@
+"""A compact subset of the oracle pins that can run against any build of the oracle's C file.
+
+Run as ``python -m tests.oracle_core_pins path/to/lib.so`` it swaps that library in and exits
+non-zero if a pin fails (used to check that planted mistakes are caught)."""
+import ctypes
+import sys
+
+import numpy as np
+
+from paper_2605_06068_amd import workloads as W
+from tests.dense_reference import dense_attention, e4m3_to_f64
+
+
+def core_pins(oracle):
+    """Raises AssertionError if a pin fails."""
+    t = oracle.e4m3_table()
+    lib = e4m3_to_f64(np.arange(256, dtype=np.uint8))
+    ok = ~np.isnan(lib)
+    assert np.array_equal(t[ok], lib[ok]) and np.isnan(t[~ok]).all()
+    for kv in (W.KV_BF16, W.KV_FP8_E4M3):
+        b = W.make_batch("m", 5, [1, 37, 100], 8, 2, 64, 16, kv, num_blocks=20, max_blocks_per_seq=9)
+        r = oracle.decode_batch(b, want_f64=True)
+        want, _ = dense_attention(b)
+        assert np.isfinite(r["out_f64"]).all()
+        assert np.max(np.abs(r["out_f64"] - want)) <= 1e-12
+
+
+
+
+def main(so_path):
+    from oracle import pa_oracle
+
+    good = pa_oracle.lib()
+    other = ctypes.CDLL(so_path)
+    for fn in ("pa_oracle_decode", "pa_oracle_e4m3_table"):
+        getattr(other, fn).restype = getattr(good, fn).restype
+        getattr(other, fn).argtypes = getattr(good, fn).argtypes
+    pa_oracle._lib = other
+    core_pins(pa_oracle)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1])

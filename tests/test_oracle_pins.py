@@ -1,0 +1,283 @@
+"""Pins that tie the CPU oracle to things other than itself (all CPU, no GPU).
+
+The paper prints no worked numeric example for attention, so the pins are: closed forms
+(one token, equal V rows, zero query, two tokens with sigmoid weights), invariants (weights
+sum to one, score-shift invariance, physical-block permutation, poison in dead slots),
+dense library softmax on gathered matrices (scipy, torch SDPA in float64), a two-segment
+log-sum-exp merge identity, and the e4m3 byte table against the format's corner values and
+torch's float8_e4m3fn cast.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2605_06068_amd import workloads as W
+from tests.dense_reference import dense_attention, e4m3_to_f64, torch_sdpa, widen_bf16
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bf16(x):
+    return W.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def tiny(seed, lens, Hq=4, Hkv=2, D=64, kv=W.KV_BF16, **kw):
+    return W.make_batch("t", seed, lens, Hq, Hkv, D, 16, kv, **kw)
+
+
+# ---------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_single_token_returns_v_exactly(oracle, kv):
+    b = tiny(11, [1, 1, 1], Hq=8, Hkv=4, D=64, kv=kv, num_blocks=7)
+    out = oracle.decode_batch(b)["out"]
+    G = b.group
+    for s in range(3):
+        phys = b.block_tables[s, 0]
+        for h in range(8):
+            g = h // G
+            raw = b.v_cache[phys, g, 0]
+            if kv == W.KV_BF16:
+                want = W.bf16_bits_to_f32(raw)
+            else:
+                want = (e4m3_to_f64(raw) * np.float64(b.v_scale[g])).astype(np.float32)
+            assert np.array_equal(out[s, h], want)
+
+
+def test_single_token_heads_map_to_their_kv_head(oracle):
+    # V row of KV head g holds the constant g+1: query head h must return (h // G) + 1.
+    b = tiny(12, [1], Hq=8, Hkv=4, D=64, table_kind="identity")
+    for g in range(4):
+        b.v_cache[:, g] = bf16(np.float32(g + 1))
+    out = oracle.decode_batch(b)["out"]
+    for h in range(8):
+        assert np.all(out[0, h] == h // 2 + 1)
+
+
+def test_equal_v_rows_return_that_row(oracle):
+    b = tiny(13, [53, 16, 17])
+    row = bf16(np.linspace(-2, 2, 64))
+    b.v_cache[:] = row
+    out = oracle.decode_batch(b, want_f64=True)["out_f64"]
+    want = widen_bf16(row)
+    assert np.max(np.abs(out - want)) <= 1e-14 * 4
+
+
+def test_zero_query_gives_mean_of_v(oracle):
+    b = tiny(14, [45, 7])
+    b.q[:] = 0
+    out = oracle.decode_batch(b, want_f64=True, want_probs=True)
+    for s, L in enumerate(b.context_lens):
+        for h in range(4):
+            t = np.arange(L)
+            v = widen_bf16(b.v_cache[b.block_tables[s, t // 16], h // 2, t % 16])
+            assert np.allclose(out["out_f64"][s, h], v.mean(axis=0), rtol=0, atol=1e-13)
+            assert np.allclose(out["probs"][s, h, :L], 1.0 / L, rtol=1e-13, atol=0)
+
+
+def test_equal_k_rows_give_uniform_weights(oracle):
+    b = tiny(15, [33])
+    b.k_cache[:] = bf16(np.random.default_rng(0).standard_normal(64))
+    p = oracle.decode_batch(b, want_probs=True)["probs"]
+    assert np.allclose(p[0, :, :33], 1.0 / 33, rtol=1e-13, atol=0)
+    assert np.all(p[0, :, 33:] == 0)
+
+
+def test_two_tokens_sigmoid_weights(oracle):
+    # scores s0, s1 -> weights sigmoid(s0-s1), sigmoid(s1-s0); q = e_3 * a, k0 = e_3 * c0, k1 = e_3 * c1.
+    b = tiny(16, [2], Hq=2, Hkv=1, D=64, table_kind="identity")
+    b.q[:] = 0
+    b.k_cache[:] = 0
+    a, c0, c1 = 3.0, 1.5, -0.25
+    b.q[0, :, 3] = bf16(a)
+    b.k_cache[0, 0, 0, 3] = bf16(c0)
+    b.k_cache[0, 0, 1, 3] = bf16(c1)
+    out = oracle.decode_batch(b, want_f64=True, want_probs=True, want_lse=True)
+    scale = float(b.scale)  # 1/8 exactly
+    s0, s1 = scale * a * c0, scale * a * c1
+    w0 = 1.0 / (1.0 + math.exp(s1 - s0))
+    v0 = widen_bf16(b.v_cache[0, 0, 0])
+    v1 = widen_bf16(b.v_cache[0, 0, 1])
+    assert abs(out["probs"][0, 0, 0] - w0) <= 1e-15
+    assert abs(out["probs"][0, 0, 1] - (1 - w0)) <= 1e-15
+    assert np.allclose(out["out_f64"][0, 0], w0 * v0 + (1 - w0) * v1, rtol=0, atol=1e-15)
+    assert abs(out["lse"][0, 0] - math.log(math.exp(s0) + math.exp(s1))) <= 1e-15
+
+
+def test_scale_multiplies_the_scores(oracle):
+    # doubling the scale equals doubling q (exact in bf16)
+    b = tiny(17, [40, 21])
+    r1 = oracle.decode(b.q, b.k_cache, b.v_cache, b.block_tables, b.context_lens, np.float32(0.25), want_f64=True)
+    q2 = bf16(W.bf16_bits_to_f32(b.q) * 2)
+    r2 = oracle.decode(q2, b.k_cache, b.v_cache, b.block_tables, b.context_lens, np.float32(0.125), want_f64=True)
+    assert np.allclose(r1["out_f64"], r2["out_f64"], rtol=0, atol=1e-14)
+    r3 = oracle.decode(b.q, b.k_cache, b.v_cache, b.block_tables, b.context_lens, np.float32(0.125), want_f64=True)
+    assert np.max(np.abs(r1["out_f64"] - r3["out_f64"])) > 1e-3
+
+
+# ---------------------------------------------------------------- invariants
+def test_weights_sum_to_one_and_vanish_past_the_context(oracle):
+    b = W.make_config(1)
+    p = oracle.decode_batch(b, want_probs=True)["probs"]
+    assert np.max(np.abs(p.sum(-1) - 1.0)) <= 1e-12
+    for s, L in enumerate(b.context_lens):
+        assert np.all(p[s, :, L:] == 0) and np.all(p[s, :, :L] > 0)
+
+
+def test_adding_a_vector_to_every_k_row_changes_nothing(oracle):
+    # integer-valued K, q and u keep every sum exact in bf16 and float64
+    rng = np.random.default_rng(18)
+    b = tiny(18, [37, 64])
+    b.k_cache[:] = bf16(rng.integers(-8, 9, size=b.k_cache.shape))
+    b.q[:] = bf16(rng.integers(-2, 3, size=b.q.shape))
+    base = oracle.decode_batch(b, want_f64=True)["out_f64"]
+    u = rng.integers(-8, 9, size=64).astype(np.float32)
+    b.k_cache[:] = bf16(W.bf16_bits_to_f32(b.k_cache) + u)
+    moved = oracle.decode_batch(b, want_f64=True)["out_f64"]
+    assert np.max(np.abs(moved - base)) <= 1e-12
+
+
+def test_permuting_physical_blocks_is_bit_identical(oracle):
+    b = W.make_config(1)
+    base = oracle.decode_batch(b, want_f64=True)["out_f64"]
+    perm = np.random.default_rng(19).permutation(b.num_blocks)  # new id of old block i is perm[i]
+    k2 = np.empty_like(b.k_cache)
+    v2 = np.empty_like(b.v_cache)
+    k2[perm] = b.k_cache
+    v2[perm] = b.v_cache
+    t2 = np.where(b.block_tables >= 0, perm[np.maximum(b.block_tables, 0)], -1).astype(np.int32)
+    moved = oracle.decode(b.q, k2, v2, t2, b.context_lens, b.scale, want_f64=True)["out_f64"]
+    assert np.array_equal(moved, base)
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_dead_slots_and_unused_table_entries_never_matter(oracle, kv):
+    lens = [37, 100, 1, 16]
+    clean = tiny(20, lens, kv=kv, num_blocks=24, max_blocks_per_seq=9, poison=False)
+    dirty = tiny(20, lens, kv=kv, num_blocks=24, max_blocks_per_seq=9, poison=True)
+    nan_pat = W.BF16_NAN_BITS if kv == W.KV_BF16 else W.FP8_NAN_BYTE
+    assert (dirty.k_cache == nan_pat).any() and not np.array_equal(dirty.k_cache, clean.k_cache)
+    dirty.block_tables[dirty.block_tables < 0] = 2 ** 30  # garbage ids past the valid prefix
+    a = oracle.decode_batch(clean)["out"]
+    d = oracle.decode_batch(dirty)["out"]
+    assert np.isfinite(d).all() and np.array_equal(a, d)
+
+
+def test_zero_length_sequence_gives_zero_row(oracle):
+    b = tiny(21, [0, 5, 0], num_blocks=4, max_blocks_per_seq=2)
+    r = oracle.decode_batch(b, want_lse=True)
+    assert np.all(r["out"][0] == 0) and np.all(r["out"][2] == 0) and np.isfinite(r["out"]).all()
+    assert np.all(np.isneginf(r["lse"][0]))
+
+
+def test_bad_block_id_inside_the_context_is_an_error(oracle):
+    b = tiny(22, [20])
+    b.block_tables[0, 1] = b.num_blocks
+    with pytest.raises(RuntimeError):
+        oracle.decode_batch(b)
+
+
+# ---------------------------------------------------------------- dense library references
+@pytest.mark.parametrize("case", [
+    dict(seed=1001, config=1),
+    dict(seed=31, lens=[1, 15, 16, 17, 255], Hq=8, Hkv=2, D=128),
+    dict(seed=32, lens=[64, 3], Hq=6, Hkv=6, D=64),
+    dict(seed=33, lens=[200], Hq=8, Hkv=1, D=128, sigma=2.0),
+    dict(seed=34, lens=[77, 130], Hq=16, Hkv=2, D=128, kv=W.KV_FP8_E4M3),
+])
+def test_matches_dense_softmax_from_scipy_and_torch(oracle, case):
+    case = dict(case)
+    if "config" in case:
+        b = W.make_config(case["config"], seed=case["seed"])
+    else:
+        b = tiny(case.pop("seed"), case.pop("lens"), **case)
+    r = oracle.decode_batch(b, want_f64=True, want_lse=True)
+    want, want_lse = dense_attention(b)
+    assert np.max(np.abs(r["out_f64"] - want)) <= 1e-12
+    assert np.max(np.abs(r["lse"] - want_lse)) <= 1e-12
+    assert np.max(np.abs(r["out_f64"] - torch_sdpa(b))) <= 1e-10
+    # the float32 result is the float64 one rounded once
+    assert np.array_equal(r["out"], r["out_f64"].astype(np.float32))
+
+
+def test_row_selection_equals_full_run(oracle):
+    b = W.make_config(1)
+    full = oracle.decode_batch(b)["out"]
+    rows = [(1, 3), (0, 0), (1, 0)]
+    sel = oracle.decode_batch(b, rows=rows)["out"]
+    for i, (s, h) in enumerate(rows):
+        assert np.array_equal(sel[i], full[s, h])
+
+
+def test_two_segment_log_sum_exp_merge_identity(oracle):
+    """Attention over [0,L) equals the LSE-weighted merge of attention over [0,m) and [m,L),
+    for every m that is a multiple of the block size: the identity split-K relies on."""
+    b = tiny(40, [100], Hq=4, Hkv=2, D=64, table_kind="permuted")
+    whole = oracle.decode_batch(b, want_f64=True)["out_f64"][0]
+    L = 100
+    for m in range(16, L, 16):
+        left = oracle.decode(b.q, b.k_cache, b.v_cache, b.block_tables, np.array([m], np.int32), b.scale,
+                             want_f64=True, want_lse=True)
+        t_right = np.full_like(b.block_tables, -1)
+        nb = b.block_tables.shape[1] - m // 16
+        t_right[0, :nb] = b.block_tables[0, m // 16:]
+        right = oracle.decode(b.q, b.k_cache, b.v_cache, t_right, np.array([L - m], np.int32), b.scale,
+                              want_f64=True, want_lse=True)
+        la, lb = left["lse"][0][:, None], right["lse"][0][:, None]
+        mx = np.maximum(la, lb)
+        wa, wb = np.exp(la - mx), np.exp(lb - mx)
+        merged = (wa * left["out_f64"][0] + wb * right["out_f64"][0]) / (wa + wb)
+        assert np.max(np.abs(merged - whole)) <= 1e-12
+
+
+# ---------------------------------------------------------------- fp8 table
+def test_e4m3_table_corner_values_and_torch_cast(oracle):
+    t = oracle.e4m3_table()
+    assert t[0x00] == 0.0 and t[0x01] == 2.0 ** -9 and t[0x07] == 7 * 2.0 ** -9
+    assert t[0x08] == 2.0 ** -6 and t[0x38] == 1.0 and t[0x40] == 2.0 and t[0x7E] == 448.0
+    assert math.isnan(t[0x7F]) and math.isnan(t[0xFF])
+    assert np.array_equal(t[0x80:0xFF], -t[0x00:0x7F]) and np.signbit(t[0x80])
+    lib = e4m3_to_f64(np.arange(256, dtype=np.uint8))
+    ok = ~np.isnan(lib)
+    assert ok.sum() == 254 and np.array_equal(t[ok], lib[ok]) and np.isnan(t[~ok]).all()
+
+
+def test_fp8_scales_belong_to_their_kv_head(oracle):
+    # identical bytes in every head, distinct scales: outputs must scale with v_scale[h // G]
+    b = tiny(41, [1], Hq=4, Hkv=2, D=64, kv=W.KV_FP8_E4M3, table_kind="identity")
+    b.v_cache[:, 1] = b.v_cache[:, 0]
+    b.v_scale[:] = [0.5, 3.0]
+    out = oracle.decode_batch(b)["out"]
+    assert np.array_equal(out[0, 2], out[0, 0] * 6) and np.array_equal(out[0, 3], out[0, 1] * 6)
+    # k_scale scales the scores: a huge K scale on head 1 turns its softmax into an argmax
+    b = tiny(42, [30], Hq=4, Hkv=2, D=64, kv=W.KV_FP8_E4M3)
+    b.k_scale[:] = [1e-6, 50.0]
+    p = oracle.decode_batch(b, want_probs=True)["probs"][0]
+    assert np.allclose(p[0, :30], 1 / 30, rtol=1e-3) and p[2, :30].max() > 0.99
+
+
+# ---------------------------------------------------------------- indexing helpers
+def test_visited_blocks_and_split_ranges_match_brute_force(oracle):
+    b = W.make_config(1)
+    assert oracle.visited_blocks(b.block_tables, b.context_lens, 16, 0).tolist() == b.block_tables[0, :3].tolist()
+    assert oracle.visited_blocks(b.block_tables, b.context_lens, 16, 1).tolist() == b.block_tables[1, :7].tolist()
+    for L in [0, 1, 15, 16, 17, 255, 256, 257, 1000]:
+        for C in [16, 48, 256, 1024]:
+            s, e = oracle.split_ranges(L, C)
+            owner = np.full(L, -1)
+            for i, (lo, hi) in enumerate(zip(s, e)):
+                assert 0 <= lo < hi <= L and hi - lo <= C
+                assert np.all(owner[lo:hi] == -1)
+                owner[lo:hi] = i
+            assert np.all(owner >= 0)  # a partition of [0, L)
+            assert np.array_equal(owner, np.arange(L) // C)  # token t belongs to chunk t // C
+
+
+# ---------------------------------------------------------------- stored regression values
+def test_config1_golden_values(oracle):
+    """Values written by tests/golden/make_golden.py (which calls only the oracle)."""
+    want = np.loadtxt(os.path.join(GOLDEN, "config1_seed1001_out.txt"))
+    b = W.make_config(1)
+    got = oracle.decode_batch(b, want_f64=True)["out_f64"].reshape(-1, 64)
+    assert np.max(np.abs(got - want)) <= 1e-15
