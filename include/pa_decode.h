@@ -1,0 +1,157 @@
+/*
+ * pa_decode — batched single-token decode attention over a paged (block-table) KV cache
+ * with grouped-query heads, for AMD MI355X (gfx950).  C ABI of libpa_decode.so.
+ *
+ * The operation is the attention step of autoregressive decoding in the serving stack the
+ * paper describes for its standard LLM scenario (Appendix A, Scenario A: a dense decoder
+ * with grouped-query attention, 32 query heads sharing 8 key/value heads, served with a
+ * paged KV cache and continuous batching).  For every sequence b and query head h, with
+ * G = num_q_heads / num_kv_heads and KV head g = h / G:
+ *
+ *     out[b][h][:] = sum_t softmax_t( scale * <q[b][h], K_t> ) * V_t,   t in [0, context_lens[b])
+ *     K_t = deq(k_cache[ block_tables[b][t / block_size] ][g][t % block_size][:]),  V_t likewise
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers owned by the caller, contiguous in the layouts
+ *     below and 16-byte aligned.  The shape struct and the split-plan arrays are HOST memory.
+ *   - The library allocates no device memory, keeps no state between calls, never reads device
+ *     memory on the host, and (except pa_decode_profile) never synchronises: work is enqueued on
+ *     the given HIP stream (hipStream_t passed as void*, NULL = the default stream) and the call
+ *     returns at once.  Calls that share a workspace must be ordered by the caller.
+ *   - Errors are return codes (pa_status).  Everything the host can check (null pointers, shape,
+ *     alignment, workspace size) is rejected BEFORE any launch; the contents of block_tables and
+ *     context_lens are trusted: ids of valid tokens must lie in [0, num_blocks) and
+ *     0 <= context_lens[b] <= max_context_len.
+ *   - Table entries past ceil(context_lens[b] / block_size), token slots past context_lens[b] in
+ *     a sequence's last block, and blocks no sequence owns are never dereferenced / never
+ *     influence the result (they may hold garbage ids and NaN patterns).
+ *   - context_lens[b] counts the token appended in this step.  context_lens[b] == 0 yields a zero
+ *     output row.
+ *
+ * Layouts (row-major)
+ *     q             [batch, num_q_heads, head_dim]                        bf16
+ *     k_cache       [num_blocks, num_kv_heads, block_size, head_dim]      bf16, or e4m3 bytes
+ *     v_cache       [num_blocks, num_kv_heads, block_size, head_dim]      same type as k_cache
+ *     block_tables  [batch, max_blocks_per_seq]                           int32
+ *     context_lens  [batch]                                               int32
+ *     k_scale, v_scale [num_kv_heads]                                     float32 (fp8 KV only)
+ *     out           [batch, num_q_heads, head_dim]                        float32
+ *
+ * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
+ * 1 <= G <= 16; PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no infinities, 0x7F/0xFF NaN)
+ * with one float32 scale per KV head for K and one for V.
+ */
+#ifndef PA_DECODE_H
+#define PA_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pa_status {
+    PA_OK = 0,
+    PA_ERR_INVALID_ARG = 1,         /* null pointer, misaligned pointer, inconsistent shape */
+    PA_ERR_UNSUPPORTED = 2,         /* well-formed but outside the supported set above */
+    PA_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes < pa_decode_workspace_size() */
+    PA_ERR_HIP = 4                  /* a HIP runtime call (launch, event) failed */
+} pa_status;
+
+typedef enum pa_kv_dtype { PA_KV_BF16 = 0, PA_KV_FP8_E4M3 = 1 } pa_kv_dtype;
+
+/* Host-side description of one call.  Everything the launch plan depends on is here, so the
+ * plan never needs the device-resident context_lens. */
+typedef struct pa_shape {
+    int32_t batch;
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t head_dim;
+    int32_t block_size;
+    int32_t max_blocks_per_seq; /* row stride of block_tables */
+    int32_t num_blocks;         /* blocks in the pool (k_cache.shape[0]) */
+    int32_t max_context_len;    /* host-known upper bound on context_lens; 0 = max_blocks_per_seq * block_size */
+    int32_t split_tokens;       /* 0 = library heuristic; otherwise the split length C to use
+                                   (a positive multiple of block_size) */
+} pa_shape;
+
+/* Split length C (tokens) the library uses for this shape: flash-decoding style split-K over the
+ * context.  A pure function of the shape (never of device data); a multiple of block_size.
+ * Returns a negative pa_status on an invalid / unsupported shape. */
+int32_t pa_split_tokens(const pa_shape *shape, pa_kv_dtype kv_dtype);
+
+/* Upper bound on the number of splits of any sequence: ceil(max_context_len / C). */
+int32_t pa_max_splits(const pa_shape *shape, pa_kv_dtype kv_dtype);
+
+/* The split plan of one sequence of context_len tokens, as the kernels apply it on the device:
+ * n = ceil(context_len / C) splits, split s covers tokens [s*C, min((s+1)*C, context_len)).
+ * Writes at most cap (start, end) pairs into the HOST arrays and returns n (0 for
+ * context_len <= 0), or a negative pa_status. */
+int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, int32_t context_len, int32_t *starts,
+                      int32_t *ends, int32_t cap);
+
+/* Bytes of device workspace pa_decode needs for this shape (partial outputs and log-sum-exps of
+ * the splits).  0 when the shape never splits.  Returns 0 as well for an invalid shape (pa_decode
+ * then reports the error). */
+size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
+
+/*
+ * The decode attention step.  Enqueues a partition kernel (block-table walk, K/V tile loads,
+ * scores, online softmax, PV; one partial per (sequence, query head, split)) and, when the shape
+ * can split, a merge kernel that combines the partials by their log-sum-exps into out.
+ *
+ *   q, k_cache, v_cache, block_tables, context_lens, out   device, layouts above
+ *   scale            softmax scale applied to q.K (e.g. 1/sqrt(head_dim))
+ *   k_scale, v_scale device float32[num_kv_heads]; required for PA_KV_FP8_E4M3, ignored (may be
+ *                    NULL) for PA_KV_BF16
+ *   workspace        device, 256-byte aligned, >= pa_decode_workspace_size() bytes; may be NULL
+ *                    when that size is 0.  Contents on entry are irrelevant; only entries written
+ *                    by this call are read back.
+ *   stream           hipStream_t
+ *
+ * The result is deterministic run to run (no floating-point atomics).
+ */
+pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                    const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,
+                    const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
+                    size_t workspace_bytes, void *stream);
+
+/*
+ * Same computation with the production indexing code instrumented (slow; for tests).  In
+ * addition to out it records, for checking the block-table walk and the split boundaries bit
+ * for bit:
+ *   visited_blocks [batch, num_kv_heads, max_blocks_per_seq, 2] int32 device: for logical block j
+ *                  of sequence b, the physical id the kernel used for its K loads ([..,0]) and
+ *                  for its V loads ([..,1]).  Entries of blocks the kernel never touched keep
+ *                  the caller's initial contents.
+ *   split_ranges   [batch, num_kv_heads, pa_max_splits(), 2] int32 device: (start, end) token
+ *                  range each non-empty split processed; untouched for empty splits.
+ */
+pa_status pa_decode_trace(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                          const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,
+                          const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
+                          size_t workspace_bytes, void *stream, int32_t *visited_blocks, int32_t *split_ranges);
+
+/*
+ * Measurement helper: runs pa_decode `steps` times on `stream` with HIP events around each
+ * kernel, SYNCHRONISES the stream, and returns the mean duration in milliseconds of the
+ * partition kernel and of the merge kernel (0 when no merge is launched).  HOST output pointers.
+ */
+pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                            const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,
+                            const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
+                            size_t workspace_bytes, void *stream, int32_t steps, float *partition_ms,
+                            float *merge_ms);
+
+/* Name of the partition kernel variant pa_decode picks for this shape ("mfma" for wide
+ * query-head groups, "valu" otherwise); NULL for an invalid shape.  Static storage. */
+const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
+
+/* Human-readable name of a status code.  Static storage. */
+const char *pa_status_string(pa_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PA_DECODE_H */

@@ -1,0 +1,225 @@
+"""Thin ctypes binding over libpa_decode.so — same names as the C ABI in include/pa_decode.h.
+
+Argument marshalling only: device tensors are torch CUDA tensors (torch supplies device
+memory and the current HIP stream), shapes go in a ``pa_shape`` struct, and every step of the
+computation runs inside the library's kernels.  There is no CPU fallback: if the library is
+missing or cannot be loaded, ``lib()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libpa_decode.so")
+
+PA_OK = 0
+PA_ERR_INVALID_ARG = 1
+PA_ERR_UNSUPPORTED = 2
+PA_ERR_WORKSPACE_TOO_SMALL = 3
+PA_ERR_HIP = 4
+
+PA_KV_BF16 = 0
+PA_KV_FP8_E4M3 = 1
+
+EXPORTS = ("pa_split_tokens", "pa_max_splits", "pa_split_plan", "pa_decode_workspace_size", "pa_decode",
+           "pa_decode_trace", "pa_decode_profile", "pa_kernel_variant", "pa_status_string")
+
+
+class pa_shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_blocks",
+        "max_context_len", "split_tokens")]
+
+
+class PaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Open the in-tree library.  It is built by ``paper_2605_06068_amd.build.build()`` (hipcc);
+    when no build exists yet this builds it once.  Raises if that is impossible."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+
+        _build.build()
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
+    shp = ctypes.POINTER(pa_shape)
+    fp = ctypes.POINTER(ctypes.c_float)
+    L.pa_split_tokens.restype = i32
+    L.pa_split_tokens.argtypes = [shp, ctypes.c_int]
+    L.pa_max_splits.restype = i32
+    L.pa_max_splits.argtypes = [shp, ctypes.c_int]
+    L.pa_split_plan.restype = i32
+    L.pa_split_plan.argtypes = [shp, ctypes.c_int, i32, i32p, i32p, i32]
+    L.pa_decode_workspace_size.restype = ctypes.c_size_t
+    L.pa_decode_workspace_size.argtypes = [shp, ctypes.c_int]
+    common = [vp, vp, vp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, shp, vp, ctypes.c_size_t, vp]
+    L.pa_decode.restype = ctypes.c_int
+    L.pa_decode.argtypes = common
+    L.pa_decode_trace.restype = ctypes.c_int
+    L.pa_decode_trace.argtypes = common + [vp, vp]
+    L.pa_decode_profile.restype = ctypes.c_int
+    L.pa_decode_profile.argtypes = common + [i32, fp, fp]
+    L.pa_kernel_variant.restype = ctypes.c_char_p
+    L.pa_kernel_variant.argtypes = [shp, ctypes.c_int]
+    L.pa_status_string.restype = ctypes.c_char_p
+    L.pa_status_string.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().pa_status_string(int(status)).decode()
+
+
+def make_shape(batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks,
+               max_context_len=0, split_tokens=0) -> pa_shape:
+    return pa_shape(int(batch), int(num_q_heads), int(num_kv_heads), int(head_dim), int(block_size),
+                    int(max_blocks_per_seq), int(num_blocks), int(max_context_len), int(split_tokens))
+
+
+def _neg_is_error(v: int, where: str) -> int:
+    if v < 0:
+        raise PaError(-v, where)
+    return v
+
+
+def pa_split_tokens(shape: pa_shape, kv_dtype: int) -> int:
+    return _neg_is_error(lib().pa_split_tokens(ctypes.byref(shape), kv_dtype), "pa_split_tokens")
+
+
+def pa_max_splits(shape: pa_shape, kv_dtype: int) -> int:
+    return _neg_is_error(lib().pa_max_splits(ctypes.byref(shape), kv_dtype), "pa_max_splits")
+
+
+def pa_split_plan(shape: pa_shape, kv_dtype: int, context_len: int):
+    """Returns (starts, ends) lists of the splits of one sequence."""
+    n = _neg_is_error(lib().pa_split_plan(ctypes.byref(shape), kv_dtype, int(context_len), None, None, 0),
+                      "pa_split_plan")
+    starts = (ctypes.c_int32 * max(n, 1))()
+    ends = (ctypes.c_int32 * max(n, 1))()
+    n2 = _neg_is_error(lib().pa_split_plan(ctypes.byref(shape), kv_dtype, int(context_len), starts, ends, n),
+                       "pa_split_plan")
+    assert n2 == n
+    return list(starts[:n]), list(ends[:n])
+
+
+def pa_decode_workspace_size(shape: pa_shape, kv_dtype: int) -> int:
+    return int(lib().pa_decode_workspace_size(ctypes.byref(shape), kv_dtype))
+
+
+def pa_kernel_variant(shape: pa_shape, kv_dtype: int) -> Optional[str]:
+    r = lib().pa_kernel_variant(ctypes.byref(shape), kv_dtype)
+    return None if r is None else r.decode()
+
+
+def _dev_ptr(t, name):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _common_args(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
+                 workspace, stream):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return [_dev_ptr(q, "q"), _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+            _dev_ptr(block_tables, "block_tables"), _dev_ptr(context_lens, "context_lens"),
+            ctypes.c_float(float(scale)), int(kv_dtype), _dev_ptr(out, "out"), _dev_ptr(k_scale, "k_scale"),
+            _dev_ptr(v_scale, "v_scale"), ctypes.byref(shape), _dev_ptr(workspace, "workspace"),
+            ctypes.c_size_t(ws_bytes), _stream_ptr(stream)]
+
+
+def pa_decode(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale=None, v_scale=None, *,
+              shape: pa_shape, workspace=None, stream=None) -> None:
+    """Enqueue one decode attention step on ``stream`` (default: torch's current stream)."""
+    st = lib().pa_decode(*_common_args(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale,
+                                       v_scale, shape, workspace, stream))
+    if st != PA_OK:
+        raise PaError(st, "pa_decode")
+
+
+def pa_decode_trace(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale=None, v_scale=None,
+                    *, shape: pa_shape, workspace=None, stream=None, visited_blocks, split_ranges) -> None:
+    st = lib().pa_decode_trace(*_common_args(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out,
+                                             k_scale, v_scale, shape, workspace, stream),
+                               _dev_ptr(visited_blocks, "visited_blocks"), _dev_ptr(split_ranges, "split_ranges"))
+    if st != PA_OK:
+        raise PaError(st, "pa_decode_trace")
+
+
+def pa_decode_profile(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale=None,
+                      v_scale=None, *, shape: pa_shape, workspace=None, stream=None, steps: int = 10):
+    """Returns (partition_ms, merge_ms): mean kernel durations over ``steps`` runs (synchronises)."""
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    st = lib().pa_decode_profile(*_common_args(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out,
+                                               k_scale, v_scale, shape, workspace, stream),
+                                 int(steps), ctypes.byref(a), ctypes.byref(b))
+    if st != PA_OK:
+        raise PaError(st, "pa_decode_profile")
+    return float(a.value), float(b.value)
+
+
+# --------------------------------------------------------------------------------------
+# Convenience for tests and the benchmark: put a host-side batch (numpy arrays with the
+# fields of workloads.DecodeBatch) into device memory.  torch is used for memory only.
+# --------------------------------------------------------------------------------------
+class DeviceBatch:
+    def __init__(self, batch, device="cuda:0", max_context_len: Optional[int] = None, split_tokens: int = 0):
+        import numpy as np
+        import torch
+
+        dev = torch.device(device)
+        self.host = batch
+        self.kv_dtype = int(batch.kv_dtype)
+        self.scale = float(batch.scale)
+
+        def up(a):
+            return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+        # bf16 bit patterns travel as int16 storage; the library only sees the pointer
+        self.q = up(batch.q.view(np.int16))
+        kv_view = np.int16 if self.kv_dtype == PA_KV_BF16 else np.uint8
+        self.k_cache = up(batch.k_cache.view(kv_view))
+        self.v_cache = up(batch.v_cache.view(kv_view))
+        self.block_tables = up(batch.block_tables)
+        self.context_lens = up(batch.context_lens)
+        self.k_scale = up(batch.k_scale)
+        self.v_scale = up(batch.v_scale)
+        self.out = torch.full((batch.batch, batch.num_q_heads, batch.head_dim), float("nan"), dtype=torch.float32,
+                              device=dev)
+        if max_context_len is None:
+            max_context_len = int(batch.context_lens.max(initial=0))
+        self.shape = make_shape(batch.batch, batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.block_size,
+                                batch.max_blocks_per_seq, batch.num_blocks, max_context_len, split_tokens)
+        nbytes = pa_decode_workspace_size(self.shape, self.kv_dtype)
+        # NaN-filled so that a read of an entry this call did not write shows up in the output
+        self.workspace = None if nbytes == 0 else torch.full((nbytes // 4,), float("nan"), dtype=torch.float32,
+                                                             device=dev)
+
+    def args(self):
+        return (self.q, self.k_cache, self.v_cache, self.block_tables, self.context_lens, self.scale, self.kv_dtype,
+                self.out, self.k_scale, self.v_scale)
+
+    def decode(self, stream=None):
+        pa_decode(*self.args(), shape=self.shape, workspace=self.workspace, stream=stream)
+        return self.out

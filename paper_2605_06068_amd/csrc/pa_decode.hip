@@ -1,0 +1,285 @@
+// Host side of libpa_decode.so: argument checks, the launch plan (a pure function of the
+// host-known shape) and the kernel launches behind the C ABI declared in include/pa_decode.h.
+#include "pa_decode.h"
+
+#include <hip/hip_runtime.h>
+
+#include <vector>
+
+#include "pa_device.hpp"
+#include "pa_merge.hpp"
+#include "pa_partition_valu.hpp"
+
+namespace {
+
+using pa::Params;
+
+constexpr int32_t kDefaultSplitTokens = 256;
+constexpr int kMaxGroupValu = 8;
+
+struct Plan {
+    int32_t C;         // split length, tokens
+    int32_t S;         // max splits per sequence
+    int32_t max_ctx;   // resolved max context length
+    size_t lse_offset; // byte offset of the lse array inside the workspace
+    size_t ws_bytes;
+};
+
+pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
+{
+    if (!s) return PA_ERR_INVALID_ARG;
+    if (kv != PA_KV_BF16 && kv != PA_KV_FP8_E4M3) return PA_ERR_INVALID_ARG;
+    if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->head_dim <= 0 || s->block_size <= 0 ||
+        s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->split_tokens < 0)
+        return PA_ERR_INVALID_ARG;
+    if (s->num_q_heads % s->num_kv_heads != 0) return PA_ERR_INVALID_ARG;
+    if ((int64_t)s->max_context_len > (int64_t)s->max_blocks_per_seq * s->block_size) return PA_ERR_INVALID_ARG;
+    if (s->split_tokens % s->block_size != 0) return PA_ERR_INVALID_ARG;
+    if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
+    if (s->head_dim != 64 && s->head_dim != 128) return PA_ERR_UNSUPPORTED;
+    if (s->num_q_heads / s->num_kv_heads > kMaxGroupValu) return PA_ERR_UNSUPPORTED;
+    if (s->batch > 65535 || s->num_kv_heads > 65535 || s->num_q_heads > 65535) return PA_ERR_UNSUPPORTED;
+    if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
+    return PA_OK;
+}
+
+pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
+{
+    const pa_status st = check_shape(s, kv);
+    if (st != PA_OK) return st;
+    plan->max_ctx = s->max_context_len > 0 ? s->max_context_len : s->max_blocks_per_seq * s->block_size;
+    plan->C = s->split_tokens > 0 ? s->split_tokens : kDefaultSplitTokens;
+    plan->S = (plan->max_ctx + plan->C - 1) / plan->C;
+    if (plan->S < 1) plan->S = 1;
+    if (plan->S == 1) {
+        plan->lse_offset = 0;
+        plan->ws_bytes = 0;
+    } else {
+        const size_t rows = (size_t)s->batch * s->num_q_heads * plan->S;
+        const size_t o_bytes = rows * s->head_dim * sizeof(float);
+        plan->lse_offset = (o_bytes + 255) / 256 * 256;
+        plan->ws_bytes = plan->lse_offset + (rows * sizeof(float) + 255) / 256 * 256;
+    }
+    return PA_OK;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+template <int D, int GMAX, int KV>
+void launch_valu(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    if (trace)
+        hipLaunchKernelGGL((pa::partition_valu_kernel<D, GMAX, KV, true>), grid, dim3(64), 0, st, p);
+    else
+        hipLaunchKernelGGL((pa::partition_valu_kernel<D, GMAX, KV, false>), grid, dim3(64), 0, st, p);
+}
+
+template <int D, int KV>
+void launch_valu_g(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    if (p.G <= 2)
+        launch_valu<D, 2, KV>(p, trace, grid, st);
+    else if (p.G <= 4)
+        launch_valu<D, 4, KV>(p, trace, grid, st);
+    else
+        launch_valu<D, 8, KV>(p, trace, grid, st);
+}
+
+struct Events {
+    hipEvent_t before, between, after;
+};
+
+pa_status run(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
+              const int32_t* context_lens, float scale, pa_kv_dtype kv, float* out, const float* k_scale,
+              const float* v_scale, const pa_shape* shape, void* workspace, size_t workspace_bytes, void* stream,
+              int32_t* trace_blocks, int32_t* trace_ranges, bool trace, const Events* ev)
+{
+    Plan plan;
+    const pa_status st = make_plan(shape, kv, &plan);
+    if (st != PA_OK) return st;
+    if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !out) return PA_ERR_INVALID_ARG;
+    if (kv == PA_KV_FP8_E4M3 && (!k_scale || !v_scale)) return PA_ERR_INVALID_ARG;
+    if (!aligned(q, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(out, 16) ||
+        !aligned(block_tables, 4) || !aligned(context_lens, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 4))
+        return PA_ERR_INVALID_ARG;
+    if (!(scale == scale) || scale * 0.f != 0.f) return PA_ERR_INVALID_ARG;  // NaN or infinite
+    if (trace && (!trace_blocks || !trace_ranges)) return PA_ERR_INVALID_ARG;
+    if (plan.ws_bytes > 0) {
+        if (!workspace || !aligned(workspace, 256)) return PA_ERR_INVALID_ARG;
+        if (workspace_bytes < plan.ws_bytes) return PA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    if (shape->batch == 0) return PA_OK;
+
+    Params p{};
+    p.q = static_cast<const uint16_t*>(q);
+    p.k_cache = k_cache;
+    p.v_cache = v_cache;
+    p.block_tables = block_tables;
+    p.context_lens = context_lens;
+    p.k_scale = k_scale;
+    p.v_scale = v_scale;
+    p.out = out;
+    p.part_o = plan.S > 1 ? static_cast<float*>(workspace) : nullptr;
+    p.part_lse = plan.S > 1 ? reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.lse_offset) : nullptr;
+    p.trace_blocks = trace ? trace_blocks : nullptr;
+    p.trace_ranges = trace ? trace_ranges : nullptr;
+    p.scale_log2 = scale * pa::kLog2e;
+    p.B = shape->batch;
+    p.Hq = shape->num_q_heads;
+    p.Hkv = shape->num_kv_heads;
+    p.G = shape->num_q_heads / shape->num_kv_heads;
+    p.MB = shape->max_blocks_per_seq;
+    p.C = plan.C;
+    p.S = plan.S;
+
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (ev && hipEventRecord(ev->before, hs) != hipSuccess) return PA_ERR_HIP;
+
+    const dim3 grid(plan.S, p.Hkv, p.B);
+    if (shape->head_dim == 128) {
+        if (kv == PA_KV_BF16)
+            launch_valu_g<128, pa::KV_BF16>(p, trace, grid, hs);
+        else
+            launch_valu_g<128, pa::KV_FP8>(p, trace, grid, hs);
+    } else {
+        if (kv == PA_KV_BF16)
+            launch_valu_g<64, pa::KV_BF16>(p, trace, grid, hs);
+        else
+            launch_valu_g<64, pa::KV_FP8>(p, trace, grid, hs);
+    }
+    if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+    if (ev && hipEventRecord(ev->between, hs) != hipSuccess) return PA_ERR_HIP;
+
+    if (plan.S > 1) {
+        const dim3 mgrid(p.Hq, p.B);
+        if (shape->head_dim == 128)
+            hipLaunchKernelGGL((pa::merge_kernel<128>), mgrid, dim3(64), 0, hs, p);
+        else
+            hipLaunchKernelGGL((pa::merge_kernel<64>), mgrid, dim3(64), 0, hs, p);
+        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+    }
+    if (ev && hipEventRecord(ev->after, hs) != hipSuccess) return PA_ERR_HIP;
+    return PA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t pa_split_tokens(const pa_shape* shape, pa_kv_dtype kv_dtype)
+{
+    Plan plan;
+    const pa_status st = make_plan(shape, kv_dtype, &plan);
+    return st == PA_OK ? plan.C : -(int32_t)st;
+}
+
+int32_t pa_max_splits(const pa_shape* shape, pa_kv_dtype kv_dtype)
+{
+    Plan plan;
+    const pa_status st = make_plan(shape, kv_dtype, &plan);
+    return st == PA_OK ? plan.S : -(int32_t)st;
+}
+
+int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, int32_t context_len, int32_t* starts,
+                      int32_t* ends, int32_t cap)
+{
+    Plan plan;
+    const pa_status st = make_plan(shape, kv_dtype, &plan);
+    if (st != PA_OK) return -(int32_t)st;
+    if (context_len > plan.max_ctx || cap < 0 || (cap > 0 && (!starts || !ends))) return -(int32_t)PA_ERR_INVALID_ARG;
+    if (context_len <= 0) return 0;
+    const int32_t n = (context_len + plan.C - 1) / plan.C;
+    for (int32_t s = 0; s < n && s < cap; ++s) {
+        starts[s] = s * plan.C;
+        const int64_t e = (int64_t)(s + 1) * plan.C;
+        ends[s] = e < context_len ? (int32_t)e : context_len;
+    }
+    return n;
+}
+
+size_t pa_decode_workspace_size(const pa_shape* shape, pa_kv_dtype kv_dtype)
+{
+    Plan plan;
+    return make_plan(shape, kv_dtype, &plan) == PA_OK ? plan.ws_bytes : 0;
+}
+
+pa_status pa_decode(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
+                    const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, float* out, const float* k_scale,
+                    const float* v_scale, const pa_shape* shape, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
+               workspace, workspace_bytes, stream, nullptr, nullptr, false, nullptr);
+}
+
+pa_status pa_decode_trace(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
+                          const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, float* out,
+                          const float* k_scale, const float* v_scale, const pa_shape* shape, void* workspace,
+                          size_t workspace_bytes, void* stream, int32_t* visited_blocks, int32_t* split_ranges)
+{
+    return run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
+               workspace, workspace_bytes, stream, visited_blocks, split_ranges, true, nullptr);
+}
+
+pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
+                            const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, float* out,
+                            const float* k_scale, const float* v_scale, const pa_shape* shape, void* workspace,
+                            size_t workspace_bytes, void* stream, int32_t steps, float* partition_ms, float* merge_ms)
+{
+    if (steps <= 0 || steps > 100000 || !partition_ms || !merge_ms) return PA_ERR_INVALID_ARG;
+    std::vector<Events> evs((size_t)steps);
+    pa_status st = PA_OK;
+    size_t created = 0;
+    for (; created < evs.size(); ++created) {
+        Events& e = evs[created];
+        if (hipEventCreate(&e.before) != hipSuccess) { st = PA_ERR_HIP; break; }
+        if (hipEventCreate(&e.between) != hipSuccess) { (void)hipEventDestroy(e.before); st = PA_ERR_HIP; break; }
+        if (hipEventCreate(&e.after) != hipSuccess) {
+            (void)hipEventDestroy(e.before); (void)hipEventDestroy(e.between); st = PA_ERR_HIP; break;
+        }
+    }
+    for (int32_t i = 0; st == PA_OK && i < steps; ++i)
+        st = run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
+                 workspace, workspace_bytes, stream, nullptr, nullptr, false, &evs[(size_t)i]);
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess && st == PA_OK) st = PA_ERR_HIP;
+    if (st == PA_OK && shape->batch > 0) {
+        double part = 0.0, merge = 0.0;
+        for (const Events& e : evs) {
+            float a = 0.f, b = 0.f;
+            if (hipEventElapsedTime(&a, e.before, e.between) != hipSuccess ||
+                hipEventElapsedTime(&b, e.between, e.after) != hipSuccess) { st = PA_ERR_HIP; break; }
+            part += a;
+            merge += b;
+        }
+        *partition_ms = (float)(part / steps);
+        *merge_ms = pa_max_splits(shape, kv_dtype) > 1 ? (float)(merge / steps) : 0.f;
+    } else if (st == PA_OK) {
+        *partition_ms = 0.f;
+        *merge_ms = 0.f;
+    }
+    for (size_t i = 0; i < created; ++i) {
+        (void)hipEventDestroy(evs[i].before);
+        (void)hipEventDestroy(evs[i].between);
+        (void)hipEventDestroy(evs[i].after);
+    }
+    return st;
+}
+
+const char* pa_kernel_variant(const pa_shape* shape, pa_kv_dtype kv_dtype)
+{
+    if (check_shape(shape, kv_dtype) != PA_OK) return nullptr;
+    return "valu";
+}
+
+const char* pa_status_string(pa_status status)
+{
+    switch (status) {
+        case PA_OK: return "PA_OK";
+        case PA_ERR_INVALID_ARG: return "PA_ERR_INVALID_ARG";
+        case PA_ERR_UNSUPPORTED: return "PA_ERR_UNSUPPORTED";
+        case PA_ERR_WORKSPACE_TOO_SMALL: return "PA_ERR_WORKSPACE_TOO_SMALL";
+        case PA_ERR_HIP: return "PA_ERR_HIP";
+    }
+    return "PA_ERR_UNKNOWN";
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+// Device-side helpers shared by the partition and merge kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pa {
+
+constexpr int kWave = 64;
+constexpr int kBlockSize = 16;          // tokens per KV block (the only block size supported)
+constexpr float kNegBig = -1.0e30f;     // "minus infinity" that stays finite under subtraction
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+enum : int { KV_BF16 = 0, KV_FP8 = 1 };
+
+// Everything a launch needs.  Pointers are device memory.
+struct Params {
+    const uint16_t* q;            // [B, Hq, D] bf16
+    const void* k_cache;          // [NB, Hkv, 16, D]
+    const void* v_cache;
+    const int32_t* block_tables;  // [B, MB]
+    const int32_t* context_lens;  // [B]
+    const float* k_scale;         // [Hkv] or null
+    const float* v_scale;
+    float* out;                   // [B, Hq, D]
+    float* part_o;                // [B, Hq, S, D] normalised partial outputs (null when S == 1)
+    float* part_lse;              // [B, Hq, S]   log2-domain log-sum-exp of each partial
+    int32_t* trace_blocks;        // [B, Hkv, MB, 2] or null
+    int32_t* trace_ranges;        // [B, Hkv, S, 2] or null
+    float scale_log2;             // softmax scale * log2(e)
+    int32_t B, Hq, Hkv, G, MB;
+    int32_t C;                    // split length in tokens (multiple of 16)
+    int32_t S;                    // max splits per sequence
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// OCP e4m3 byte -> float, by bit manipulation (exact; NaN bytes are never read from valid slots).
+__device__ __forceinline__ float e4m3_to_f32(uint32_t byte)
+{
+    const uint32_t sign = (byte & 0x80u) << 24;
+    const uint32_t mag = byte & 0x7fu;
+    // normal numbers: move exponent/mantissa into place and rebias (127 - 7 = 120)
+    float r = __uint_as_float((mag << 20) + (120u << 23));
+    // subnormals (exponent field 0): value = mant * 2^-9
+    if (mag < 8u) r = (float)mag * 0.001953125f;
+    return __uint_as_float(__float_as_uint(r) | sign);
+}
+
+// DPP moves inside rows of 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16
+
+// Sum over aligned groups of LANES lanes (8 or 16); every lane of the group gets the total.
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v)
+{
+    v += dpp_f<kDppXor1>(v);
+    v += dpp_f<kDppXor2>(v);
+    v += dpp_f<kDppHalfMirror>(v);
+    if (LANES == 16) v += dpp_f<kDppMirror>(v);
+    return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+}  // namespace pa

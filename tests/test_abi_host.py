@@ -1,0 +1,130 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, plans splits as the definition says, and rejects bad arguments before any
+launch."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_06068_amd import binding as pa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def shape(**kw):
+    base = dict(batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
+                num_blocks=1024, max_context_len=0, split_tokens=0)
+    base.update(kw)
+    return pa.make_shape(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pa_decode.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(pa_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(pa.EXPORTS), declared ^ set(pa.EXPORTS)
+    L = pa.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    assert pa.status_string(pa.PA_OK) == "PA_OK"
+    assert pa.status_string(pa.PA_ERR_WORKSPACE_TOO_SMALL) == "PA_ERR_WORKSPACE_TOO_SMALL"
+    assert pa.status_string(77) == "PA_ERR_UNKNOWN"
+
+
+def test_shape_struct_matches_header_field_order():
+    header = open(os.path.join(ROOT, "include", "pa_decode.h")).read()
+    body = re.search(r"typedef struct pa_shape \{(.*?)\} pa_shape;", header, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"int32_t\s+([a-z_]+);", body)
+    assert fields == [f[0] for f in pa.pa_shape._fields_]
+    assert ctypes.sizeof(pa.pa_shape) == 4 * len(fields)
+
+
+@pytest.mark.parametrize("kv", [pa.PA_KV_BF16, pa.PA_KV_FP8_E4M3])
+def test_split_plan_is_the_definition(oracle, kv):
+    for forced in [0, 16, 48, 256, 1024, 4096]:
+        s = shape(split_tokens=forced)
+        C = pa.pa_split_tokens(s, kv)
+        assert C > 0 and C % 16 == 0 and (forced == 0 or C == forced)
+        assert pa.pa_max_splits(s, kv) == -(-4096 // C)
+        for L in [0, 1, 15, 16, 17, C - 1, C, C + 1, 2 * C, 4095, 4096]:
+            if L > 4096:
+                continue
+            starts, ends = pa.pa_split_plan(s, kv, L)
+            os_, oe = oracle.split_ranges(L, C)
+            assert starts == os_.tolist() and ends == oe.tolist()
+
+
+def test_split_length_depends_on_host_shape_only():
+    a = pa.pa_split_tokens(shape(max_context_len=4096), pa.PA_KV_BF16)
+    b = pa.pa_split_tokens(shape(max_context_len=4096), pa.PA_KV_BF16)
+    assert a == b
+    # a context bound that fits one split needs no workspace
+    s1 = shape(max_context_len=a)
+    assert pa.pa_max_splits(s1, pa.PA_KV_BF16) == 1 and pa.pa_decode_workspace_size(s1, pa.PA_KV_BF16) == 0
+
+
+def test_workspace_size_covers_partials():
+    s = shape(split_tokens=256)
+    S = pa.pa_max_splits(s, pa.PA_KV_BF16)
+    assert S == 16
+    need = 4 * 32 * S * (128 + 1) * 4
+    got = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
+    assert need <= got <= need + 512
+
+
+@pytest.mark.parametrize("bad,code", [
+    (dict(num_q_heads=30), pa.PA_ERR_INVALID_ARG),
+    (dict(batch=-1), pa.PA_ERR_INVALID_ARG),
+    (dict(max_context_len=256 * 16 + 1), pa.PA_ERR_INVALID_ARG),
+    (dict(split_tokens=24), pa.PA_ERR_INVALID_ARG),
+    (dict(head_dim=96), pa.PA_ERR_UNSUPPORTED),
+    (dict(block_size=32, split_tokens=0), pa.PA_ERR_UNSUPPORTED),
+    (dict(num_q_heads=8 * 32), pa.PA_ERR_UNSUPPORTED),
+])
+def test_bad_shapes_are_rejected(bad, code):
+    s = shape(**bad)
+    with pytest.raises(pa.PaError) as e:
+        pa.pa_split_tokens(s, pa.PA_KV_BF16)
+    assert e.value.status == code
+    assert pa.pa_decode_workspace_size(s, pa.PA_KV_BF16) == 0
+    assert pa.pa_kernel_variant(s, pa.PA_KV_BF16) is None
+
+
+def _raw_decode(s, kv=pa.PA_KV_BF16, q=0x1000, k=0x2000, v=0x3000, bt=0x4000, cl=0x5000, out=0x6000, ks=None, vs=None,
+                ws=None, ws_bytes=0, scale=0.1):
+    """Calls pa_decode with fake device addresses: only paths that return before a launch."""
+    vp = ctypes.c_void_p
+    return pa.lib().pa_decode(vp(q), vp(k), vp(v), vp(bt), vp(cl), ctypes.c_float(scale), kv, vp(out), vp(ks), vp(vs),
+                              ctypes.byref(s), vp(ws), ctypes.c_size_t(ws_bytes), None)
+
+
+def test_pointer_and_workspace_checks_return_before_any_launch():
+    s = shape()
+    assert _raw_decode(s, q=None) == pa.PA_ERR_INVALID_ARG
+    assert _raw_decode(s, out=None) == pa.PA_ERR_INVALID_ARG
+    assert _raw_decode(s, k=0x2004) == pa.PA_ERR_INVALID_ARG  # misaligned
+    assert _raw_decode(s, kv=7) == pa.PA_ERR_INVALID_ARG
+    assert _raw_decode(s, kv=pa.PA_KV_FP8_E4M3) == pa.PA_ERR_INVALID_ARG  # fp8 without scales
+    assert _raw_decode(s, scale=float("nan")) == pa.PA_ERR_INVALID_ARG
+    need = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
+    assert need > 0
+    assert _raw_decode(s, ws=None) == pa.PA_ERR_INVALID_ARG
+    assert _raw_decode(s, ws=0x10000, ws_bytes=need - 1) == pa.PA_ERR_WORKSPACE_TOO_SMALL
+    assert _raw_decode(s, ws=0x10010, ws_bytes=need) == pa.PA_ERR_INVALID_ARG  # workspace not 256-aligned
+    # an empty batch is a successful no-op
+    assert _raw_decode(shape(batch=0)) == pa.PA_OK
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+
+    s = shape(batch=1, max_context_len=16)
+    t = torch.zeros(16)
+    with pytest.raises(ValueError):
+        pa.pa_decode(t, t, t, t, t, 0.1, pa.PA_KV_BF16, t, shape=s)

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 CPU oracle on the same
+seeded inputs, plus bit-exact checks of the block-table walk and the split boundaries."""
+import time
+
+import numpy as np
+import pytest
+
+from paper_2605_06068_amd import workloads as W
+from tests.parity import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pa():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2605_06068_amd import binding
+
+    binding.lib()
+    return binding
+
+
+def run_gpu(pa, batch, **kw):
+    import torch
+
+    dev = pa.DeviceBatch(batch, **kw)
+    out = dev.decode()
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), dev
+
+
+def check(pa, oracle, batch, what, **kw):
+    print(f"[case] {what} seed={batch.seed} B={batch.batch} Hq={batch.num_q_heads} Hkv={batch.num_kv_heads} "
+          f"D={batch.head_dim} kv={batch.kv_dtype} tokens={batch.total_tokens} {kw}", flush=True)
+    got, dev = run_gpu(pa, batch, **kw)
+    want = oracle.decode_batch(batch)["out"]
+    err = assert_parity(got, want, batch.kv_dtype, what)
+    print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e} C={pa.pa_split_tokens(dev.shape, dev.kv_dtype)}", flush=True)
+    return got, want
+
+
+# ------------------------------------------------------------------ the five configs
+@pytest.mark.parametrize("seed", [1001, 2001, 3001, None])
+def test_config1_tiny(pa, oracle, seed):
+    seed = int(time.time()) % 100000 + 10 if seed is None else seed
+    check(pa, oracle, W.make_config(1, seed=seed), "config1")
+
+
+@pytest.mark.parametrize("config,kwargs", [
+    (2, dict(length_scale=0.25)),
+    (3, dict(length_scale=1 / 32, batch_limit=4)),
+    (4, dict(length_scale=1 / 8)),
+    (5, dict(length_scale=1 / 16, batch_limit=16)),
+])
+@pytest.mark.parametrize("seed_base", [1000, 2000])
+def test_configs_reduced_lengths(pa, oracle, config, kwargs, seed_base):
+    b = W.make_config(config, seed=seed_base + config, **kwargs)
+    check(pa, oracle, b, f"config{config}-reduced")
+
+
+@pytest.mark.parametrize("config", [2, 3, 4, 5])
+def test_configs_full_size(pa, oracle, config):
+    """Full-size batches in the launch configuration the benchmark times (default split plan,
+    max_context_len = the batch maximum); the oracle covers every output row."""
+    b = W.make_config(config)
+    check(pa, oracle, b, f"config{config}-full")
+
+
+# ------------------------------------------------------------------ shapes and edges
+@pytest.mark.parametrize("Hq,Hkv,D", [(1, 1, 64), (1, 1, 128), (4, 4, 128), (2, 1, 64), (6, 2, 128), (8, 1, 128),
+                                      (16, 2, 64), (5, 1, 128), (12, 4, 64)])
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_head_shapes(pa, oracle, Hq, Hkv, D, kv):
+    b = W.make_batch("shapes", 50 + Hq + D, [1, 15, 16, 17, 300, 257, 512], Hq, Hkv, D, 16, kv, num_blocks=90,
+                     max_blocks_per_seq=40)
+    check(pa, oracle, b, "head-shapes")
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("C", [16, 48, 256, 1024, 4096])
+def test_forced_split_sweep(pa, oracle, kv, C):
+    lens = [1, 16, 47, 48, 49, 255, 256, 257, 1023, 1025, 2000]
+    b = W.make_batch("splits", 60, lens, 8, 2, 128, 16, kv)
+    got, want = check(pa, oracle, b, f"split-sweep C={C}", split_tokens=C)
+    ref, _ = run_gpu(pa, b, split_tokens=4096)
+    tol = 1e-4 if kv == W.KV_BF16 else 1e-3
+    assert np.max(np.abs(got - ref)) <= tol  # different split lengths agree closely with each other
+
+
+def test_single_token_context_returns_v_exactly(pa):
+    for kv in (W.KV_BF16, W.KV_FP8_E4M3):
+        b = W.make_batch("l1", 70, [1, 1, 1, 1], 8, 2, 128, 16, kv, num_blocks=9)
+        if kv == W.KV_FP8_E4M3:
+            # every finite e4m3 byte once: 254 values over the two KV heads of sequence 0
+            vals = np.array([x for x in range(256) if x not in (0x7F, 0xFF)] + [0, 0x80], dtype=np.uint8)
+            b.v_cache[b.block_tables[0, 0], :, 0, :] = vals.reshape(2, 128)
+            b.v_scale[:] = [0.5, 2.0]  # powers of two keep the product exact in float32
+        got, _ = run_gpu(pa, b)
+        for s in range(4):
+            for h in range(8):
+                raw = b.v_cache[b.block_tables[s, 0], h // 4, 0]
+                if kv == W.KV_BF16:
+                    want = W.bf16_bits_to_f32(raw)
+                else:
+                    import torch
+
+                    want = torch.from_numpy(raw.copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy() \
+                        * b.v_scale[h // 4]
+                assert np.array_equal(got[s, h], want), (kv, s, h)
+
+
+def test_zero_length_and_poisoned_inputs(pa, oracle):
+    for kv in (W.KV_BF16, W.KV_FP8_E4M3):
+        b = W.make_batch("edge", 71, [0, 33, 0, 700, 16], 8, 2, 128, 16, kv, num_blocks=60, max_blocks_per_seq=50)
+        b.block_tables[b.block_tables < 0] = 2 ** 30  # garbage ids behind the valid prefix
+        got, want = check(pa, oracle, b, "zero-length+poison")
+        assert np.all(got[0] == 0) and np.all(got[2] == 0)
+        # a host bound above the real maximum changes the grid, not the result
+        got2, _ = run_gpu(pa, b, max_context_len=800)
+        assert np.array_equal(got, got2)
+
+
+def test_runs_are_bit_identical(pa):
+    b = W.make_config(2, length_scale=0.25)
+    a1, _ = run_gpu(pa, b)
+    a2, _ = run_gpu(pa, b)
+    assert np.array_equal(a1, a2)
+
+
+# ------------------------------------------------------------------ bit-exact indexing
+def one_hot_batch(kv, lens, Hq, Hkv, D, targets, seed):
+    """q = 64*e_0 for every head; the target token's K row is 64*e_0 (all others 0), so the target
+    outweighs every other token by exp(4096*scale) and all other weights underflow to 0.  V rows
+    hold their own logical position as base-16 digits in dims 0..3 (exact in bf16 and e4m3) and
+    the sequence index in dim 4."""
+    b = W.make_batch("onehot", seed, lens, Hq, Hkv, D, 16, kv)
+    b.q[:] = 0
+    b.q[:, :, 0] = W.f32_to_bf16_bits(np.float32(64))
+    zero = 0
+    b.k_cache[:] = zero
+    b.v_cache[:] = zero
+    enc = (lambda x: W.f32_to_bf16_bits(np.float32(x))) if kv == W.KV_BF16 else \
+        (lambda x: W.f32_to_e4m3_bytes(np.array([x], np.float32))[0])
+    if kv == W.KV_FP8_E4M3:
+        b.k_scale[:] = 1.0
+        b.v_scale[:] = 1.0
+    for s, L in enumerate(lens):
+        for t in range(L):
+            phys, slot = b.block_tables[s, t // 16], t % 16
+            for d in range(4):
+                b.v_cache[phys, :, slot, d] = enc((t >> (4 * d)) & 15)
+            b.v_cache[phys, :, slot, 4] = enc(s % 16)
+        t = targets[s]
+        b.k_cache[b.block_tables[s, t // 16], :, t % 16, 0] = enc(64)
+    return b
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("C", [0, 48, 256])
+def test_one_hot_probe_reads_exactly_the_target_slot(pa, kv, C):
+    L = 700
+    Cr = 256 if C == 0 else C
+    edge = sorted({0, 15, 16, 17, Cr - 1, Cr, Cr + 1, 2 * Cr - 1, 2 * Cr, L - 17, L - 16, L - 2, L - 1})
+    lens = [L] * len(edge)
+    b = one_hot_batch(kv, lens, 8, 2, 128, edge, 80)
+    got, _ = run_gpu(pa, b, split_tokens=C)
+    for s, t in enumerate(edge):
+        digits = got[s, :, :5]
+        want = np.array([(t >> (4 * d)) & 15 for d in range(4)] + [s % 16], dtype=np.float32)
+        assert np.array_equal(digits, np.broadcast_to(want, digits.shape)), (s, t, digits[0])
+
+
+@pytest.mark.parametrize("config,kwargs,C", [
+    (1, {}, 0), (1, {}, 16), (2, dict(length_scale=0.25), 0), (4, dict(length_scale=1 / 8), 0),
+    (4, dict(length_scale=1 / 8), 48), (5, dict(length_scale=1 / 16, batch_limit=8), 0),
+])
+def test_trace_matches_block_tables_and_split_plan(pa, oracle, config, kwargs, C):
+    import torch
+
+    b = W.make_config(config, **kwargs)
+    dev = pa.DeviceBatch(b, split_tokens=C)
+    S = pa.pa_max_splits(dev.shape, dev.kv_dtype)
+    Cr = pa.pa_split_tokens(dev.shape, dev.kv_dtype)
+    visited = torch.full((b.batch, b.num_kv_heads, b.max_blocks_per_seq, 2), -7, dtype=torch.int32, device="cuda")
+    ranges = torch.full((b.batch, b.num_kv_heads, S, 2), -7, dtype=torch.int32, device="cuda")
+    pa.pa_decode_trace(*dev.args(), shape=dev.shape, workspace=dev.workspace, visited_blocks=visited,
+                       split_ranges=ranges)
+    torch.cuda.synchronize()
+    visited, ranges = visited.cpu().numpy(), ranges.cpu().numpy()
+    for s in range(b.batch):
+        ids = oracle.visited_blocks(b.block_tables, b.context_lens, 16, s)
+        starts, ends = oracle.split_ranges(int(b.context_lens[s]), Cr)
+        hs, he = pa.pa_split_plan(dev.shape, dev.kv_dtype, int(b.context_lens[s]))
+        assert hs == starts.tolist() and he == ends.tolist()
+        for g in range(b.num_kv_heads):
+            assert np.array_equal(visited[s, g, :len(ids), 0], ids) and np.array_equal(visited[s, g, :len(ids), 1], ids)
+            assert np.all(visited[s, g, len(ids):] == -7)  # nothing past the context was dereferenced
+            assert np.array_equal(ranges[s, g, :len(starts), 0], starts)
+            assert np.array_equal(ranges[s, g, :len(starts), 1], ends)
+            assert np.all(ranges[s, g, len(starts):] == -7)
+    # the instrumented run computes the same output as the plain one
+    want = oracle.decode_batch(b)["out"]
+    assert_parity(dev.out.cpu().numpy(), want, b.kv_dtype, "trace-run")
+
+
+def test_profile_entry_reports_kernel_times(pa):
+    b = W.make_config(2, length_scale=0.25)
+    dev = pa.DeviceBatch(b)
+    part_ms, merge_ms = pa.pa_decode_profile(*dev.args(), shape=dev.shape, workspace=dev.workspace, steps=5)
+    assert part_ms > 0 and merge_ms >= 0
