@@ -8,6 +8,7 @@
 
 #include "pa_device.hpp"
 #include "pa_merge.hpp"
+#include "pa_partition_mfma.hpp"
 #include "pa_partition_valu.hpp"
 
 namespace {
@@ -15,7 +16,10 @@ namespace {
 using pa::Params;
 
 constexpr int32_t kDefaultSplitTokens = 256;
-constexpr int kMaxGroupValu = 8;
+constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds in registers
+constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
+constexpr int kMinGroupMfma = 4;   // below this the padded tile is mostly empty: vector-ALU kernel
+constexpr int kMfmaStages = 3;     // depth of the LDS tile ring of the matrix-core kernel
 
 struct Plan {
     int32_t C;         // split length, tokens
@@ -24,6 +28,13 @@ struct Plan {
     size_t lse_offset; // byte offset of the lse array inside the workspace
     size_t ws_bytes;
 };
+
+// The matrix-core kernel covers head_dim 128 with bf16 KV and groups of 4..16 query heads.
+bool use_mfma(const pa_shape* s, pa_kv_dtype kv)
+{
+    const int G = s->num_q_heads / s->num_kv_heads;
+    return s->head_dim == 128 && kv == PA_KV_BF16 && G >= kMinGroupMfma && G <= kMaxGroupMfma;
+}
 
 pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
 {
@@ -37,7 +48,7 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->split_tokens % s->block_size != 0) return PA_ERR_INVALID_ARG;
     if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return PA_ERR_UNSUPPORTED;
-    if (s->num_q_heads / s->num_kv_heads > kMaxGroupValu) return PA_ERR_UNSUPPORTED;
+    if (s->num_q_heads / s->num_kv_heads > (use_mfma(s, kv) ? kMaxGroupMfma : kMaxGroupValu)) return PA_ERR_UNSUPPORTED;
     if (s->batch > 65535 || s->num_kv_heads > 65535 || s->num_q_heads > 65535) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
     return PA_OK;
@@ -136,7 +147,12 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     if (ev && hipEventRecord(ev->before, hs) != hipSuccess) return PA_ERR_HIP;
 
     const dim3 grid(plan.S, p.Hkv, p.B);
-    if (shape->head_dim == 128) {
+    if (use_mfma(shape, kv)) {
+        if (trace)
+            hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, true>), grid, dim3(64), 0, hs, p);
+        else
+            hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, false>), grid, dim3(64), 0, hs, p);
+    } else if (shape->head_dim == 128) {
         if (kv == PA_KV_BF16)
             launch_valu_g<128, pa::KV_BF16>(p, trace, grid, hs);
         else
@@ -267,7 +283,7 @@ pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_ca
 const char* pa_kernel_variant(const pa_shape* shape, pa_kv_dtype kv_dtype)
 {
     if (check_shape(shape, kv_dtype) != PA_OK) return nullptr;
-    return "valu";
+    return use_mfma(shape, kv_dtype) ? "mfma" : "valu";
 }
 
 const char* pa_status_string(pa_status status)

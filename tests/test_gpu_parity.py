@@ -85,8 +85,7 @@ def test_forced_split_sweep(pa, oracle, kv, C):
     b = W.make_batch("splits", 60, lens, 8, 2, 128, 16, kv)
     got, want = check(pa, oracle, b, f"split-sweep C={C}", split_tokens=C)
     ref, _ = run_gpu(pa, b, split_tokens=4096)
-    tol = 1e-4 if kv == W.KV_BF16 else 1e-3
-    assert np.max(np.abs(got - ref)) <= tol  # different split lengths agree closely with each other
+    assert_parity(got, ref, kv, "against the unsplit run")  # split lengths agree with each other too
 
 
 def test_single_token_context_returns_v_exactly(pa):
