@@ -33,7 +33,7 @@ def parse_args():
                     help="named config (default 2: the Llama-3-8B-shaped batch the metric is quoted on)")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--pools", type=int, default=0, help="KV pool copies to rotate over (0 = enough for >= 2 GB)")
-    ap.add_argument("--split-tokens", type=int, default=0, help="force the split length (0 = library heuristic)")
+    ap.add_argument("--partitions", type=int, default=0, help="force the number of partitions (0 = library heuristic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -64,7 +64,7 @@ def main():
     pool_bytes = batch.k_cache.nbytes + batch.v_cache.nbytes
     n_pools = args.pools if args.pools > 0 else max(2, min(8, -(-(2 << 30) // max(pool_bytes, 1))))
 
-    dev = pa.DeviceBatch(batch, split_tokens=args.split_tokens)
+    dev = pa.DeviceBatch(batch, num_partitions=args.partitions)
     pools = [(dev.k_cache, dev.v_cache)]
     for _ in range(n_pools - 1):
         pools.append((dev.k_cache.clone(), dev.v_cache.clone()))
@@ -133,7 +133,7 @@ def main():
             "workload": batch.name, "batch": batch.batch, "num_q_heads": batch.num_q_heads,
             "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "block_size": batch.block_size,
             "total_context_tokens": batch.total_tokens, "kv_bytes": kv_bytes, "seed": batch.seed,
-            "kv_pool_copies": n_pools, "split_tokens": pa.pa_split_tokens(dev.shape, dev.kv_dtype),
+            "kv_pool_copies": n_pools, "num_partitions": pa.pa_num_partitions(dev.shape, dev.kv_dtype),
             "kernel_variant": pa.pa_kernel_variant(dev.shape, dev.kv_dtype),
         },
         "roofline": {

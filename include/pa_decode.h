@@ -38,7 +38,7 @@
  *     out           [batch, num_q_heads, head_dim]                        float32
  *
  * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
- * 1 <= G <= 16; PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no infinities, 0x7F/0xFF NaN)
+ * 1 <= G <= 16 (G <= 8 for head_dim 64 or fp8 KV); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no infinities, 0x7F/0xFF NaN)
  * with one float32 scale per KV head for K and one for V.
  */
 #ifndef PA_DECODE_H
@@ -72,34 +72,43 @@ typedef struct pa_shape {
     int32_t max_blocks_per_seq; /* row stride of block_tables */
     int32_t num_blocks;         /* blocks in the pool (k_cache.shape[0]) */
     int32_t max_context_len;    /* host-known upper bound on context_lens; 0 = max_blocks_per_seq * block_size */
-    int32_t split_tokens;       /* 0 = library heuristic; otherwise the split length C to use
-                                   (a positive multiple of block_size) */
+    int32_t num_partitions;     /* 0 = library heuristic; otherwise the number P of partitions of the
+                                   split plan below (1 .. 65535; tests force values) */
 } pa_shape;
 
-/* Split length C (tokens) the library uses for this shape: flash-decoding style split-K over the
- * context.  A pure function of the shape (never of device data); a multiple of block_size.
- * Returns a negative pa_status on an invalid / unsupported shape. */
-int32_t pa_split_tokens(const pa_shape *shape, pa_kv_dtype kv_dtype);
+/*
+ * The split plan (flash-decoding style split-K over the context, balanced over the whole batch).
+ * The context of sequence b is cut into tiles of 32 tokens: tiles_b = ceil(context_lens[b] / 32)
+ * (0 for an empty context); the tiles of all sequences, in batch order, form one global tile
+ * sequence of length T.  It is cut into P contiguous ranges, partition k owning global tiles
+ * [floor(k*T/P), floor((k+1)*T/P)).  One wavefront per (partition, KV head) processes a range;
+ * a sequence that lies inside one range is finished there, a sequence that a range boundary
+ * cuts gets one partial result per range it touches and the merge kernel combines them by
+ * their log-sum-exps.  P is a pure function of the shape and of the device's compute-unit count
+ * (never of device data); the boundaries follow from the context lengths on the device.
+ *
+ * pa_num_partitions: P for this shape, or a negative pa_status on an invalid / unsupported shape.
+ */
+int32_t pa_num_partitions(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
-/* Upper bound on the number of splits of any sequence: ceil(max_context_len / C). */
-int32_t pa_max_splits(const pa_shape *shape, pa_kv_dtype kv_dtype);
+/*
+ * The plan as the kernels apply it, computed on the host from a HOST copy of the context
+ * lengths: block_partition (HOST, [batch, max_blocks_per_seq]) receives, for every KV block
+ * that holds a valid token, the index of the partition that processes it, and -1 elsewhere.
+ * Returns T, or a negative pa_status (bad shape, null pointer, a length above max_context_len).
+ */
+int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, const int32_t *context_lens,
+                      int32_t *block_partition);
 
-/* The split plan of one sequence of context_len tokens, as the kernels apply it on the device:
- * n = ceil(context_len / C) splits, split s covers tokens [s*C, min((s+1)*C, context_len)).
- * Writes at most cap (start, end) pairs into the HOST arrays and returns n (0 for
- * context_len <= 0), or a negative pa_status. */
-int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, int32_t context_len, int32_t *starts,
-                      int32_t *ends, int32_t cap);
-
-/* Bytes of device workspace pa_decode needs for this shape (partial outputs and log-sum-exps of
- * the splits).  0 when the shape never splits.  Returns 0 as well for an invalid shape (pa_decode
- * then reports the error). */
+/* Bytes of device workspace pa_decode needs for this shape: two partial results (normalised
+ * output row + log-sum-exp per query head) per partition.  0 when P == 1.  Returns 0 as well for
+ * an invalid shape (pa_decode then reports the error). */
 size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
 /*
  * The decode attention step.  Enqueues a partition kernel (block-table walk, K/V tile loads,
- * scores, online softmax, PV; one partial per (sequence, query head, split)) and, when the shape
- * can split, a merge kernel that combines the partials by their log-sum-exps into out.
+ * scores, online softmax, PV; final rows for sequences inside one partition, partials for the
+ * others) and, when P > 1, a merge kernel that combines the partials by their log-sum-exps.
  *
  *   q, k_cache, v_cache, block_tables, context_lens, out   device, layouts above
  *   scale            softmax scale applied to q.K (e.g. 1/sqrt(head_dim))
@@ -121,17 +130,16 @@ pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, con
  * Same computation with the production indexing code instrumented (slow; for tests).  In
  * addition to out it records, for checking the block-table walk and the split boundaries bit
  * for bit:
- *   visited_blocks [batch, num_kv_heads, max_blocks_per_seq, 2] int32 device: for logical block j
- *                  of sequence b, the physical id the kernel used for its K loads ([..,0]) and
- *                  for its V loads ([..,1]).  Entries of blocks the kernel never touched keep
- *                  the caller's initial contents.
- *   split_ranges   [batch, num_kv_heads, pa_max_splits(), 2] int32 device: (start, end) token
- *                  range each non-empty split processed; untouched for empty splits.
+ *   visited_blocks [batch, num_kv_heads, max_blocks_per_seq, 3] int32 device: for logical block j
+ *                  of sequence b and KV head g, the physical id the kernel used for its K loads
+ *                  ([..,0]) and for its V loads ([..,1]) and the partition that processed it
+ *                  ([..,2]).  Entries of blocks the kernel never touched keep the caller's initial
+ *                  contents.
  */
 pa_status pa_decode_trace(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                           const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,
                           const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
-                          size_t workspace_bytes, void *stream, int32_t *visited_blocks, int32_t *split_ranges);
+                          size_t workspace_bytes, void *stream, int32_t *visited_blocks);
 
 /*
  * Measurement helper: runs pa_decode `steps` times on `stream` with HIP events around each
@@ -144,8 +152,9 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
                             size_t workspace_bytes, void *stream, int32_t steps, float *partition_ms,
                             float *merge_ms);
 
-/* Name of the partition kernel variant pa_decode picks for this shape ("mfma" for wide
- * query-head groups, "valu" otherwise); NULL for an invalid shape.  Static storage. */
+/* Name of the partition kernel variant pa_decode picks for this shape ("mfma": matrix cores, for
+ * head_dim 128, bf16 KV and groups of 4..16 query heads; "valu" otherwise); NULL for an invalid
+ * shape.  Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
 /* Human-readable name of a status code.  Static storage. */

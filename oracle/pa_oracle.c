@@ -236,23 +236,38 @@ int32_t pa_oracle_visited_blocks(const int32_t *block_tables, const int32_t *con
 }
 
 /*
- * The split-K partition of a context of L tokens into chunks of C tokens, written from
- * its definition: n = ceil(L / C) chunks, chunk s covers tokens [s*C, min((s+1)*C, L)).
- * Fills starts/ends (at most cap entries) and returns n (0 for L <= 0).
+ * The split plan written from its definition (the product states it in its public header):
+ * every sequence is cut into tiles of 32 tokens, tiles_b = ceil(L_b / 32); the tiles of all
+ * sequences in batch order are numbered 0 .. T-1; partition k of P owns the global tiles t with
+ * floor(k*T/P) <= t < floor((k+1)*T/P).  For every KV block (16 tokens, so two per tile) that
+ * holds a valid token this writes the owning partition into block_partition[b*MB + j], and -1
+ * for every other entry.  Done the slow way: each tile searches all partitions.  Returns T.
  */
-int32_t pa_oracle_split_ranges(int32_t L, int32_t C, int32_t *starts, int32_t *ends, int32_t cap)
+int64_t pa_oracle_block_partition(const int32_t *context_lens, int32_t B, int32_t MB, int32_t BS, int32_t P,
+                                  int32_t *block_partition)
 {
-    if (L <= 0 || C <= 0)
-        return 0;
-    int32_t n = 0;
-    for (int32_t lo = 0; lo < L; lo += C) {
-        if (n < cap) {
-            starts[n] = lo;
-            ends[n] = lo + C < L ? lo + C : L;
+    const int tile_tokens = 32;
+    int64_t T = 0;
+    for (int32_t b = 0; b < B; ++b)
+        if (context_lens[b] > 0)
+            T += (context_lens[b] + tile_tokens - 1) / tile_tokens;
+    for (int64_t i = 0; i < (int64_t)B * MB; ++i)
+        block_partition[i] = -1;
+    int64_t t = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t L = context_lens[b];
+        for (int32_t first = 0; first < L; first += tile_tokens, ++t) {
+            int32_t owner = -1;
+            for (int32_t k = 0; k < P; ++k) {
+                int64_t lo = ((int64_t)k * T) / P, hi = ((int64_t)(k + 1) * T) / P;
+                if (lo <= t && t < hi)
+                    owner = k;
+            }
+            for (int32_t tok = first; tok < L && tok < first + tile_tokens; tok += BS)
+                block_partition[(int64_t)b * MB + tok / BS] = owner;
         }
-        ++n;
     }
-    return n;
+    return T;
 }
 
 int pa_oracle_num_threads(void)

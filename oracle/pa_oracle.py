@@ -46,8 +46,8 @@ def lib() -> ctypes.CDLL:
         L.pa_oracle_e4m3_table.argtypes = [p]
         L.pa_oracle_visited_blocks.restype = i32
         L.pa_oracle_visited_blocks.argtypes = [p, p, i32, i32, i32, p, i32]
-        L.pa_oracle_split_ranges.restype = i32
-        L.pa_oracle_split_ranges.argtypes = [i32, i32, p, p, i32]
+        L.pa_oracle_block_partition.restype = i64
+        L.pa_oracle_block_partition.argtypes = [p, i32, i32, i32, i32, p]
         L.pa_oracle_num_threads.restype = ctypes.c_int
         L.pa_oracle_num_threads.argtypes = []
         _lib = L
@@ -132,12 +132,13 @@ def visited_blocks(block_tables: np.ndarray, context_lens: np.ndarray, block_siz
     return ids[:n].copy()
 
 
-def split_ranges(context_len: int, split_tokens: int):
-    cap = 0 if context_len <= 0 or split_tokens <= 0 else (context_len + split_tokens - 1) // split_tokens
-    s = np.zeros(max(cap, 1), dtype=np.int32)
-    e = np.zeros(max(cap, 1), dtype=np.int32)
-    n = lib().pa_oracle_split_ranges(int(context_len), int(split_tokens), _ptr(s), _ptr(e), cap)
-    return s[:n].copy(), e[:n].copy()
+def block_partition(context_lens: np.ndarray, max_blocks_per_seq: int, block_size: int, num_partitions: int):
+    """Owner partition of every KV block under the balanced split plan; returns (T, [B, MB] int32)."""
+    context_lens = _c(context_lens, np.int32)
+    out = np.zeros((len(context_lens), max_blocks_per_seq), dtype=np.int32)
+    T = lib().pa_oracle_block_partition(_ptr(context_lens), len(context_lens), max_blocks_per_seq, block_size,
+                                        int(num_partitions), _ptr(out))
+    return int(T), out
 
 
 def num_threads() -> int:

@@ -23,14 +23,14 @@ PA_ERR_HIP = 4
 PA_KV_BF16 = 0
 PA_KV_FP8_E4M3 = 1
 
-EXPORTS = ("pa_split_tokens", "pa_max_splits", "pa_split_plan", "pa_decode_workspace_size", "pa_decode",
+EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa_decode",
            "pa_decode_trace", "pa_decode_profile", "pa_kernel_variant", "pa_status_string")
 
 
 class pa_shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_blocks",
-        "max_context_len", "split_tokens")]
+        "max_context_len", "num_partitions")]
 
 
 class PaError(RuntimeError):
@@ -56,19 +56,17 @@ def lib() -> ctypes.CDLL:
     vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
     shp = ctypes.POINTER(pa_shape)
     fp = ctypes.POINTER(ctypes.c_float)
-    L.pa_split_tokens.restype = i32
-    L.pa_split_tokens.argtypes = [shp, ctypes.c_int]
-    L.pa_max_splits.restype = i32
-    L.pa_max_splits.argtypes = [shp, ctypes.c_int]
+    L.pa_num_partitions.restype = i32
+    L.pa_num_partitions.argtypes = [shp, ctypes.c_int]
     L.pa_split_plan.restype = i32
-    L.pa_split_plan.argtypes = [shp, ctypes.c_int, i32, i32p, i32p, i32]
+    L.pa_split_plan.argtypes = [shp, ctypes.c_int, i32p, i32p]
     L.pa_decode_workspace_size.restype = ctypes.c_size_t
     L.pa_decode_workspace_size.argtypes = [shp, ctypes.c_int]
     common = [vp, vp, vp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, shp, vp, ctypes.c_size_t, vp]
     L.pa_decode.restype = ctypes.c_int
     L.pa_decode.argtypes = common
     L.pa_decode_trace.restype = ctypes.c_int
-    L.pa_decode_trace.argtypes = common + [vp, vp]
+    L.pa_decode_trace.argtypes = common + [vp]
     L.pa_decode_profile.restype = ctypes.c_int
     L.pa_decode_profile.argtypes = common + [i32, fp, fp]
     L.pa_kernel_variant.restype = ctypes.c_char_p
@@ -84,9 +82,9 @@ def status_string(status: int) -> str:
 
 
 def make_shape(batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks,
-               max_context_len=0, split_tokens=0) -> pa_shape:
+               max_context_len=0, num_partitions=0) -> pa_shape:
     return pa_shape(int(batch), int(num_q_heads), int(num_kv_heads), int(head_dim), int(block_size),
-                    int(max_blocks_per_seq), int(num_blocks), int(max_context_len), int(split_tokens))
+                    int(max_blocks_per_seq), int(num_blocks), int(max_context_len), int(num_partitions))
 
 
 def _neg_is_error(v: int, where: str) -> int:
@@ -95,24 +93,21 @@ def _neg_is_error(v: int, where: str) -> int:
     return v
 
 
-def pa_split_tokens(shape: pa_shape, kv_dtype: int) -> int:
-    return _neg_is_error(lib().pa_split_tokens(ctypes.byref(shape), kv_dtype), "pa_split_tokens")
+def pa_num_partitions(shape: pa_shape, kv_dtype: int) -> int:
+    return _neg_is_error(lib().pa_num_partitions(ctypes.byref(shape), kv_dtype), "pa_num_partitions")
 
 
-def pa_max_splits(shape: pa_shape, kv_dtype: int) -> int:
-    return _neg_is_error(lib().pa_max_splits(ctypes.byref(shape), kv_dtype), "pa_max_splits")
+def pa_split_plan(shape: pa_shape, kv_dtype: int, context_lens):
+    """Host plan for a host copy of the context lengths: returns (T, block_partition [B, MB] numpy int32)."""
+    import numpy as np
 
-
-def pa_split_plan(shape: pa_shape, kv_dtype: int, context_len: int):
-    """Returns (starts, ends) lists of the splits of one sequence."""
-    n = _neg_is_error(lib().pa_split_plan(ctypes.byref(shape), kv_dtype, int(context_len), None, None, 0),
-                      "pa_split_plan")
-    starts = (ctypes.c_int32 * max(n, 1))()
-    ends = (ctypes.c_int32 * max(n, 1))()
-    n2 = _neg_is_error(lib().pa_split_plan(ctypes.byref(shape), kv_dtype, int(context_len), starts, ends, n),
-                       "pa_split_plan")
-    assert n2 == n
-    return list(starts[:n]), list(ends[:n])
+    lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    assert lens.shape == (shape.batch,)
+    out = np.zeros((shape.batch, shape.max_blocks_per_seq), dtype=np.int32)
+    T = _neg_is_error(lib().pa_split_plan(ctypes.byref(shape), kv_dtype,
+                                          lens.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                          out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))), "pa_split_plan")
+    return T, out
 
 
 def pa_decode_workspace_size(shape: pa_shape, kv_dtype: int) -> int:
@@ -159,10 +154,10 @@ def pa_decode(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, 
 
 
 def pa_decode_trace(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale=None, v_scale=None,
-                    *, shape: pa_shape, workspace=None, stream=None, visited_blocks, split_ranges) -> None:
+                    *, shape: pa_shape, workspace=None, stream=None, visited_blocks) -> None:
     st = lib().pa_decode_trace(*_common_args(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out,
                                              k_scale, v_scale, shape, workspace, stream),
-                               _dev_ptr(visited_blocks, "visited_blocks"), _dev_ptr(split_ranges, "split_ranges"))
+                               _dev_ptr(visited_blocks, "visited_blocks"))
     if st != PA_OK:
         raise PaError(st, "pa_decode_trace")
 
@@ -184,7 +179,7 @@ def pa_decode_profile(q, k_cache, v_cache, block_tables, context_lens, scale, kv
 # fields of workloads.DecodeBatch) into device memory.  torch is used for memory only.
 # --------------------------------------------------------------------------------------
 class DeviceBatch:
-    def __init__(self, batch, device="cuda:0", max_context_len: Optional[int] = None, split_tokens: int = 0):
+    def __init__(self, batch, device="cuda:0", max_context_len: Optional[int] = None, num_partitions: int = 0):
         import numpy as np
         import torch
 
@@ -210,7 +205,7 @@ class DeviceBatch:
         if max_context_len is None:
             max_context_len = int(batch.context_lens.max(initial=0))
         self.shape = make_shape(batch.batch, batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.block_size,
-                                batch.max_blocks_per_seq, batch.num_blocks, max_context_len, split_tokens)
+                                batch.max_blocks_per_seq, batch.num_blocks, max_context_len, num_partitions)
         nbytes = pa_decode_workspace_size(self.shape, self.kv_dtype)
         # NaN-filled so that a read of an entry this call did not write shows up in the output
         self.workspace = None if nbytes == 0 else torch.full((nbytes // 4,), float("nan"), dtype=torch.float32,

@@ -1,5 +1,6 @@
 // Host side of libpa_decode.so: argument checks, the launch plan (a pure function of the
-// host-known shape) and the kernel launches behind the C ABI declared in include/pa_decode.h.
+// host-known shape and the device's compute-unit count) and the kernel launches behind the C ABI
+// declared in include/pa_decode.h.
 #include "pa_decode.h"
 
 #include <hip/hip_runtime.h>
@@ -10,22 +11,25 @@
 #include "pa_merge.hpp"
 #include "pa_partition_mfma.hpp"
 #include "pa_partition_valu.hpp"
+#include "pa_plan.hpp"
 
 namespace {
 
 using pa::Params;
 
-constexpr int32_t kDefaultSplitTokens = 256;
 constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds in registers
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
 constexpr int kMinGroupMfma = 4;   // below this the padded tile is mostly empty: vector-ALU kernel
-constexpr int kMfmaStages = 3;     // depth of the LDS tile ring of the matrix-core kernel
+constexpr int kMfmaStages = 2;     // depth of the LDS tile ring of the matrix-core kernel
+constexpr int kLdsPerCu = 160 * 1024;
+constexpr int kValuWavesPerCu = 8;
+constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
+constexpr int kMaxPartitions = 65535;
 
 struct Plan {
-    int32_t C;         // split length, tokens
-    int32_t S;         // max splits per sequence
-    int32_t max_ctx;   // resolved max context length
-    size_t lse_offset; // byte offset of the lse array inside the workspace
+    int32_t P;          // partitions of the global tile sequence
+    int32_t max_ctx;    // resolved max context length
+    size_t lse_offset;  // byte offset of the lse array inside the workspace
     size_t ws_bytes;
 };
 
@@ -36,21 +40,43 @@ bool use_mfma(const pa_shape* s, pa_kv_dtype kv)
     return s->head_dim == 128 && kv == PA_KV_BF16 && G >= kMinGroupMfma && G <= kMaxGroupMfma;
 }
 
+int mfma_group_pad(int G) { return G <= 4 ? 4 : (G <= 8 ? 8 : 16); }
+
+// Compute units of the current device (cached per process; 256 when there is no device).
+int compute_units()
+{
+    static int cached = 0;
+    if (cached > 0) return cached;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+        cached = n;
+    } else {
+        (void)hipGetLastError();
+        cached = kDefaultCus;
+    }
+    return cached;
+}
+
 pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
 {
     if (!s) return PA_ERR_INVALID_ARG;
     if (kv != PA_KV_BF16 && kv != PA_KV_FP8_E4M3) return PA_ERR_INVALID_ARG;
     if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->head_dim <= 0 || s->block_size <= 0 ||
-        s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->split_tokens < 0)
+        s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->num_partitions < 0)
         return PA_ERR_INVALID_ARG;
     if (s->num_q_heads % s->num_kv_heads != 0) return PA_ERR_INVALID_ARG;
     if ((int64_t)s->max_context_len > (int64_t)s->max_blocks_per_seq * s->block_size) return PA_ERR_INVALID_ARG;
-    if (s->split_tokens % s->block_size != 0) return PA_ERR_INVALID_ARG;
     if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return PA_ERR_UNSUPPORTED;
     if (s->num_q_heads / s->num_kv_heads > (use_mfma(s, kv) ? kMaxGroupMfma : kMaxGroupValu)) return PA_ERR_UNSUPPORTED;
-    if (s->batch > 65535 || s->num_kv_heads > 65535 || s->num_q_heads > 65535) return PA_ERR_UNSUPPORTED;
+    if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
+    // the global tile index and the launch grid are 32-bit
+    const int64_t max_ctx = s->max_context_len > 0 ? s->max_context_len : (int64_t)s->max_blocks_per_seq * s->block_size;
+    const int64_t tile_bound = (int64_t)s->batch * ((max_ctx + pa::kTileTokens - 1) / pa::kTileTokens);
+    if (tile_bound > INT32_MAX / 2) return PA_ERR_UNSUPPORTED;
+    if ((int64_t)kMaxPartitions * s->num_kv_heads > INT32_MAX) return PA_ERR_UNSUPPORTED;
     return PA_OK;
 }
 
@@ -59,14 +85,27 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     const pa_status st = check_shape(s, kv);
     if (st != PA_OK) return st;
     plan->max_ctx = s->max_context_len > 0 ? s->max_context_len : s->max_blocks_per_seq * s->block_size;
-    plan->C = s->split_tokens > 0 ? s->split_tokens : kDefaultSplitTokens;
-    plan->S = (plan->max_ctx + plan->C - 1) / plan->C;
-    if (plan->S < 1) plan->S = 1;
-    if (plan->S == 1) {
+    if (s->num_partitions > 0) {
+        plan->P = s->num_partitions;
+    } else {
+        // one resident wave per (partition, KV head): as many partitions as the device holds at once,
+        // but never more than there can be tiles
+        const int G = s->num_q_heads / s->num_kv_heads;
+        const int waves_per_cu = use_mfma(s, kv)
+                                     ? kLdsPerCu / pa::mfma_lds_bytes(kMfmaStages, mfma_group_pad(G))
+                                     : kValuWavesPerCu;
+        int64_t P = (int64_t)compute_units() * waves_per_cu / s->num_kv_heads;
+        const int64_t tile_bound = (int64_t)s->batch * ((plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens);
+        if (P > tile_bound) P = tile_bound;
+        if (P > kMaxPartitions) P = kMaxPartitions;
+        if (P < 1) P = 1;
+        plan->P = (int32_t)P;
+    }
+    if (plan->P == 1) {
         plan->lse_offset = 0;
         plan->ws_bytes = 0;
     } else {
-        const size_t rows = (size_t)s->batch * s->num_q_heads * plan->S;
+        const size_t rows = (size_t)2 * plan->P * s->num_q_heads;
         const size_t o_bytes = rows * s->head_dim * sizeof(float);
         plan->lse_offset = (o_bytes + 255) / 256 * 256;
         plan->ws_bytes = plan->lse_offset + (rows * sizeof(float) + 255) / 256 * 256;
@@ -96,6 +135,15 @@ void launch_valu_g(const Params& p, bool trace, dim3 grid, hipStream_t st)
         launch_valu<D, 8, KV>(p, trace, grid, st);
 }
 
+template <int GPAD>
+void launch_mfma(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    if (trace)
+        hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, GPAD, true>), grid, dim3(64), 0, st, p);
+    else
+        hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, GPAD, false>), grid, dim3(64), 0, st, p);
+}
+
 struct Events {
     hipEvent_t before, between, after;
 };
@@ -103,7 +151,7 @@ struct Events {
 pa_status run(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
               const int32_t* context_lens, float scale, pa_kv_dtype kv, float* out, const float* k_scale,
               const float* v_scale, const pa_shape* shape, void* workspace, size_t workspace_bytes, void* stream,
-              int32_t* trace_blocks, int32_t* trace_ranges, bool trace, const Events* ev)
+              int32_t* trace_blocks, bool trace, const Events* ev)
 {
     Plan plan;
     const pa_status st = make_plan(shape, kv, &plan);
@@ -114,7 +162,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         !aligned(block_tables, 4) || !aligned(context_lens, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 4))
         return PA_ERR_INVALID_ARG;
     if (!(scale == scale) || scale * 0.f != 0.f) return PA_ERR_INVALID_ARG;  // NaN or infinite
-    if (trace && (!trace_blocks || !trace_ranges)) return PA_ERR_INVALID_ARG;
+    if (trace && !trace_blocks) return PA_ERR_INVALID_ARG;
     if (plan.ws_bytes > 0) {
         if (!workspace || !aligned(workspace, 256)) return PA_ERR_INVALID_ARG;
         if (workspace_bytes < plan.ws_bytes) return PA_ERR_WORKSPACE_TOO_SMALL;
@@ -130,28 +178,29 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.k_scale = k_scale;
     p.v_scale = v_scale;
     p.out = out;
-    p.part_o = plan.S > 1 ? static_cast<float*>(workspace) : nullptr;
-    p.part_lse = plan.S > 1 ? reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.lse_offset) : nullptr;
+    p.part_o = plan.P > 1 ? static_cast<float*>(workspace) : nullptr;
+    p.part_lse = plan.P > 1 ? reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.lse_offset) : nullptr;
     p.trace_blocks = trace ? trace_blocks : nullptr;
-    p.trace_ranges = trace ? trace_ranges : nullptr;
     p.scale_log2 = scale * pa::kLog2e;
     p.B = shape->batch;
     p.Hq = shape->num_q_heads;
     p.Hkv = shape->num_kv_heads;
     p.G = shape->num_q_heads / shape->num_kv_heads;
     p.MB = shape->max_blocks_per_seq;
-    p.C = plan.C;
-    p.S = plan.S;
+    p.P = plan.P;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (ev && hipEventRecord(ev->before, hs) != hipSuccess) return PA_ERR_HIP;
 
-    const dim3 grid(plan.S, p.Hkv, p.B);
+    const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
     if (use_mfma(shape, kv)) {
-        if (trace)
-            hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, true>), grid, dim3(64), 0, hs, p);
+        const int gpad = mfma_group_pad(p.G);
+        if (gpad == 4)
+            launch_mfma<4>(p, trace, grid, hs);
+        else if (gpad == 8)
+            launch_mfma<8>(p, trace, grid, hs);
         else
-            hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, false>), grid, dim3(64), 0, hs, p);
+            launch_mfma<16>(p, trace, grid, hs);
     } else if (shape->head_dim == 128) {
         if (kv == PA_KV_BF16)
             launch_valu_g<128, pa::KV_BF16>(p, trace, grid, hs);
@@ -166,8 +215,8 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
     if (ev && hipEventRecord(ev->between, hs) != hipSuccess) return PA_ERR_HIP;
 
-    if (plan.S > 1) {
-        const dim3 mgrid(p.Hq, p.B);
+    if (plan.P > 1) {
+        const dim3 mgrid(p.Hq, plan.P - 1);
         if (shape->head_dim == 128)
             hipLaunchKernelGGL((pa::merge_kernel<128>), mgrid, dim3(64), 0, hs, p);
         else
@@ -182,35 +231,39 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
 
 extern "C" {
 
-int32_t pa_split_tokens(const pa_shape* shape, pa_kv_dtype kv_dtype)
+int32_t pa_num_partitions(const pa_shape* shape, pa_kv_dtype kv_dtype)
 {
     Plan plan;
     const pa_status st = make_plan(shape, kv_dtype, &plan);
-    return st == PA_OK ? plan.C : -(int32_t)st;
+    return st == PA_OK ? plan.P : -(int32_t)st;
 }
 
-int32_t pa_max_splits(const pa_shape* shape, pa_kv_dtype kv_dtype)
-{
-    Plan plan;
-    const pa_status st = make_plan(shape, kv_dtype, &plan);
-    return st == PA_OK ? plan.S : -(int32_t)st;
-}
-
-int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, int32_t context_len, int32_t* starts,
-                      int32_t* ends, int32_t cap)
+int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, const int32_t* context_lens,
+                      int32_t* block_partition)
 {
     Plan plan;
     const pa_status st = make_plan(shape, kv_dtype, &plan);
     if (st != PA_OK) return -(int32_t)st;
-    if (context_len > plan.max_ctx || cap < 0 || (cap > 0 && (!starts || !ends))) return -(int32_t)PA_ERR_INVALID_ARG;
-    if (context_len <= 0) return 0;
-    const int32_t n = (context_len + plan.C - 1) / plan.C;
-    for (int32_t s = 0; s < n && s < cap; ++s) {
-        starts[s] = s * plan.C;
-        const int64_t e = (int64_t)(s + 1) * plan.C;
-        ends[s] = e < context_len ? (int32_t)e : context_len;
+    if (shape->batch > 0 && (!context_lens || !block_partition)) return -(int32_t)PA_ERR_INVALID_ARG;
+    int64_t T = 0;
+    for (int32_t b = 0; b < shape->batch; ++b) {
+        if (context_lens[b] > plan.max_ctx) return -(int32_t)PA_ERR_INVALID_ARG;
+        T += pa::tiles_of(context_lens[b]);
     }
-    return n;
+    const int32_t MB = shape->max_blocks_per_seq;
+    int32_t k = 0;
+    int64_t t = 0;  // global index of the current tile
+    for (int32_t b = 0; b < shape->batch; ++b) {
+        const int32_t L = context_lens[b];
+        const int32_t nblk = L > 0 ? (L + pa::kBlockSize - 1) / pa::kBlockSize : 0;
+        for (int32_t j = 0; j < MB; ++j) block_partition[(int64_t)b * MB + j] = -1;
+        for (int32_t lt = 0; lt < pa::tiles_of(L); ++lt, ++t) {
+            while (k + 1 < plan.P && pa::part_begin(k + 1, (int)T, plan.P) <= t) ++k;
+            block_partition[(int64_t)b * MB + 2 * lt] = k;
+            if (2 * lt + 1 < nblk) block_partition[(int64_t)b * MB + 2 * lt + 1] = k;
+        }
+    }
+    return (int32_t)T;
 }
 
 size_t pa_decode_workspace_size(const pa_shape* shape, pa_kv_dtype kv_dtype)
@@ -224,16 +277,16 @@ pa_status pa_decode(const void* q, const void* k_cache, const void* v_cache, con
                     const float* v_scale, const pa_shape* shape, void* workspace, size_t workspace_bytes, void* stream)
 {
     return run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
-               workspace, workspace_bytes, stream, nullptr, nullptr, false, nullptr);
+               workspace, workspace_bytes, stream, nullptr, false, nullptr);
 }
 
 pa_status pa_decode_trace(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
                           const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, float* out,
                           const float* k_scale, const float* v_scale, const pa_shape* shape, void* workspace,
-                          size_t workspace_bytes, void* stream, int32_t* visited_blocks, int32_t* split_ranges)
+                          size_t workspace_bytes, void* stream, int32_t* visited_blocks)
 {
     return run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
-               workspace, workspace_bytes, stream, visited_blocks, split_ranges, true, nullptr);
+               workspace, workspace_bytes, stream, visited_blocks, true, nullptr);
 }
 
 pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
@@ -255,7 +308,7 @@ pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_ca
     }
     for (int32_t i = 0; st == PA_OK && i < steps; ++i)
         st = run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
-                 workspace, workspace_bytes, stream, nullptr, nullptr, false, &evs[(size_t)i]);
+                 workspace, workspace_bytes, stream, nullptr, false, &evs[(size_t)i]);
     if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess && st == PA_OK) st = PA_ERR_HIP;
     if (st == PA_OK && shape->batch > 0) {
         double part = 0.0, merge = 0.0;
@@ -267,7 +320,7 @@ pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_ca
             merge += b;
         }
         *partition_ms = (float)(part / steps);
-        *merge_ms = pa_max_splits(shape, kv_dtype) > 1 ? (float)(merge / steps) : 0.f;
+        *merge_ms = pa_num_partitions(shape, kv_dtype) > 1 ? (float)(merge / steps) : 0.f;
     } else if (st == PA_OK) {
         *partition_ms = 0.f;
         *merge_ms = 0.f;

@@ -23,14 +23,12 @@ struct Params {
     const float* k_scale;         // [Hkv] or null
     const float* v_scale;
     float* out;                   // [B, Hq, D]
-    float* part_o;                // [B, Hq, S, D] normalised partial outputs (null when S == 1)
-    float* part_lse;              // [B, Hq, S]   log2-domain log-sum-exp of each partial
-    int32_t* trace_blocks;        // [B, Hkv, MB, 2] or null
-    int32_t* trace_ranges;        // [B, Hkv, S, 2] or null
+    float* part_o;                // [2P, Hq, D] normalised partial outputs (null when P == 1)
+    float* part_lse;              // [2P, Hq]    log2-domain log-sum-exp of each partial
+    int32_t* trace_blocks;        // [B, Hkv, MB, 3] or null
     float scale_log2;             // softmax scale * log2(e)
     int32_t B, Hq, Hkv, G, MB;
-    int32_t C;                    // split length in tokens (multiple of 16)
-    int32_t S;                    // max splits per sequence
+    int32_t P;                    // number of partitions of the global tile sequence
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

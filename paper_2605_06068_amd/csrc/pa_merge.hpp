@@ -1,11 +1,16 @@
-// Merge kernel: combines the per-split partial outputs of one (sequence, query head) row by
-// their log-sum-exps.  With lse_s = log2(sum_t 2^(score_t)) over split s and o_s the split's
+// Merge kernel: combines the partial results of every sequence that a partition boundary cuts
+// (see pa_plan.hpp).  With lse_s = log2(sum_t 2^(score_t)) over segment s and o_s the segment's
 // normalised output, out = sum_s w_s o_s / sum_s w_s with w_s = 2^(lse_s - max_s lse_s).
-// Rows whose sequence has a single split were written to `out` by the partition kernel and
-// are skipped here; only entries of splits s < ceil(L/C), which the partition kernel of the
-// same call wrote, are read.
+//
+// One wavefront per (partition boundary j in [1, P), query head).  Boundary j sits at global
+// tile part_begin(j).  The wave whose boundary is the FIRST one strictly inside a sequence b
+// merges that sequence; all other waves exit.  The partials of b come from the partitions
+// k = j-1, j, j+1, ... whose ranges intersect b: slot 2k when b holds partition k's first tile,
+// slot 2k+1 otherwise (only possible for k = j-1).  Only slots written by the partition kernel
+// of the same call are read.
 #pragma once
 #include "pa_device.hpp"
+#include "pa_plan.hpp"
 
 namespace pa {
 
@@ -13,36 +18,86 @@ template <int D>
 __global__ __launch_bounds__(64) void merge_kernel(const Params p)
 {
     constexpr int V = D / kWave;  // floats per lane (1 or 2)
-    const int h = blockIdx.x, b = blockIdx.y;
-    const int L = p.context_lens[b];
-    if (L <= p.C) return;
-    const int n = (L + p.C - 1) / p.C;
+    __shared__ int s_slot[kWave];
+    __shared__ float s_w[kWave];
+    const int h = blockIdx.x;
+    const int j = blockIdx.y + 1;
     const int lane = threadIdx.x;
-    const int64_t row = (int64_t)b * p.Hq + h;
-    const float* lse = p.part_lse + row * p.S;
-    const float* po = p.part_o + row * p.S * D;
+    const int P = p.P;
 
-    float mx = kNegBig;
-    for (int s = lane; s < n; s += kWave) mx = fmaxf(mx, lse[s]);
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+    const int T = total_tiles(p.context_lens, p.B, lane);
+    if (T <= 0) return;
+    const int bj = part_begin(j, T, P);
+    if (bj <= 0 || bj >= T) return;
+    int b, cum;
+    locate_tile(p.context_lens, p.B, bj, lane, b, cum);
+    if (cum == bj) return;                             // the boundary falls between two sequences
+    if (j > 1 && part_begin(j - 1, T, P) > cum) return;  // an earlier boundary inside b does the merge
+    const int end_b = cum + tiles_of(p.context_lens[b]);
 
-    float acc[V], wsum = 0.f;
+    float acc[V], wsum = 0.f, mrun = kNegBig;
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
-    for (int s = 0; s < n; ++s) {
-        const float w = fast_exp2(lse[s] - mx);
-        wsum += w;
-        if (V == 2) {
-            const float2 x = *reinterpret_cast<const float2*>(po + (int64_t)s * D + lane * 2);
-            acc[0] = fmaf(w, x.x, acc[0]);
-            acc[V - 1] = fmaf(w, x.y, acc[V - 1]);
-        } else {
-            acc[0] = fmaf(w, po[(int64_t)s * D + lane], acc[0]);
+
+    for (int base = j - 1; base < P; base += kWave) {
+        const int kk = base + lane;
+        bool valid = false;
+        int slot = 0;
+        if (kk < P) {
+            const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
+            valid = hi > lo && lo < end_b && hi > cum;
+            slot = 2 * kk + ((kk == j - 1 && lo != cum) ? 1 : 0);
         }
+        const unsigned long long vmask = __ballot(valid);
+        if (vmask == 0ull) break;
+        const float lse = valid ? p.part_lse[(int64_t)slot * p.Hq + h] : kNegBig;
+        float cm = lse;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) cm = fmaxf(cm, __shfl_xor(cm, o, kWave));
+        const float m_new = fmaxf(mrun, cm);
+        const float rescale = fast_exp2(mrun - m_new);
+        const float w = valid ? fast_exp2(lse - m_new) : 0.f;
+        float ws = w;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) ws += __shfl_xor(ws, o, kWave);
+        wsum = wsum * rescale + ws;
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] *= rescale;
+        mrun = m_new;
+
+        // compact the valid (slot, weight) pairs, then stream the partial rows 8 at a time
+        const int pos = __popcll(vmask & ((1ull << lane) - 1ull));
+        const int cnt = __popcll(vmask);
+        if (valid) {
+            s_slot[pos] = slot;
+            s_w[pos] = w;
+        }
+        __syncthreads();
+        for (int i0 = 0; i0 < cnt; i0 += 8) {
+            float wv[8];
+            float2 xv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = min(i0 + u, cnt - 1);
+                wv[u] = (i0 + u < cnt) ? s_w[idx] : 0.f;
+                const float* row = p.part_o + ((int64_t)s_slot[idx] * p.Hq + h) * D;
+                if (V == 2) {
+                    xv[u] = *reinterpret_cast<const float2*>(row + lane * 2);
+                } else {
+                    xv[u].x = row[lane];
+                    xv[u].y = 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                acc[0] = fmaf(wv[u], xv[u].x, acc[0]);
+                if (V == 2) acc[V - 1] = fmaf(wv[u], xv[u].y, acc[V - 1]);
+            }
+        }
+        __syncthreads();
     }
     const float inv = 1.f / wsum;
-    float* dst = p.out + row * D;
+    float* dst = p.out + ((int64_t)b * p.Hq + h) * D;
     if (V == 2) {
         *reinterpret_cast<float2*>(dst + lane * 2) = make_float2(acc[0] * inv, acc[V - 1] * inv);
     } else {

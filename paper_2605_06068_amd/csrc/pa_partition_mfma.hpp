@@ -1,12 +1,15 @@
-// Partition kernel, matrix-core variant (head_dim 128): for query-head groups wide enough to
-// form a matrix tile (4 <= G <= 16; the group is padded to the 16 columns of an MFMA tile).
-// One wavefront per (sequence, KV head, split); no workgroup barriers.
+// Partition kernel, matrix-core variant (head_dim 128, bf16 KV): for query-head groups wide
+// enough to form a matrix tile (4 <= G <= 16; the group is padded to the 16 columns of an MFMA
+// tile).  One wavefront per (partition, KV head) walks its balanced range of the batch's global
+// tile sequence (see pa_plan.hpp); no workgroup barriers, no atomics.
 //
 // Data path per 32-token tile (two KV blocks):
 //   HBM --global_load_lds (16 B/lane, 1 KB per instruction)--> LDS ring of NSTAGE tiles
 //   K:  ds_read_b128 in MFMA operand layout -> S^T[token, head] = K . Q^T   (mfma 16x16x32 bf16)
 //   online softmax on S^T in registers (lane = head column, 8 tokens per lane per tile)
 //   V:  ds_read_b64_tr_b16 (transposing LDS read) -> out^T[dim, head] += V^T . P^T
+// The ring keeps running across sequence boundaries inside the range; the query rows of each
+// new sequence travel through a small LDS ring of their own, ahead of its first tile.
 //
 // LDS tile layout: row t (one token, 256 B) at byte t*256; the 16-byte piece holding dims
 // [8c, 8c+8) sits at piece position c ^ (t & 15).  The XOR swizzle is applied on the *global*
@@ -19,22 +22,31 @@
 // 4*(l/16)+e of the first block (e<4) or of the second block (e>=4) makes the score registers,
 // once exponentiated and packed to bf16, the B operand of the PV product as they stand.  The
 // V^T operand is read with the same k-index convention.
+//
+// Wait-count discipline: the LDS-DMA loads are issued and awaited by hand (s_waitcnt vmcnt(N)
+// with N = number of *newer DMA loads* allowed to stay in flight).  Loads complete in order,
+// so "at most N operations outstanding" implies every load older than the newest N has landed,
+// whatever else (stores, extra loads) is in flight: other traffic only makes a wait stricter.
+// Everything else the loop needs from memory comes through the scalar cache (block ids,
+// context lengths), which the vector-memory counter does not see.
 #pragma once
 #include "pa_device.hpp"
+#include "pa_plan.hpp"
 
 namespace pa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
-constexpr int kTileTokens = 32;
 constexpr int kRowBytes = 256;    // 128 bf16
 constexpr int kSlabBytes = 4096;  // one (block, head): 16 rows
 constexpr int kStageBytes = 4 * kSlabBytes;  // K block 0, K block 1, V block 0, V block 1
 constexpr int kDmaPerTile = 16;   // 1 KB each
+
+// LDS bytes one workgroup (one wave) of the kernel uses.
+constexpr int mfma_lds_bytes(int nstage, int gpad) { return nstage * (kStageBytes + gpad * kRowBytes); }
 
 // 16-byte-per-lane load from global memory straight into LDS.  LDS destination is
 // lds_addr + lane*16 (wave-uniform lds_addr goes through M0); the global source is
@@ -61,44 +73,65 @@ __device__ __forceinline__ void wait_tile(int later_tiles)
     else wait_vmcnt<EXTRA>();
 }
 
-// The LDS-DMA loads above are issued and awaited by hand, invisibly to the compiler's own
-// wait-count bookkeeping.  An ordinary load whose result is first used inside the tile loop
-// would make the compiler wait there for *all* outstanding vector-memory operations, i.e.
-// drain the ring every iteration.  Passing the loaded register through an empty asm makes the
-// compiler complete the load at this point instead.
-template <typename T>
-__device__ __forceinline__ void settle(T& v)
-{
-    asm volatile("" : "+v"(v));
-}
-
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-template <int NSTAGE, bool TRACE>
+// Position inside the global tile sequence: sequence b, its length and tile count, local tile.
+struct Cursor {
+    int b, lt, nt, L;
+};
+
+__device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, int B)
+{
+    if (++c.lt < c.nt) return;
+    c.lt = 0;
+    do {
+        ++c.b;
+        c.L = c.b < B ? uniform_load(context_lens, c.b) : 0;
+        c.nt = tiles_of(c.L);
+    } while (c.nt == 0 && c.b < B);
+}
+
+template <int NSTAGE, int GPAD, bool TRACE>
 __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 {
     constexpr int D = 128;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring depth");
-    __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * kStageBytes];
+    static_assert(GPAD == 4 || GPAD == 8 || GPAD == 16, "padded group width");
+    constexpr int kQSlot = GPAD * kRowBytes;
+    __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(NSTAGE, GPAD)];
 
-    const int s = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    const int L = p.context_lens[b];
-    const int start = s * p.C;
     const int lane = threadIdx.x;
+    const int g = blockIdx.x % p.Hkv;
+    const int k = blockIdx.x / p.Hkv;
     const int G = p.G;
-    if (L <= 0 && s == 0) {  // empty context: the output rows of this group are zero
-        for (int i = lane; i < G * D; i += kWave) p.out[((int64_t)b * p.Hq + g * G) * D + i] = 0.f;
-    }
-    if (start >= L) return;
-    const int end = min(start + p.C, L);
+    const int B = p.B;
     const int n = lane & 15;   // head column / row-in-block, depending on the operand
     const int q4 = lane >> 4;  // 0..3
 
-    if (TRACE && lane == 0) {
-        int32_t* r = p.trace_ranges + (((int64_t)b * p.Hkv + g) * p.S + s) * 2;
-        r[0] = start;
-        r[1] = end;
+    // ---- this wave's range of the global tile sequence
+    const int T = __builtin_amdgcn_readfirstlane(total_tiles(p.context_lens, B, lane));
+    if (k == 0) {  // empty contexts: their output rows are zero
+        for (int b0 = 0; b0 < B; b0 += kWave) {
+            const int b = b0 + lane;
+            if (b < B && p.context_lens[b] <= 0) {
+                float* row = p.out + ((int64_t)b * p.Hq + g * G) * D;
+                for (int i = 0; i < G * D; ++i) row[i] = 0.f;
+            }
+        }
     }
+    const int t_lo = part_begin(k, T, p.P), t_hi = part_begin(k + 1, T, p.P);
+    if (t_lo >= t_hi) return;
+    const int ntiles = t_hi - t_lo;
+    int first_b, first_cum;
+    locate_tile(p.context_lens, B, t_lo, lane, first_b, first_cum);
+    first_b = __builtin_amdgcn_readfirstlane(first_b);
+    first_cum = __builtin_amdgcn_readfirstlane(first_cum);
+    Cursor ic;  // issue side
+    ic.b = first_b;
+    ic.lt = t_lo - first_cum;
+    ic.L = uniform_load(p.context_lens, first_b);
+    ic.nt = tiles_of(ic.L);
+    Cursor cc = ic;  // compute side
 
     // ---- per-lane address pieces
     uint32_t dma_off[4];  // global byte offset inside a slab for DMA instruction i (rows 4i..4i+3)
@@ -108,8 +141,12 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         dma_off[i] = t * kRowBytes + ((n ^ t) << 4);
     }
     uint32_t kread[4];  // LDS byte offset inside a slab of this lane's K operand piece for k-step kk
+    uint32_t qread[4];  // same for the query slab (padding columns read row 0 and are zeroed)
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) kread[kk] = n * kRowBytes + (((4 * kk + q4) ^ n) << 4);
+    for (int kk = 0; kk < 4; ++kk) {
+        kread[kk] = n * kRowBytes + (((4 * kk + q4) ^ n) << 4);
+        qread[kk] = n < G ? kread[kk] : ((4 * kk + q4) << 4);
+    }
     uint32_t vread[8];  // LDS byte offset inside a slab of this lane's transposing-read source for dim tile dt
     {
         const int row = 4 * q4 + (n >> 2);
@@ -118,88 +155,72 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             vread[dt] = row * kRowBytes + ((n & 1) << 3) + (((2 * dt + ((n >> 1) & 1)) ^ row) << 4);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-
-    // ---- Q^T operand: head n of the group (zero for padding columns), dims 32kk + 8*q4 + [0,8)
-    bf16x8 qreg[4];
-    {
-        const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + g * G + (n < G ? n : 0)) * D + 8 * q4;
-        uint4 w[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) w[kk] = *reinterpret_cast<const uint4*>(qrow + 32 * kk);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (n >= G) w[kk] = make_uint4(0, 0, 0, 0);
-            settle(w[kk].x); settle(w[kk].y); settle(w[kk].z); settle(w[kk].w);
-            qreg[kk] = as_bf16x8(w[kk]);
-        }
-    }
-
-    // ---- block table of this split, 64 entries at a time, one per lane
-    const int32_t* table = p.block_tables + (int64_t)b * p.MB;
-    const int jb = start / kBlockSize;
-    const int nblk = (end + kBlockSize - 1) / kBlockSize - jb;
-    const int ntiles = (nblk + 1) / 2;
-    int tbl = (lane < nblk) ? table[jb + lane] : 0;
-    settle(tbl);
-    int phys0 = 0;
+    const uint32_t ldsq = lds0 + NSTAGE * kStageBytes;
+    const char* qslots = smem + NSTAGE * kStageBytes;
 
     const int64_t head_stride = (int64_t)p.Hkv * kSlabBytes;  // bytes between physical blocks
     const char* kc = static_cast<const char*>(p.k_cache) + (int64_t)g * kSlabBytes;
     const char* vc = static_cast<const char*>(p.v_cache) + (int64_t)g * kSlabBytes;
 
-    auto issue = [&](int tile, int stage) {
-        if (tile > 0 && (tile & 31) == 0) {  // next 64 table entries
-            const int base = 2 * tile;
-            tbl = (base + lane < nblk) ? table[jb + base + lane] : 0;
-            settle(tbl);
+    int q_issue = 0;  // query slot the issue side fills next
+    auto issue = [&](int i, int stage) {
+        if (i == 0 || ic.lt == 0) {  // a new segment starts: send its query rows ahead of its first tile
+            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.Hq + g * G) * kRowBytes;
+#pragma unroll
+            for (int r = 0; r < GPAD / 4; ++r) {
+                const uint32_t off = (4 * r + q4 < G) ? dma_off[r] : (dma_off[r] & 255u);
+                dma16(ldsq + q_issue * kQSlot + r * 1024, off, qb);
+            }
+            q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
+        }
+        const int nblk = (ic.L + kBlockSize - 1) / kBlockSize;
+        const int32_t* table = p.block_tables + (int64_t)ic.b * p.MB;
+        const int j0 = 2 * ic.lt;
+        int phys[2], nvalid[2];
+        phys[0] = uniform_load(table, j0);
+        nvalid[0] = min(kBlockSize, ic.L - j0 * kBlockSize);
+        if (j0 + 1 < nblk) {
+            phys[1] = uniform_load(table, j0 + 1);
+            nvalid[1] = min(kBlockSize, ic.L - (j0 + 1) * kBlockSize);
+        } else {  // no second block: re-read row 0 of the first one, masked out of the softmax later
+            phys[1] = phys[0];
+            nvalid[1] = 1;
+        }
+        if (TRACE && lane == 0) {
+            int32_t* v = p.trace_blocks + (((int64_t)ic.b * p.Hkv + g) * p.MB + j0) * 3;
+            v[0] = phys[0]; v[1] = phys[0]; v[2] = k;
+            if (j0 + 1 < nblk) { v[3] = phys[1]; v[4] = phys[1]; v[5] = k; }
         }
         const uint32_t ldst = lds0 + stage * kStageBytes;
-        const char* kb[2];
-        const char* vb[2];
-        int nvalid[2];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int jj = 2 * tile + sub;
-            int phys;
-            if (jj < nblk) {
-                phys = __builtin_amdgcn_readlane(tbl, jj & 63);
-                nvalid[sub] = min(kBlockSize, end - (jb + jj) * kBlockSize);
-                if (sub == 0) phys0 = phys;
-                if (TRACE && lane == 0) {
-                    int32_t* v = p.trace_blocks + (((int64_t)b * p.Hkv + g) * p.MB + jb + jj) * 2;
-                    v[0] = phys;
-                    v[1] = phys;
-                }
-            } else {  // block beyond the split: re-read row 0 of the tile's first block, masked later
-                phys = phys0;
-                nvalid[sub] = 1;
-            }
-            kb[sub] = kc + phys * head_stride;
-            vb[sub] = vc + phys * head_stride;
-        }
         // rows past the context hold garbage (possibly NaN patterns): load row 0 of the block instead
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub) {
+            const char* kb = kc + phys[sub] * head_stride;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t off = (4 * i + q4 < nvalid[sub]) ? dma_off[i] : (dma_off[i] & 255u);
-                dma16(ldst + sub * kSlabBytes + i * 1024, off, kb[sub]);
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t off = (4 * r + q4 < nvalid[sub]) ? dma_off[r] : (dma_off[r] & 255u);
+                dma16(ldst + sub * kSlabBytes + r * 1024, off, kb);
             }
+        }
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub) {
+            const char* vb = vc + phys[sub] * head_stride;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t off = (4 * i + q4 < nvalid[sub]) ? dma_off[i] : (dma_off[i] & 255u);
-                dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + i * 1024, off, vb[sub]);
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t off = (4 * r + q4 < nvalid[sub]) ? dma_off[r] : (dma_off[r] & 255u);
+                dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024, off, vb);
             }
+        }
+        advance(ic, p.context_lens, B);
     };
 
     // ---- online softmax state: lane = head n, tokens 4*q4+{0..3} of each block
-    float qs = p.scale_log2;
+    const float qs = p.scale_log2;
     float m = kNegBig, lsum = 0.f;
     f32x4 acc[8];
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 qreg[4];
+    int q_comp = 0;       // query slot of the segment being computed
+    int seg_first_lt = 0;
 
     // ---- prologue: fill the ring
 #pragma unroll
@@ -220,8 +241,24 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         const char* kbuf = smem + stage * kStageBytes;
         const char* vbuf = kbuf + 2 * kSlabBytes;
 
+        wait_tile<kDmaPerTile / 2, NSTAGE>(later);  // K of this tile (and its segment's query rows) landed
+        if (tile == 0 || cc.lt == 0) {  // segment start
+            m = kNegBig;
+            lsum = 0.f;
+            seg_first_lt = cc.lt;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const char* qsl = qslots + q_comp * kQSlot;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                uint4 w = *reinterpret_cast<const uint4*>(qsl + qread[kk]);
+                if (n >= G) w = make_uint4(0, 0, 0, 0);
+                qreg[kk] = as_bf16x8(w);
+            }
+            q_comp = (q_comp + 1 == NSTAGE) ? 0 : q_comp + 1;
+        }
+
         // ---- scores: S^T[token, head] for the two blocks of the tile
-        wait_tile<kDmaPerTile / 2, NSTAGE>(later);
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
@@ -232,12 +269,12 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         }
 
         // ---- online softmax (log2 domain)
-        const int t0 = start + tile * kTileTokens + 4 * q4;
+        const int t0 = cc.lt * kTileTokens + 4 * q4;
         float x[8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            x[r] = (t0 + r < end) ? s0[r] * qs : kNegBig;
-            x[4 + r] = (t0 + kBlockSize + r < end) ? s1[r] * qs : kNegBig;
+            x[r] = (t0 + r < cc.L) ? s0[r] * qs : kNegBig;
+            x[4 + r] = (t0 + kBlockSize + r < cc.L) ? s1[r] * qs : kNegBig;
         }
         float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
         mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
@@ -269,26 +306,30 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
             acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, acc[dt], 0, 0, 0);
         }
-        stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
-    }
 
-    // ---- epilogue: finish the row sums, normalise, write
-    lsum += __shfl_xor(lsum, 16, kWave);
-    lsum += __shfl_xor(lsum, 32, kWave);
-    if (n < G) {
-        const float inv = 1.f / lsum;
-        const int hq = g * G + n;
-        float* dst;
-        if (p.S == 1 || L <= p.C) {
-            dst = p.out + ((int64_t)b * p.Hq + hq) * D;
-        } else {
-            dst = p.part_o + (((int64_t)b * p.Hq + hq) * p.S + s) * D;
-            if (q4 == 0) p.part_lse[((int64_t)b * p.Hq + hq) * p.S + s] = m + fast_log2(lsum);
-        }
+        // ---- segment end: finish the row sums, normalise, write
+        if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
+            float l = lsum + __shfl_xor(lsum, 16, kWave);
+            l += __shfl_xor(l, 32, kWave);
+            if (n < G) {
+                const float inv = 1.f / l;
+                const int hq = g * G + n;
+                float* dst;
+                if (seg_first_lt == 0 && cc.lt == cc.nt - 1) {  // the whole sequence: final result
+                    dst = p.out + ((int64_t)cc.b * p.Hq + hq) * D;
+                } else {
+                    const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.Hq + hq;
+                    dst = p.part_o + slot * D;
+                    if (q4 == 0) p.part_lse[slot] = m + fast_log2(l);
+                }
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-            *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
-                make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
+                for (int dt = 0; dt < 8; ++dt)
+                    *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
+                        make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
+            }
+        }
+        advance(cc, p.context_lens, B);
+        stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
     }
 }
 

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def shape(**kw):
     base = dict(batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
-                num_blocks=1024, max_context_len=0, split_tokens=0)
+                num_blocks=1024, max_context_len=0, num_partitions=0)
     base.update(kw)
     return pa.make_shape(**base)
 
@@ -47,50 +47,55 @@ def test_shape_struct_matches_header_field_order():
 
 @pytest.mark.parametrize("kv", [pa.PA_KV_BF16, pa.PA_KV_FP8_E4M3])
 def test_split_plan_is_the_definition(oracle, kv):
-    for forced in [0, 16, 48, 256, 1024, 4096]:
-        s = shape(split_tokens=forced)
-        C = pa.pa_split_tokens(s, kv)
-        assert C > 0 and C % 16 == 0 and (forced == 0 or C == forced)
-        assert pa.pa_max_splits(s, kv) == -(-4096 // C)
-        for L in [0, 1, 15, 16, 17, C - 1, C, C + 1, 2 * C, 4095, 4096]:
-            if L > 4096:
-                continue
-            starts, ends = pa.pa_split_plan(s, kv, L)
-            os_, oe = oracle.split_ranges(L, C)
-            assert starts == os_.tolist() and ends == oe.tolist()
+    rng = np.random.default_rng(3)
+    for B, lens in ((4, [0, 1, 4096, 33]), (4, [4096] * 4), (4, [31, 32, 33, 64]), (64, rng.integers(1, 4097, 64)),
+                    (3, [0, 0, 0])):
+        for forced in [0, 1, 2, 3, 7, 64, 1000]:
+            s = shape(batch=B, num_partitions=forced)
+            P = pa.pa_num_partitions(s, kv)
+            assert P >= 1 and (forced == 0 or P == forced)
+            T, plan = pa.pa_split_plan(s, kv, lens)
+            To, want = oracle.block_partition(np.asarray(lens, np.int32), 256, 16, P)
+            assert T == To and np.array_equal(plan, want)
 
 
-def test_split_length_depends_on_host_shape_only():
-    a = pa.pa_split_tokens(shape(max_context_len=4096), pa.PA_KV_BF16)
-    b = pa.pa_split_tokens(shape(max_context_len=4096), pa.PA_KV_BF16)
-    assert a == b
-    # a context bound that fits one split needs no workspace
-    s1 = shape(max_context_len=a)
-    assert pa.pa_max_splits(s1, pa.PA_KV_BF16) == 1 and pa.pa_decode_workspace_size(s1, pa.PA_KV_BF16) == 0
+def test_partition_count_depends_on_host_shape_only():
+    a = pa.pa_num_partitions(shape(max_context_len=4096), pa.PA_KV_BF16)
+    b = pa.pa_num_partitions(shape(max_context_len=4096), pa.PA_KV_BF16)
+    assert a == b and a >= 1
+    # never more partitions than there can be tiles; a single partition needs no workspace
+    s1 = shape(batch=1, max_context_len=32)
+    assert pa.pa_num_partitions(s1, pa.PA_KV_BF16) == 1 and pa.pa_decode_workspace_size(s1, pa.PA_KV_BF16) == 0
+    assert pa.pa_num_partitions(shape(batch=2, max_context_len=96), pa.PA_KV_BF16) <= 6
 
 
 def test_workspace_size_covers_partials():
-    s = shape(split_tokens=256)
-    S = pa.pa_max_splits(s, pa.PA_KV_BF16)
-    assert S == 16
-    need = 4 * 32 * S * (128 + 1) * 4
+    s = shape(num_partitions=16)
+    need = 2 * 16 * 32 * (128 + 1) * 4
     got = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
     assert need <= got <= need + 512
+
+
+def test_split_plan_rejects_lengths_above_the_bound():
+    s = shape(max_context_len=100)
+    with pytest.raises(pa.PaError):
+        pa.pa_split_plan(s, pa.PA_KV_BF16, [1, 2, 101, 4])
 
 
 @pytest.mark.parametrize("bad,code", [
     (dict(num_q_heads=30), pa.PA_ERR_INVALID_ARG),
     (dict(batch=-1), pa.PA_ERR_INVALID_ARG),
     (dict(max_context_len=256 * 16 + 1), pa.PA_ERR_INVALID_ARG),
-    (dict(split_tokens=24), pa.PA_ERR_INVALID_ARG),
+    (dict(num_partitions=-3), pa.PA_ERR_INVALID_ARG),
+    (dict(num_partitions=70000), pa.PA_ERR_UNSUPPORTED),
     (dict(head_dim=96), pa.PA_ERR_UNSUPPORTED),
-    (dict(block_size=32, split_tokens=0), pa.PA_ERR_UNSUPPORTED),
+    (dict(block_size=32), pa.PA_ERR_UNSUPPORTED),
     (dict(num_q_heads=8 * 32), pa.PA_ERR_UNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected(bad, code):
     s = shape(**bad)
     with pytest.raises(pa.PaError) as e:
-        pa.pa_split_tokens(s, pa.PA_KV_BF16)
+        pa.pa_num_partitions(s, pa.PA_KV_BF16)
     assert e.value.status == code
     assert pa.pa_decode_workspace_size(s, pa.PA_KV_BF16) == 0
     assert pa.pa_kernel_variant(s, pa.PA_KV_BF16) is None

@@ -37,7 +37,8 @@ def check(pa, oracle, batch, what, **kw):
     got, dev = run_gpu(pa, batch, **kw)
     want = oracle.decode_batch(batch)["out"]
     err = assert_parity(got, want, batch.kv_dtype, what)
-    print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e} C={pa.pa_split_tokens(dev.shape, dev.kv_dtype)}", flush=True)
+    print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e} P={pa.pa_num_partitions(dev.shape, dev.kv_dtype)} "
+          f"{pa.pa_kernel_variant(dev.shape, dev.kv_dtype)}", flush=True)
     return got, want
 
 
@@ -62,7 +63,7 @@ def test_configs_reduced_lengths(pa, oracle, config, kwargs, seed_base):
 
 @pytest.mark.parametrize("config", [2, 3, 4, 5])
 def test_configs_full_size(pa, oracle, config):
-    """Full-size batches in the launch configuration the benchmark times (default split plan,
+    """Full-size batches in the launch configuration the benchmark times (default plan,
     max_context_len = the batch maximum); the oracle covers every output row."""
     b = W.make_config(config)
     check(pa, oracle, b, f"config{config}-full")
@@ -70,22 +71,33 @@ def test_configs_full_size(pa, oracle, config):
 
 # ------------------------------------------------------------------ shapes and edges
 @pytest.mark.parametrize("Hq,Hkv,D", [(1, 1, 64), (1, 1, 128), (4, 4, 128), (2, 1, 64), (6, 2, 128), (8, 1, 128),
-                                      (16, 2, 64), (5, 1, 128), (12, 4, 64)])
+                                      (16, 2, 64), (5, 1, 128), (12, 4, 64), (16, 1, 128), (24, 2, 128), (4, 1, 128)])
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
 def test_head_shapes(pa, oracle, Hq, Hkv, D, kv):
-    b = W.make_batch("shapes", 50 + Hq + D, [1, 15, 16, 17, 300, 257, 512], Hq, Hkv, D, 16, kv, num_blocks=90,
-                     max_blocks_per_seq=40)
+    if Hq // Hkv > 8 and (kv == W.KV_FP8_E4M3 or D == 64):
+        pytest.skip("groups wider than 8 are supported for head_dim 128 with bf16 KV only")
+    b = W.make_batch("shapes", 50 + Hq + D, [1, 15, 16, 17, 300, 257, 512, 31, 32, 33], Hq, Hkv, D, 16, kv,
+                     num_blocks=100, max_blocks_per_seq=40)
     check(pa, oracle, b, "head-shapes")
+    check(pa, oracle, b, "head-shapes P=5", num_partitions=5)
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("C", [16, 48, 256, 1024, 4096])
-def test_forced_split_sweep(pa, oracle, kv, C):
-    lens = [1, 16, 47, 48, 49, 255, 256, 257, 1023, 1025, 2000]
+@pytest.mark.parametrize("P", [1, 2, 3, 7, 64, 1000])
+def test_forced_partition_sweep(pa, oracle, kv, P):
+    """Any number of partitions gives the same answer: one (no split, no merge), a few (long
+    sequences cut several times), more than there are tiles (empty partitions)."""
+    lens = [1, 16, 47, 48, 49, 0, 255, 256, 257, 1023, 1025, 2000, 31, 32, 33, 64, 65]
     b = W.make_batch("splits", 60, lens, 8, 2, 128, 16, kv)
-    got, want = check(pa, oracle, b, f"split-sweep C={C}", split_tokens=C)
-    ref, _ = run_gpu(pa, b, split_tokens=4096)
-    assert_parity(got, ref, kv, "against the unsplit run")  # split lengths agree with each other too
+    got, want = check(pa, oracle, b, f"partition-sweep P={P}", num_partitions=P)
+    ref, _ = run_gpu(pa, b, num_partitions=1)
+    assert_parity(got, ref, kv, "against the unsplit run")  # partition counts agree with each other too
+
+
+def test_one_sequence_cut_by_every_partition(pa, oracle):
+    b = W.make_batch("long1", 61, [5000], 8, 2, 128, 16, W.KV_BF16)
+    for P in (2, 9, 100, 157):
+        check(pa, oracle, b, f"single-sequence P={P}", num_partitions=P)
 
 
 def test_single_token_context_returns_v_exactly(pa):
@@ -112,13 +124,17 @@ def test_single_token_context_returns_v_exactly(pa):
 
 def test_zero_length_and_poisoned_inputs(pa, oracle):
     for kv in (W.KV_BF16, W.KV_FP8_E4M3):
-        b = W.make_batch("edge", 71, [0, 33, 0, 700, 16], 8, 2, 128, 16, kv, num_blocks=60, max_blocks_per_seq=50)
+        b = W.make_batch("edge", 71, [0, 33, 0, 700, 16, 0], 8, 2, 128, 16, kv, num_blocks=60, max_blocks_per_seq=50)
         b.block_tables[b.block_tables < 0] = 2 ** 30  # garbage ids behind the valid prefix
         got, want = check(pa, oracle, b, "zero-length+poison")
-        assert np.all(got[0] == 0) and np.all(got[2] == 0)
-        # a host bound above the real maximum changes the grid, not the result
+        assert np.all(got[0] == 0) and np.all(got[2] == 0) and np.all(got[5] == 0)
+        # a host bound above the real maximum may change the plan, not the result
         got2, _ = run_gpu(pa, b, max_context_len=800)
-        assert np.array_equal(got, got2)
+        assert_parity(got2, want, kv, "loose host bound")
+        # an all-empty batch
+        e = W.make_batch("empty", 72, [0, 0, 0], 8, 2, 128, 16, kv, num_blocks=2, max_blocks_per_seq=2)
+        got3, _ = run_gpu(pa, e, num_partitions=4)
+        assert np.all(got3 == 0)
 
 
 def test_runs_are_bit_identical(pa):
@@ -137,9 +153,8 @@ def one_hot_batch(kv, lens, Hq, Hkv, D, targets, seed):
     b = W.make_batch("onehot", seed, lens, Hq, Hkv, D, 16, kv)
     b.q[:] = 0
     b.q[:, :, 0] = W.f32_to_bf16_bits(np.float32(64))
-    zero = 0
-    b.k_cache[:] = zero
-    b.v_cache[:] = zero
+    b.k_cache[:] = 0
+    b.v_cache[:] = 0
     enc = (lambda x: W.f32_to_bf16_bits(np.float32(x))) if kv == W.KV_BF16 else \
         (lambda x: W.f32_to_e4m3_bytes(np.array([x], np.float32))[0])
     if kv == W.KV_FP8_E4M3:
@@ -157,48 +172,47 @@ def one_hot_batch(kv, lens, Hq, Hkv, D, targets, seed):
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("C", [0, 48, 256])
-def test_one_hot_probe_reads_exactly_the_target_slot(pa, kv, C):
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2)])
+@pytest.mark.parametrize("P", [0, 1, 6, 29])
+def test_one_hot_probe_reads_exactly_the_target_slot(pa, kv, Hq, Hkv, P):
     L = 700
-    Cr = 256 if C == 0 else C
-    edge = sorted({0, 15, 16, 17, Cr - 1, Cr, Cr + 1, 2 * Cr - 1, 2 * Cr, L - 17, L - 16, L - 2, L - 1})
+    edge = sorted({0, 15, 16, 17, 31, 32, 33, 255, 256, 257, 351, 352, L - 17, L - 16, L - 2, L - 1})
     lens = [L] * len(edge)
-    b = one_hot_batch(kv, lens, 8, 2, 128, edge, 80)
-    got, _ = run_gpu(pa, b, split_tokens=C)
+    b = one_hot_batch(kv, lens, Hq, Hkv, 128, edge, 80)
+    got, _ = run_gpu(pa, b, num_partitions=P)
     for s, t in enumerate(edge):
         digits = got[s, :, :5]
         want = np.array([(t >> (4 * d)) & 15 for d in range(4)] + [s % 16], dtype=np.float32)
         assert np.array_equal(digits, np.broadcast_to(want, digits.shape)), (s, t, digits[0])
 
 
-@pytest.mark.parametrize("config,kwargs,C", [
-    (1, {}, 0), (1, {}, 16), (2, dict(length_scale=0.25), 0), (4, dict(length_scale=1 / 8), 0),
-    (4, dict(length_scale=1 / 8), 48), (5, dict(length_scale=1 / 16, batch_limit=8), 0),
+@pytest.mark.parametrize("config,kwargs,P", [
+    (1, {}, 0), (1, {}, 3), (2, dict(length_scale=0.25), 0), (4, dict(length_scale=1 / 8), 0),
+    (4, dict(length_scale=1 / 8), 37), (5, dict(length_scale=1 / 16, batch_limit=8), 0), (2, {}, 0), (4, {}, 0),
 ])
-def test_trace_matches_block_tables_and_split_plan(pa, oracle, config, kwargs, C):
+def test_trace_matches_block_tables_and_split_plan(pa, oracle, config, kwargs, P):
+    """The instrumented production kernels report which physical block they read for every logical
+    block (K and V) and which partition processed it: both must equal, bit for bit, the oracle's
+    block-table walk and the split plan written from its definition (and the host plan)."""
     import torch
 
     b = W.make_config(config, **kwargs)
-    dev = pa.DeviceBatch(b, split_tokens=C)
-    S = pa.pa_max_splits(dev.shape, dev.kv_dtype)
-    Cr = pa.pa_split_tokens(dev.shape, dev.kv_dtype)
-    visited = torch.full((b.batch, b.num_kv_heads, b.max_blocks_per_seq, 2), -7, dtype=torch.int32, device="cuda")
-    ranges = torch.full((b.batch, b.num_kv_heads, S, 2), -7, dtype=torch.int32, device="cuda")
-    pa.pa_decode_trace(*dev.args(), shape=dev.shape, workspace=dev.workspace, visited_blocks=visited,
-                       split_ranges=ranges)
+    dev = pa.DeviceBatch(b, num_partitions=P)
+    Pr = pa.pa_num_partitions(dev.shape, dev.kv_dtype)
+    visited = torch.full((b.batch, b.num_kv_heads, b.max_blocks_per_seq, 3), -7, dtype=torch.int32, device="cuda")
+    pa.pa_decode_trace(*dev.args(), shape=dev.shape, workspace=dev.workspace, visited_blocks=visited)
     torch.cuda.synchronize()
-    visited, ranges = visited.cpu().numpy(), ranges.cpu().numpy()
+    visited = visited.cpu().numpy()
+    T, owner = oracle.block_partition(b.context_lens, b.max_blocks_per_seq, 16, Pr)
+    Th, owner_host = pa.pa_split_plan(dev.shape, dev.kv_dtype, b.context_lens)
+    assert Th == T and np.array_equal(owner_host, owner)
     for s in range(b.batch):
         ids = oracle.visited_blocks(b.block_tables, b.context_lens, 16, s)
-        starts, ends = oracle.split_ranges(int(b.context_lens[s]), Cr)
-        hs, he = pa.pa_split_plan(dev.shape, dev.kv_dtype, int(b.context_lens[s]))
-        assert hs == starts.tolist() and he == ends.tolist()
+        n = len(ids)
         for g in range(b.num_kv_heads):
-            assert np.array_equal(visited[s, g, :len(ids), 0], ids) and np.array_equal(visited[s, g, :len(ids), 1], ids)
-            assert np.all(visited[s, g, len(ids):] == -7)  # nothing past the context was dereferenced
-            assert np.array_equal(ranges[s, g, :len(starts), 0], starts)
-            assert np.array_equal(ranges[s, g, :len(starts), 1], ends)
-            assert np.all(ranges[s, g, len(starts):] == -7)
+            assert np.array_equal(visited[s, g, :n, 0], ids) and np.array_equal(visited[s, g, :n, 1], ids)
+            assert np.array_equal(visited[s, g, :n, 2], owner[s, :n])
+            assert np.all(visited[s, g, n:] == -7)  # nothing past the context was dereferenced
     # the instrumented run computes the same output as the plain one
     want = oracle.decode_batch(b)["out"]
     assert_parity(dev.out.cpu().numpy(), want, b.kv_dtype, "trace-run")

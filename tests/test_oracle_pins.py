@@ -258,20 +258,37 @@ def test_fp8_scales_belong_to_their_kv_head(oracle):
 
 
 # ---------------------------------------------------------------- indexing helpers
-def test_visited_blocks_and_split_ranges_match_brute_force(oracle):
+def test_visited_blocks_follow_the_table(oracle):
     b = W.make_config(1)
     assert oracle.visited_blocks(b.block_tables, b.context_lens, 16, 0).tolist() == b.block_tables[0, :3].tolist()
     assert oracle.visited_blocks(b.block_tables, b.context_lens, 16, 1).tolist() == b.block_tables[1, :7].tolist()
-    for L in [0, 1, 15, 16, 17, 255, 256, 257, 1000]:
-        for C in [16, 48, 256, 1024]:
-            s, e = oracle.split_ranges(L, C)
-            owner = np.full(L, -1)
-            for i, (lo, hi) in enumerate(zip(s, e)):
-                assert 0 <= lo < hi <= L and hi - lo <= C
-                assert np.all(owner[lo:hi] == -1)
-                owner[lo:hi] = i
-            assert np.all(owner >= 0)  # a partition of [0, L)
-            assert np.array_equal(owner, np.arange(L) // C)  # token t belongs to chunk t // C
+
+
+def test_block_partition_is_a_balanced_contiguous_cut(oracle):
+    """Properties the split plan's definition fixes, checked without re-using its formula: every
+    valid block has exactly one owner, owners never decrease along the batch's token order, both
+    blocks of a 32-token tile share an owner, and the tile counts of the partitions differ by at
+    most one (floor(k*T/P) cuts)."""
+    rng = np.random.default_rng(5)
+    for lens in ([37, 100], [0, 5, 0, 700, 16, 1], rng.integers(1, 3000, size=40).tolist(), [5000], [0, 0]):
+        lens = np.asarray(lens, dtype=np.int32)
+        MB = int(max(1, -(-int(lens.max()) // 16))) + 2
+        for P in (1, 2, 3, 7, 64, 1000):
+            T, owner = oracle.block_partition(lens, MB, 16, P)
+            assert T == sum(-(-int(L) // 32) for L in lens if L > 0)
+            seq = []
+            for bi, L in enumerate(lens):
+                nblk = -(-int(L) // 16) if L > 0 else 0
+                assert np.all(owner[bi, nblk:] == -1) and np.all(owner[bi, :nblk] >= 0)
+                row = owner[bi, :nblk]
+                assert np.all(row[0::2][:len(row[1::2])] == row[1::2])  # tile = two blocks, one owner
+                seq.extend(row[0::2].tolist())  # one entry per tile
+            assert len(seq) == T and all(x <= y for x, y in zip(seq, seq[1:])) and all(0 <= x < P for x in seq)
+            counts = np.bincount(np.asarray(seq, dtype=np.int64), minlength=P) if T else np.zeros(P, int)
+            assert counts.max() - counts.min() <= 1 and counts.sum() == T
+            if T:
+                # closed form of the first and last cut
+                assert counts[P - 1] == T - (P - 1) * T // P and counts[0] == T // P
 
 
 # ---------------------------------------------------------------- stored regression values
