@@ -38,8 +38,8 @@
  *     out           [batch, num_q_heads, head_dim]                        float32
  *
  * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
- * 1 <= G <= 16 (G <= 8 for head_dim 64 or fp8 KV); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no infinities, 0x7F/0xFF NaN)
- * with one float32 scale per KV head for K and one for V.
+ * 1 <= G <= 16 (G <= 8 for head_dim 64); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
+ * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
  */
 #ifndef PA_DECODE_H
 #define PA_DECODE_H
@@ -153,7 +153,7 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
                             float *merge_ms);
 
 /* Name of the partition kernel variant pa_decode picks for this shape ("mfma": matrix cores, for
- * head_dim 128, bf16 KV and groups of 4..16 query heads; "valu" otherwise); NULL for an invalid
+ * head_dim 128 and groups of 4..16 query heads; "valu" otherwise); NULL for an invalid
  * shape.  Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 

@@ -20,7 +20,8 @@ using pa::Params;
 constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds in registers
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
 constexpr int kMinGroupMfma = 4;   // below this the padded tile is mostly empty: vector-ALU kernel
-constexpr int kMfmaStages = 2;     // depth of the LDS tile ring of the matrix-core kernel
+constexpr int kMfmaStagesBf16 = 2;  // depth of the LDS tile ring of the matrix-core kernel, bf16 KV
+constexpr int kMfmaStagesFp8 = 3;   // same for fp8 KV (tiles are half the size)
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kValuWavesPerCu = 8;
 constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
@@ -33,12 +34,14 @@ struct Plan {
     size_t ws_bytes;
 };
 
-// The matrix-core kernel covers head_dim 128 with bf16 KV and groups of 4..16 query heads.
+// The matrix-core kernel covers head_dim 128 and groups of 4..16 query heads.
 bool use_mfma(const pa_shape* s, pa_kv_dtype kv)
 {
     const int G = s->num_q_heads / s->num_kv_heads;
-    return s->head_dim == 128 && kv == PA_KV_BF16 && G >= kMinGroupMfma && G <= kMaxGroupMfma;
+    return s->head_dim == 128 && G >= kMinGroupMfma && G <= kMaxGroupMfma;
 }
+
+int mfma_stages(pa_kv_dtype kv) { return kv == PA_KV_BF16 ? kMfmaStagesBf16 : kMfmaStagesFp8; }
 
 int mfma_group_pad(int G) { return G <= 4 ? 4 : (G <= 8 ? 8 : 16); }
 
@@ -92,7 +95,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         // but never more than there can be tiles
         const int G = s->num_q_heads / s->num_kv_heads;
         const int waves_per_cu = use_mfma(s, kv)
-                                     ? kLdsPerCu / pa::mfma_lds_bytes(kMfmaStages, mfma_group_pad(G))
+                                     ? kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv), mfma_group_pad(G), (int)kv)
                                      : kValuWavesPerCu;
         int64_t P = (int64_t)compute_units() * waves_per_cu / s->num_kv_heads;
         const int64_t tile_bound = (int64_t)s->batch * ((plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens);
@@ -135,13 +138,25 @@ void launch_valu_g(const Params& p, bool trace, dim3 grid, hipStream_t st)
         launch_valu<D, 8, KV>(p, trace, grid, st);
 }
 
-template <int GPAD>
+template <int NSTAGE, int GPAD, int KV>
 void launch_mfma(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
     if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, GPAD, true>), grid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_kernel<NSTAGE, GPAD, KV, true>), grid, dim3(64), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_kernel<kMfmaStages, GPAD, false>), grid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_kernel<NSTAGE, GPAD, KV, false>), grid, dim3(64), 0, st, p);
+}
+
+template <int NSTAGE, int KV>
+void launch_mfma_g(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    const int gpad = mfma_group_pad(p.G);
+    if (gpad == 4)
+        launch_mfma<NSTAGE, 4, KV>(p, trace, grid, st);
+    else if (gpad == 8)
+        launch_mfma<NSTAGE, 8, KV>(p, trace, grid, st);
+    else
+        launch_mfma<NSTAGE, 16, KV>(p, trace, grid, st);
 }
 
 struct Events {
@@ -194,13 +209,10 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
 
     const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
     if (use_mfma(shape, kv)) {
-        const int gpad = mfma_group_pad(p.G);
-        if (gpad == 4)
-            launch_mfma<4>(p, trace, grid, hs);
-        else if (gpad == 8)
-            launch_mfma<8>(p, trace, grid, hs);
+        if (kv == PA_KV_BF16)
+            launch_mfma_g<kMfmaStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
         else
-            launch_mfma<16>(p, trace, grid, hs);
+            launch_mfma_g<kMfmaStagesFp8, pa::KV_FP8>(p, trace, grid, hs);
     } else if (shape->head_dim == 128) {
         if (kv == PA_KV_BF16)
             launch_valu_g<128, pa::KV_BF16>(p, trace, grid, hs);

@@ -40,13 +40,39 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
-constexpr int kRowBytes = 256;    // 128 bf16
-constexpr int kSlabBytes = 4096;  // one (block, head): 16 rows
-constexpr int kStageBytes = 4 * kSlabBytes;  // K block 0, K block 1, V block 0, V block 1
-constexpr int kDmaPerTile = 16;   // 1 KB each
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// LDS bytes one workgroup (one wave) of the kernel uses.
-constexpr int mfma_lds_bytes(int nstage, int gpad) { return nstage * (kStageBytes + gpad * kRowBytes); }
+constexpr int kQRowBytes = 256;  // one query row: 128 bf16
+
+// Storage geometry of one (block, head) slab of the KV cache, head_dim 128.
+template <int KV>
+struct KvGeom {
+    static constexpr int kRow = KV == KV_BF16 ? 256 : 128;  // bytes per token row
+    static constexpr int kSlab = kBlockSize * kRow;          // 16 rows
+    static constexpr int kPieces = kRow / 16;                // 16-byte pieces per row
+    static constexpr int kRowsPerDma = kWave / kPieces;      // rows one 1 KB wave-wide load covers
+    static constexpr int kDmaPerSlab = kSlab / 1024;
+    static constexpr int kStage = 4 * kSlab;                 // K block 0, K block 1, V block 0, V block 1
+    static constexpr int kDmaPerTile = 4 * kDmaPerSlab;
+};
+
+// LDS bytes one workgroup (one wave) of the kernel uses: tile ring + query-row ring.
+constexpr int mfma_lds_bytes(int nstage, int gpad, int kv)
+{
+    return nstage * ((kv == KV_BF16 ? KvGeom<KV_BF16>::kStage : KvGeom<KV_FP8>::kStage) + gpad * kQRowBytes);
+}
+
+// eight e4m3 bytes -> eight bf16 (exact), in byte order
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi)
+{
+    const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)lo, 1.0f, false);
+    const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)lo, 1.0f, true);
+    const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)hi, 1.0f, false);
+    const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)hi, 1.0f, true);
+    return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
 
 // 16-byte-per-lane load from global memory straight into LDS.  LDS destination is
 // lds_addr + lane*16 (wave-uniform lds_addr goes through M0); the global source is
@@ -63,13 +89,14 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-// wait until at most `later_tiles` whole tiles plus EXTRA loads are still in flight
-template <int EXTRA, int NSTAGE>
+// wait until at most `later_tiles` whole tiles (PER_TILE loads each) plus EXTRA loads are still in flight
+template <int EXTRA, int NSTAGE, int PER_TILE>
 __device__ __forceinline__ void wait_tile(int later_tiles)
 {
-    if (NSTAGE >= 4 && later_tiles >= 3) wait_vmcnt<3 * kDmaPerTile + EXTRA>();
-    else if (NSTAGE >= 3 && later_tiles == 2) wait_vmcnt<2 * kDmaPerTile + EXTRA>();
-    else if (later_tiles == 1) wait_vmcnt<1 * kDmaPerTile + EXTRA>();
+    static_assert(3 * PER_TILE + EXTRA <= 63, "vmcnt is a 6-bit counter");
+    if (NSTAGE >= 4 && later_tiles >= 3) wait_vmcnt<3 * PER_TILE + EXTRA>();
+    else if (NSTAGE >= 3 && later_tiles == 2) wait_vmcnt<2 * PER_TILE + EXTRA>();
+    else if (later_tiles == 1) wait_vmcnt<1 * PER_TILE + EXTRA>();
     else wait_vmcnt<EXTRA>();
 }
 
@@ -91,14 +118,18 @@ __device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, 
     } while (c.nt == 0 && c.b < B);
 }
 
-template <int NSTAGE, int GPAD, bool TRACE>
+template <int NSTAGE, int GPAD, int KV, bool TRACE>
 __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 {
     constexpr int D = 128;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring depth");
     static_assert(GPAD == 4 || GPAD == 8 || GPAD == 16, "padded group width");
-    constexpr int kQSlot = GPAD * kRowBytes;
-    __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(NSTAGE, GPAD)];
+    using Geo = KvGeom<KV>;
+    constexpr int kSlabBytes = Geo::kSlab;
+    constexpr int kStageBytes = Geo::kStage;
+    constexpr int kDmaPerTile = Geo::kDmaPerTile;
+    constexpr int kQSlot = GPAD * kQRowBytes;
+    __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(NSTAGE, GPAD, KV)];
 
     const int lane = threadIdx.x;
     const int g = blockIdx.x % p.Hkv;
@@ -134,25 +165,45 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     Cursor cc = ic;  // compute side
 
     // ---- per-lane address pieces
-    uint32_t dma_off[4];  // global byte offset inside a slab for DMA instruction i (rows 4i..4i+3)
+    // LDS-DMA of a KV slab: instruction r covers rows r*kRowsPerDma ..; this lane's global byte offset
+    uint32_t dma_off[Geo::kDmaPerSlab];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int t = 4 * i + q4;
-        dma_off[i] = t * kRowBytes + ((n ^ t) << 4);
+    for (int r = 0; r < Geo::kDmaPerSlab; ++r) {
+        const int t = r * Geo::kRowsPerDma + lane / Geo::kPieces;
+        dma_off[r] = t * Geo::kRow + (((lane % Geo::kPieces) ^ (t & (Geo::kPieces - 1))) << 4);
+    }
+    // LDS-DMA of the query rows (always bf16: 4 rows of 256 B per instruction)
+    uint32_t qdma_off[GPAD / 4];
+#pragma unroll
+    for (int r = 0; r < GPAD / 4; ++r) {
+        const int t = 4 * r + q4;
+        qdma_off[r] = t * kQRowBytes + ((n ^ t) << 4);
     }
     uint32_t kread[4];  // LDS byte offset inside a slab of this lane's K operand piece for k-step kk
     uint32_t qread[4];  // same for the query slab (padding columns read row 0 and are zeroed)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-        kread[kk] = n * kRowBytes + (((4 * kk + q4) ^ n) << 4);
-        qread[kk] = n < G ? kread[kk] : ((4 * kk + q4) << 4);
+        if (KV == KV_BF16)  // 16 bytes: dims 32kk + 8q4 + [0,8) of token n
+            kread[kk] = n * Geo::kRow + (((4 * kk + q4) ^ n) << 4);
+        else                // 8 bytes: the same dims, half of 16-byte piece 2kk + q4/2
+            kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & 7)) << 4) + ((q4 & 1) << 3);
+        qread[kk] = n < G ? (uint32_t)(n * kQRowBytes + (((4 * kk + q4) ^ n) << 4)) : (uint32_t)((4 * kk + q4) << 4);
     }
-    uint32_t vread[8];  // LDS byte offset inside a slab of this lane's transposing-read source for dim tile dt
-    {
+    // LDS byte offset (inside the V half of a stage) of this lane's transposing-read source for dim tile dt.
+    // bf16: one read per block, rows = tokens 4q4 + n/4, 8 bytes = 4 dims.  fp8: one read for both blocks,
+    // rows n/2 = 0..3 -> tokens 4q4.. of block 0, rows 4..7 -> the same tokens of block 1, 8 bytes = 8 dims.
+    uint32_t vread[8];
+    if (KV == KV_BF16) {
         const int row = 4 * q4 + (n >> 2);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt)
-            vread[dt] = row * kRowBytes + ((n & 1) << 3) + (((2 * dt + ((n >> 1) & 1)) ^ row) << 4);
+            vread[dt] = row * Geo::kRow + ((n & 1) << 3) + (((2 * dt + ((n >> 1) & 1)) ^ row) << 4);
+    } else {
+        const int r = n >> 1;
+        const int tok = 4 * q4 + (r & 3);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+            vread[dt] = (r >> 2) * kSlabBytes + tok * Geo::kRow + ((dt ^ (tok & 7)) << 4) + ((n & 1) << 3);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t ldsq = lds0 + NSTAGE * kStageBytes;
@@ -165,10 +216,10 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     int q_issue = 0;  // query slot the issue side fills next
     auto issue = [&](int i, int stage) {
         if (i == 0 || ic.lt == 0) {  // a new segment starts: send its query rows ahead of its first tile
-            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.Hq + g * G) * kRowBytes;
+            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.Hq + g * G) * kQRowBytes;
 #pragma unroll
             for (int r = 0; r < GPAD / 4; ++r) {
-                const uint32_t off = (4 * r + q4 < G) ? dma_off[r] : (dma_off[r] & 255u);
+                const uint32_t off = (4 * r + q4 < G) ? qdma_off[r] : (qdma_off[r] & (kQRowBytes - 1));
                 dma16(ldsq + q_issue * kQSlot + r * 1024, off, qb);
             }
             q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
@@ -197,25 +248,26 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         for (int sub = 0; sub < 2; ++sub) {
             const char* kb = kc + phys[sub] * head_stride;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t off = (4 * r + q4 < nvalid[sub]) ? dma_off[r] : (dma_off[r] & 255u);
-                dma16(ldst + sub * kSlabBytes + r * 1024, off, kb);
+            for (int r = 0; r < Geo::kDmaPerSlab; ++r) {
+                const bool live = r * Geo::kRowsPerDma + lane / Geo::kPieces < nvalid[sub];
+                dma16(ldst + sub * kSlabBytes + r * 1024, live ? dma_off[r] : (dma_off[r] & (Geo::kRow - 1)), kb);
             }
         }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const char* vb = vc + phys[sub] * head_stride;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t off = (4 * r + q4 < nvalid[sub]) ? dma_off[r] : (dma_off[r] & 255u);
-                dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024, off, vb);
+            for (int r = 0; r < Geo::kDmaPerSlab; ++r) {
+                const bool live = r * Geo::kRowsPerDma + lane / Geo::kPieces < nvalid[sub];
+                dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024, live ? dma_off[r] : (dma_off[r] & (Geo::kRow - 1)), vb);
             }
         }
         advance(ic, p.context_lens, B);
     };
 
     // ---- online softmax state: lane = head n, tokens 4*q4+{0..3} of each block
-    const float qs = p.scale_log2;
+    const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;  // K scale folded in
+    const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
     float m = kNegBig, lsum = 0.f;
     f32x4 acc[8];
     bf16x8 qreg[4];
@@ -241,7 +293,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         const char* kbuf = smem + stage * kStageBytes;
         const char* vbuf = kbuf + 2 * kSlabBytes;
 
-        wait_tile<kDmaPerTile / 2, NSTAGE>(later);  // K of this tile (and its segment's query rows) landed
+        wait_tile<kDmaPerTile / 2, NSTAGE, kDmaPerTile>(later);  // K of this tile (and its segment's query rows) landed
         if (tile == 0 || cc.lt == 0) {  // segment start
             m = kNegBig;
             lsum = 0.f;
@@ -262,8 +314,16 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 a0 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kread[kk]));
-            const bf16x8 a1 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kSlabBytes + kread[kk]));
+            bf16x8 a0, a1;
+            if (KV == KV_BF16) {
+                a0 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kread[kk]));
+                a1 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kSlabBytes + kread[kk]));
+            } else {
+                const uint2 w0 = *reinterpret_cast<const uint2*>(kbuf + kread[kk]);
+                const uint2 w1 = *reinterpret_cast<const uint2*>(kbuf + kSlabBytes + kread[kk]);
+                a0 = fp8x8_to_bf16x8(w0.x, w0.y);
+                a1 = fp8x8_to_bf16x8(w1.x, w1.y);
+            }
             s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[kk], s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[kk], s1, 0, 0, 0);
         }
@@ -298,12 +358,18 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         for (int r = 0; r < 8; ++r) pb[r] = (__bf16)x[r];
 
         // ---- out^T[dim, head] += V^T . P^T
-        wait_tile<0, NSTAGE>(later);
+        wait_tile<0, NSTAGE, kDmaPerTile>(later);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            const i16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + vread[dt]));
-            const i16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + kSlabBytes + vread[dt]));
-            const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+            bf16x8 va;
+            if (KV == KV_BF16) {
+                const i16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + vread[dt]));
+                const i16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + kSlabBytes + vread[dt]));
+                va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+            } else {
+                const i32x2 v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(vbuf + vread[dt]));
+                va = fp8x8_to_bf16x8((uint32_t)v[0], (uint32_t)v[1]);
+            }
             acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, acc[dt], 0, 0, 0);
         }
 
@@ -312,7 +378,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             float l = lsum + __shfl_xor(lsum, 16, kWave);
             l += __shfl_xor(l, 32, kWave);
             if (n < G) {
-                const float inv = 1.f / l;
+                const float inv = vs / l;
                 const int hq = g * G + n;
                 float* dst;
                 if (seg_first_lt == 0 && cc.lt == cc.nt - 1) {  // the whole sequence: final result
