@@ -21,7 +21,8 @@ constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds i
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
 constexpr int kMinGroupMfma = 4;   // below this the padded tile is mostly empty: vector-ALU kernel
 constexpr int kMfmaStagesBf16 = 2;  // depth of the LDS tile ring of the matrix-core kernel, bf16 KV
-constexpr int kMfmaStagesFp8 = 3;   // same for fp8 KV (tiles are half the size)
+constexpr int kMfmaStagesFp8 = 4;   // same for fp8 KV (tiles are half the size)
+constexpr int kMfmaWavesPerCu = 4;  // one wave per SIMD measured best; more, thinner waves were slower
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kValuWavesPerCu = 8;
 constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
@@ -94,8 +95,9 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         // one resident wave per (partition, KV head): as many partitions as the device holds at once,
         // but never more than there can be tiles
         const int G = s->num_q_heads / s->num_kv_heads;
+        const int lds_fit = kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv), mfma_group_pad(G), (int)kv);
         const int waves_per_cu = use_mfma(s, kv)
-                                     ? kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv), mfma_group_pad(G), (int)kv)
+                                     ? (lds_fit < kMfmaWavesPerCu ? lds_fit : kMfmaWavesPerCu)
                                      : kValuWavesPerCu;
         int64_t P = (int64_t)compute_units() * waves_per_cu / s->num_kv_heads;
         const int64_t tile_bound = (int64_t)s->batch * ((plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens);

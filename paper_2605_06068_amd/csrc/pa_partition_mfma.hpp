@@ -353,9 +353,14 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;
         }
-        bf16x8 pb;
+        // P^T operand as a bf16 pair (high part + rounding remainder): 16 significant bits, so
+        // the weights lose nothing that matters against the fp32 accumulation
+        bf16x8 pb, pb_lo;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) pb[r] = (__bf16)x[r];
+        for (int r = 0; r < 8; ++r) {
+            pb[r] = (__bf16)x[r];
+            pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
+        }
 
         // ---- out^T[dim, head] += V^T . P^T
         wait_tile<0, NSTAGE, kDmaPerTile>(later);
@@ -371,6 +376,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 va = fp8x8_to_bf16x8((uint32_t)v[0], (uint32_t)v[1]);
             }
             acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, acc[dt], 0, 0, 0);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo, acc[dt], 0, 0, 0);
         }
 
         // ---- segment end: finish the row sums, normalise, write
