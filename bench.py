@@ -38,6 +38,30 @@ def parse_args():
     return ap.parse_args()
 
 
+def recorded_traffic(workload_name: str):
+    """HBM bytes per launch of the partition kernel, from the committed counter summary
+    (profiles/partition_<workload>_pmc.txt: FETCH_SIZE and WRITE_SIZE, scaled by what the same
+    counters read for a copy of known size).  None when there is no summary for this workload or
+    the kernel sources changed since the counters were taken."""
+    from paper_2605_06068_amd import build as pa_build
+
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"partition_{workload_name}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    with open(path) as fh:
+        for line in fh:
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                kv[k.strip()] = v.strip()
+    if kv.get("kernel_source_sha256") != pa_build.source_digest():
+        return None
+    try:
+        return int(float(kv["traffic_bytes_per_launch"]))
+    except (KeyError, ValueError):
+        return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -138,7 +162,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "kernel": "partition", "achieved": round(part_gbps, 2), "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": round(part_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+            "unit": "GB/s", "frac": round(part_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(batch.name),
             "partition_ms": round(part_ms, 5), "merge_ms": round(merge_ms, 5),
         },
     }

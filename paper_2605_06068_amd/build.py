@@ -26,6 +26,19 @@ def _deps():
     return [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(INCLUDE, "pa_decode.h")]
 
 
+def source_digest() -> str:
+    """SHA-256 over the kernel sources (names and contents): identifies the code a measurement belongs to."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(CSRC)):
+        if f.endswith((".hip", ".hpp")):
+            h.update(f.encode())
+            with open(os.path.join(CSRC, f), "rb") as fh:
+                h.update(fh.read())
+    return h.hexdigest()
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True

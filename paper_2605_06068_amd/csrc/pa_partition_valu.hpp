@@ -49,7 +49,7 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
     const int row = lane / CH;
 
     // ---- this wave's range of the global tile sequence
-    const int T = __builtin_amdgcn_readfirstlane(total_tiles(p.context_lens, B, lane));
+    const RangeStart rs = find_range(p.context_lens, B, k, p.P, lane);
     if (k == 0) {  // empty contexts: their output rows are zero
         for (int b0 = 0; b0 < B; b0 += kWave) {
             const int b = b0 + lane;
@@ -59,16 +59,12 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
             }
         }
     }
-    const int t_lo = part_begin(k, T, p.P), t_hi = part_begin(k + 1, T, p.P);
-    if (t_lo >= t_hi) return;
-    const int ntiles = t_hi - t_lo;
-    int first_b, first_cum;
-    locate_tile(p.context_lens, B, t_lo, lane, first_b, first_cum);
-    first_b = __builtin_amdgcn_readfirstlane(first_b);
-    first_cum = __builtin_amdgcn_readfirstlane(first_cum);
+    if (rs.t_lo >= rs.t_hi) return;
+    const int ntiles = rs.t_hi - rs.t_lo;
+    const int first_b = rs.b;
     int b = first_b;
-    int lt = t_lo - first_cum;
-    int L = __builtin_amdgcn_readfirstlane(p.context_lens[b]);
+    int lt = rs.t_lo - rs.cum;
+    int L = rs.L;
     int nt = tiles_of(L);
     int seg_first_lt = lt;
 

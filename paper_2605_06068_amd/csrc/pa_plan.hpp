@@ -76,6 +76,59 @@ __device__ __forceinline__ void locate_tile(const int32_t* context_lens, int B, 
     }
 }
 
+// Where partition k of P starts: total tile count T, the partition's global tile range
+// [t_lo, t_hi), and for a non-empty range the sequence b that holds tile t_lo, the number of
+// tiles before b and b's context length.  All 64 lanes must call; results are wave-uniform.
+// A batch of up to 64 sequences needs a single load of the context lengths.
+struct RangeStart {
+    int T, t_lo, t_hi, b, cum, L;
+};
+
+__device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, int B, int k, int P, int lane)
+{
+    RangeStart r;
+    r.b = 0;
+    r.cum = 0;
+    r.L = 0;
+    if (B <= kWave) {
+        const int L = lane < B ? context_lens[lane] : 0;
+        const int n = tiles_of(L);
+        const int incl = wave_inclusive_scan(n, lane);
+        r.T = __builtin_amdgcn_readlane(incl, kWave - 1);
+        r.t_lo = part_begin(k, r.T, P);
+        r.t_hi = part_begin(k + 1, r.T, P);
+        if (r.t_lo < r.t_hi) {
+            const unsigned long long hit = __ballot(incl > r.t_lo);
+            const int l = __ffsll((long long)hit) - 1;
+            r.b = l;
+            r.cum = __builtin_amdgcn_readlane(incl - n, l);
+            r.L = __builtin_amdgcn_readlane(L, l);
+        }
+        return r;
+    }
+    r.T = __builtin_amdgcn_readfirstlane(total_tiles(context_lens, B, lane));
+    r.t_lo = part_begin(k, r.T, P);
+    r.t_hi = part_begin(k + 1, r.T, P);
+    if (r.t_lo >= r.t_hi) return r;
+    int carry = 0;
+    for (int b0 = 0; b0 < B; b0 += kWave) {
+        const int b = b0 + lane;
+        const int L = b < B ? context_lens[b] : 0;
+        const int n = tiles_of(L);
+        const int incl = wave_inclusive_scan(n, lane) + carry;
+        const unsigned long long hit = __ballot(incl > r.t_lo);
+        if (hit != 0ull) {
+            const int l = __ffsll((long long)hit) - 1;
+            r.b = b0 + l;
+            r.cum = __builtin_amdgcn_readlane(incl - n, l);
+            r.L = __builtin_amdgcn_readlane(L, l);
+            break;
+        }
+        carry = __builtin_amdgcn_readlane(incl, kWave - 1);
+    }
+    return r;
+}
+
 // Uniform (scalar-cache) load of a 32-bit word: keeps table and length lookups off the
 // vector-memory counter that the hand-scheduled LDS-DMA ring relies on.
 __device__ __forceinline__ int32_t uniform_load(const int32_t* p, int64_t idx)
