@@ -40,12 +40,12 @@ def parse_args():
 
 def recorded_traffic(workload_name: str):
     """HBM bytes per launch of the partition kernel, from the committed counter summary
-    (profiles/partition_<workload>_pmc.txt: FETCH_SIZE and WRITE_SIZE, scaled by what the same
+    (profiles/partition_<workload>.txt: FETCH_SIZE and WRITE_SIZE, scaled by what the same
     counters read for a copy of known size).  None when there is no summary for this workload or
     the kernel sources changed since the counters were taken."""
     from paper_2605_06068_amd import build as pa_build
 
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"partition_{workload_name}_pmc.txt")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"partition_{workload_name}.txt")
     if not os.path.exists(path):
         return None
     kv = {}

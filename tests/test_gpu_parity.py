@@ -144,6 +144,25 @@ def test_runs_are_bit_identical(pa):
     assert np.array_equal(a1, a2)
 
 
+@pytest.mark.parametrize("config,kwargs,P", [(2, dict(length_scale=0.25), 0), (1, {}, 3),
+                                             (5, dict(length_scale=1 / 16, batch_limit=16), 0)])
+def test_repeated_calls_share_one_workspace(pa, oracle, config, kwargs, P):
+    """The workspace carries nothing from one call to the next: poison it (and the output)
+    between calls and every call must still produce the same bits."""
+    b = W.make_config(config, **kwargs)
+    dev = pa.DeviceBatch(b, num_partitions=P)
+    want = oracle.decode_batch(b)["out"]
+    first = None
+    for i in range(3):
+        dev.out.fill_(float("nan"))
+        if dev.workspace is not None:
+            dev.workspace.fill_(float("nan"))
+        got = dev.decode().cpu().numpy()
+        assert_parity(got, want, b.kv_dtype, f"call {i}")
+        first = got if first is None else first
+        assert np.array_equal(got, first)
+
+
 # ------------------------------------------------------------------ bit-exact indexing
 def one_hot_batch(kv, lens, Hq, Hkv, D, targets, seed):
     """q = 64*e_0 for every head; the target token's K row is 64*e_0 (all others 0), so the target
