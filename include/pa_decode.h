@@ -127,6 +127,26 @@ pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, con
                     size_t workspace_bytes, void *stream);
 
 /*
+ * The write that precedes the decode step in a serving loop (the paper's scenarios keep the
+ * KV cache paged and append to it token by token: Appendix A, Scenarios A and C): stores the key
+ * and value rows of the token generated in this step into the cache, at logical position
+ * context_lens[b] - 1 of sequence b (the lengths already count the new token; sequences with
+ * context_lens[b] <= 0 are skipped), i.e. into block block_tables[b][(L-1) / block_size], slot
+ * (L-1) % block_size.
+ *
+ *   k_new, v_new   device bf16 [batch, num_kv_heads, head_dim], 16-byte aligned
+ *   k_cache, v_cache, block_tables, context_lens   device, layouts above (caches are written)
+ *   kv_dtype       PA_KV_BF16: rows are copied.  PA_KV_FP8_E4M3: every element is divided by its
+ *                  KV head's scale (k_scale / v_scale, float32 division) and rounded to the nearest
+ *                  e4m3 value, ties to even, saturating at +-448.  Inputs must be finite.
+ *
+ * One kernel on `stream`; no workspace; can be captured into a HIP graph together with pa_decode.
+ */
+pa_status pa_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                       const int32_t *block_tables, const int32_t *context_lens, pa_kv_dtype kv_dtype,
+                       const float *k_scale, const float *v_scale, const pa_shape *shape, void *stream);
+
+/*
  * Same computation with the production indexing code instrumented (slow; for tests).  In
  * addition to out it records, for checking the block-table walk and the split boundaries bit
  * for bit:

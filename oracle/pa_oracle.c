@@ -270,6 +270,68 @@ int64_t pa_oracle_block_partition(const int32_t *context_lens, int32_t B, int32_
     return T;
 }
 
+/*
+ * Nearest e4m3 code of a finite float: round to nearest, ties to the code with an even mantissa
+ * (codes are consecutive, so "even code"), saturating at +-448; the sign bit is copied.  Found the
+ * slow way: compare against every non-negative finite code value.
+ */
+unsigned pa_oracle_e4m3_encode(float x)
+{
+    unsigned sign = signbit(x) ? 0x80u : 0u;
+    double mag = fabs((double)x);
+    unsigned best = 0;
+    double best_err = INFINITY;
+    for (unsigned code = 0; code <= 0x7Eu; ++code) {
+        double err = fabs(e4m3_value(code) - mag);
+        if (err < best_err || (err == best_err && (code & 1u) == 0)) {
+            best = code;
+            best_err = err;
+        }
+    }
+    return sign | best;
+}
+
+/*
+ * KV append by its definition: for every sequence with L_b > 0 the new token's key and value
+ * rows (bf16, [B, Hkv, D]) go to logical position L_b - 1, i.e. block block_tables[b][(L_b-1)/BS],
+ * slot (L_b-1) % BS.  bf16 caches receive the bit patterns unchanged; e4m3 caches receive
+ * encode(float(x) / scale[g]) with the division in float32 (the precision the product states for
+ * this decision).  Returns 0, -1 bad argument, -2 block id outside the pool.
+ */
+int pa_oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, void *k_cache, void *v_cache,
+                        const int32_t *block_tables, const int32_t *context_lens, int kv_dtype, const float *k_scale,
+                        const float *v_scale, int32_t B, int32_t Hkv, int32_t D, int32_t BS, int32_t MB, int32_t NB)
+{
+    if (!k_new || !v_new || !k_cache || !v_cache || !block_tables || !context_lens)
+        return -1;
+    if (kv_dtype == PA_ORACLE_KV_FP8_E4M3 && (!k_scale || !v_scale))
+        return -1;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t L = context_lens[b];
+        if (L <= 0)
+            continue;
+        int32_t t = L - 1;
+        int64_t phys = block_tables[(int64_t)b * MB + t / BS];
+        if (phys < 0 || phys >= NB)
+            return -2;
+        for (int32_t g = 0; g < Hkv; ++g)
+            for (int32_t d = 0; d < D; ++d) {
+                int64_t src = ((int64_t)b * Hkv + g) * D + d;
+                int64_t dst = ((phys * Hkv + g) * BS + t % BS) * (int64_t)D + d;
+                if (kv_dtype == PA_ORACLE_KV_BF16) {
+                    ((uint16_t *)k_cache)[dst] = k_new[src];
+                    ((uint16_t *)v_cache)[dst] = v_new[src];
+                } else {
+                    float kq = (float)bf16_value(k_new[src]) / k_scale[g];
+                    float vq = (float)bf16_value(v_new[src]) / v_scale[g];
+                    ((uint8_t *)k_cache)[dst] = (uint8_t)pa_oracle_e4m3_encode(kq);
+                    ((uint8_t *)v_cache)[dst] = (uint8_t)pa_oracle_e4m3_encode(vq);
+                }
+            }
+    }
+    return 0;
+}
+
 int pa_oracle_num_threads(void)
 {
     int n = 1;

@@ -24,7 +24,7 @@ PA_KV_BF16 = 0
 PA_KV_FP8_E4M3 = 1
 
 EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa_decode",
-           "pa_decode_trace", "pa_decode_profile", "pa_kernel_variant", "pa_status_string")
+           "pa_kv_append", "pa_decode_trace", "pa_decode_profile", "pa_kernel_variant", "pa_status_string")
 
 
 class pa_shape(ctypes.Structure):
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.pa_decode_trace.argtypes = common + [vp]
     L.pa_decode_profile.restype = ctypes.c_int
     L.pa_decode_profile.argtypes = common + [i32, fp, fp]
+    L.pa_kv_append.restype = ctypes.c_int
+    L.pa_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, shp, vp]
     L.pa_kernel_variant.restype = ctypes.c_char_p
     L.pa_kernel_variant.argtypes = [shp, ctypes.c_int]
     L.pa_status_string.restype = ctypes.c_char_p
@@ -151,6 +153,17 @@ def pa_decode(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, 
                                        v_scale, shape, workspace, stream))
     if st != PA_OK:
         raise PaError(st, "pa_decode")
+
+
+def pa_kv_append(k_new, v_new, k_cache, v_cache, block_tables, context_lens, kv_dtype, k_scale=None, v_scale=None, *,
+                 shape: pa_shape, stream=None) -> None:
+    """Enqueue the append of this step's key/value rows into the paged cache."""
+    st = lib().pa_kv_append(_dev_ptr(k_new, "k_new"), _dev_ptr(v_new, "v_new"), _dev_ptr(k_cache, "k_cache"),
+                            _dev_ptr(v_cache, "v_cache"), _dev_ptr(block_tables, "block_tables"),
+                            _dev_ptr(context_lens, "context_lens"), int(kv_dtype), _dev_ptr(k_scale, "k_scale"),
+                            _dev_ptr(v_scale, "v_scale"), ctypes.byref(shape), _stream_ptr(stream))
+    if st != PA_OK:
+        raise PaError(st, "pa_kv_append")
 
 
 def pa_decode_trace(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale=None, v_scale=None,

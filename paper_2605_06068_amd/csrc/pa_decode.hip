@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "pa_device.hpp"
+#include "pa_kv_append.hpp"
 #include "pa_merge.hpp"
 #include "pa_partition_mfma.hpp"
 #include "pa_partition_valu.hpp"
@@ -345,6 +346,43 @@ pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_ca
         (void)hipEventDestroy(evs[i].after);
     }
     return st;
+}
+
+pa_status pa_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache, const int32_t* block_tables,
+                       const int32_t* context_lens, pa_kv_dtype kv_dtype, const float* k_scale, const float* v_scale,
+                       const pa_shape* shape, void* stream)
+{
+    const pa_status st = check_shape(shape, kv_dtype);
+    if (st != PA_OK) return st;
+    if (!k_new || !v_new || !k_cache || !v_cache || !block_tables || !context_lens) return PA_ERR_INVALID_ARG;
+    if (kv_dtype == PA_KV_FP8_E4M3 && (!k_scale || !v_scale)) return PA_ERR_INVALID_ARG;
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) ||
+        !aligned(block_tables, 4) || !aligned(context_lens, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 4))
+        return PA_ERR_INVALID_ARG;
+    if (shape->batch == 0) return PA_OK;
+    const int64_t threads = (int64_t)shape->batch * shape->num_kv_heads * (shape->head_dim / 8);
+    if ((threads + 255) / 256 > INT32_MAX) return PA_ERR_UNSUPPORTED;
+    const dim3 grid((uint32_t)((threads + 255) / 256));
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const uint16_t* kn = static_cast<const uint16_t*>(k_new);
+    const uint16_t* vn = static_cast<const uint16_t*>(v_new);
+    const int B = shape->batch, Hkv = shape->num_kv_heads, MB = shape->max_blocks_per_seq;
+    if (shape->head_dim == 128) {
+        if (kv_dtype == PA_KV_BF16)
+            hipLaunchKernelGGL((pa::kv_append_kernel<128, pa::KV_BF16>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
+                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+        else
+            hipLaunchKernelGGL((pa::kv_append_kernel<128, pa::KV_FP8>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
+                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+    } else {
+        if (kv_dtype == PA_KV_BF16)
+            hipLaunchKernelGGL((pa::kv_append_kernel<64, pa::KV_BF16>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
+                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+        else
+            hipLaunchKernelGGL((pa::kv_append_kernel<64, pa::KV_FP8>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
+                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+    }
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }
 
 const char* pa_kernel_variant(const pa_shape* shape, pa_kv_dtype kv_dtype)

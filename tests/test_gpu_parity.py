@@ -100,6 +100,21 @@ def test_one_sequence_cut_by_every_partition(pa, oracle):
         check(pa, oracle, b, f"single-sequence P={P}", num_partitions=P)
 
 
+@pytest.mark.parametrize("B", [63, 64, 65, 130, 300])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2)])
+def test_many_short_sequences_with_gaps(pa, oracle, B, Hq, Hkv):
+    """More sequences than lanes (the length scan runs in 64-sequence chunks), empty sequences
+    sprinkled in, ranges that span dozens of sequences; several partition counts."""
+    rng = np.random.default_rng(B)
+    lens = rng.integers(1, 120, size=B)
+    lens[rng.random(B) < 0.2] = 0
+    lens[0] = 0
+    lens[B - 1] = 0 if B % 2 else 77
+    b = W.make_batch("many", 90 + B, lens.tolist(), Hq, Hkv, 128, 16, W.KV_BF16, max_blocks_per_seq=8)
+    for P in (0, 1, 7, 50):
+        check(pa, oracle, b, f"many-sequences P={P}", num_partitions=P)
+
+
 def test_single_token_context_returns_v_exactly(pa):
     for kv in (W.KV_BF16, W.KV_FP8_E4M3):
         b = W.make_batch("l1", 70, [1, 1, 1, 1], 8, 2, 128, 16, kv, num_blocks=9)

@@ -257,6 +257,60 @@ def test_fp8_scales_belong_to_their_kv_head(oracle):
     assert np.allclose(p[0, :30], 1 / 30, rtol=1e-3) and p[2, :30].max() > 0.99
 
 
+# ---------------------------------------------------------------- KV append
+def test_e4m3_encoder_matches_torch_cast_and_the_format_rules(oracle):
+    import torch
+
+    rng = np.random.default_rng(50)
+    xs = np.concatenate([
+        rng.standard_normal(2000).astype(np.float32) * np.float32(3.0),
+        (rng.standard_normal(500) * 100).astype(np.float32),
+        (rng.standard_normal(500) * 2.0 ** -7).astype(np.float32),
+        np.array([0.0, -0.0, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 5 * 2.0 ** -10, 1.0625, 1.1875, 447.9, 448.0, -448.0,
+                  463.9], dtype=np.float32),
+    ])
+    inside = np.abs(xs) < 464  # torch's cast has no saturation: beyond this it returns NaN
+    want = torch.from_numpy(xs[inside]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle.e4m3_encode(x) for x in xs[inside]], dtype=np.uint8)
+    assert np.array_equal(got, want)
+    # saturation and sign, by the rule itself
+    assert oracle.e4m3_encode(464.0) == 0x7E and oracle.e4m3_encode(1e30) == 0x7E and oracle.e4m3_encode(-1e30) == 0xFE
+    # decode(encode(v)) == v for every finite code value
+    t = oracle.e4m3_table()
+    for code in range(256):
+        if not math.isnan(t[code]):
+            assert oracle.e4m3_encode(t[code]) == code
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_kv_append_writes_exactly_the_last_slot(oracle, kv):
+    rng = np.random.default_rng(51)
+    b = tiny(51, [17, 0, 32, 1, 100], Hq=4, Hkv=2, D=64, kv=kv, poison=False)
+    k0, v0 = b.k_cache.copy(), b.v_cache.copy()
+    k_new = bf16(rng.standard_normal((5, 2, 64)))
+    v_new = bf16(rng.standard_normal((5, 2, 64)))
+    oracle.kv_append(k_new, v_new, b.k_cache, b.v_cache, b.block_tables, b.context_lens, kv, b.k_scale, b.v_scale)
+    changed = np.zeros(b.k_cache.shape[:3], dtype=bool)
+    for s, L in enumerate(b.context_lens):
+        if L <= 0:
+            continue
+        phys, slot = b.block_tables[s, (L - 1) // 16], (L - 1) % 16
+        changed[phys, :, slot] = True
+        for g in range(2):
+            if kv == W.KV_BF16:
+                assert np.array_equal(b.k_cache[phys, g, slot], k_new[s, g])
+                assert np.array_equal(b.v_cache[phys, g, slot], v_new[s, g])
+            else:
+                kq = W.bf16_bits_to_f32(k_new[s, g]) / np.float32(b.k_scale[g])
+                vq = W.bf16_bits_to_f32(v_new[s, g]) / np.float32(b.v_scale[g])
+                assert np.array_equal(b.k_cache[phys, g, slot], W.f32_to_e4m3_bytes(kq))
+                assert np.array_equal(b.v_cache[phys, g, slot], W.f32_to_e4m3_bytes(vq))
+    assert np.array_equal(b.k_cache[~changed], k0[~changed]) and np.array_equal(b.v_cache[~changed], v0[~changed])
+    # appended rows are what the attention oracle then sees at position L-1
+    out = oracle.decode_batch(b, want_probs=True)
+    assert np.isfinite(out["out"]).all()
+
+
 # ---------------------------------------------------------------- indexing helpers
 def test_visited_blocks_follow_the_table(oracle):
     b = W.make_config(1)
