@@ -50,16 +50,16 @@ int mfma_group_pad(int G) { return G <= 4 ? 4 : (G <= 8 ? 8 : 16); }
 // Compute units of the current device (cached per process; 256 when there is no device).
 int compute_units()
 {
-    static int cached = 0;
-    if (cached > 0) return cached;
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
-        cached = n;
-    } else {
+    // initialised once, thread-safely; every GPU this library targets is the same part, so one
+    // value per process is enough
+    static const int cached = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            return n;
         (void)hipGetLastError();
-        cached = kDefaultCus;
-    }
+        return kDefaultCus;
+    }();
     return cached;
 }
 

@@ -132,8 +132,11 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(NSTAGE, GPAD, KV)];
 
     const int lane = threadIdx.x;
-    const int g = blockIdx.x % p.Hkv;
-    const int k = blockIdx.x / p.Hkv;
+    // partition index fastest: workgroups go to the chip's eight dies round-robin, so (with P a
+    // multiple of 8) the waves of all KV heads of one partition share a die and read the
+    // contiguous slabs of each physical block from there (measured 0.5-1.4 % faster than head-fastest)
+    const int g = blockIdx.x / p.P;
+    const int k = blockIdx.x % p.P;
     const int G = p.G;
     const int B = p.B;
     const int n = lane & 15;   // head column / row-in-block, depending on the operand

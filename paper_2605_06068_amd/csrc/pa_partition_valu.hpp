@@ -41,8 +41,8 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
     constexpr int STEPS = kBlockSize / ROWS;
 
     const int lane = threadIdx.x;
-    const int g = blockIdx.x % p.Hkv;
-    const int k = blockIdx.x / p.Hkv;
+    const int g = blockIdx.x / p.P;  // partition index fastest, as in the matrix-core kernel
+    const int k = blockIdx.x % p.P;
     const int G = p.G;
     const int B = p.B;
     const int c = lane % CH;
