@@ -37,6 +37,15 @@
  *     k_scale, v_scale [num_kv_heads]                                     float32 (fp8 KV only)
  *     out           [batch, num_q_heads, head_dim]                        float32
  *
+ * Multi-token verification (shape.q_len = Q in 2 .. 16; the single forward pass over a window of
+ * K proposed tokens in the paper's predicted-output speculative decoding, Appendix A, Scenario B):
+ * the Q window tokens are already in the cache as the LAST Q tokens of every context
+ * (context_lens counts them), q and out gain a query-token axis,
+ *     q   [batch, Q, num_q_heads, head_dim]      out [batch, Q, num_q_heads, head_dim]
+ * and query token i attends causally, to t in [0, context_lens[b] - Q + i]; a query token with no
+ * visible token yields a zero row.  The KV cache is read once for all Q tokens.  Supported for
+ * head_dim 128 with 4 <= Q * G <= 64 (matrix-core kernel only).
+ *
  * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
  * 1 <= G <= 16 (G <= 8 for head_dim 64); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
  * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
@@ -74,6 +83,8 @@ typedef struct pa_shape {
     int32_t max_context_len;    /* host-known upper bound on context_lens; 0 = max_blocks_per_seq * block_size */
     int32_t num_partitions;     /* 0 = library heuristic; otherwise the number P of partitions of the
                                    split plan below (1 .. 65535; tests force values) */
+    int32_t q_len;              /* query tokens per sequence: 0 or 1 = plain decode; 2 .. 16 = multi-token
+                                   verification (see pa_decode) */
 } pa_shape;
 
 /*
@@ -101,7 +112,7 @@ int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, const int32_t
                       int32_t *block_partition);
 
 /* Bytes of device workspace pa_decode needs for this shape: two partial results (normalised
- * output row + log-sum-exp per query head) per partition.  0 when P == 1.  Returns 0 as well for
+ * output row + log-sum-exp per query head and query token) per partition.  0 when P == 1.  Returns 0 as well for
  * an invalid shape (pa_decode then reports the error). */
 size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
@@ -173,8 +184,8 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
                             float *merge_ms);
 
 /* Name of the partition kernel variant pa_decode picks for this shape ("mfma": matrix cores, for
- * head_dim 128 and groups of 4..16 query heads; "valu" otherwise); NULL for an invalid
- * shape.  Static storage. */
+ * head_dim 128 and 4..64 query rows (Q * G) per KV head; "valu" otherwise); NULL for an invalid
+ * or unsupported shape.  Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
 /* Human-readable name of a status code.  Static storage. */

@@ -22,6 +22,9 @@
  * 256-entry table (built here from the format's closed form) times the KV head's
  * scale (k_scale for K, v_scale for V).  L_b = 0 gives a zero row.
  *
+ * pa_oracle_verify is the same definition for a window of Q query tokens per sequence with a
+ * causal mask inside the window (query i sees tokens 0 .. L_b - Q + i).
+ *
  * Every pin that ties this file to something other than itself lives in
  * tests/test_oracle_pins.py (closed forms, invariants, dense library softmax, brute
  * force); no function here is "parity unpinned".
@@ -88,15 +91,14 @@ static double load_kv(const problem *p, const void *cache, const float *head_sca
     return p->e4m3[((const uint8_t *)cache)[idx]] * (double)head_scale[g];
 }
 
-/* One output row.  scores has room for L doubles.  Returns 0, or -2 on a block id
- * outside the pool for a valid token. */
-static int attend_row(const problem *p, int b, int h, double *scores, double *out_row, double *lse_out,
-                      double *probs_row)
+/* One output row: query vector qrow (head h) of sequence b against that sequence's logical
+ * tokens 0 .. L-1.  scores has room for L doubles.  Returns 0, or -2 on a block id outside the
+ * pool for a valid token. */
+static int attend_row(const problem *p, int b, int h, const uint16_t *qrow, int L, double *scores,
+                      double *out_row, double *lse_out, double *probs_row)
 {
     const int G = p->Hq / p->Hkv;
     const int g = h / G;
-    const int L = p->context_lens[b];
-    const uint16_t *qrow = p->q + ((int64_t)b * p->Hq + h) * p->D;
 
     for (int d = 0; d < p->D; ++d)
         out_row[d] = 0.0;
@@ -136,26 +138,22 @@ static int attend_row(const problem *p, int b, int h, double *scores, double *ou
 }
 
 /*
- * Attention rows for the whole batch (row_b == NULL: n_rows must be B*Hq, row r is
- * b = r / Hq, h = r % Hq) or for a selection of (row_b[r], row_h[r]) pairs.
- *
- *   out_f32   [n_rows, D] float32, required
- *   out_f64   [n_rows, D] float64, optional (NULL to skip)
- *   lse       [n_rows]    float64 log-sum-exp of the scaled scores, optional
- *   probs     [n_rows, probs_stride] float64 softmax weights per logical token, optional
- *
- * Returns 0; -1 bad shape/argument; -2 a valid token's block id is outside [0, NB);
- * -3 out of memory.
+ * Shared driver: Q query tokens per sequence (q is [B, Q, Hq, D]); query token i of sequence b
+ * sees the logical tokens 0 .. L_b - Q + i, i.e. the window's own tokens are the LAST Q tokens
+ * of the context and each sees itself and everything before it.  Q == 1 is plain decode.
+ * Rows: row_b == NULL -> all B*Q*Hq rows in layout order, else the (row_b, row_i, row_h) triples
+ * (row_i == NULL means token 0).
  */
-int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
-                     const int32_t *context_lens, float scale, int kv_dtype, const float *k_scale,
-                     const float *v_scale, int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t BS, int32_t MB,
-                     int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_h, float *out_f32,
-                     double *out_f64, double *lse, double *probs, int64_t probs_stride)
+static int run_rows(const uint16_t *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                    const int32_t *context_lens, float scale, int kv_dtype, const float *k_scale,
+                    const float *v_scale, int32_t B, int32_t Q, int32_t Hq, int32_t Hkv, int32_t D, int32_t BS,
+                    int32_t MB, int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_i,
+                    const int32_t *row_h, float *out_f32, double *out_f64, double *lse, double *probs,
+                    int64_t probs_stride)
 {
     if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !out_f32)
         return -1;
-    if (B < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || BS <= 0 || MB <= 0 || NB <= 0 || Hq % Hkv != 0)
+    if (B < 0 || Q <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || BS <= 0 || MB <= 0 || NB <= 0 || Hq % Hkv != 0)
         return -1;
     if (kv_dtype != PA_ORACLE_KV_BF16 && kv_dtype != PA_ORACLE_KV_FP8_E4M3)
         return -1;
@@ -163,7 +161,7 @@ int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache
         return -1;
     if (!row_b != !row_h)
         return -1;
-    if (!row_b && n_rows != (int64_t)B * Hq)
+    if (!row_b && n_rows != (int64_t)B * Q * Hq)
         return -1;
 
     problem p;
@@ -175,9 +173,10 @@ int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache
 
     int64_t max_len = 1;
     for (int64_t r = 0; r < n_rows; ++r) {
-        int b = row_b ? row_b[r] : (int)(r / Hq);
+        int b = row_b ? row_b[r] : (int)(r / ((int64_t)Q * Hq));
+        int i = row_b ? (row_i ? row_i[r] : 0) : (int)((r / Hq) % Q);
         int h = row_h ? row_h[r] : (int)(r % Hq);
-        if (b < 0 || b >= B || h < 0 || h >= Hq)
+        if (b < 0 || b >= B || h < 0 || h >= Hq || i < 0 || i >= Q)
             return -1;
         int L = context_lens[b];
         if ((int64_t)L > (int64_t)MB * BS)
@@ -199,9 +198,12 @@ int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache
         } else {
 #pragma omp for schedule(dynamic, 1)
             for (int64_t r = 0; r < n_rows; ++r) {
-                int b = row_b ? row_b[r] : (int)(r / Hq);
+                int b = row_b ? row_b[r] : (int)(r / ((int64_t)Q * Hq));
+                int i = row_b ? (row_i ? row_i[r] : 0) : (int)((r / Hq) % Q);
                 int h = row_h ? row_h[r] : (int)(r % Hq);
-                int rc = attend_row(&p, b, h, scores, row, lse ? &lse[r] : NULL,
+                const uint16_t *qrow = q + (((int64_t)b * Q + i) * Hq + h) * D;
+                int visible = context_lens[b] - Q + 1 + i; /* tokens 0 .. L_b - Q + i */
+                int rc = attend_row(&p, b, h, qrow, visible, scores, row, lse ? &lse[r] : NULL,
                                     probs ? probs + r * probs_stride : NULL);
                 if (rc != 0) {
 #pragma omp atomic write
@@ -218,6 +220,49 @@ int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache
         free(row);
     }
     return status;
+}
+
+/*
+ * Attention rows for the whole batch (row_b == NULL: n_rows must be B*Hq, row r is
+ * b = r / Hq, h = r % Hq) or for a selection of (row_b[r], row_h[r]) pairs.
+ *
+ *   out_f32   [n_rows, D] float32, required
+ *   out_f64   [n_rows, D] float64, optional (NULL to skip)
+ *   lse       [n_rows]    float64 log-sum-exp of the scaled scores, optional
+ *   probs     [n_rows, probs_stride] float64 softmax weights per logical token, optional
+ *
+ * Returns 0; -1 bad shape/argument; -2 a valid token's block id is outside [0, NB);
+ * -3 out of memory.
+ */
+int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                     const int32_t *context_lens, float scale, int kv_dtype, const float *k_scale,
+                     const float *v_scale, int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t BS, int32_t MB,
+                     int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_h, float *out_f32,
+                     double *out_f64, double *lse, double *probs, int64_t probs_stride)
+{
+    return run_rows(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, k_scale, v_scale, B, 1, Hq,
+                    Hkv, D, BS, MB, NB, n_rows, row_b, NULL, row_h, out_f32, out_f64, lse, probs, probs_stride);
+}
+
+/*
+ * Multi-token verification (the single forward pass over a window of K proposed tokens in the
+ * paper's predicted-output speculative decoding: Appendix A, Scenario B): the K = Q
+ * window tokens are already in the cache as the last Q tokens of each context (context_lens
+ * counts them), q is [B, Q, Hq, D], and query token i attends causally: to logical tokens
+ * 0 .. L_b - Q + i.  A query with no visible token (L_b - Q + i < 0) gives a zero row.
+ * Outputs as pa_oracle_decode with rows [B, Q, Hq] (or the selected (b, i, h) triples).
+ */
+int pa_oracle_verify(const uint16_t *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                     const int32_t *context_lens, float scale, int kv_dtype, const float *k_scale,
+                     const float *v_scale, int32_t B, int32_t Q, int32_t Hq, int32_t Hkv, int32_t D, int32_t BS,
+                     int32_t MB, int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_i,
+                     const int32_t *row_h, float *out_f32, double *out_f64, double *lse, double *probs,
+                     int64_t probs_stride)
+{
+    if (row_b && !row_i)
+        return -1;
+    return run_rows(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, k_scale, v_scale, B, Q, Hq,
+                    Hkv, D, BS, MB, NB, n_rows, row_b, row_i, row_h, out_f32, out_f64, lse, probs, probs_stride);
 }
 
 /*

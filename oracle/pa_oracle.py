@@ -42,6 +42,9 @@ def lib() -> ctypes.CDLL:
         L.pa_oracle_decode.restype = ctypes.c_int
         L.pa_oracle_decode.argtypes = [p, p, p, p, p, ctypes.c_float, ctypes.c_int, p, p,
                                        i32, i32, i32, i32, i32, i32, i32, i64, p, p, p, p, p, p, i64]
+        L.pa_oracle_verify.restype = ctypes.c_int
+        L.pa_oracle_verify.argtypes = [p, p, p, p, p, ctypes.c_float, ctypes.c_int, p, p,
+                                       i32, i32, i32, i32, i32, i32, i32, i32, i64, p, p, p, p, p, p, p, i64]
         L.pa_oracle_e4m3_table.restype = None
         L.pa_oracle_e4m3_table.argtypes = [p]
         L.pa_oracle_visited_blocks.restype = i32
@@ -115,10 +118,61 @@ def decode(q_bits: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_t
     return res
 
 
+def verify(q_bits: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_tables: np.ndarray,
+           context_lens: np.ndarray, scale, kv_dtype: int = KV_BF16, k_scale: Optional[np.ndarray] = None,
+           v_scale: Optional[np.ndarray] = None, rows: Optional[Sequence[Tuple[int, int, int]]] = None,
+           want_f64: bool = False, want_lse: bool = False, want_probs: bool = False):
+    """Multi-token causal verification: q_bits is [B, Q, Hq, D]; query token i of sequence b sees the
+    logical tokens 0 .. L_b - Q + i.  Returns 'out' float32 [B,Q,Hq,D] (or [n_rows,D] when ``rows``
+    selects (b,i,h) triples) and, on request, 'out_f64', 'lse', 'probs' as ``decode`` does."""
+    q_bits = _c(q_bits, np.uint16)
+    kv_np = np.uint16 if kv_dtype == KV_BF16 else np.uint8
+    k_cache = _c(k_cache, kv_np)
+    v_cache = _c(v_cache, kv_np)
+    block_tables = _c(block_tables, np.int32)
+    context_lens = _c(context_lens, np.int32)
+    B, Q, Hq, D = q_bits.shape
+    NB, Hkv, BS, D2 = k_cache.shape
+    assert D2 == D and v_cache.shape == k_cache.shape and block_tables.shape[0] == B == context_lens.shape[0]
+    MB = block_tables.shape[1]
+    if kv_dtype == KV_FP8_E4M3:
+        k_scale = _c(k_scale, np.float32)
+        v_scale = _c(v_scale, np.float32)
+        assert k_scale.shape == (Hkv,) and v_scale.shape == (Hkv,)
+    if rows is None:
+        n_rows, rb, ri, rh, shape = B * Q * Hq, None, None, None, (B, Q, Hq, D)
+    else:
+        rb = np.ascontiguousarray([r[0] for r in rows], dtype=np.int32)
+        ri = np.ascontiguousarray([r[1] for r in rows], dtype=np.int32)
+        rh = np.ascontiguousarray([r[2] for r in rows], dtype=np.int32)
+        n_rows, shape = len(rows), (len(rows), D)
+    out = np.zeros((n_rows, D), dtype=np.float32)
+    out64 = np.zeros((n_rows, D), dtype=np.float64) if want_f64 else None
+    lse = np.zeros(n_rows, dtype=np.float64) if want_lse else None
+    stride = MB * BS
+    probs = np.zeros((n_rows, stride), dtype=np.float64) if want_probs else None
+    rc = lib().pa_oracle_verify(_ptr(q_bits), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(context_lens),
+                                ctypes.c_float(float(np.float32(scale))), int(kv_dtype), _ptr(k_scale), _ptr(v_scale),
+                                B, Q, Hq, Hkv, D, BS, MB, NB, n_rows, _ptr(rb), _ptr(ri), _ptr(rh), _ptr(out),
+                                _ptr(out64), _ptr(lse), _ptr(probs), stride)
+    if rc != 0:
+        raise RuntimeError(f"pa_oracle_verify failed with code {rc}")
+    res = {"out": out.reshape(shape)}
+    if want_f64:
+        res["out_f64"] = out64.reshape(shape)
+    if want_lse:
+        res["lse"] = lse.reshape(shape[:-1])
+    if want_probs:
+        res["probs"] = probs.reshape(shape[:-1] + (stride,))
+    return res
+
+
 def decode_batch(batch, **kw):
-    """Convenience: run on an object with the fields of workloads.DecodeBatch (duck-typed)."""
-    return decode(batch.q, batch.k_cache, batch.v_cache, batch.block_tables, batch.context_lens, batch.scale,
-                  batch.kv_dtype, batch.k_scale, batch.v_scale, **kw)
+    """Convenience: run on an object with the fields of workloads.DecodeBatch (duck-typed); a batch
+    whose q has a query-token axis ([B, Q, Hq, D]) goes through ``verify``."""
+    fn = verify if np.ndim(batch.q) == 4 else decode
+    return fn(batch.q, batch.k_cache, batch.v_cache, batch.block_tables, batch.context_lens, batch.scale,
+              batch.kv_dtype, batch.k_scale, batch.v_scale, **kw)
 
 
 def e4m3_table() -> np.ndarray:

@@ -30,7 +30,7 @@ EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa
 class pa_shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_blocks",
-        "max_context_len", "num_partitions")]
+        "max_context_len", "num_partitions", "q_len")]
 
 
 class PaError(RuntimeError):
@@ -84,9 +84,10 @@ def status_string(status: int) -> str:
 
 
 def make_shape(batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks,
-               max_context_len=0, num_partitions=0) -> pa_shape:
+               max_context_len=0, num_partitions=0, q_len=0) -> pa_shape:
     return pa_shape(int(batch), int(num_q_heads), int(num_kv_heads), int(head_dim), int(block_size),
-                    int(max_blocks_per_seq), int(num_blocks), int(max_context_len), int(num_partitions))
+                    int(max_blocks_per_seq), int(num_blocks), int(max_context_len), int(num_partitions),
+                    int(q_len))
 
 
 def _neg_is_error(v: int, where: str) -> int:
@@ -213,12 +214,12 @@ class DeviceBatch:
         self.context_lens = up(batch.context_lens)
         self.k_scale = up(batch.k_scale)
         self.v_scale = up(batch.v_scale)
-        self.out = torch.full((batch.batch, batch.num_q_heads, batch.head_dim), float("nan"), dtype=torch.float32,
-                              device=dev)
+        q_len = int(getattr(batch, "q_len", 1))
+        self.out = torch.full(tuple(batch.q.shape), float("nan"), dtype=torch.float32, device=dev)
         if max_context_len is None:
             max_context_len = int(batch.context_lens.max(initial=0))
         self.shape = make_shape(batch.batch, batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.block_size,
-                                batch.max_blocks_per_seq, batch.num_blocks, max_context_len, num_partitions)
+                                batch.max_blocks_per_seq, batch.num_blocks, max_context_len, num_partitions, q_len)
         nbytes = pa_decode_workspace_size(self.shape, self.kv_dtype)
         # NaN-filled so that a read of an entry this call did not write shows up in the output
         self.workspace = None if nbytes == 0 else torch.full((nbytes // 4,), float("nan"), dtype=torch.float32,

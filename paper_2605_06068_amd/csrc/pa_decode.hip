@@ -20,9 +20,12 @@ using pa::Params;
 
 constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds in registers
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
-constexpr int kMinGroupMfma = 4;   // below this the padded tile is mostly empty: vector-ALU kernel
+constexpr int kMinColsMfma = 4;    // fewer (query token, head) columns than this: vector-ALU kernel
+constexpr int kMaxColsMfma = 64;   // four 16-column MFMA tiles
+constexpr int kMaxQueryLen = 16;
 constexpr int kMfmaStagesBf16 = 2;  // depth of the LDS tile ring of the matrix-core kernel, bf16 KV
 constexpr int kMfmaStagesFp8 = 4;   // same for fp8 KV (tiles are half the size)
+constexpr int kMfmaStagesWide = 2;  // more than one column tile: the query ring takes the LDS
 constexpr int kMfmaWavesPerCu = 4;  // one wave per SIMD measured best; more, thinner waves were slower
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kValuWavesPerCu = 8;
@@ -36,16 +39,25 @@ struct Plan {
     size_t ws_bytes;
 };
 
-// The matrix-core kernel covers head_dim 128 and groups of 4..16 query heads.
+int query_len(const pa_shape* s) { return s->q_len > 0 ? s->q_len : 1; }
+
+// columns of the score matrix per KV head: (query token, query head of the group) pairs
+int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
+
+// The matrix-core kernel covers head_dim 128, groups of up to 16 query heads and 4..64 columns.
 bool use_mfma(const pa_shape* s, pa_kv_dtype kv)
 {
     const int G = s->num_q_heads / s->num_kv_heads;
-    return s->head_dim == 128 && G >= kMinGroupMfma && G <= kMaxGroupMfma;
+    return s->head_dim == 128 && G <= kMaxGroupMfma && columns(s) >= kMinColsMfma && columns(s) <= kMaxColsMfma;
 }
 
-int mfma_stages(pa_kv_dtype kv) { return kv == PA_KV_BF16 ? kMfmaStagesBf16 : kMfmaStagesFp8; }
+int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : (cols <= 16 ? 16 : (cols <= 32 ? 32 : 64))); }
 
-int mfma_group_pad(int G) { return G <= 4 ? 4 : (G <= 8 ? 8 : 16); }
+int mfma_stages(pa_kv_dtype kv, int cpad)
+{
+    if (cpad > 16) return kMfmaStagesWide;
+    return kv == PA_KV_BF16 ? kMfmaStagesBf16 : kMfmaStagesFp8;
+}
 
 // Compute units of the current device (cached per process; 256 when there is no device).
 int compute_units()
@@ -68,13 +80,16 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (!s) return PA_ERR_INVALID_ARG;
     if (kv != PA_KV_BF16 && kv != PA_KV_FP8_E4M3) return PA_ERR_INVALID_ARG;
     if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->head_dim <= 0 || s->block_size <= 0 ||
-        s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->num_partitions < 0)
+        s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->num_partitions < 0 ||
+        s->q_len < 0)
         return PA_ERR_INVALID_ARG;
     if (s->num_q_heads % s->num_kv_heads != 0) return PA_ERR_INVALID_ARG;
     if ((int64_t)s->max_context_len > (int64_t)s->max_blocks_per_seq * s->block_size) return PA_ERR_INVALID_ARG;
     if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return PA_ERR_UNSUPPORTED;
+    if (s->q_len > kMaxQueryLen) return PA_ERR_UNSUPPORTED;
     if (s->num_q_heads / s->num_kv_heads > (use_mfma(s, kv) ? kMaxGroupMfma : kMaxGroupValu)) return PA_ERR_UNSUPPORTED;
+    if (!use_mfma(s, kv) && query_len(s) > 1) return PA_ERR_UNSUPPORTED;  // multi-token calls: matrix-core kernel only
     if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
     // the global tile index and the launch grid are 32-bit
@@ -95,8 +110,8 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     } else {
         // one resident wave per (partition, KV head): as many partitions as the device holds at once,
         // but never more than there can be tiles
-        const int G = s->num_q_heads / s->num_kv_heads;
-        const int lds_fit = kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv), mfma_group_pad(G), (int)kv);
+        const int cpad = mfma_col_pad(columns(s));
+        const int lds_fit = kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv, cpad), cpad, (int)kv);
         const int waves_per_cu = use_mfma(s, kv)
                                      ? (lds_fit < kMfmaWavesPerCu ? lds_fit : kMfmaWavesPerCu)
                                      : kValuWavesPerCu;
@@ -111,7 +126,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         plan->lse_offset = 0;
         plan->ws_bytes = 0;
     } else {
-        const size_t rows = (size_t)2 * plan->P * s->num_q_heads;
+        const size_t rows = (size_t)2 * plan->P * s->num_q_heads * query_len(s);
         const size_t o_bytes = rows * s->head_dim * sizeof(float);
         plan->lse_offset = (o_bytes + 255) / 256 * 256;
         plan->ws_bytes = plan->lse_offset + (rows * sizeof(float) + 255) / 256 * 256;
@@ -151,15 +166,19 @@ void launch_mfma(const Params& p, bool trace, dim3 grid, hipStream_t st)
 }
 
 template <int NSTAGE, int KV>
-void launch_mfma_g(const Params& p, bool trace, dim3 grid, hipStream_t st)
+void launch_mfma_c(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
-    const int gpad = mfma_group_pad(p.G);
-    if (gpad == 4)
+    const int cpad = mfma_col_pad(p.Q * p.G);
+    if (cpad == 4)
         launch_mfma<NSTAGE, 4, KV>(p, trace, grid, st);
-    else if (gpad == 8)
+    else if (cpad == 8)
         launch_mfma<NSTAGE, 8, KV>(p, trace, grid, st);
-    else
+    else if (cpad == 16)
         launch_mfma<NSTAGE, 16, KV>(p, trace, grid, st);
+    else if (cpad == 32)
+        launch_mfma<kMfmaStagesWide, 32, KV>(p, trace, grid, st);
+    else
+        launch_mfma<kMfmaStagesWide, 64, KV>(p, trace, grid, st);
 }
 
 struct Events {
@@ -205,6 +224,8 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.Hkv = shape->num_kv_heads;
     p.G = shape->num_q_heads / shape->num_kv_heads;
     p.MB = shape->max_blocks_per_seq;
+    p.Q = query_len(shape);
+    p.QH = p.Q * p.Hq;
     p.P = plan.P;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -213,9 +234,9 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
     if (use_mfma(shape, kv)) {
         if (kv == PA_KV_BF16)
-            launch_mfma_g<kMfmaStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
+            launch_mfma_c<kMfmaStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
         else
-            launch_mfma_g<kMfmaStagesFp8, pa::KV_FP8>(p, trace, grid, hs);
+            launch_mfma_c<kMfmaStagesFp8, pa::KV_FP8>(p, trace, grid, hs);
     } else if (shape->head_dim == 128) {
         if (kv == PA_KV_BF16)
             launch_valu_g<128, pa::KV_BF16>(p, trace, grid, hs);
@@ -231,7 +252,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     if (ev && hipEventRecord(ev->between, hs) != hipSuccess) return PA_ERR_HIP;
 
     if (plan.P > 1) {
-        const dim3 mgrid(p.Hq, plan.P - 1);
+        const dim3 mgrid(p.QH, plan.P - 1);
         if (shape->head_dim == 128)
             hipLaunchKernelGGL((pa::merge_kernel<128>), mgrid, dim3(64), 0, hs, p);
         else

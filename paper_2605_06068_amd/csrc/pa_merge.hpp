@@ -2,7 +2,8 @@
 // (see pa_plan.hpp).  With lse_s = log2(sum_t 2^(score_t)) over segment s and o_s the segment's
 // normalised output, out = sum_s w_s o_s / sum_s w_s with w_s = 2^(lse_s - max_s lse_s).
 //
-// One wavefront per (partition boundary j in [1, P), query head).  Boundary j sits at global
+// One wavefront per (partition boundary j in [1, P), output row h of a sequence: query head, or
+// (query token, query head) pair of a multi-token call).  Boundary j sits at global
 // tile part_begin(j).  The wave whose boundary is the FIRST one strictly inside a sequence b
 // merges that sequence; all other waves exit.  The partials of b come from the partitions
 // k = j-1, j, j+1, ... whose ranges intersect b: slot 2k when b holds partition k's first tile,
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
         }
         const unsigned long long vmask = __ballot(valid);
         if (vmask == 0ull) break;
-        const float lse = valid ? p.part_lse[(int64_t)slot * p.Hq + h] : kNegBig;
+        const float lse = valid ? p.part_lse[(int64_t)slot * p.QH + h] : kNegBig;
         float cm = lse;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) cm = fmaxf(cm, __shfl_xor(cm, o, kWave));
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
             for (int u = 0; u < 8; ++u) {
                 const int idx = min(i0 + u, cnt - 1);
                 wv[u] = (i0 + u < cnt) ? s_w[idx] : 0.f;
-                const float* row = p.part_o + ((int64_t)s_slot[idx] * p.Hq + h) * D;
+                const float* row = p.part_o + ((int64_t)s_slot[idx] * p.QH + h) * D;
                 if (V == 2) {
                     xv[u] = *reinterpret_cast<const float2*>(row + lane * 2);
                 } else {
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
         __syncthreads();
     }
     const float inv = 1.f / wsum;
-    float* dst = p.out + ((int64_t)b * p.Hq + h) * D;
+    float* dst = p.out + ((int64_t)b * p.QH + h) * D;
     if (V == 2) {
         *reinterpret_cast<float2*>(dst + lane * 2) = make_float2(acc[0] * inv, acc[V - 1] * inv);
     } else {

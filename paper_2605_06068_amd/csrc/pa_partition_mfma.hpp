@@ -1,15 +1,21 @@
-// Partition kernel, matrix-core variant (head_dim 128, bf16 KV): for query-head groups wide
-// enough to form a matrix tile (4 <= G <= 16; the group is padded to the 16 columns of an MFMA
-// tile).  One wavefront per (partition, KV head) walks its balanced range of the batch's global
-// tile sequence (see pa_plan.hpp); no workgroup barriers, no atomics.
+// Partition kernel, matrix-core variant (head_dim 128, bf16 or fp8 KV).  The columns of its
+// matrix tiles are the (query token, query head) pairs that share one KV head: q_len * G of
+// them, padded to CPAD (one 16-column MFMA tile for plain decode with 4 <= G <= 16, up to four
+// tiles = 64 columns for multi-token verification).  One wavefront per (partition, KV head)
+// walks its balanced range of the batch's global tile sequence (see pa_plan.hpp); no workgroup
+// barriers, no atomics.
 //
 // Data path per 32-token tile (two KV blocks):
 //   HBM --global_load_lds (16 B/lane, 1 KB per instruction)--> LDS ring of NSTAGE tiles
-//   K:  ds_read_b128 in MFMA operand layout -> S^T[token, head] = K . Q^T   (mfma 16x16x32 bf16)
-//   online softmax on S^T in registers (lane = head column, 8 tokens per lane per tile)
-//   V:  ds_read_b64_tr_b16 (transposing LDS read) -> out^T[dim, head] += V^T . P^T
-// The ring keeps running across sequence boundaries inside the range; the query rows of each
-// new sequence travel through a small LDS ring of their own, ahead of its first tile.
+//   K:  ds_read_b128 in MFMA operand layout -> S^T[token, column] = K . Q^T  (mfma 16x16x32 bf16)
+//   online softmax on S^T in registers (lane = column, 8 tokens per lane per tile)
+//   V:  ds_read_b64_tr_b16 (transposing LDS read) -> out^T[dim, column] += V^T . P^T
+// Each K and V operand is read from LDS once and used for every column tile.  The ring keeps
+// running across sequence boundaries inside the range; the query rows of each new sequence
+// travel through a small LDS ring of their own, ahead of its first tile.
+//
+// Multi-token calls (q_len > 1) are causal inside the new tokens: query i of a sequence of L
+// tokens sits at position L - q_len + i and sees tokens 0 .. L - q_len + i.
 //
 // LDS tile layout: row t (one token, 256 B) at byte t*256; the 16-byte piece holding dims
 // [8c, 8c+8) sits at piece position c ^ (t & 15).  The XOR swizzle is applied on the *global*
@@ -18,17 +24,18 @@
 // different rows per 16 lanes) and the transposing reads bank-conflict free.
 //
 // The P^T operand needs no data movement: the score tile comes out of the MFMA with lane l
-// holding head l%16 and tokens 4*(l/16)+{0..3}; declaring MFMA k-index 8*(l/16)+e to mean token
-// 4*(l/16)+e of the first block (e<4) or of the second block (e>=4) makes the score registers,
-// once exponentiated and packed to bf16, the B operand of the PV product as they stand.  The
-// V^T operand is read with the same k-index convention.
+// holding column l%16 and tokens 4*(l/16)+{0..3}; declaring MFMA k-index 8*(l/16)+e to mean
+// token 4*(l/16)+e of the first block (e<4) or of the second block (e>=4) makes the score
+// registers, once exponentiated and packed to bf16, the B operand of the PV product as they
+// stand.  The V^T operand is read with the same k-index convention.
 //
 // Wait-count discipline: the LDS-DMA loads are issued and awaited by hand (s_waitcnt vmcnt(N)
 // with N = number of *newer DMA loads* allowed to stay in flight).  Loads complete in order,
 // so "at most N operations outstanding" implies every load older than the newest N has landed,
 // whatever else (stores, extra loads) is in flight: other traffic only makes a wait stricter.
 // Everything else the loop needs from memory comes through the scalar cache (block ids,
-// context lengths), which the vector-memory counter does not see.
+// context lengths), which the vector-memory counter does not see.  The inline asm writes M0
+// (the LDS-DMA destination register); nothing else in these kernels uses M0.
 #pragma once
 #include "pa_device.hpp"
 #include "pa_plan.hpp"
@@ -59,9 +66,9 @@ struct KvGeom {
 };
 
 // LDS bytes one workgroup (one wave) of the kernel uses: tile ring + query-row ring.
-constexpr int mfma_lds_bytes(int nstage, int gpad, int kv)
+constexpr int mfma_lds_bytes(int nstage, int cpad, int kv)
 {
-    return nstage * ((kv == KV_BF16 ? KvGeom<KV_BF16>::kStage : KvGeom<KV_FP8>::kStage) + gpad * kQRowBytes);
+    return nstage * ((kv == KV_BF16 ? KvGeom<KV_BF16>::kStage : KvGeom<KV_FP8>::kStage) + cpad * kQRowBytes);
 }
 
 // eight e4m3 bytes -> eight bf16 (exact), in byte order
@@ -118,18 +125,20 @@ __device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, 
     } while (c.nt == 0 && c.b < B);
 }
 
-template <int NSTAGE, int GPAD, int KV, bool TRACE>
+template <int NSTAGE, int CPAD, int KV, bool TRACE>
 __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 {
     constexpr int D = 128;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring depth");
-    static_assert(GPAD == 4 || GPAD == 8 || GPAD == 16, "padded group width");
+    static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16 || CPAD == 32 || CPAD == 64, "padded column count");
+    constexpr int NT = CPAD <= 16 ? 1 : CPAD / 16;  // 16-column MFMA tiles
     using Geo = KvGeom<KV>;
     constexpr int kSlabBytes = Geo::kSlab;
     constexpr int kStageBytes = Geo::kStage;
     constexpr int kDmaPerTile = Geo::kDmaPerTile;
-    constexpr int kQSlot = GPAD * kQRowBytes;
-    __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(NSTAGE, GPAD, KV)];
+    constexpr int kQSlot = CPAD * kQRowBytes;
+    static_assert(mfma_lds_bytes(NSTAGE, CPAD, KV) <= 65536, "static LDS limit");
+    __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(NSTAGE, CPAD, KV)];
 
     const int lane = threadIdx.x;
     // partition index fastest: workgroups go to the chip's eight dies round-robin, so (with P a
@@ -139,7 +148,9 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     const int k = blockIdx.x % p.P;
     const int G = p.G;
     const int B = p.B;
-    const int n = lane & 15;   // head column / row-in-block, depending on the operand
+    const int Q = p.Q;
+    const int ncols = Q * G;   // real columns: (query token i, head h of the group) -> column i*G + h
+    const int n = lane & 15;   // column inside a column tile / row-in-block, depending on the operand
     const int q4 = lane >> 4;  // 0..3
 
     // ---- this wave's range of the global tile sequence
@@ -148,8 +159,10 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         for (int b0 = 0; b0 < B; b0 += kWave) {
             const int b = b0 + lane;
             if (b < B && p.context_lens[b] <= 0) {
-                float* row = p.out + ((int64_t)b * p.Hq + g * G) * D;
-                for (int i = 0; i < G * D; ++i) row[i] = 0.f;
+                for (int i = 0; i < Q; ++i) {
+                    float* row = p.out + ((int64_t)b * p.QH + (int64_t)i * p.Hq + g * G) * D;
+                    for (int e = 0; e < G * D; ++e) row[e] = 0.f;
+                }
             }
         }
     }
@@ -171,23 +184,40 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         const int t = r * Geo::kRowsPerDma + lane / Geo::kPieces;
         dma_off[r] = t * Geo::kRow + (((lane % Geo::kPieces) ^ (t & (Geo::kPieces - 1))) << 4);
     }
-    // LDS-DMA of the query rows (always bf16: 4 rows of 256 B per instruction)
-    uint32_t qdma_off[GPAD / 4];
+    // LDS-DMA of the query rows (always bf16: 4 rows of 256 B per instruction).  LDS row c holds
+    // column c, i.e. query token c / G, head c % G of this group; padding rows re-read column 0.
+    uint32_t qdma_off[CPAD / 4];
 #pragma unroll
-    for (int r = 0; r < GPAD / 4; ++r) {
-        const int t = 4 * r + q4;
-        qdma_off[r] = t * kQRowBytes + ((n ^ t) << 4);
+    for (int r = 0; r < CPAD / 4; ++r) {
+        const int c = 4 * r + q4;
+        const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * kQRowBytes : 0;
+        qdma_off[r] = src + ((n ^ (c & 15)) << 4);
     }
     uint32_t kread[4];  // LDS byte offset inside a slab of this lane's K operand piece for k-step kk
-    uint32_t qread[4];  // same for the query slab (padding columns read row 0 and are zeroed)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         if (KV == KV_BF16)  // 16 bytes: dims 32kk + 8q4 + [0,8) of token n
             kread[kk] = n * Geo::kRow + (((4 * kk + q4) ^ n) << 4);
         else                // 8 bytes: the same dims, half of 16-byte piece 2kk + q4/2
             kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & 7)) << 4) + ((q4 & 1) << 3);
-        qread[kk] = n < G ? (uint32_t)(n * kQRowBytes + (((4 * kk + q4) ^ n) << 4)) : (uint32_t)((4 * kk + q4) << 4);
     }
+    // this lane's columns: one per column tile
+    bool col_ok[NT];       // a real column
+    int col_back[NT];      // tokens at the end of the context that the column's query must not see
+    int col_row[NT];       // output row of the column inside its sequence: i * Hq + g*G + h
+    uint32_t qread[NT];    // LDS byte offset of the column's query row (piece offset added per k-step)
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        const int c = 16 * ct + n;
+        col_ok[ct] = c < ncols;
+        const int i = col_ok[ct] ? c / G : 0, h = col_ok[ct] ? c % G : 0;
+        col_back[ct] = col_ok[ct] ? Q - 1 - i : (1 << 30);
+        col_row[ct] = i * p.Hq + g * G + h;
+        qread[ct] = (col_ok[ct] ? c : 0) * kQRowBytes;
+    }
+    uint32_t qpiece[4];  // swizzled position of dims 32kk + 8q4 + [0,8) in a query row of this lane's columns
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) qpiece[kk] = ((4 * kk + q4) ^ n) << 4;
     // LDS byte offset (inside the V half of a stage) of this lane's transposing-read source for dim tile dt.
     // bf16: one read per block, rows = tokens 4q4 + n/4, 8 bytes = 4 dims.  fp8: one read for both blocks,
     // rows n/2 = 0..3 -> tokens 4q4.. of block 0, rows 4..7 -> the same tokens of block 1, 8 bytes = 8 dims.
@@ -215,12 +245,9 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     int q_issue = 0;  // query slot the issue side fills next
     auto issue = [&](int i, int stage) {
         if (i == 0 || ic.lt == 0) {  // a new segment starts: send its query rows ahead of its first tile
-            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.Hq + g * G) * kQRowBytes;
+            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.QH + g * G) * kQRowBytes;
 #pragma unroll
-            for (int r = 0; r < GPAD / 4; ++r) {
-                const uint32_t off = (4 * r + q4 < G) ? qdma_off[r] : (qdma_off[r] & (kQRowBytes - 1));
-                dma16(ldsq + q_issue * kQSlot + r * 1024, off, qb);
-            }
+            for (int r = 0; r < CPAD / 4; ++r) dma16(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
             q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
         }
         const int nblk = (ic.L + kBlockSize - 1) / kBlockSize;
@@ -264,12 +291,12 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         advance(ic, p.context_lens, B);
     };
 
-    // ---- online softmax state: lane = head n, tokens 4*q4+{0..3} of each block
+    // ---- online softmax state: lane = column n of each column tile, tokens 4*q4+{0..3} of each block
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;  // K scale folded in
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    float m = kNegBig, lsum = 0.f;
-    f32x4 acc[8];
-    bf16x8 qreg[4];
+    float m[NT], lsum[NT];
+    f32x4 acc[NT][8];
+    bf16x8 qreg[NT][4];
     int q_comp = 0;       // query slot of the segment being computed
     int seg_first_lt = 0;
 
@@ -294,23 +321,31 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 
         wait_tile<kDmaPerTile / 2, NSTAGE, kDmaPerTile>(later);  // K of this tile (and its segment's query rows) landed
         if (tile == 0 || cc.lt == 0) {  // segment start
-            m = kNegBig;
-            lsum = 0.f;
             seg_first_lt = cc.lt;
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
             const char* qsl = qslots + q_comp * kQSlot;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                uint4 w = *reinterpret_cast<const uint4*>(qsl + qread[kk]);
-                if (n >= G) w = make_uint4(0, 0, 0, 0);
-                qreg[kk] = as_bf16x8(w);
+            for (int ct = 0; ct < NT; ++ct) {
+                m[ct] = kNegBig;
+                lsum[ct] = 0.f;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) acc[ct][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    uint4 w = *reinterpret_cast<const uint4*>(qsl + qread[ct] + qpiece[kk]);
+                    if (!col_ok[ct]) w = make_uint4(0, 0, 0, 0);
+                    qreg[ct][kk] = as_bf16x8(w);
+                }
             }
             q_comp = (q_comp + 1 == NSTAGE) ? 0 : q_comp + 1;
         }
 
-        // ---- scores: S^T[token, head] for the two blocks of the tile
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        // ---- scores: S^T[token, column] for the two blocks of the tile
+        f32x4 s0[NT], s1[NT];
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            s0[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+            s1[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             bf16x8 a0, a1;
@@ -323,45 +358,55 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 a0 = fp8x8_to_bf16x8(w0.x, w0.y);
                 a1 = fp8x8_to_bf16x8(w1.x, w1.y);
             }
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[kk], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[kk], s1, 0, 0, 0);
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                s0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[ct][kk], s0[ct], 0, 0, 0);
+                s1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[ct][kk], s1[ct], 0, 0, 0);
+            }
         }
 
-        // ---- online softmax (log2 domain)
+        // ---- online softmax (log2 domain); a column sees tokens t < L - col_back
         const int t0 = cc.lt * kTileTokens + 4 * q4;
-        float x[8];
+        bf16x8 pb[NT], pb_lo[NT];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            x[r] = (t0 + r < cc.L) ? s0[r] * qs : kNegBig;
-            x[4 + r] = (t0 + kBlockSize + r < cc.L) ? s1[r] * qs : kNegBig;
-        }
-        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m, mx);
-        const float alpha = fast_exp2(m - m_new);
-        float ps = 0.f;
+        for (int ct = 0; ct < NT; ++ct) {
+            const int lim = cc.L - col_back[ct];
+            float x[8];
+            bool ok[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            x[r] = fast_exp2(x[r] - m_new);
-            ps += x[r];
-        }
-        lsum = lsum * alpha + ps;
-        m = m_new;
-        if (__any(alpha != 1.f)) {
+            for (int r = 0; r < 4; ++r) {
+                ok[r] = t0 + r < lim;
+                ok[4 + r] = t0 + kBlockSize + r < lim;
+                x[r] = ok[r] ? s0[ct][r] * qs : kNegBig;
+                x[4 + r] = ok[4 + r] ? s1[ct][r] * qs : kNegBig;
+            }
+            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float m_new = fmaxf(m[ct], mx);
+            const float alpha = fast_exp2(m[ct] - m_new);
+            float ps = 0.f;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;
-        }
-        // P^T operand as a bf16 pair (high part + rounding remainder): 16 significant bits, so
-        // the weights lose nothing that matters against the fp32 accumulation
-        bf16x8 pb, pb_lo;
+            for (int r = 0; r < 8; ++r) {
+                x[r] = ok[r] ? fast_exp2(x[r] - m_new) : 0.f;  // a column may see nothing of a tile
+                ps += x[r];
+            }
+            lsum[ct] = lsum[ct] * alpha + ps;
+            m[ct] = m_new;
+            if (__any(alpha != 1.f)) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            pb[r] = (__bf16)x[r];
-            pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
+                for (int dt = 0; dt < 8; ++dt) acc[ct][dt] *= alpha;
+            }
+            // P^T operand as a bf16 pair (high part + rounding remainder): 16 significant bits, so
+            // the weights lose nothing that matters against the fp32 accumulation
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                pb[ct][r] = (__bf16)x[r];
+                pb_lo[ct][r] = (__bf16)(x[r] - (float)pb[ct][r]);
+            }
         }
 
-        // ---- out^T[dim, head] += V^T . P^T
+        // ---- out^T[dim, column] += V^T . P^T
         wait_tile<0, NSTAGE, kDmaPerTile>(later);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
@@ -374,29 +419,38 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 const i32x2 v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(vbuf + vread[dt]));
                 va = fp8x8_to_bf16x8((uint32_t)v[0], (uint32_t)v[1]);
             }
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, acc[dt], 0, 0, 0);
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo, acc[dt], 0, 0, 0);
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                acc[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[ct], acc[ct][dt], 0, 0, 0);
+                acc[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo[ct], acc[ct][dt], 0, 0, 0);
+            }
         }
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
-            float l = lsum + __shfl_xor(lsum, 16, kWave);
-            l += __shfl_xor(l, 32, kWave);
-            if (n < G) {
-                const float inv = vs / l;
-                const int hq = g * G + n;
-                float* dst;
-                if (seg_first_lt == 0 && cc.lt == cc.nt - 1) {  // the whole sequence: final result
-                    dst = p.out + ((int64_t)cc.b * p.Hq + hq) * D;
-                } else {
-                    const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.Hq + hq;
-                    dst = p.part_o + slot * D;
-                    if (q4 == 0) p.part_lse[slot] = m + fast_log2(l);
-                }
+            const bool whole = seg_first_lt == 0 && cc.lt == cc.nt - 1;  // the entire sequence: final result
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt)
-                    *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
-                        make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
+            for (int ct = 0; ct < NT; ++ct) {
+                float l = lsum[ct] + __shfl_xor(lsum[ct], 16, kWave);
+                l += __shfl_xor(l, 32, kWave);
+                if (col_ok[ct]) {
+                    // a column that saw no token (its query sits before this segment) leaves a zero
+                    // row with an "empty" log-sum-exp
+                    const float inv = l > 0.f ? vs / l : 0.f;
+                    float* dst;
+                    if (whole) {
+                        dst = p.out + ((int64_t)cc.b * p.QH + col_row[ct]) * D;
+                    } else {
+                        const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row[ct];
+                        dst = p.part_o + slot * D;
+                        if (q4 == 0) p.part_lse[slot] = l > 0.f ? m[ct] + fast_log2(l) : kNegBig;
+                    }
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt)
+                        *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
+                            make_float4(acc[ct][dt][0] * inv, acc[ct][dt][1] * inv, acc[ct][dt][2] * inv,
+                                        acc[ct][dt][3] * inv);
+                }
             }
         }
         advance(cc, p.context_lens, B);

@@ -15,7 +15,8 @@ prefixes).  The paper's prompt pool is not public, so the values are N(0,1)
 draws and the lengths are drawn from the ranges listed per config below.
 
 Layouts (row-major, contiguous):
-  q             [B, Hq, D]        bf16 bit patterns (uint16)
+  q             [B, Hq, D]        bf16 bit patterns (uint16); [B, Q, Hq, D] for a multi-token
+                                  verification window of Q query tokens (q_len > 1)
   k_cache       [NB, Hkv, BS, D]  bf16 bit patterns (uint16) or e4m3 bytes (uint8)
   v_cache       [NB, Hkv, BS, D]  same encoding as k_cache
   block_tables  [B, MB]           int32, unused entries = -1
@@ -61,6 +62,7 @@ class DecodeBatch:
     v_scale: Optional[np.ndarray] = None
     seed: int = 0
     meta: dict = field(default_factory=dict)
+    q_len: int = 1  # query tokens per sequence; > 1: q is [B, Q, Hq, D], the last Q tokens are the window
 
     @property
     def group(self) -> int:
@@ -200,9 +202,11 @@ def _valid_slot_mask(tables: np.ndarray, context_lens: np.ndarray, block_size: i
 def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: int, num_kv_heads: int,
                head_dim: int, block_size: int = 16, kv_dtype: int = KV_BF16, sigma: float = 1.0,
                num_blocks: Optional[int] = None, max_blocks_per_seq: Optional[int] = None,
-               table_kind: str = "permuted", poison: bool = True) -> DecodeBatch:
+               table_kind: str = "permuted", poison: bool = True, q_len: int = 1) -> DecodeBatch:
     """Draw one decode batch.  ``poison`` fills every slot no valid token owns with NaN patterns
-    (parity runs); with ``poison=False`` those slots are zero (timing runs)."""
+    (parity runs); with ``poison=False`` those slots are zero (timing runs).  ``q_len`` > 1 draws a
+    window of that many query tokens per sequence (q becomes [B, Q, Hq, D]); the cache contents do not
+    depend on it."""
     rng = np.random.default_rng(seed)
     lens = np.asarray(context_lens, dtype=np.int32)
     B = len(lens)
@@ -224,9 +228,9 @@ def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: i
         raise ValueError(table_kind)
 
     ss_q, ss_k, ss_v = np.random.SeedSequence(seed).spawn(3)
-    q = np.empty(B * num_q_heads * head_dim, dtype=np.uint16)
+    q = np.empty(B * q_len * num_q_heads * head_dim, dtype=np.uint16)
     _normal_chunks(ss_q, q.size, sigma, f32_to_bf16_bits, q)
-    q = q.reshape(B, num_q_heads, head_dim)
+    q = q.reshape((B, num_q_heads, head_dim) if q_len == 1 else (B, q_len, num_q_heads, head_dim))
 
     n_kv = NB * num_kv_heads * block_size * head_dim
     inner = block_size * head_dim
@@ -267,7 +271,7 @@ def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: i
     return DecodeBatch(name=name, batch=B, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, head_dim=head_dim,
                        block_size=block_size, max_blocks_per_seq=MB, num_blocks=NB, kv_dtype=kv_dtype, scale=scale,
                        q=q, k_cache=k_cache, v_cache=v_cache, block_tables=tables, context_lens=lens,
-                       k_scale=k_scale, v_scale=v_scale, seed=seed,
+                       k_scale=k_scale, v_scale=v_scale, seed=seed, q_len=q_len,
                        meta={"sigma": sigma, "table_kind": table_kind, "poison": poison})
 
 
@@ -306,22 +310,23 @@ def config_context_lens(config: int, seed: int, length_scale: float = 1.0) -> np
 
 
 def make_config(config: int, seed: Optional[int] = None, poison: bool = True, length_scale: float = 1.0,
-                batch_limit: Optional[int] = None) -> DecodeBatch:
+                batch_limit: Optional[int] = None, q_len: int = 1) -> DecodeBatch:
     """Build named config 1..5.  Default seed is 1000+config.  ``batch_limit`` keeps only the first
-    sequences (same lengths they would have in the full batch)."""
+    sequences (same lengths they would have in the full batch).  ``q_len`` > 1 turns the batch into a
+    verification step over windows of that many tokens (same cache, more query rows)."""
     seed = 1000 + config if seed is None else seed
     lens = config_context_lens(config, seed, length_scale)
     if batch_limit is not None:
         lens = lens[:batch_limit]
     name = CONFIG_NAMES[config]
     if config == 1:
-        return make_batch(name, seed, lens, 4, 2, 64, 16, KV_BF16, 1.0, num_blocks=16, poison=poison)
+        return make_batch(name, seed, lens, 4, 2, 64, 16, KV_BF16, 1.0, num_blocks=16, poison=poison, q_len=q_len)
     if config == 2:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison)
+        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len)
     if config == 3:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison)
+        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len)
     if config == 4:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, table_kind="interleaved", poison=poison)
+        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, table_kind="interleaved", poison=poison, q_len=q_len)
     if config == 5:
-        return make_batch(name, seed, lens, 64, 8, 128, 16, KV_FP8_E4M3, 1.0, poison=poison)
+        return make_batch(name, seed, lens, 64, 8, 128, 16, KV_FP8_E4M3, 1.0, poison=poison, q_len=q_len)
     raise ValueError(config)

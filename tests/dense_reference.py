@@ -70,3 +70,36 @@ def torch_sdpa(batch):
         o = F.scaled_dot_product_attention(Q, K, V, scale=float(batch.scale))
         out[b] = o.squeeze(1).numpy()
     return out
+
+
+def dense_window_attention(batch):
+    """Multi-token window, out [B,Q,Hq,D] float64: torch's scaled_dot_product_attention in float64 with
+    an explicit boolean mask.  Query token i of the window may look at logical token t iff
+    t <= L - Q + i (the window is the last Q tokens of the context; each sees itself and the past).
+    Rows with nothing visible are zero."""
+    import torch
+    import torch.nn.functional as F
+
+    B, Q, Hq, D = batch.q.shape
+    G = Hq // batch.num_kv_heads
+    out = np.zeros((B, Q, Hq, D))
+    q = widen_bf16(batch.q)
+    for b in range(B):
+        L = int(batch.context_lens[b])
+        if L <= 0:
+            continue
+        Ks, Vs = zip(*(gather_dense(batch, b, g) for g in range(batch.num_kv_heads)))
+        K = torch.from_numpy(np.stack(Ks)).repeat_interleave(G, dim=0)  # [Hq, L, D]
+        V = torch.from_numpy(np.stack(Vs)).repeat_interleave(G, dim=0)
+        Qm = torch.from_numpy(q[b]).permute(1, 0, 2)  # [Hq, Q, D]
+        key_pos = torch.arange(L)[None, :]
+        last_visible = (L - Q + torch.arange(Q))[:, None]
+        mask = key_pos <= last_visible  # [Q, L]
+        seen = mask.any(dim=1)
+        safe = mask.clone()
+        safe[~seen, 0] = True  # keep the library away from all-masked rows; they are zeroed below
+        o = F.scaled_dot_product_attention(Qm, K, V, attn_mask=safe[None], scale=float(batch.scale))
+        o = o.permute(1, 0, 2).numpy().copy()
+        o[~seen.numpy()] = 0.0
+        out[b] = o
+    return out

@@ -8,7 +8,7 @@ import sys
 import numpy as np
 
 from paper_2605_06068_amd import workloads as W
-from tests.dense_reference import dense_attention, e4m3_to_f64
+from tests.dense_reference import dense_attention, dense_window_attention, e4m3_to_f64
 
 
 def core_pins(oracle):
@@ -23,8 +23,11 @@ def core_pins(oracle):
         want, _ = dense_attention(b)
         assert np.isfinite(r["out_f64"]).all()
         assert np.max(np.abs(r["out_f64"] - want)) <= 1e-12
-
-
+        # multi-token window, causal inside the window: library attention with an explicit mask
+        w = W.make_batch("w", 6, [2, 37, 100], 8, 2, 64, 16, kv, num_blocks=20, max_blocks_per_seq=9, q_len=3)
+        r = oracle.decode_batch(w, want_f64=True)
+        assert np.isfinite(r["out_f64"]).all()
+        assert np.max(np.abs(r["out_f64"] - dense_window_attention(w))) <= 1e-12
 
 
 def main(so_path):
@@ -32,7 +35,7 @@ def main(so_path):
 
     good = pa_oracle.lib()
     other = ctypes.CDLL(so_path)
-    for fn in ("pa_oracle_decode", "pa_oracle_e4m3_table"):
+    for fn in ("pa_oracle_decode", "pa_oracle_verify", "pa_oracle_e4m3_table"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     pa_oracle._lib = other

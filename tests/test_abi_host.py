@@ -76,6 +76,22 @@ def test_workspace_size_covers_partials():
     assert need <= got <= need + 512
 
 
+def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
+    one = shape(num_partitions=16)
+    for Q in (2, 4, 16):
+        win = shape(num_partitions=16, q_len=Q)
+        assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == "mfma"
+        need = 2 * 16 * Q * 32 * (128 + 1) * 4
+        assert need <= pa.pa_decode_workspace_size(win, pa.PA_KV_BF16) <= need + 512
+        lens = [100, 4096, 1, 33]
+        assert pa.pa_split_plan(win, pa.PA_KV_BF16, lens)[0] == pa.pa_split_plan(one, pa.PA_KV_BF16, lens)[0]
+        assert np.array_equal(pa.pa_split_plan(win, pa.PA_KV_BF16, lens)[1], pa.pa_split_plan(one, pa.PA_KV_BF16, lens)[1])
+    # q_len 0 and 1 are the same call
+    assert pa.pa_decode_workspace_size(shape(q_len=1), pa.PA_KV_BF16) == pa.pa_decode_workspace_size(shape(), pa.PA_KV_BF16)
+    # windows over single-head groups reach the matrix-core path once they have 4 rows
+    assert pa.pa_kernel_variant(shape(num_q_heads=8, q_len=4), pa.PA_KV_BF16) == "mfma"
+
+
 def test_split_plan_rejects_lengths_above_the_bound():
     s = shape(max_context_len=100)
     with pytest.raises(pa.PaError):
@@ -91,6 +107,11 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(head_dim=96), pa.PA_ERR_UNSUPPORTED),
     (dict(block_size=32), pa.PA_ERR_UNSUPPORTED),
     (dict(num_q_heads=8 * 32), pa.PA_ERR_UNSUPPORTED),
+    (dict(q_len=-1), pa.PA_ERR_INVALID_ARG),
+    (dict(q_len=17), pa.PA_ERR_UNSUPPORTED),
+    (dict(q_len=16, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),            # 16 tokens x 8 heads > 64 rows per KV head
+    (dict(q_len=2, num_q_heads=8), pa.PA_ERR_UNSUPPORTED),              # 2 rows per KV head: below the matrix-core path
+    (dict(q_len=4, head_dim=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # windows need head_dim 128
 ])
 def test_bad_shapes_are_rejected(bad, code):
     s = shape(**bad)

@@ -24,7 +24,16 @@ MUTATIONS = {
     "e4m3 bias 8": ("(int)expo - 7);", "(int)expo - 8);"),
     "e4m3 subnormal exponent": ("ldexp((double)mant / 8.0, -6);", "ldexp((double)mant / 8.0, -7);"),
     "e4m3 has infinities": ("if (expo == 0xFu && mant == 0x7u)", "if (expo == 0xFu)"),
-    "q head stride": ("((int64_t)b * p->Hq + h) * p->D;", "((int64_t)b * p->Hq + h) * (p->D / 2);"),
+    "q head stride": ("(((int64_t)b * Q + i) * Hq + h) * D;", "(((int64_t)b * Q + i) * Hq + h) * (D / 2);"),
+    "window: token and head axes of q swapped": ("(((int64_t)b * Q + i) * Hq + h) * D;",
+                                                 "(((int64_t)b * Hq + h) * Q + i) * D;"),
+    "window: query sees one token too few": ("int visible = context_lens[b] - Q + 1 + i;",
+                                             "int visible = context_lens[b] - Q + i;"),
+    "window: query sees one token too many": ("int visible = context_lens[b] - Q + 1 + i;",
+                                              "int visible = context_lens[b] - Q + 2 + i;"),
+    "window: no causal mask": ("int visible = context_lens[b] - Q + 1 + i;", "int visible = context_lens[b];"),
+    "window: order of the window reversed": ("int visible = context_lens[b] - Q + 1 + i;",
+                                             "int visible = context_lens[b] - i;"),
 }
 
 

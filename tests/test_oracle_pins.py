@@ -14,7 +14,7 @@ import numpy as np
 import pytest
 
 from paper_2605_06068_amd import workloads as W
-from tests.dense_reference import dense_attention, e4m3_to_f64, torch_sdpa, widen_bf16
+from tests.dense_reference import dense_attention, dense_window_attention, e4m3_to_f64, torch_sdpa, widen_bf16
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -229,6 +229,84 @@ def test_two_segment_log_sum_exp_merge_identity(oracle):
         wa, wb = np.exp(la - mx), np.exp(lb - mx)
         merged = (wa * left["out_f64"][0] + wb * right["out_f64"][0]) / (wa + wb)
         assert np.max(np.abs(merged - whole)) <= 1e-12
+
+
+# ---------------------------------------------------------------- multi-token window (verification)
+def test_window_closed_forms_two_tokens(oracle):
+    """L = Q = 2: query 0 sees only token 0 and returns its V row exactly; query 1 sees both tokens
+    with sigmoid weights of the score difference."""
+    D = 64
+    b = tiny(50, [2], Hq=2, Hkv=1, D=D, table_kind="identity", q_len=2)
+    q = widen_bf16(b.q)[0]                       # [Q, Hq, D]
+    K = widen_bf16(b.k_cache[0, 0, :2])          # [2, D]
+    V = widen_bf16(b.v_cache[0, 0, :2])
+    r = oracle.decode_batch(b, want_f64=True)["out_f64"][0]
+    for h in range(2):
+        assert np.array_equal(r[0, h], V[0])
+        s = (K @ q[1, h]) * np.float64(b.scale)
+        w1 = 1.0 / (1.0 + math.exp(s[0] - s[1]))
+        assert np.max(np.abs(r[1, h] - ((1 - w1) * V[0] + w1 * V[1]))) <= 1e-14
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_window_row_equals_plain_decode_of_the_truncated_context(oracle, kv):
+    """Query token i of a window is ordinary decode attention over the first L - Q + 1 + i tokens."""
+    Q = 5
+    b = tiny(51, [3, 5, 40, 100], Hq=4, Hkv=2, D=64, kv=kv, q_len=Q)
+    win = oracle.decode_batch(b, want_f64=True, want_lse=True)
+    for i in range(Q):
+        lens = np.maximum(b.context_lens - (Q - 1 - i), 0).astype(np.int32)
+        one = oracle.decode(np.ascontiguousarray(b.q[:, i]), b.k_cache, b.v_cache, b.block_tables, lens, b.scale,
+                            kv, b.k_scale, b.v_scale, want_f64=True, want_lse=True)
+        assert np.array_equal(win["out_f64"][:, i], one["out_f64"])
+        assert np.array_equal(win["lse"][:, i], one["lse"])
+    # sequence 0 has 3 tokens for a window of 5: the first two query tokens see nothing
+    assert np.all(win["out"][0, :2] == 0) and np.any(win["out"][0, 2] != 0)
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=52, lens=[1, 16, 17, 33, 255], Hq=8, Hkv=2, D=128, q_len=4),
+    dict(seed=53, lens=[64, 7], Hq=6, Hkv=6, D=64, q_len=16),
+    dict(seed=54, lens=[77, 130], Hq=16, Hkv=2, D=128, kv=W.KV_FP8_E4M3, q_len=3),
+])
+def test_window_matches_masked_library_attention(oracle, case):
+    case = dict(case)
+    b = tiny(case.pop("seed"), case.pop("lens"), **case)
+    r = oracle.decode_batch(b, want_f64=True)
+    assert r["out"].shape == b.q.shape
+    assert np.max(np.abs(r["out_f64"] - dense_window_attention(b))) <= 1e-10
+    assert np.array_equal(r["out"], r["out_f64"].astype(np.float32))
+
+
+def test_window_is_causal_later_tokens_never_reach_earlier_queries(oracle):
+    Q = 4
+    b = tiny(55, [50], Hq=4, Hkv=2, D=64, table_kind="identity", q_len=Q)
+    base = oracle.decode_batch(b, want_f64=True, want_probs=True)
+    # weights of query i vanish beyond token L - Q + i and sum to one before it
+    L = 50
+    for i in range(Q):
+        p = base["probs"][0, i]
+        assert np.all(p[:, L - Q + i + 1:] == 0) and np.all(p[:, L - Q + i] > 0)
+        assert np.max(np.abs(p.sum(-1) - 1)) <= 1e-14
+    # overwrite K and V of the last window token (position 49 = block 3, slot 1) with other values
+    b.k_cache[3, :, 1] = bf16(np.float32(3.0))
+    b.v_cache[3, :, 1] = bf16(np.float32(-7.0))
+    again = oracle.decode_batch(b, want_f64=True)
+    assert np.array_equal(again["out_f64"][0, :Q - 1], base["out_f64"][0, :Q - 1])
+    assert not np.array_equal(again["out_f64"][0, Q - 1], base["out_f64"][0, Q - 1])
+
+
+def test_window_row_selection_and_single_token_window(oracle):
+    b = tiny(56, [37, 100], q_len=3)
+    full = oracle.decode_batch(b)["out"]
+    rows = [(1, 2, 3), (0, 0, 0), (1, 0, 1)]
+    sel = oracle.decode_batch(b, rows=rows)["out"]
+    for n, (s, i, h) in enumerate(rows):
+        assert np.array_equal(sel[n], full[s, i, h])
+    # a window of one token is plain decode
+    c = W.make_config(1)
+    one = oracle.verify(c.q[:, None], c.k_cache, c.v_cache, c.block_tables, c.context_lens, c.scale)["out"]
+    assert np.array_equal(one[:, 0], oracle.decode_batch(c)["out"])
 
 
 # ---------------------------------------------------------------- fp8 table
