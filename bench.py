@@ -34,6 +34,9 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--pools", type=int, default=0, help="KV pool copies to rotate over (0 = enough for >= 2 GB)")
     ap.add_argument("--partitions", type=int, default=0, help="force the number of partitions (0 = library heuristic)")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per sequence (default 1: plain decode, the metric's workload; 2..16 times "
+                         "the multi-token verification call over the same KV cache instead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -82,7 +85,7 @@ def main():
     torch.cuda.set_device(0)
 
     t0 = time.time()
-    batch = W.make_config(args.workload, seed=args.seed, poison=False)
+    batch = W.make_config(args.workload, seed=args.seed, poison=False, q_len=args.q_len)
     gen_s = time.time() - t0
     kv_bytes = batch.kv_bytes
     pool_bytes = batch.k_cache.nbytes + batch.v_cache.nbytes
@@ -157,7 +160,8 @@ def main():
         "dtype": "bf16" if batch.kv_dtype == W.KV_BF16 else "fp8_e4m3",
         "data": "synthetic",
         "config": {
-            "workload": batch.name, "batch": batch.batch, "num_q_heads": batch.num_q_heads,
+            "workload": batch.name if args.q_len == 1 else f"{batch.name}_qlen{args.q_len}", "q_len": args.q_len,
+            "batch": batch.batch, "num_q_heads": batch.num_q_heads,
             "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "block_size": batch.block_size,
             "total_context_tokens": batch.total_tokens, "kv_bytes": kv_bytes, "seed": batch.seed,
             "kv_pool_copies": n_pools, "num_partitions": pa.pa_num_partitions(dev.shape, dev.kv_dtype),
@@ -189,7 +193,7 @@ def main():
         result["cpu_baseline"] = {
             "value": round(kv_bytes / per / 1e9, 3), "unit": "GB/s", "cores": pa_oracle.num_threads(),
             "kind": "oracle", "tokens_per_s": round(batch.batch / per, 1), "s_per_step": round(per, 4),
-            "sample": f"the full {batch.name} batch (all {batch.batch * batch.num_q_heads} output rows), "
+            "sample": f"the full {batch.name} batch (all {batch.batch * args.q_len * batch.num_q_heads} output rows), "
                       f"{n} repetitions, float64, OpenMP over rows",
             "gpu_vs_oracle_max_abs_err": err,
         }

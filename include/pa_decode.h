@@ -44,7 +44,7 @@
  *     q   [batch, Q, num_q_heads, head_dim]      out [batch, Q, num_q_heads, head_dim]
  * and query token i attends causally, to t in [0, context_lens[b] - Q + i]; a query token with no
  * visible token yields a zero row.  The KV cache is read once for all Q tokens.  Supported for
- * head_dim 128 with 4 <= Q * G <= 64 (matrix-core kernel only).
+ * head_dim 128 with 4 <= Q * G <= 128 (matrix-core kernels only).
  *
  * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
  * 1 <= G <= 16 (G <= 8 for head_dim 64); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
@@ -184,7 +184,7 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
                             float *merge_ms);
 
 /* Name of the partition kernel variant pa_decode picks for this shape ("mfma": matrix cores, for
- * head_dim 128 and 4..64 query rows (Q * G) per KV head; "valu" otherwise); NULL for an invalid
+ * head_dim 128 and 4..128 query rows (Q * G) per KV head; "valu" otherwise); NULL for an invalid
  * or unsupported shape.  Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 

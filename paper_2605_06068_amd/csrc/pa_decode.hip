@@ -11,6 +11,7 @@
 #include "pa_kv_append.hpp"
 #include "pa_merge.hpp"
 #include "pa_partition_mfma.hpp"
+#include "pa_partition_mfma_wide.hpp"
 #include "pa_partition_valu.hpp"
 #include "pa_plan.hpp"
 
@@ -21,11 +22,14 @@ using pa::Params;
 constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds in registers
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
 constexpr int kMinColsMfma = 4;    // fewer (query token, head) columns than this: vector-ALU kernel
-constexpr int kMaxColsMfma = 64;   // four 16-column MFMA tiles
+constexpr int kMaxColsOneWave = 16; // up to here one wave per (partition, KV head); above, a workgroup of waves
+constexpr int kMaxColsMfma = 128;  // eight 16-column MFMA tiles, one per wave of the widest workgroup
 constexpr int kMaxQueryLen = 16;
 constexpr int kMfmaStagesBf16 = 2;  // depth of the LDS tile ring of the matrix-core kernel, bf16 KV
 constexpr int kMfmaStagesFp8 = 4;   // same for fp8 KV (tiles are half the size)
-constexpr int kMfmaStagesWide = 2;  // more than one column tile: the query ring takes the LDS
+constexpr int kWideStagesBf16 = 4;  // ring depth of the multi-wave kernel (shared by the workgroup's waves)
+constexpr int kWideStagesFp8 = 4;
+constexpr int kWideWavesPerCu = 8;  // resident waves per compute unit the multi-wave plan aims at
 constexpr int kMfmaWavesPerCu = 4;  // one wave per SIMD measured best; more, thinner waves were slower
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kValuWavesPerCu = 8;
@@ -44,19 +48,34 @@ int query_len(const pa_shape* s) { return s->q_len > 0 ? s->q_len : 1; }
 // columns of the score matrix per KV head: (query token, query head of the group) pairs
 int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
 
-// The matrix-core kernel covers head_dim 128, groups of up to 16 query heads and 4..64 columns.
+// The matrix-core kernels cover head_dim 128, groups of up to 16 query heads and 4..128 columns.
 bool use_mfma(const pa_shape* s, pa_kv_dtype kv)
 {
     const int G = s->num_q_heads / s->num_kv_heads;
     return s->head_dim == 128 && G <= kMaxGroupMfma && columns(s) >= kMinColsMfma && columns(s) <= kMaxColsMfma;
 }
 
-int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : (cols <= 16 ? 16 : (cols <= 32 ? 32 : 64))); }
+int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : 16); }
 
-int mfma_stages(pa_kv_dtype kv, int cpad)
+int mfma_stages(pa_kv_dtype kv) { return kv == PA_KV_BF16 ? kMfmaStagesBf16 : kMfmaStagesFp8; }
+
+// waves per workgroup of the multi-wave kernel: one per 16 columns, rounded up to a power of two
+int wide_waves(int cols) { return cols <= 32 ? 2 : (cols <= 64 ? 4 : 8); }
+
+int wide_stages(pa_kv_dtype kv) { return kv == PA_KV_BF16 ? kWideStagesBf16 : kWideStagesFp8; }
+
+// waves (one-wave kernel) or workgroups (multi-wave kernel) of the matrix-core path resident per compute unit
+int mfma_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
 {
-    if (cpad > 16) return kMfmaStagesWide;
-    return kv == PA_KV_BF16 ? kMfmaStagesBf16 : kMfmaStagesFp8;
+    const int cols = columns(s);
+    if (cols <= kMaxColsOneWave) {
+        const int fit = kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv), mfma_col_pad(cols), (int)kv);
+        return fit < kMfmaWavesPerCu ? fit : kMfmaWavesPerCu;
+    }
+    const int nw = wide_waves(cols);
+    const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(nw, wide_stages(kv), (int)kv);
+    const int want = kWideWavesPerCu / nw;
+    return fit < want ? fit : want;
 }
 
 // Compute units of the current device (cached per process; 256 when there is no device).
@@ -108,14 +127,10 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     if (s->num_partitions > 0) {
         plan->P = s->num_partitions;
     } else {
-        // one resident wave per (partition, KV head): as many partitions as the device holds at once,
+        // one resident wave (or workgroup) per (partition, KV head): as many partitions as the device holds at once,
         // but never more than there can be tiles
-        const int cpad = mfma_col_pad(columns(s));
-        const int lds_fit = kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv, cpad), cpad, (int)kv);
-        const int waves_per_cu = use_mfma(s, kv)
-                                     ? (lds_fit < kMfmaWavesPerCu ? lds_fit : kMfmaWavesPerCu)
-                                     : kValuWavesPerCu;
-        int64_t P = (int64_t)compute_units() * waves_per_cu / s->num_kv_heads;
+        const int groups_per_cu = use_mfma(s, kv) ? mfma_groups_per_cu(s, kv) : kValuWavesPerCu;
+        int64_t P = (int64_t)compute_units() * groups_per_cu / s->num_kv_heads;
         const int64_t tile_bound = (int64_t)s->batch * ((plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens);
         if (P > tile_bound) P = tile_bound;
         if (P > kMaxPartitions) P = kMaxPartitions;
@@ -173,12 +188,29 @@ void launch_mfma_c(const Params& p, bool trace, dim3 grid, hipStream_t st)
         launch_mfma<NSTAGE, 4, KV>(p, trace, grid, st);
     else if (cpad == 8)
         launch_mfma<NSTAGE, 8, KV>(p, trace, grid, st);
-    else if (cpad == 16)
-        launch_mfma<NSTAGE, 16, KV>(p, trace, grid, st);
-    else if (cpad == 32)
-        launch_mfma<kMfmaStagesWide, 32, KV>(p, trace, grid, st);
     else
-        launch_mfma<kMfmaStagesWide, 64, KV>(p, trace, grid, st);
+        launch_mfma<NSTAGE, 16, KV>(p, trace, grid, st);
+}
+
+template <int NW, int NSTAGE, int KV>
+void launch_wide(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    if (trace)
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, true>), grid, dim3(NW * 64), 0, st, p);
+    else
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, false>), grid, dim3(NW * 64), 0, st, p);
+}
+
+template <int NSTAGE, int KV>
+void launch_wide_w(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    const int nw = wide_waves(p.Q * p.G);
+    if (nw == 2)
+        launch_wide<2, NSTAGE, KV>(p, trace, grid, st);
+    else if (nw == 4)
+        launch_wide<4, NSTAGE, KV>(p, trace, grid, st);
+    else
+        launch_wide<8, NSTAGE, KV>(p, trace, grid, st);
 }
 
 struct Events {
@@ -232,7 +264,12 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     if (ev && hipEventRecord(ev->before, hs) != hipSuccess) return PA_ERR_HIP;
 
     const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
-    if (use_mfma(shape, kv)) {
+    if (use_mfma(shape, kv) && columns(shape) > kMaxColsOneWave) {
+        if (kv == PA_KV_BF16)
+            launch_wide_w<kWideStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
+        else
+            launch_wide_w<kWideStagesFp8, pa::KV_FP8>(p, trace, grid, hs);
+    } else if (use_mfma(shape, kv)) {
         if (kv == PA_KV_BF16)
             launch_mfma_c<kMfmaStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
         else

@@ -70,6 +70,28 @@ __device__ __forceinline__ float group_sum(float v)
     return v;
 }
 
+// Reductions over the four 16-lane rows of a wave (lanes l, l^16, l^32, l^48) with gfx950's
+// row-swapping permutes: permlane16_swap(x, x) returns {rows 0,0,2,2 ; rows 1,1,3,3} of x and
+// permlane32_swap(x, x) returns {rows 0,1,0,1 ; rows 2,3,2,3}, so each step is one swap and
+// one VALU op instead of a round trip through the LDS crossbar.  Every lane gets the result.
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float rows_max(float v)
+{
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ float rows_sum(float v)
+{
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 

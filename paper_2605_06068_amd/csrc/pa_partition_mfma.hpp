@@ -1,17 +1,16 @@
-// Partition kernel, matrix-core variant (head_dim 128, bf16 or fp8 KV).  The columns of its
-// matrix tiles are the (query token, query head) pairs that share one KV head: q_len * G of
-// them, padded to CPAD (one 16-column MFMA tile for plain decode with 4 <= G <= 16, up to four
-// tiles = 64 columns for multi-token verification).  One wavefront per (partition, KV head)
-// walks its balanced range of the batch's global tile sequence (see pa_plan.hpp); no workgroup
-// barriers, no atomics.
+// Partition kernel, matrix-core variant (head_dim 128, bf16 or fp8 KV) for up to 16 columns.
+// The columns of its matrix tile are the (query token, query head) pairs that share one KV
+// head: q_len * G of them (plain decode: the G heads of the group), padded to CPAD = 4, 8 or
+// 16 inside one 16-column MFMA tile.  One wavefront per (partition, KV head) walks its balanced
+// range of the batch's global tile sequence (see pa_plan.hpp); no workgroup barriers, no
+// atomics.  More columns than 16 go to the multi-wave kernel in pa_partition_mfma_wide.hpp.
 //
 // Data path per 32-token tile (two KV blocks):
 //   HBM --global_load_lds (16 B/lane, 1 KB per instruction)--> LDS ring of NSTAGE tiles
 //   K:  ds_read_b128 in MFMA operand layout -> S^T[token, column] = K . Q^T  (mfma 16x16x32 bf16)
 //   online softmax on S^T in registers (lane = column, 8 tokens per lane per tile)
 //   V:  ds_read_b64_tr_b16 (transposing LDS read) -> out^T[dim, column] += V^T . P^T
-// Each K and V operand is read from LDS once and used for every column tile.  The ring keeps
-// running across sequence boundaries inside the range; the query rows of each new sequence
+// The ring keeps running across sequence boundaries inside the range; the query rows of each new sequence
 // travel through a small LDS ring of their own, ahead of its first tile.
 //
 // Multi-token calls (q_len > 1) are causal inside the new tokens: query i of a sequence of L
@@ -130,8 +129,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 {
     constexpr int D = 128;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring depth");
-    static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16 || CPAD == 32 || CPAD == 64, "padded column count");
-    constexpr int NT = CPAD <= 16 ? 1 : CPAD / 16;  // 16-column MFMA tiles
+    static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16, "padded column count");
     using Geo = KvGeom<KV>;
     constexpr int kSlabBytes = Geo::kSlab;
     constexpr int kStageBytes = Geo::kStage;
@@ -150,7 +148,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     const int B = p.B;
     const int Q = p.Q;
     const int ncols = Q * G;   // real columns: (query token i, head h of the group) -> column i*G + h
-    const int n = lane & 15;   // column inside a column tile / row-in-block, depending on the operand
+    const int n = lane & 15;   // column of the tile / row-in-block, depending on the operand
     const int q4 = lane >> 4;  // 0..3
 
     // ---- this wave's range of the global tile sequence
@@ -201,20 +199,12 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         else                // 8 bytes: the same dims, half of 16-byte piece 2kk + q4/2
             kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & 7)) << 4) + ((q4 & 1) << 3);
     }
-    // this lane's columns: one per column tile
-    bool col_ok[NT];       // a real column
-    int col_back[NT];      // tokens at the end of the context that the column's query must not see
-    int col_row[NT];       // output row of the column inside its sequence: i * Hq + g*G + h
-    uint32_t qread[NT];    // LDS byte offset of the column's query row (piece offset added per k-step)
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct) {
-        const int c = 16 * ct + n;
-        col_ok[ct] = c < ncols;
-        const int i = col_ok[ct] ? c / G : 0, h = col_ok[ct] ? c % G : 0;
-        col_back[ct] = col_ok[ct] ? Q - 1 - i : (1 << 30);
-        col_row[ct] = i * p.Hq + g * G + h;
-        qread[ct] = (col_ok[ct] ? c : 0) * kQRowBytes;
-    }
+    // this lane's column n
+    const bool col_ok = n < ncols;                                 // a real column
+    const int col_i = col_ok ? n / G : 0, col_h = col_ok ? n % G : 0;
+    const int col_back = col_ok ? Q - 1 - col_i : (1 << 30);       // tokens at the end of the context its query must not see
+    const int col_row = col_i * p.Hq + g * G + col_h;              // its output row inside its sequence
+    const uint32_t qread = (col_ok ? n : 0) * kQRowBytes;          // LDS byte offset of its query row
     uint32_t qpiece[4];  // swizzled position of dims 32kk + 8q4 + [0,8) in a query row of this lane's columns
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) qpiece[kk] = ((4 * kk + q4) ^ n) << 4;
@@ -291,12 +281,12 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         advance(ic, p.context_lens, B);
     };
 
-    // ---- online softmax state: lane = column n of each column tile, tokens 4*q4+{0..3} of each block
+    // ---- online softmax state: lane = column n, tokens 4*q4+{0..3} of each block
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;  // K scale folded in
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    float m[NT], lsum[NT];
-    f32x4 acc[NT][8];
-    bf16x8 qreg[NT][4];
+    float m = kNegBig, lsum = 0.f;
+    f32x4 acc[8];
+    bf16x8 qreg[4];
     int q_comp = 0;       // query slot of the segment being computed
     int seg_first_lt = 0;
 
@@ -323,29 +313,21 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         if (tile == 0 || cc.lt == 0) {  // segment start
             seg_first_lt = cc.lt;
             const char* qsl = qslots + q_comp * kQSlot;
+            m = kNegBig;
+            lsum = 0.f;
 #pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                m[ct] = kNegBig;
-                lsum[ct] = 0.f;
+            for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) acc[ct][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    uint4 w = *reinterpret_cast<const uint4*>(qsl + qread[ct] + qpiece[kk]);
-                    if (!col_ok[ct]) w = make_uint4(0, 0, 0, 0);
-                    qreg[ct][kk] = as_bf16x8(w);
-                }
+            for (int kk = 0; kk < 4; ++kk) {
+                uint4 w = *reinterpret_cast<const uint4*>(qsl + qread + qpiece[kk]);
+                if (!col_ok) w = make_uint4(0, 0, 0, 0);
+                qreg[kk] = as_bf16x8(w);
             }
             q_comp = (q_comp + 1 == NSTAGE) ? 0 : q_comp + 1;
         }
 
         // ---- scores: S^T[token, column] for the two blocks of the tile
-        f32x4 s0[NT], s1[NT];
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            s0[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-            s1[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             bf16x8 a0, a1;
@@ -358,52 +340,45 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 a0 = fp8x8_to_bf16x8(w0.x, w0.y);
                 a1 = fp8x8_to_bf16x8(w1.x, w1.y);
             }
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                s0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[ct][kk], s0[ct], 0, 0, 0);
-                s1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[ct][kk], s1[ct], 0, 0, 0);
-            }
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[kk], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[kk], s1, 0, 0, 0);
         }
 
-        // ---- online softmax (log2 domain); a column sees tokens t < L - col_back
+        // ---- online softmax (log2 domain); the column sees tokens t < L - col_back
         const int t0 = cc.lt * kTileTokens + 4 * q4;
-        bf16x8 pb[NT], pb_lo[NT];
+        const int lim = cc.L - col_back;
+        float x[8];
+        bool ok[8];
 #pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            const int lim = cc.L - col_back[ct];
-            float x[8];
-            bool ok[8];
+        for (int r = 0; r < 4; ++r) {
+            ok[r] = t0 + r < lim;
+            ok[4 + r] = t0 + kBlockSize + r < lim;
+            x[r] = ok[r] ? s0[r] * qs : kNegBig;
+            x[4 + r] = ok[4 + r] ? s1[r] * qs : kNegBig;
+        }
+        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        mx = rows_max(mx);
+        const float m_new = fmaxf(m, mx);
+        const float alpha = fast_exp2(m - m_new);
+        float ps = 0.f;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                ok[r] = t0 + r < lim;
-                ok[4 + r] = t0 + kBlockSize + r < lim;
-                x[r] = ok[r] ? s0[ct][r] * qs : kNegBig;
-                x[4 + r] = ok[4 + r] ? s1[ct][r] * qs : kNegBig;
-            }
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            const float m_new = fmaxf(m[ct], mx);
-            const float alpha = fast_exp2(m[ct] - m_new);
-            float ps = 0.f;
+        for (int r = 0; r < 8; ++r) {
+            x[r] = ok[r] ? fast_exp2(x[r] - m_new) : 0.f;  // a column may see nothing of a tile
+            ps += x[r];
+        }
+        lsum = lsum * alpha + ps;
+        m = m_new;
+        if (__any(alpha != 1.f)) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                x[r] = ok[r] ? fast_exp2(x[r] - m_new) : 0.f;  // a column may see nothing of a tile
-                ps += x[r];
-            }
-            lsum[ct] = lsum[ct] * alpha + ps;
-            m[ct] = m_new;
-            if (__any(alpha != 1.f)) {
+            for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;
+        }
+        // P^T operand as a bf16 pair (high part + rounding remainder): 16 significant bits, so
+        // the weights lose nothing that matters against the fp32 accumulation
+        bf16x8 pb, pb_lo;
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) acc[ct][dt] *= alpha;
-            }
-            // P^T operand as a bf16 pair (high part + rounding remainder): 16 significant bits, so
-            // the weights lose nothing that matters against the fp32 accumulation
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                pb[ct][r] = (__bf16)x[r];
-                pb_lo[ct][r] = (__bf16)(x[r] - (float)pb[ct][r]);
-            }
+        for (int r = 0; r < 8; ++r) {
+            pb[r] = (__bf16)x[r];
+            pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
         }
 
         // ---- out^T[dim, column] += V^T . P^T
@@ -419,38 +394,30 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 const i32x2 v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(vbuf + vread[dt]));
                 va = fp8x8_to_bf16x8((uint32_t)v[0], (uint32_t)v[1]);
             }
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                acc[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[ct], acc[ct][dt], 0, 0, 0);
-                acc[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo[ct], acc[ct][dt], 0, 0, 0);
-            }
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, acc[dt], 0, 0, 0);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo, acc[dt], 0, 0, 0);
         }
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
             const bool whole = seg_first_lt == 0 && cc.lt == cc.nt - 1;  // the entire sequence: final result
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                float l = lsum[ct] + __shfl_xor(lsum[ct], 16, kWave);
-                l += __shfl_xor(l, 32, kWave);
-                if (col_ok[ct]) {
-                    // a column that saw no token (its query sits before this segment) leaves a zero
-                    // row with an "empty" log-sum-exp
-                    const float inv = l > 0.f ? vs / l : 0.f;
-                    float* dst;
-                    if (whole) {
-                        dst = p.out + ((int64_t)cc.b * p.QH + col_row[ct]) * D;
-                    } else {
-                        const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row[ct];
-                        dst = p.part_o + slot * D;
-                        if (q4 == 0) p.part_lse[slot] = l > 0.f ? m[ct] + fast_log2(l) : kNegBig;
-                    }
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt)
-                        *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
-                            make_float4(acc[ct][dt][0] * inv, acc[ct][dt][1] * inv, acc[ct][dt][2] * inv,
-                                        acc[ct][dt][3] * inv);
+            const float l = rows_sum(lsum);
+            if (col_ok) {
+                // a column that saw no token (its query sits before this segment) leaves a zero
+                // row with an "empty" log-sum-exp
+                const float inv = l > 0.f ? vs / l : 0.f;
+                float* dst;
+                if (whole) {
+                    dst = p.out + ((int64_t)cc.b * p.QH + col_row) * D;
+                } else {
+                    const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
+                    dst = p.part_o + slot * D;
+                    if (q4 == 0) p.part_lse[slot] = l > 0.f ? m + fast_log2(l) : kNegBig;
                 }
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt)
+                    *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
+                        make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
             }
         }
         advance(cc, p.context_lens, B);

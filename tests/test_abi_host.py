@@ -78,6 +78,7 @@ def test_workspace_size_covers_partials():
 
 def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     one = shape(num_partitions=16)
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_BF16) == "mfma"  # 128 rows per KV head
     for Q in (2, 4, 16):
         win = shape(num_partitions=16, q_len=Q)
         assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == "mfma"
@@ -109,7 +110,7 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(num_q_heads=8 * 32), pa.PA_ERR_UNSUPPORTED),
     (dict(q_len=-1), pa.PA_ERR_INVALID_ARG),
     (dict(q_len=17), pa.PA_ERR_UNSUPPORTED),
-    (dict(q_len=16, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),            # 16 tokens x 8 heads > 64 rows per KV head
+    (dict(q_len=16, num_q_heads=128), pa.PA_ERR_UNSUPPORTED),           # 16 tokens x 16 heads > 128 rows per KV head
     (dict(q_len=2, num_q_heads=8), pa.PA_ERR_UNSUPPORTED),              # 2 rows per KV head: below the matrix-core path
     (dict(q_len=4, head_dim=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # windows need head_dim 128
 ])
