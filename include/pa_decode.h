@@ -46,6 +46,16 @@
  * visible token yields a zero row.  The KV cache is read once for all Q tokens.  Supported for
  * head_dim 128 with 4 <= Q * G <= 128 (matrix-core kernels only).
  *
+ * Shared prefix (shape.shared_prefix_blocks > 0; the long common prompt prefix of the paper's
+ * prompt-caching workload, Appendix A, Scenario C: many concurrent requests over one cached
+ * prefix of tens of thousands of tokens plus short individual suffixes): the result is the same
+ * attention as above, but the blocks of the prefix (rounded down to whole tiles of two blocks)
+ * are read once for the whole batch, with the (sequence, head) pairs as matrix columns, instead
+ * of once per sequence; the rest of every context is processed per sequence as usual and a merge
+ * kernel joins the two by their log-sum-exps.  The promise is not checked on the device: block
+ * ids of the prefix are taken from row 0 of block_tables.  Supported for plain decode
+ * (q_len <= 1), head_dim 128 and 4 <= G <= 16.
+ *
  * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
  * 1 <= G <= 16 (G <= 8 for head_dim 64); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
  * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
@@ -85,6 +95,10 @@ typedef struct pa_shape {
                                    split plan below (1 .. 65535; tests force values) */
     int32_t q_len;              /* query tokens per sequence: 0 or 1 = plain decode; 2 .. 16 = multi-token
                                    verification (see pa_decode) */
+    int32_t shared_prefix_blocks; /* 0, or the caller's promise that the first shared_prefix_blocks entries of
+                                   every row of block_tables are the same physical blocks (a prompt prefix
+                                   cached once for the whole batch) and every context is at least that long:
+                                   those blocks are then read once for all sequences (see pa_decode) */
 } pa_shape;
 
 /*
@@ -106,13 +120,17 @@ int32_t pa_num_partitions(const pa_shape *shape, pa_kv_dtype kv_dtype);
  * The plan as the kernels apply it, computed on the host from a HOST copy of the context
  * lengths: block_partition (HOST, [batch, max_blocks_per_seq]) receives, for every KV block
  * that holds a valid token, the index of the partition that processes it, and -1 elsewhere.
+ * With a shared prefix T counts the tiles after the prefix only, a length below the prefix is an
+ * error, and the entries of the prefix blocks hold -2 - r, r being the range of the prefix tiles
+ * (cut into balanced ranges in the same way) whose workgroups read the block.
  * Returns T, or a negative pa_status (bad shape, null pointer, a length above max_context_len).
  */
 int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, const int32_t *context_lens,
                       int32_t *block_partition);
 
 /* Bytes of device workspace pa_decode needs for this shape: two partial results (normalised
- * output row + log-sum-exp per query head and query token) per partition.  0 when P == 1.  Returns 0 as well for
+ * output row + log-sum-exp per query head and query token) per partition; with a shared prefix in
+ * addition one partial result per range of the prefix and one log-sum-exp per output row.  0 when P == 1.  Returns 0 as well for
  * an invalid shape (pa_decode then reports the error). */
 size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
@@ -166,6 +184,7 @@ pa_status pa_kv_append(const void *k_new, const void *v_new, void *k_cache, void
  *                  ([..,0]) and for its V loads ([..,1]) and the partition that processed it
  *                  ([..,2]).  Entries of blocks the kernel never touched keep the caller's initial
  *                  contents.
+ * Shapes with a shared prefix are PA_ERR_UNSUPPORTED here.
  */
 pa_status pa_decode_trace(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                           const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,

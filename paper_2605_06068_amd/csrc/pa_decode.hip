@@ -41,9 +41,18 @@ struct Plan {
     int32_t max_ctx;    // resolved max context length
     size_t lse_offset;  // byte offset of the lse array inside the workspace
     size_t ws_bytes;
+    // shared-prefix calls
+    int32_t skip_tiles;       // tiles of the shared prefix (0: none)
+    int32_t Pp;               // partitions of the prefix tiles
+    int32_t prefix_waves;     // waves per workgroup of the prefix pass
+    int32_t prefix_groups;    // column groups of the prefix pass (16 * prefix_waves columns each)
+    size_t seq_lse_offset, prefix_o_offset, prefix_lse_offset;
 };
 
 int query_len(const pa_shape* s) { return s->q_len > 0 ? s->q_len : 1; }
+
+// tiles (pairs of blocks) at the head of every block table that the whole batch shares
+int shared_tiles(const pa_shape* s) { return s->shared_prefix_blocks / 2; }
 
 // columns of the score matrix per KV head: (query token, query head of the group) pairs
 int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
@@ -100,8 +109,9 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (kv != PA_KV_BF16 && kv != PA_KV_FP8_E4M3) return PA_ERR_INVALID_ARG;
     if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->head_dim <= 0 || s->block_size <= 0 ||
         s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->num_partitions < 0 ||
-        s->q_len < 0)
+        s->q_len < 0 || s->shared_prefix_blocks < 0)
         return PA_ERR_INVALID_ARG;
+    if (s->shared_prefix_blocks > s->max_blocks_per_seq) return PA_ERR_INVALID_ARG;
     if (s->num_q_heads % s->num_kv_heads != 0) return PA_ERR_INVALID_ARG;
     if ((int64_t)s->max_context_len > (int64_t)s->max_blocks_per_seq * s->block_size) return PA_ERR_INVALID_ARG;
     if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
@@ -110,6 +120,11 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->num_q_heads / s->num_kv_heads > (use_mfma(s, kv) ? kMaxGroupMfma : kMaxGroupValu)) return PA_ERR_UNSUPPORTED;
     if (!use_mfma(s, kv) && query_len(s) > 1) return PA_ERR_UNSUPPORTED;  // multi-token calls: matrix-core kernel only
     if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
+    if (shared_tiles(s) > 0) {
+        // the per-sequence pass runs on the one-wave matrix-core kernel, the prefix pass on the multi-wave one
+        if (query_len(s) > 1 || !use_mfma(s, kv) || s->batch < 1) return PA_ERR_UNSUPPORTED;
+        if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens) return PA_ERR_INVALID_ARG;
+    }
     if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
     // the global tile index and the launch grid are 32-bit
     const int64_t max_ctx = s->max_context_len > 0 ? s->max_context_len : (int64_t)s->max_blocks_per_seq * s->block_size;
@@ -124,6 +139,10 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     const pa_status st = check_shape(s, kv);
     if (st != PA_OK) return st;
     plan->max_ctx = s->max_context_len > 0 ? s->max_context_len : s->max_blocks_per_seq * s->block_size;
+    plan->skip_tiles = shared_tiles(s);
+    // tiles the per-sequence kernel can meet at most (those after a shared prefix)
+    const int64_t tile_bound =
+        (int64_t)s->batch * ((plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens - plan->skip_tiles);
     if (s->num_partitions > 0) {
         plan->P = s->num_partitions;
     } else {
@@ -131,20 +150,39 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         // but never more than there can be tiles
         const int groups_per_cu = use_mfma(s, kv) ? mfma_groups_per_cu(s, kv) : kValuWavesPerCu;
         int64_t P = (int64_t)compute_units() * groups_per_cu / s->num_kv_heads;
-        const int64_t tile_bound = (int64_t)s->batch * ((plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens);
         if (P > tile_bound) P = tile_bound;
         if (P > kMaxPartitions) P = kMaxPartitions;
         if (P < 1) P = 1;
         plan->P = (int32_t)P;
     }
-    if (plan->P == 1) {
-        plan->lse_offset = 0;
-        plan->ws_bytes = 0;
-    } else {
-        const size_t rows = (size_t)2 * plan->P * s->num_q_heads * query_len(s);
-        const size_t o_bytes = rows * s->head_dim * sizeof(float);
-        plan->lse_offset = (o_bytes + 255) / 256 * 256;
-        plan->ws_bytes = plan->lse_offset + (rows * sizeof(float) + 255) / 256 * 256;
+    const size_t rows = (size_t)2 * plan->P * s->num_q_heads * query_len(s);
+    const size_t o_bytes = plan->P == 1 ? 0 : rows * s->head_dim * sizeof(float);
+    const auto pad = [](size_t n) { return (n + 255) / 256 * 256; };
+    plan->lse_offset = pad(o_bytes);
+    plan->ws_bytes = plan->P == 1 ? 0 : plan->lse_offset + pad(rows * sizeof(float));
+    plan->Pp = 0;
+    plan->prefix_waves = plan->prefix_groups = 0;
+    plan->seq_lse_offset = plan->prefix_o_offset = plan->prefix_lse_offset = 0;
+    if (plan->skip_tiles > 0) {
+        // the prefix pass: columns are the (sequence, head of the group) pairs, 16 per wave, at most
+        // kMaxColsMfma per workgroup, further column groups beyond that
+        const int cols = s->batch * (s->num_q_heads / s->num_kv_heads);
+        const int group_cols = cols < kMaxColsMfma ? cols : kMaxColsMfma;
+        plan->prefix_waves = wide_waves(group_cols);
+        plan->prefix_groups = (cols + 16 * plan->prefix_waves - 1) / (16 * plan->prefix_waves);
+        const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(plan->prefix_waves, wide_stages(kv), (int)kv);
+        const int want = kWideWavesPerCu / plan->prefix_waves;
+        const int per_cu = fit < want ? fit : want;
+        int64_t Pp = (int64_t)compute_units() * per_cu / ((int64_t)s->num_kv_heads * plan->prefix_groups);
+        if (s->num_partitions > 0) Pp = s->num_partitions;  // tests force both counts with one knob
+        if (Pp > plan->skip_tiles) Pp = plan->skip_tiles;
+        if (Pp < 1) Pp = 1;
+        plan->Pp = (int32_t)Pp;
+        const size_t out_rows = (size_t)s->batch * s->num_q_heads;
+        plan->seq_lse_offset = plan->ws_bytes;
+        plan->prefix_o_offset = plan->seq_lse_offset + pad(out_rows * sizeof(float));
+        plan->prefix_lse_offset = plan->prefix_o_offset + pad((size_t)plan->Pp * out_rows * s->head_dim * sizeof(float));
+        plan->ws_bytes = plan->prefix_lse_offset + pad((size_t)plan->Pp * out_rows * sizeof(float));
     }
     return PA_OK;
 }
@@ -196,9 +234,9 @@ template <int NW, int NSTAGE, int KV>
 void launch_wide(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
     if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, true>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, true, false>), grid, dim3(NW * 64), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, false>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
 }
 
 template <int NSTAGE, int KV>
@@ -211,6 +249,18 @@ void launch_wide_w(const Params& p, bool trace, dim3 grid, hipStream_t st)
         launch_wide<4, NSTAGE, KV>(p, trace, grid, st);
     else
         launch_wide<8, NSTAGE, KV>(p, trace, grid, st);
+}
+
+// the pass over the prefix all sequences share
+template <int NSTAGE, int KV>
+void launch_prefix(const Params& p, int nw, dim3 grid, hipStream_t st)
+{
+    if (nw == 2)
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<2, NSTAGE, KV, false, true>), grid, dim3(128), 0, st, p);
+    else if (nw == 4)
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<4, NSTAGE, KV, false, true>), grid, dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<8, NSTAGE, KV, false, true>), grid, dim3(512), 0, st, p);
 }
 
 struct Events {
@@ -232,6 +282,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         return PA_ERR_INVALID_ARG;
     if (!(scale == scale) || scale * 0.f != 0.f) return PA_ERR_INVALID_ARG;  // NaN or infinite
     if (trace && !trace_blocks) return PA_ERR_INVALID_ARG;
+    if (trace && plan.skip_tiles > 0) return PA_ERR_UNSUPPORTED;  // no instrumented prefix pass
     if (plan.ws_bytes > 0) {
         if (!workspace || !aligned(workspace, 256)) return PA_ERR_INVALID_ARG;
         if (workspace_bytes < plan.ws_bytes) return PA_ERR_WORKSPACE_TOO_SMALL;
@@ -259,10 +310,26 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.Q = query_len(shape);
     p.QH = p.Q * p.Hq;
     p.P = plan.P;
+    p.skip_tiles = plan.skip_tiles;
+    p.Pp = plan.Pp;
+    if (plan.skip_tiles > 0) {
+        char* ws = static_cast<char*>(workspace);
+        p.seq_lse = reinterpret_cast<float*>(ws + plan.seq_lse_offset);
+        p.prefix_o = reinterpret_cast<float*>(ws + plan.prefix_o_offset);
+        p.prefix_lse = reinterpret_cast<float*>(ws + plan.prefix_lse_offset);
+    }
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (ev && hipEventRecord(ev->before, hs) != hipSuccess) return PA_ERR_HIP;
 
+    if (plan.skip_tiles > 0) {
+        const dim3 pgrid((uint32_t)plan.Pp * (uint32_t)p.Hkv * (uint32_t)plan.prefix_groups);
+        if (kv == PA_KV_BF16)
+            launch_prefix<kWideStagesBf16, pa::KV_BF16>(p, plan.prefix_waves, pgrid, hs);
+        else
+            launch_prefix<kWideStagesFp8, pa::KV_FP8>(p, plan.prefix_waves, pgrid, hs);
+        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+    }
     const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
     if (use_mfma(shape, kv) && columns(shape) > kMaxColsOneWave) {
         if (kv == PA_KV_BF16)
@@ -288,7 +355,11 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
     if (ev && hipEventRecord(ev->between, hs) != hipSuccess) return PA_ERR_HIP;
 
-    if (plan.P > 1) {
+    if (plan.skip_tiles > 0) {
+        const dim3 mgrid(p.Hq, p.B);
+        hipLaunchKernelGGL((pa::merge_prefix_kernel<128>), mgrid, dim3(64), 0, hs, p);
+        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+    } else if (plan.P > 1) {
         const dim3 mgrid(p.QH, plan.P - 1);
         if (shape->head_dim == 128)
             hipLaunchKernelGGL((pa::merge_kernel<128>), mgrid, dim3(64), 0, hs, p);
@@ -318,10 +389,12 @@ int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, const int32_t
     const pa_status st = make_plan(shape, kv_dtype, &plan);
     if (st != PA_OK) return -(int32_t)st;
     if (shape->batch > 0 && (!context_lens || !block_partition)) return -(int32_t)PA_ERR_INVALID_ARG;
+    const int skip = plan.skip_tiles;
     int64_t T = 0;
     for (int32_t b = 0; b < shape->batch; ++b) {
         if (context_lens[b] > plan.max_ctx) return -(int32_t)PA_ERR_INVALID_ARG;
-        T += pa::tiles_of(context_lens[b]);
+        if (context_lens[b] < skip * pa::kTileTokens) return -(int32_t)PA_ERR_INVALID_ARG;  // shorter than the shared prefix
+        T += pa::tiles_of(context_lens[b], skip);
     }
     const int32_t MB = shape->max_blocks_per_seq;
     int32_t k = 0;
@@ -330,7 +403,12 @@ int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, const int32_t
         const int32_t L = context_lens[b];
         const int32_t nblk = L > 0 ? (L + pa::kBlockSize - 1) / pa::kBlockSize : 0;
         for (int32_t j = 0; j < MB; ++j) block_partition[(int64_t)b * MB + j] = -1;
-        for (int32_t lt = 0; lt < pa::tiles_of(L); ++lt, ++t) {
+        for (int32_t pt = 0; pt < skip; ++pt) {  // shared prefix: range pt of the prefix pass, written as -2 - range
+            const int32_t kp = pa::part_of(pt, skip, plan.Pp);
+            block_partition[(int64_t)b * MB + 2 * pt] = -2 - kp;
+            block_partition[(int64_t)b * MB + 2 * pt + 1] = -2 - kp;
+        }
+        for (int32_t lt = skip; lt < skip + pa::tiles_of(L, skip); ++lt, ++t) {
             while (k + 1 < plan.P && pa::part_begin(k + 1, (int)T, plan.P) <= t) ++k;
             block_partition[(int64_t)b * MB + 2 * lt] = k;
             if (2 * lt + 1 < nblk) block_partition[(int64_t)b * MB + 2 * lt + 1] = k;
@@ -393,7 +471,7 @@ pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_ca
             merge += b;
         }
         *partition_ms = (float)(part / steps);
-        *merge_ms = pa_num_partitions(shape, kv_dtype) > 1 ? (float)(merge / steps) : 0.f;
+        *merge_ms = (pa_num_partitions(shape, kv_dtype) > 1 || shared_tiles(shape) > 0) ? (float)(merge / steps) : 0.f;
     } else if (st == PA_OK) {
         *partition_ms = 0.f;
         *merge_ms = 0.f;

@@ -31,6 +31,13 @@ struct Params {
     int32_t Q;                    // query tokens per sequence (1 = plain decode)
     int32_t QH;                   // Q * Hq: output rows per sequence (q, out and the partials are [.., Q, Hq, D])
     int32_t P;                    // number of partitions of the global tile sequence
+    // shared-prefix calls only (skip_tiles > 0): the first skip_tiles tiles of every sequence are one
+    // and the same physical blocks; a pass of its own reads them once for all sequences
+    int32_t skip_tiles;           // tiles of the shared prefix (0: no shared prefix)
+    int32_t Pp;                   // partitions of the prefix tiles
+    float* seq_lse;               // [B, Hq]  log-sum-exp of the rows in `out` that still lack the prefix part
+    float* prefix_o;              // [Pp, B*Hq, D] normalised partial outputs over the prefix
+    float* prefix_lse;            // [Pp, B*Hq]
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

@@ -106,4 +106,123 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
     }
 }
 
+// Merge kernel of shared-prefix calls.  One wavefront per (query head h, sequence b) combines, by
+// their log-sum-exps, every piece of that output row:
+//   - the Pp partials of the prefix pass (slot kp of prefix_o / prefix_lse), and
+//   - what the per-sequence pass produced over the rest of the context: nothing (the context ends
+//     with the prefix), or the row already in `out` with its log-sum-exp in seq_lse (the rest lies
+//     inside one partition), or the partials of the partitions that cut it (slots as above).
+// The row in `out` is read before it is overwritten by the same wave.
+template <int D>
+__global__ __launch_bounds__(64) void merge_prefix_kernel(const Params p)
+{
+    constexpr int V = D / kWave;
+    __shared__ const float* s_row[kWave];
+    __shared__ float s_w[kWave];
+    const int h = blockIdx.x;
+    const int b = blockIdx.y;
+    const int lane = threadIdx.x;
+    const int skip = p.skip_tiles;
+    const int P = p.P;
+    const int64_t rows = (int64_t)p.B * p.Hq;
+    const int64_t row = (int64_t)b * p.Hq + h;
+
+    // the sequence's own tiles (those after the prefix) inside the global tile sequence
+    const int T = total_tiles(p.context_lens, p.B, lane, skip);
+    int before = 0;
+    for (int b0 = 0; b0 < b; b0 += kWave) {
+        const int bb = b0 + lane;
+        before += bb < b ? tiles_of(p.context_lens[bb], skip) : 0;
+    }
+    const int cum = wave_sum(before);
+    const int nb = tiles_of(p.context_lens[b], skip);
+    int k_first = 0, nrest = 0;
+    bool inside_one = false;
+    if (nb > 0) {
+        k_first = part_of(cum, T, P);
+        const int k_last = part_of(cum + nb - 1, T, P);
+        inside_one = k_first == k_last;
+        nrest = inside_one ? 1 : k_last - k_first + 1;
+    }
+    const int nsrc = p.Pp + nrest;
+
+    float acc[V], wsum = 0.f, mrun = kNegBig;
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.f;
+
+    for (int base = 0; base < nsrc; base += kWave) {
+        const int s = base + lane;
+        bool valid = s < nsrc;
+        const float* src = p.out;
+        float lse = kNegBig;
+        if (valid) {
+            if (s < p.Pp) {
+                src = p.prefix_o + ((int64_t)s * rows + row) * D;
+                lse = p.prefix_lse[(int64_t)s * rows + row];
+            } else if (inside_one) {
+                src = p.out + row * D;
+                lse = p.seq_lse[row];
+            } else {
+                const int kk = k_first + (s - p.Pp);
+                const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
+                valid = hi > lo;  // partitions without tiles wrote nothing
+                const int64_t slot = (int64_t)(2 * kk + ((kk == k_first && lo != cum) ? 1 : 0)) * p.Hq + h;
+                src = p.part_o + slot * D;
+                if (valid) lse = p.part_lse[slot];
+            }
+        }
+        float cm = lse;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) cm = fmaxf(cm, __shfl_xor(cm, o, kWave));
+        const float m_new = fmaxf(mrun, cm);
+        const float rescale = fast_exp2(mrun - m_new);
+        const float w = valid ? fast_exp2(lse - m_new) : 0.f;
+        float ws = w;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) ws += __shfl_xor(ws, o, kWave);
+        wsum = wsum * rescale + ws;
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] *= rescale;
+        mrun = m_new;
+
+        const unsigned long long vmask = __ballot(valid);
+        const int pos = __popcll(vmask & ((1ull << lane) - 1ull));
+        const int cnt = __popcll(vmask);
+        if (valid) {
+            s_row[pos] = src;
+            s_w[pos] = w;
+        }
+        __syncthreads();
+        for (int i0 = 0; i0 < cnt; i0 += 8) {
+            float wv[8];
+            float2 xv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = min(i0 + u, cnt - 1);
+                wv[u] = (i0 + u < cnt) ? s_w[idx] : 0.f;
+                const float* r = s_row[idx];
+                if (V == 2) {
+                    xv[u] = *reinterpret_cast<const float2*>(r + lane * 2);
+                } else {
+                    xv[u].x = r[lane];
+                    xv[u].y = 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                acc[0] = fmaf(wv[u], xv[u].x, acc[0]);
+                if (V == 2) acc[V - 1] = fmaf(wv[u], xv[u].y, acc[V - 1]);
+            }
+        }
+        __syncthreads();
+    }
+    const float inv = 1.f / wsum;
+    float* dst = p.out + row * D;
+    if (V == 2) {
+        *reinterpret_cast<float2*>(dst + lane * 2) = make_float2(acc[0] * inv, acc[V - 1] * inv);
+    } else {
+        dst[lane] = acc[0] * inv;
+    }
+}
+
 }  // namespace pa

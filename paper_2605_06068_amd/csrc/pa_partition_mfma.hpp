@@ -113,14 +113,14 @@ struct Cursor {
     int b, lt, nt, L;
 };
 
-__device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, int B)
+__device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, int B, int skip = 0)
 {
     if (++c.lt < c.nt) return;
     c.lt = 0;
     do {
         ++c.b;
         c.L = c.b < B ? uniform_load(context_lens, c.b) : 0;
-        c.nt = tiles_of(c.L);
+        c.nt = tiles_of(c.L, skip);
     } while (c.nt == 0 && c.b < B);
 }
 
@@ -150,10 +150,13 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     const int ncols = Q * G;   // real columns: (query token i, head h of the group) -> column i*G + h
     const int n = lane & 15;   // column of the tile / row-in-block, depending on the operand
     const int q4 = lane >> 4;  // 0..3
+    // shared-prefix calls: local tile lt of a sequence is its tile lt + skip; the tiles before belong
+    // to the prefix pass, and no row this kernel writes is final (the merge adds the prefix part)
+    const int skip = p.skip_tiles;
 
     // ---- this wave's range of the global tile sequence
-    const RangeStart rs = find_range(p.context_lens, B, k, p.P, lane);
-    if (k == 0) {  // empty contexts: their output rows are zero
+    const RangeStart rs = find_range(p.context_lens, B, k, p.P, lane, skip);
+    if (k == 0 && skip == 0) {  // empty contexts: their output rows are zero
         for (int b0 = 0; b0 < B; b0 += kWave) {
             const int b = b0 + lane;
             if (b < B && p.context_lens[b] <= 0) {
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     ic.b = first_b;
     ic.lt = rs.t_lo - rs.cum;
     ic.L = rs.L;
-    ic.nt = tiles_of(ic.L);
+    ic.nt = tiles_of(ic.L, skip);
     Cursor cc = ic;  // compute side
 
     // ---- per-lane address pieces
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         }
         const int nblk = (ic.L + kBlockSize - 1) / kBlockSize;
         const int32_t* table = p.block_tables + (int64_t)ic.b * p.MB;
-        const int j0 = 2 * ic.lt;
+        const int j0 = 2 * (ic.lt + skip);
         int phys[2], nvalid[2];
         phys[0] = uniform_load(table, j0);
         nvalid[0] = min(kBlockSize, ic.L - j0 * kBlockSize);
@@ -278,7 +281,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024, live ? dma_off[r] : (dma_off[r] & (Geo::kRow - 1)), vb);
             }
         }
-        advance(ic, p.context_lens, B);
+        advance(ic, p.context_lens, B, skip);
     };
 
     // ---- online softmax state: lane = column n, tokens 4*q4+{0..3} of each block
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         }
 
         // ---- online softmax (log2 domain); the column sees tokens t < L - col_back
-        const int t0 = cc.lt * kTileTokens + 4 * q4;
+        const int t0 = (cc.lt + skip) * kTileTokens + 4 * q4;
         const int lim = cc.L - col_back;
         float x[8];
         bool ok[8];
@@ -409,6 +412,8 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 float* dst;
                 if (whole) {
                     dst = p.out + ((int64_t)cc.b * p.QH + col_row) * D;
+                    if (skip > 0 && q4 == 0)
+                        p.seq_lse[(int64_t)cc.b * p.QH + col_row] = l > 0.f ? m + fast_log2(l) : kNegBig;
                 } else {
                     const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
                     dst = p.part_o + slot * D;
@@ -420,7 +425,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                         make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
             }
         }
-        advance(cc, p.context_lens, B);
+        advance(cc, p.context_lens, B, skip);
         stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
     }
 }

@@ -19,6 +19,13 @@
 // slot with the rows of the next segment in its range, so the rows are there long before that
 // segment's first tile; after a short segment (fewer tiles than the ring is deep) the wait at
 // the segment start is tightened to cover those loads (q_age below).
+//
+// PREFIX mode is the pass over a prefix that every sequence of a decode batch shares (the same
+// physical blocks at the head of every block table).  The columns are then the (sequence, head)
+// pairs: to this kernel the batch is ONE sequence, the prefix, with one "query token" per real
+// sequence and no causal mask.  The prefix tiles are cut into Pp ranges, workgroup
+// (column group, KV head, range) leaves one partial result per column, and the prefix merge
+// kernel adds them to what the per-sequence pass computed over the rest of each context.
 #pragma once
 #include <type_traits>
 
@@ -48,7 +55,7 @@ __device__ __forceinline__ void wait_loads(int tiles)
     }
 }
 
-template <int NW, int NSTAGE, int KV, bool TRACE>
+template <int NW, int NSTAGE, int KV, bool TRACE, bool PREFIX>
 __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const Params p)
 {
     constexpr int D = 128;
@@ -65,17 +72,32 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int g = blockIdx.x / p.P;  // partition index fastest, as in the single-wave kernel
-    const int k = blockIdx.x % p.P;
+    static_assert(!(PREFIX && TRACE), "the prefix pass has no instrumented variant");
+    // partition index fastest, as in the single-wave kernel; then the KV head, then (prefix pass
+    // with more than 16*NW columns) the column group
+    const int nparts = PREFIX ? p.Pp : p.P;
+    const int k = blockIdx.x % nparts;
+    const int g = (blockIdx.x / nparts) % p.Hkv;
+    const int col0 = (blockIdx.x / nparts / p.Hkv) * (16 * NW);
     const int G = p.G;
-    const int B = p.B;
-    const int Q = p.Q;
+    const int B = PREFIX ? 1 : p.B;      // sequences as this kernel sees them
+    const int Q = PREFIX ? p.B : p.Q;    // query tokens per such sequence
     const int ncols = Q * G;
     const int n = lane & 15;
     const int q4 = lane >> 4;
 
-    const RangeStart rs = find_range(p.context_lens, B, k, p.P, lane);
-    if (k == 0 && w == 0) {  // empty contexts: their output rows are zero
+    RangeStart rs;
+    if (PREFIX) {
+        rs.T = p.skip_tiles;
+        rs.t_lo = part_begin(k, rs.T, nparts);
+        rs.t_hi = part_begin(k + 1, rs.T, nparts);
+        rs.b = 0;
+        rs.cum = 0;
+        rs.L = rs.T * kTileTokens;
+    } else {
+        rs = find_range(p.context_lens, B, k, p.P, lane);
+    }
+    if (!PREFIX && k == 0 && w == 0) {  // empty contexts: their output rows are zero
         for (int b0 = 0; b0 < B; b0 += kWave) {
             const int b = b0 + lane;
             if (b < B && p.context_lens[b] <= 0) {
@@ -116,7 +138,7 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int lc = 4 * r + q4;
-        const int c = 16 * w + lc;
+        const int c = col0 + 16 * w + lc;
         const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * kQRowBytes : 0;
         qdma_off[r] = src + ((n ^ lc) << 4);
     }
@@ -129,10 +151,12 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
             kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & 7)) << 4) + ((q4 & 1) << 3);
     }
     // this lane's column
-    const int col = 16 * w + n;
+    const int col = col0 + 16 * w + n;
     const bool col_ok = col < ncols;
+    const bool wave_active = col0 + 16 * w < ncols;  // a wave without real columns only loads its share of the tiles
     const int col_i = col_ok ? col / G : 0, col_h = col_ok ? col % G : 0;
-    const int col_back = col_ok ? Q - 1 - col_i : (1 << 30);  // tokens at the end of the context it must not see
+    // tokens at the end of the context the column must not see (prefix pass: every column sees all of it)
+    const int col_back = col_ok ? (PREFIX ? 0 : Q - 1 - col_i) : (1 << 30);
     const int col_row = col_i * p.Hq + g * G + col_h;          // output row inside its sequence
     uint32_t qpiece[4];
 #pragma unroll
@@ -159,7 +183,7 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
     const char* vc = static_cast<const char*>(p.v_cache) + (int64_t)g * kSlabBytes;
 
     auto issue_q = [&](int b) {
-        const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)b * p.QH + g * G) * kQRowBytes;
+        const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)b * (Q * p.Hq) + g * G) * kQRowBytes;
 #pragma unroll
         for (int r = 0; r < 4; ++r) dma16(ldsq + r * 1024, qdma_off[r], qb);
     };
@@ -230,6 +254,11 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
         }
         const char* kbuf = smem + stage * kStageBytes;
         const char* vbuf = kbuf + 2 * kSlabBytes;
+        if (!wave_active) {  // keeps loading and meeting the others at the barrier; nothing to compute
+            advance(cc, p.context_lens, B);
+            stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+            continue;
+        }
 
         if (seg_start) {
             seg_first_lt = cc.lt;
@@ -312,7 +341,7 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
                 pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
             }
         };
-        if ((cc.lt + 1) * kTileTokens <= cc.L - (Q - 1))
+        if (PREFIX || (cc.lt + 1) * kTileTokens <= cc.L - (Q - 1))
             softmax(std::false_type{});
         else
             softmax(std::true_type{});
@@ -342,7 +371,11 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
                 // with an "empty" log-sum-exp
                 const float inv = l > 0.f ? vs / l : 0.f;
                 float* dst;
-                if (whole) {
+                if (PREFIX) {
+                    const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row;
+                    dst = p.prefix_o + slot * D;
+                    if (q4 == 0) p.prefix_lse[slot] = m + fast_log2(l);
+                } else if (whole) {
                     dst = p.out + ((int64_t)cc.b * p.QH + col_row) * D;
                 } else {
                     const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;

@@ -21,10 +21,19 @@ namespace pa {
 
 constexpr int kTileTokens = 32;
 
-__host__ __device__ __forceinline__ int tiles_of(int L) { return L > 0 ? (L + kTileTokens - 1) / kTileTokens : 0; }
+// Tiles of a context of L tokens that this plan covers.  `skip` leading tiles belong to someone
+// else (a prefix shared by the whole batch, handled by a pass of its own): they are left out.
+__host__ __device__ __forceinline__ int tiles_of(int L, int skip = 0)
+{
+    const int n = L > 0 ? (L + kTileTokens - 1) / kTileTokens : 0;
+    return n > skip ? n - skip : 0;
+}
 
 // first global tile of partition k
 __host__ __device__ __forceinline__ int part_begin(int k, int T, int P) { return (int)(((int64_t)k * T) / P); }
+
+// the partition that owns global tile t: the largest k with part_begin(k) <= t
+__host__ __device__ __forceinline__ int part_of(int t, int T, int P) { return (int)((((int64_t)t + 1) * P - 1) / T); }
 
 __device__ __forceinline__ int wave_sum(int v)
 {
@@ -44,26 +53,27 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
 }
 
 // Total number of tiles of the batch.  All 64 lanes must call.
-__device__ __forceinline__ int total_tiles(const int32_t* context_lens, int B, int lane)
+__device__ __forceinline__ int total_tiles(const int32_t* context_lens, int B, int lane, int skip = 0)
 {
     int sum = 0;
     for (int b0 = 0; b0 < B; b0 += kWave) {
         const int b = b0 + lane;
-        sum += b < B ? tiles_of(context_lens[b]) : 0;
+        sum += b < B ? tiles_of(context_lens[b], skip) : 0;
     }
     return wave_sum(sum);
 }
 
 // The sequence that contains global tile t (0 <= t < T) and the number of tiles before it.
 // All 64 lanes must call; results are wave-uniform.
-__device__ __forceinline__ void locate_tile(const int32_t* context_lens, int B, int t, int lane, int& b_out, int& cum_out)
+__device__ __forceinline__ void locate_tile(const int32_t* context_lens, int B, int t, int lane, int& b_out, int& cum_out,
+                                            int skip = 0)
 {
     int carry = 0;
     b_out = B - 1;
     cum_out = 0;
     for (int b0 = 0; b0 < B; b0 += kWave) {
         const int b = b0 + lane;
-        const int n = b < B ? tiles_of(context_lens[b]) : 0;
+        const int n = b < B ? tiles_of(context_lens[b], skip) : 0;
         const int incl = wave_inclusive_scan(n, lane) + carry;
         const unsigned long long hit = __ballot(incl > t);
         if (hit != 0ull) {
@@ -84,7 +94,7 @@ struct RangeStart {
     int T, t_lo, t_hi, b, cum, L;
 };
 
-__device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, int B, int k, int P, int lane)
+__device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, int B, int k, int P, int lane, int skip = 0)
 {
     RangeStart r;
     r.b = 0;
@@ -92,7 +102,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     r.L = 0;
     if (B <= kWave) {
         const int L = lane < B ? context_lens[lane] : 0;
-        const int n = tiles_of(L);
+        const int n = tiles_of(L, skip);
         const int incl = wave_inclusive_scan(n, lane);
         r.T = __builtin_amdgcn_readlane(incl, kWave - 1);
         r.t_lo = part_begin(k, r.T, P);
@@ -106,7 +116,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
         }
         return r;
     }
-    r.T = __builtin_amdgcn_readfirstlane(total_tiles(context_lens, B, lane));
+    r.T = __builtin_amdgcn_readfirstlane(total_tiles(context_lens, B, lane, skip));
     r.t_lo = part_begin(k, r.T, P);
     r.t_hi = part_begin(k + 1, r.T, P);
     if (r.t_lo >= r.t_hi) return r;
@@ -114,7 +124,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     for (int b0 = 0; b0 < B; b0 += kWave) {
         const int b = b0 + lane;
         const int L = b < B ? context_lens[b] : 0;
-        const int n = tiles_of(L);
+        const int n = tiles_of(L, skip);
         const int incl = wave_inclusive_scan(n, lane) + carry;
         const unsigned long long hit = __ballot(incl > r.t_lo);
         if (hit != 0ull) {

@@ -63,6 +63,7 @@ class DecodeBatch:
     seed: int = 0
     meta: dict = field(default_factory=dict)
     q_len: int = 1  # query tokens per sequence; > 1: q is [B, Q, Hq, D], the last Q tokens are the window
+    shared_prefix_blocks: int = 0  # leading table entries that are the same physical blocks for every sequence
 
     @property
     def group(self) -> int:
@@ -78,8 +79,16 @@ class DecodeBatch:
 
     @property
     def kv_bytes(self) -> int:
-        """Bytes of K and V belonging to valid tokens (what one decode step must read)."""
+        """Bytes of K and V belonging to valid tokens (what one decode step must read when every
+        sequence reads its own context)."""
         return self.total_tokens * self.num_kv_heads * self.head_dim * 2 * self.kv_elem_bytes
+
+    @property
+    def kv_bytes_unique(self) -> int:
+        """The same with the shared prefix counted once: bytes of the distinct valid slots."""
+        shared = self.shared_prefix_blocks * self.block_size
+        tokens = self.total_tokens - (self.batch - 1) * shared if self.batch > 0 else 0
+        return tokens * self.num_kv_heads * self.head_dim * 2 * self.kv_elem_bytes
 
 
 # --------------------------------------------------------------------------------------
@@ -148,6 +157,24 @@ def interleaved_block_tables(rng: np.random.Generator, context_lens: np.ndarray,
     return tables
 
 
+def shared_prefix_block_tables(rng: np.random.Generator, context_lens: np.ndarray, block_size: int,
+                               num_blocks: int, max_blocks_per_seq: int, prefix_blocks: int) -> np.ndarray:
+    """A prompt prefix cached once: the first ``prefix_blocks`` entries of every row are the same
+    physical blocks; the rest of each sequence takes its own blocks from one random permutation."""
+    nblk = blocks_needed(context_lens, block_size)
+    assert int(nblk.min(initial=prefix_blocks)) >= prefix_blocks, "every context must cover the shared prefix"
+    own = nblk - prefix_blocks
+    assert prefix_blocks + int(own.sum()) <= num_blocks and int(nblk.max(initial=0)) <= max_blocks_per_seq
+    perm = rng.permutation(num_blocks).astype(np.int32)
+    tables = np.full((len(context_lens), max_blocks_per_seq), -1, dtype=np.int32)
+    tables[:, :prefix_blocks] = perm[:prefix_blocks]
+    pos = prefix_blocks
+    for b, n in enumerate(own):
+        tables[b, prefix_blocks:prefix_blocks + n] = perm[pos:pos + n]
+        pos += int(n)
+    return tables
+
+
 # --------------------------------------------------------------------------------------
 # value generation (chunked so that multi-GB pools never need a float32 copy of the whole)
 # --------------------------------------------------------------------------------------
@@ -202,19 +229,24 @@ def _valid_slot_mask(tables: np.ndarray, context_lens: np.ndarray, block_size: i
 def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: int, num_kv_heads: int,
                head_dim: int, block_size: int = 16, kv_dtype: int = KV_BF16, sigma: float = 1.0,
                num_blocks: Optional[int] = None, max_blocks_per_seq: Optional[int] = None,
-               table_kind: str = "permuted", poison: bool = True, q_len: int = 1) -> DecodeBatch:
+               table_kind: str = "permuted", poison: bool = True, q_len: int = 1,
+               shared_prefix_blocks: int = 0) -> DecodeBatch:
     """Draw one decode batch.  ``poison`` fills every slot no valid token owns with NaN patterns
     (parity runs); with ``poison=False`` those slots are zero (timing runs).  ``q_len`` > 1 draws a
     window of that many query tokens per sequence (q becomes [B, Q, Hq, D]); the cache contents do not
-    depend on it."""
+    depend on it.  ``shared_prefix_blocks`` > 0 makes that many leading blocks common to all sequences
+    (``table_kind`` is then ignored)."""
     rng = np.random.default_rng(seed)
     lens = np.asarray(context_lens, dtype=np.int32)
     B = len(lens)
     nblk = blocks_needed(lens, block_size)
-    NB = int(nblk.sum()) if num_blocks is None else int(num_blocks)
+    NB_needed = int(nblk.sum()) - (B - 1) * shared_prefix_blocks if shared_prefix_blocks > 0 else int(nblk.sum())
+    NB = NB_needed if num_blocks is None else int(num_blocks)
     NB = max(NB, 1)
     MB = int(max(1, nblk.max(initial=1))) if max_blocks_per_seq is None else int(max_blocks_per_seq)
-    if table_kind == "permuted":
+    if shared_prefix_blocks > 0:
+        tables = shared_prefix_block_tables(rng, lens, block_size, NB, MB, shared_prefix_blocks)
+    elif table_kind == "permuted":
         tables = permuted_block_tables(rng, lens, block_size, NB, MB)
     elif table_kind == "interleaved":
         tables = interleaved_block_tables(rng, lens, block_size, NB, MB)
@@ -272,11 +304,12 @@ def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: i
                        block_size=block_size, max_blocks_per_seq=MB, num_blocks=NB, kv_dtype=kv_dtype, scale=scale,
                        q=q, k_cache=k_cache, v_cache=v_cache, block_tables=tables, context_lens=lens,
                        k_scale=k_scale, v_scale=v_scale, seed=seed, q_len=q_len,
+                       shared_prefix_blocks=shared_prefix_blocks,
                        meta={"sigma": sigma, "table_kind": table_kind, "poison": poison})
 
 
 # --------------------------------------------------------------------------------------
-# the five named configurations
+# the named configurations
 # --------------------------------------------------------------------------------------
 CONFIG_NAMES = {
     1: "tiny_b2_gqa2_d64",
@@ -284,6 +317,7 @@ CONFIG_NAMES = {
     3: "long_b8_ctx32k-128k_bf16",
     4: "ragged_b256_ctx16-16k_bf16",
     5: "llama3_70b_heads_b128_ctx8192_fp8",
+    6: "prompt_cache_b20_prefix32k_suffix128-255_bf16",
 }
 
 
@@ -306,6 +340,11 @@ def config_context_lens(config: int, seed: int, length_scale: float = 1.0) -> np
         return np.maximum(1, np.round(np.exp(u))).astype(np.int32)
     if config == 5:
         return np.full(128, s(8192), dtype=np.int32)
+    if config == 6:
+        # 20 concurrent requests over one cached 32k-token prefix, each with a suffix of 128 tokens and up to
+        # 127 tokens generated so far
+        prefix = (s(32768) // 32) * 32
+        return (prefix + 128 + rng.integers(0, 128, size=20)).astype(np.int32)
     raise ValueError(f"unknown config {config}")
 
 
@@ -329,4 +368,8 @@ def make_config(config: int, seed: Optional[int] = None, poison: bool = True, le
         return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, table_kind="interleaved", poison=poison, q_len=q_len)
     if config == 5:
         return make_batch(name, seed, lens, 64, 8, 128, 16, KV_FP8_E4M3, 1.0, poison=poison, q_len=q_len)
+    if config == 6:
+        prefix_tokens = (max(1, int(round(32768 * length_scale))) // 32) * 32
+        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len,
+                          shared_prefix_blocks=prefix_tokens // 16)
     raise ValueError(config)

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def shape(**kw):
     base = dict(batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
-                num_blocks=1024, max_context_len=0, num_partitions=0)
+                num_blocks=1024, max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0)
     base.update(kw)
     return pa.make_shape(**base)
 
@@ -93,6 +93,51 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     assert pa.pa_kernel_variant(shape(num_q_heads=8, q_len=4), pa.PA_KV_BF16) == "mfma"
 
 
+def test_shared_prefix_plan_and_workspace():
+    B, Hq, D, prefix_blocks = 4, 32, 128, 9          # 9 blocks: 4 whole tiles are shared, the 9th block is not
+    lens = [144, 145, 400, 1000]
+    for forced in (0, 1, 3, 5):
+        s = shape(batch=B, shared_prefix_blocks=prefix_blocks, num_partitions=forced)
+        P = pa.pa_num_partitions(s, pa.PA_KV_BF16)
+        T, plan = pa.pa_split_plan(s, pa.PA_KV_BF16, lens)
+        tiles = [-(-L // 32) - 4 for L in lens]
+        assert T == sum(tiles)
+        # the prefix blocks: the same range id in every row, ranges balanced over the 4 prefix tiles
+        assert np.all(plan[:, :8] <= -2) and np.all(plan[:, :8] == plan[0, :8])
+        ranges = -2 - plan[0, :8:2]
+        assert np.array_equal(plan[0, :8:2], plan[0, 1:8:2]) and ranges[0] == 0 and np.all(np.diff(ranges) >= 0)
+        Pp = ranges[-1] + 1
+        assert 1 <= Pp <= 4 and sorted(set(ranges)) == list(range(Pp))
+        # the rest: a balanced cut of the remaining tiles in batch order
+        t = 0
+        for b, L in enumerate(lens):
+            nblk = -(-L // 16)
+            for lt in range(4, 4 + tiles[b]):
+                k = plan[b, 2 * lt]
+                assert (k * T) // P <= t < ((k + 1) * T) // P
+                if 2 * lt + 1 < nblk:
+                    assert plan[b, 2 * lt + 1] == k
+                t += 1
+            assert np.all(plan[b, nblk:] == -1)
+        # partials of the rest + one log-sum-exp per row + Pp partial results over the prefix
+        need = (0 if P == 1 else 2 * P * Hq * (D + 1) * 4) + B * Hq * 4 + Pp * B * Hq * (D + 1) * 4
+        got = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
+        assert need <= got <= need + 5 * 256
+    with pytest.raises(pa.PaError):  # a context that ends inside the shared prefix
+        pa.pa_split_plan(shape(batch=B, shared_prefix_blocks=prefix_blocks), pa.PA_KV_BF16, [144, 100, 400, 1000])
+    # one shared block is less than a tile: the call is the plain one
+    s1 = shape(batch=B, shared_prefix_blocks=1)
+    assert pa.pa_decode_workspace_size(s1, pa.PA_KV_BF16) == pa.pa_decode_workspace_size(shape(batch=B), pa.PA_KV_BF16)
+    # the instrumented entry point has no prefix pass
+    s = shape(batch=B, shared_prefix_blocks=prefix_blocks)
+    vp = ctypes.c_void_p
+    need = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
+    st = pa.lib().pa_decode_trace(vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000), vp(0x5000), ctypes.c_float(0.1), 0,
+                                  vp(0x6000), None, None, ctypes.byref(s), vp(0x10000), ctypes.c_size_t(need), None,
+                                  vp(0x7000))
+    assert st == pa.PA_ERR_UNSUPPORTED
+
+
 def test_split_plan_rejects_lengths_above_the_bound():
     s = shape(max_context_len=100)
     with pytest.raises(pa.PaError):
@@ -113,6 +158,12 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(q_len=16, num_q_heads=128), pa.PA_ERR_UNSUPPORTED),           # 16 tokens x 16 heads > 128 rows per KV head
     (dict(q_len=2, num_q_heads=8), pa.PA_ERR_UNSUPPORTED),              # 2 rows per KV head: below the matrix-core path
     (dict(q_len=4, head_dim=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # windows need head_dim 128
+    (dict(shared_prefix_blocks=-2), pa.PA_ERR_INVALID_ARG),
+    (dict(shared_prefix_blocks=257), pa.PA_ERR_INVALID_ARG),              # more than a table row holds
+    (dict(shared_prefix_blocks=8, max_context_len=100), pa.PA_ERR_INVALID_ARG),  # contexts shorter than the prefix
+    (dict(shared_prefix_blocks=8, q_len=4), pa.PA_ERR_UNSUPPORTED),
+    (dict(shared_prefix_blocks=8, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # groups of 2: no matrix-core pass
+    (dict(shared_prefix_blocks=8, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected(bad, code):
     s = shape(**bad)
