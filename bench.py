@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--q-len", type=int, default=1,
                     help="query tokens per sequence (default 1: plain decode, the metric's workload; 2..16 times "
                          "the multi-token verification call over the same KV cache instead)")
+    ap.add_argument("--window", type=int, default=0, help="sliding window in tokens (default 0: none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -88,11 +89,11 @@ def main():
     torch.cuda.set_device(0)
 
     t0 = time.time()
-    batch = W.make_config(args.workload, seed=args.seed, poison=False, q_len=args.q_len)
+    batch = W.make_config(args.workload, seed=args.seed, poison=False, q_len=args.q_len, window=args.window)
     gen_s = time.time() - t0
     shared_blocks = 0 if args.no_shared_prefix else batch.shared_prefix_blocks
     # bytes the step has to read: every valid K/V slot once per sequence that owns it, a declared shared prefix once
-    kv_bytes = batch.kv_bytes_unique if shared_blocks > 0 else batch.kv_bytes
+    kv_bytes = batch.kv_bytes_unique if shared_blocks > 0 else batch.kv_bytes_visible
     pool_bytes = batch.k_cache.nbytes + batch.v_cache.nbytes
     n_pools = args.pools if args.pools > 0 else max(2, min(8, -(-(2 << 30) // max(pool_bytes, 1))))
 
@@ -165,7 +166,9 @@ def main():
         "dtype": "bf16" if batch.kv_dtype == W.KV_BF16 else "fp8_e4m3",
         "data": "synthetic",
         "config": {
-            "workload": batch.name if args.q_len == 1 else f"{batch.name}_qlen{args.q_len}", "q_len": args.q_len,
+            "workload": batch.name + (f"_qlen{args.q_len}" if args.q_len > 1 else "")
+            + (f"_window{args.window}" if args.window > 0 else ""),
+            "q_len": args.q_len, "window": args.window,
             "batch": batch.batch, "num_q_heads": batch.num_q_heads,
             "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "block_size": batch.block_size,
             "total_context_tokens": batch.total_tokens, "kv_bytes": kv_bytes, "seed": batch.seed,

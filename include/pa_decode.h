@@ -56,6 +56,15 @@
  * ids of the prefix are taken from row 0 of block_tables.  Supported for plain decode
  * (q_len <= 1), head_dim 128 and 4 <= G <= 16.
  *
+ * Sliding window (shape.window = W > 0; attention over the last W positions only, as in the
+ * streaming encoder of the paper's Appendix A, Scenario D, whose per-stream cache is evicted in
+ * step with the window): the sum above runs over t in [max(0, p - W + 1), p], p being the query's
+ * position (context_lens[b] - 1 for plain decode, context_lens[b] - Q + i for query token i of a
+ * multi-token call).  Blocks that lie entirely before the earliest window of a sequence
+ * (before token context_lens[b] - Q - W + 1) are never dereferenced: their table entries may be
+ * stale.  Supported on the matrix-core kernels (head_dim 128, 4 <= Q * G <= 128), not together
+ * with a shared prefix.
+ *
  * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
  * 1 <= G <= 16 (G <= 8 for head_dim 64); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
  * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
@@ -99,6 +108,8 @@ typedef struct pa_shape {
                                    every row of block_tables are the same physical blocks (a prompt prefix
                                    cached once for the whole batch) and every context is at least that long:
                                    those blocks are then read once for all sequences (see pa_decode) */
+    int32_t window;             /* 0 = every query sees its whole past; W > 0 = sliding window: the query at
+                                   position t sees tokens t-W+1 .. t only (see pa_decode) */
 } pa_shape;
 
 /*
@@ -120,6 +131,8 @@ int32_t pa_num_partitions(const pa_shape *shape, pa_kv_dtype kv_dtype);
  * The plan as the kernels apply it, computed on the host from a HOST copy of the context
  * lengths: block_partition (HOST, [batch, max_blocks_per_seq]) receives, for every KV block
  * that holds a valid token, the index of the partition that processes it, and -1 elsewhere.
+ * With a sliding window only the tiles from the one holding the first visible token on are
+ * counted and assigned, and blocks entirely before that token stay -1.
  * With a shared prefix T counts the tiles after the prefix only, a length below the prefix is an
  * error, and the entries of the prefix blocks hold -2 - r, r being the range of the prefix tiles
  * (cut into balanced ranges in the same way) whose workgroups read the block.

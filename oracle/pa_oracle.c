@@ -92,9 +92,9 @@ static double load_kv(const problem *p, const void *cache, const float *head_sca
 }
 
 /* One output row: query vector qrow (head h) of sequence b against that sequence's logical
- * tokens 0 .. L-1.  scores has room for L doubles.  Returns 0, or -2 on a block id outside the
- * pool for a valid token. */
-static int attend_row(const problem *p, int b, int h, const uint16_t *qrow, int L, double *scores,
+ * tokens t_first .. L-1 (t_first = 0 unless a sliding window cuts the past off).  scores has room
+ * for L doubles.  Returns 0, or -2 on a block id outside the pool for a visible token. */
+static int attend_row(const problem *p, int b, int h, const uint16_t *qrow, int t_first, int L, double *scores,
                       double *out_row, double *lse_out, double *probs_row)
 {
     const int G = p->Hq / p->Hkv;
@@ -108,7 +108,7 @@ static int attend_row(const problem *p, int b, int h, const uint16_t *qrow, int 
         return 0;
     }
     double smax = -INFINITY;
-    for (int t = 0; t < L; ++t) {
+    for (int t = t_first; t < L; ++t) {
         int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];
         if (phys < 0 || phys >= p->NB)
             return -2;
@@ -120,11 +120,11 @@ static int attend_row(const problem *p, int b, int h, const uint16_t *qrow, int 
             smax = scores[t];
     }
     double denom = 0.0;
-    for (int t = 0; t < L; ++t) {
+    for (int t = t_first; t < L; ++t) {
         scores[t] = exp(scores[t] - smax);
         denom += scores[t];
     }
-    for (int t = 0; t < L; ++t) {
+    for (int t = t_first; t < L; ++t) {
         int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];
         double w = scores[t] / denom;
         if (probs_row)
@@ -141,16 +141,19 @@ static int attend_row(const problem *p, int b, int h, const uint16_t *qrow, int 
  * Shared driver: Q query tokens per sequence (q is [B, Q, Hq, D]); query token i of sequence b
  * sees the logical tokens 0 .. L_b - Q + i, i.e. the window's own tokens are the LAST Q tokens
  * of the context and each sees itself and everything before it.  Q == 1 is plain decode.
+ * window > 0 is a sliding window: the query at position pos sees tokens pos-window+1 .. pos only.
  * Rows: row_b == NULL -> all B*Q*Hq rows in layout order, else the (row_b, row_i, row_h) triples
  * (row_i == NULL means token 0).
  */
 static int run_rows(const uint16_t *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                     const int32_t *context_lens, float scale, int kv_dtype, const float *k_scale,
-                    const float *v_scale, int32_t B, int32_t Q, int32_t Hq, int32_t Hkv, int32_t D, int32_t BS,
-                    int32_t MB, int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_i,
+                    const float *v_scale, int32_t B, int32_t Q, int32_t window, int32_t Hq, int32_t Hkv, int32_t D,
+                    int32_t BS, int32_t MB, int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_i,
                     const int32_t *row_h, float *out_f32, double *out_f64, double *lse, double *probs,
                     int64_t probs_stride)
 {
+    if (window < 0)
+        return -1;
     if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !out_f32)
         return -1;
     if (B < 0 || Q <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || BS <= 0 || MB <= 0 || NB <= 0 || Hq % Hkv != 0)
@@ -203,7 +206,8 @@ static int run_rows(const uint16_t *q, const void *k_cache, const void *v_cache,
                 int h = row_h ? row_h[r] : (int)(r % Hq);
                 const uint16_t *qrow = q + (((int64_t)b * Q + i) * Hq + h) * D;
                 int visible = context_lens[b] - Q + 1 + i; /* tokens 0 .. L_b - Q + i */
-                int rc = attend_row(&p, b, h, qrow, visible, scores, row, lse ? &lse[r] : NULL,
+                int t_first = (window > 0 && visible > window) ? visible - window : 0;
+                int rc = attend_row(&p, b, h, qrow, t_first, visible, scores, row, lse ? &lse[r] : NULL,
                                     probs ? probs + r * probs_stride : NULL);
                 if (rc != 0) {
 #pragma omp atomic write
@@ -240,7 +244,7 @@ int pa_oracle_decode(const uint16_t *q, const void *k_cache, const void *v_cache
                      int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_h, float *out_f32,
                      double *out_f64, double *lse, double *probs, int64_t probs_stride)
 {
-    return run_rows(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, k_scale, v_scale, B, 1, Hq,
+    return run_rows(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, k_scale, v_scale, B, 1, 0, Hq,
                     Hkv, D, BS, MB, NB, n_rows, row_b, NULL, row_h, out_f32, out_f64, lse, probs, probs_stride);
 }
 
@@ -261,8 +265,30 @@ int pa_oracle_verify(const uint16_t *q, const void *k_cache, const void *v_cache
 {
     if (row_b && !row_i)
         return -1;
-    return run_rows(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, k_scale, v_scale, B, Q, Hq,
+    return run_rows(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, k_scale, v_scale, B, Q, 0, Hq,
                     Hkv, D, BS, MB, NB, n_rows, row_b, row_i, row_h, out_f32, out_f64, lse, probs, probs_stride);
+}
+
+/*
+ * Sliding-window attention (the attention pattern of the streaming encoder in the paper's
+ * Appendix A, Scenario D, here over the paged cache): as pa_oracle_verify (Q >= 1 query tokens per
+ * sequence, the last Q tokens of each context), but the query at position pos = L_b - Q + i
+ * attends to the window tokens max(0, pos - window + 1) .. pos only.  Table entries and cache
+ * contents before the earliest window of a sequence are never read.
+ */
+int pa_oracle_window(const uint16_t *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                     const int32_t *context_lens, float scale, int kv_dtype, const float *k_scale,
+                     const float *v_scale, int32_t B, int32_t Q, int32_t window, int32_t Hq, int32_t Hkv, int32_t D,
+                     int32_t BS, int32_t MB, int32_t NB, int64_t n_rows, const int32_t *row_b, const int32_t *row_i,
+                     const int32_t *row_h, float *out_f32, double *out_f64, double *lse, double *probs,
+                     int64_t probs_stride)
+{
+    if (row_b && !row_i)
+        return -1;
+    if (window <= 0)
+        return -1;
+    return run_rows(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, k_scale, v_scale, B, Q, window,
+                    Hq, Hkv, D, BS, MB, NB, n_rows, row_b, row_i, row_h, out_f32, out_f64, lse, probs, probs_stride);
 }
 
 /*
@@ -281,6 +307,28 @@ int32_t pa_oracle_visited_blocks(const int32_t *block_tables, const int32_t *con
 }
 
 /*
+ * The same under a sliding window: with `reach` = window + Q - 1 the earliest token any query of
+ * sequence b sees is max(0, L_b - reach); the blocks from the one holding that token to the end of
+ * the context are the ones a correct walk touches.  Writes their ids in logical order and returns
+ * their number; *first_block receives the logical index of the first of them.
+ */
+int32_t pa_oracle_window_blocks(const int32_t *block_tables, const int32_t *context_lens, int32_t MB, int32_t BS,
+                                int32_t b, int32_t reach, int32_t *first_block, int32_t *ids, int32_t cap)
+{
+    int32_t L = context_lens[b];
+    if (L <= 0) {
+        *first_block = 0;
+        return 0;
+    }
+    int32_t t_first = L > reach ? L - reach : 0;
+    int32_t jb = t_first / BS, je = (L - 1) / BS;
+    *first_block = jb;
+    for (int32_t j = jb; j <= je && j - jb < cap; ++j)
+        ids[j - jb] = block_tables[(int64_t)b * MB + j];
+    return je - jb + 1;
+}
+
+/*
  * The split plan written from its definition (the product states it in its public header):
  * every sequence is cut into tiles of 32 tokens, tiles_b = ceil(L_b / 32); the tiles of all
  * sequences in batch order are numbered 0 .. T-1; partition k of P owns the global tiles t with
@@ -288,20 +336,42 @@ int32_t pa_oracle_visited_blocks(const int32_t *block_tables, const int32_t *con
  * holds a valid token this writes the owning partition into block_partition[b*MB + j], and -1
  * for every other entry.  Done the slow way: each tile searches all partitions.  Returns T.
  */
+int64_t pa_oracle_block_partition_window(const int32_t *context_lens, int32_t B, int32_t MB, int32_t BS, int32_t P,
+                                         int32_t reach, int32_t *block_partition);
+
 int64_t pa_oracle_block_partition(const int32_t *context_lens, int32_t B, int32_t MB, int32_t BS, int32_t P,
                                   int32_t *block_partition)
 {
+    return pa_oracle_block_partition_window(context_lens, B, MB, BS, P, 0, block_partition);
+}
+
+/*
+ * The same plan under a sliding window (reach = window + Q - 1 > 0; 0 = no window): tiles keep
+ * their place in the sequence (tile i = tokens 32 i .. 32 i + 31), but only those that hold a token
+ * at or after t_first = max(0, L_b - reach) are numbered and assigned, and a block that lies
+ * entirely before t_first stays -1 even when its tile is assigned.
+ */
+int64_t pa_oracle_block_partition_window(const int32_t *context_lens, int32_t B, int32_t MB, int32_t BS, int32_t P,
+                                         int32_t reach, int32_t *block_partition)
+{
     const int tile_tokens = 32;
     int64_t T = 0;
-    for (int32_t b = 0; b < B; ++b)
-        if (context_lens[b] > 0)
-            T += (context_lens[b] + tile_tokens - 1) / tile_tokens;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t L = context_lens[b];
+        int32_t t_first = (reach > 0 && L > reach) ? L - reach : 0;
+        for (int32_t first = 0; first < L; first += tile_tokens)
+            if (first + tile_tokens > t_first)
+                ++T;
+    }
     for (int64_t i = 0; i < (int64_t)B * MB; ++i)
         block_partition[i] = -1;
     int64_t t = 0;
     for (int32_t b = 0; b < B; ++b) {
         int32_t L = context_lens[b];
-        for (int32_t first = 0; first < L; first += tile_tokens, ++t) {
+        int32_t t_first = (reach > 0 && L > reach) ? L - reach : 0;
+        for (int32_t first = 0; first < L; first += tile_tokens) {
+            if (first + tile_tokens <= t_first)
+                continue;
             int32_t owner = -1;
             for (int32_t k = 0; k < P; ++k) {
                 int64_t lo = ((int64_t)k * T) / P, hi = ((int64_t)(k + 1) * T) / P;
@@ -309,7 +379,9 @@ int64_t pa_oracle_block_partition(const int32_t *context_lens, int32_t B, int32_
                     owner = k;
             }
             for (int32_t tok = first; tok < L && tok < first + tile_tokens; tok += BS)
-                block_partition[(int64_t)b * MB + tok / BS] = owner;
+                if (tok + BS > t_first)
+                    block_partition[(int64_t)b * MB + tok / BS] = owner;
+            ++t;
         }
     }
     return T;

@@ -45,6 +45,13 @@ def lib() -> ctypes.CDLL:
         L.pa_oracle_verify.restype = ctypes.c_int
         L.pa_oracle_verify.argtypes = [p, p, p, p, p, ctypes.c_float, ctypes.c_int, p, p,
                                        i32, i32, i32, i32, i32, i32, i32, i32, i64, p, p, p, p, p, p, p, i64]
+        L.pa_oracle_window.restype = ctypes.c_int
+        L.pa_oracle_window.argtypes = [p, p, p, p, p, ctypes.c_float, ctypes.c_int, p, p,
+                                       i32, i32, i32, i32, i32, i32, i32, i32, i32, i64, p, p, p, p, p, p, p, i64]
+        L.pa_oracle_window_blocks.restype = i32
+        L.pa_oracle_window_blocks.argtypes = [p, p, i32, i32, i32, i32, p, p, i32]
+        L.pa_oracle_block_partition_window.restype = i64
+        L.pa_oracle_block_partition_window.argtypes = [p, i32, i32, i32, i32, i32, p]
         L.pa_oracle_e4m3_table.restype = None
         L.pa_oracle_e4m3_table.argtypes = [p]
         L.pa_oracle_visited_blocks.restype = i32
@@ -121,10 +128,11 @@ def decode(q_bits: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_t
 def verify(q_bits: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_tables: np.ndarray,
            context_lens: np.ndarray, scale, kv_dtype: int = KV_BF16, k_scale: Optional[np.ndarray] = None,
            v_scale: Optional[np.ndarray] = None, rows: Optional[Sequence[Tuple[int, int, int]]] = None,
-           want_f64: bool = False, want_lse: bool = False, want_probs: bool = False):
+           want_f64: bool = False, want_lse: bool = False, want_probs: bool = False, window: int = 0):
     """Multi-token causal verification: q_bits is [B, Q, Hq, D]; query token i of sequence b sees the
-    logical tokens 0 .. L_b - Q + i.  Returns 'out' float32 [B,Q,Hq,D] (or [n_rows,D] when ``rows``
-    selects (b,i,h) triples) and, on request, 'out_f64', 'lse', 'probs' as ``decode`` does."""
+    logical tokens 0 .. L_b - Q + i, or with ``window`` > 0 only the last ``window`` of them (sliding
+    window).  Returns 'out' float32 [B,Q,Hq,D] (or [n_rows,D] when ``rows`` selects (b,i,h) triples)
+    and, on request, 'out_f64', 'lse', 'probs' as ``decode`` does."""
     q_bits = _c(q_bits, np.uint16)
     kv_np = np.uint16 if kv_dtype == KV_BF16 else np.uint8
     k_cache = _c(k_cache, kv_np)
@@ -151,12 +159,16 @@ def verify(q_bits: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_t
     lse = np.zeros(n_rows, dtype=np.float64) if want_lse else None
     stride = MB * BS
     probs = np.zeros((n_rows, stride), dtype=np.float64) if want_probs else None
-    rc = lib().pa_oracle_verify(_ptr(q_bits), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(context_lens),
-                                ctypes.c_float(float(np.float32(scale))), int(kv_dtype), _ptr(k_scale), _ptr(v_scale),
-                                B, Q, Hq, Hkv, D, BS, MB, NB, n_rows, _ptr(rb), _ptr(ri), _ptr(rh), _ptr(out),
-                                _ptr(out64), _ptr(lse), _ptr(probs), stride)
+    common = (_ptr(q_bits), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(context_lens),
+              ctypes.c_float(float(np.float32(scale))), int(kv_dtype), _ptr(k_scale), _ptr(v_scale))
+    tail = (Hq, Hkv, D, BS, MB, NB, n_rows, _ptr(rb), _ptr(ri), _ptr(rh), _ptr(out), _ptr(out64), _ptr(lse),
+            _ptr(probs), stride)
+    if window > 0:
+        rc = lib().pa_oracle_window(*common, B, Q, int(window), *tail)
+    else:
+        rc = lib().pa_oracle_verify(*common, B, Q, *tail)
     if rc != 0:
-        raise RuntimeError(f"pa_oracle_verify failed with code {rc}")
+        raise RuntimeError(f"pa_oracle_verify / pa_oracle_window failed with code {rc}")
     res = {"out": out.reshape(shape)}
     if want_f64:
         res["out_f64"] = out64.reshape(shape)
@@ -169,10 +181,20 @@ def verify(q_bits: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_t
 
 def decode_batch(batch, **kw):
     """Convenience: run on an object with the fields of workloads.DecodeBatch (duck-typed); a batch
-    whose q has a query-token axis ([B, Q, Hq, D]) goes through ``verify``."""
-    fn = verify if np.ndim(batch.q) == 4 else decode
-    return fn(batch.q, batch.k_cache, batch.v_cache, batch.block_tables, batch.context_lens, batch.scale,
-              batch.kv_dtype, batch.k_scale, batch.v_scale, **kw)
+    whose q has a query-token axis ([B, Q, Hq, D]) goes through ``verify``, and so does one with a
+    sliding window (plain decode is then a window of one query token; rows are (b, h) pairs and
+    the result has the shape of q in both cases)."""
+    args = (batch.k_cache, batch.v_cache, batch.block_tables, batch.context_lens, batch.scale, batch.kv_dtype,
+            batch.k_scale, batch.v_scale)
+    window = int(getattr(batch, "window", 0))
+    if np.ndim(batch.q) == 4:
+        return verify(batch.q, *args, window=window, **kw)
+    if window == 0:
+        return decode(batch.q, *args, **kw)
+    rows = kw.pop("rows", None)
+    res = verify(batch.q[:, None], *args, window=window,
+                 rows=None if rows is None else [(b, 0, h) for b, h in rows], **kw)
+    return res if rows is not None else {k: v[:, 0] for k, v in res.items()}
 
 
 def e4m3_table() -> np.ndarray:
@@ -190,13 +212,28 @@ def visited_blocks(block_tables: np.ndarray, context_lens: np.ndarray, block_siz
     return ids[:n].copy()
 
 
-def block_partition(context_lens: np.ndarray, max_blocks_per_seq: int, block_size: int, num_partitions: int):
-    """Owner partition of every KV block under the balanced split plan; returns (T, [B, MB] int32)."""
+def block_partition(context_lens: np.ndarray, max_blocks_per_seq: int, block_size: int, num_partitions: int,
+                    reach: int = 0):
+    """Owner partition of every KV block under the balanced split plan; returns (T, [B, MB] int32).
+    ``reach`` = window + q_len - 1 > 0 restricts the plan to what a sliding window can see."""
     context_lens = _c(context_lens, np.int32)
     out = np.zeros((len(context_lens), max_blocks_per_seq), dtype=np.int32)
-    T = lib().pa_oracle_block_partition(_ptr(context_lens), len(context_lens), max_blocks_per_seq, block_size,
-                                        int(num_partitions), _ptr(out))
+    T = lib().pa_oracle_block_partition_window(_ptr(context_lens), len(context_lens), max_blocks_per_seq, block_size,
+                                               int(num_partitions), int(reach), _ptr(out))
     return int(T), out
+
+
+def window_blocks(block_tables: np.ndarray, context_lens: np.ndarray, block_size: int, b: int, reach: int):
+    """Blocks of sequence b that hold a token some query of a sliding-window call can see: returns
+    (logical index of the first one, their physical ids in logical order)."""
+    block_tables = _c(block_tables, np.int32)
+    context_lens = _c(context_lens, np.int32)
+    MB = block_tables.shape[1]
+    ids = np.zeros(MB, dtype=np.int32)
+    first = ctypes.c_int32(0)
+    n = lib().pa_oracle_window_blocks(_ptr(block_tables), _ptr(context_lens), MB, block_size, b, int(reach),
+                                      ctypes.byref(first), _ptr(ids), MB)
+    return int(first.value), ids[:n].copy()
 
 
 def e4m3_encode(x: float) -> int:

@@ -30,7 +30,7 @@ EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa
 class pa_shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_blocks",
-        "max_context_len", "num_partitions", "q_len", "shared_prefix_blocks")]
+        "max_context_len", "num_partitions", "q_len", "shared_prefix_blocks", "window")]
 
 
 class PaError(RuntimeError):
@@ -84,10 +84,10 @@ def status_string(status: int) -> str:
 
 
 def make_shape(batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks,
-               max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0) -> pa_shape:
+               max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0) -> pa_shape:
     return pa_shape(int(batch), int(num_q_heads), int(num_kv_heads), int(head_dim), int(block_size),
                     int(max_blocks_per_seq), int(num_blocks), int(max_context_len), int(num_partitions),
-                    int(q_len), int(shared_prefix_blocks))
+                    int(q_len), int(shared_prefix_blocks), int(window))
 
 
 def _neg_is_error(v: int, where: str) -> int:
@@ -194,7 +194,7 @@ def pa_decode_profile(q, k_cache, v_cache, block_tables, context_lens, scale, kv
 # --------------------------------------------------------------------------------------
 class DeviceBatch:
     def __init__(self, batch, device="cuda:0", max_context_len: Optional[int] = None, num_partitions: int = 0,
-                 shared_prefix_blocks: Optional[int] = None):
+                 shared_prefix_blocks: Optional[int] = None, window: Optional[int] = None):
         import numpy as np
         import torch
 
@@ -222,7 +222,8 @@ class DeviceBatch:
         self.shape = make_shape(batch.batch, batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.block_size,
                                 batch.max_blocks_per_seq, batch.num_blocks, max_context_len, num_partitions, q_len,
                                 int(getattr(batch, "shared_prefix_blocks", 0)) if shared_prefix_blocks is None
-                                else shared_prefix_blocks)
+                                else shared_prefix_blocks,
+                                int(getattr(batch, "window", 0)) if window is None else window)
         nbytes = pa_decode_workspace_size(self.shape, self.kv_dtype)
         # NaN-filled so that a read of an entry this call did not write shows up in the output
         self.workspace = None if nbytes == 0 else torch.full((nbytes // 4,), float("nan"), dtype=torch.float32,

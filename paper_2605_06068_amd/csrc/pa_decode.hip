@@ -109,7 +109,7 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (kv != PA_KV_BF16 && kv != PA_KV_FP8_E4M3) return PA_ERR_INVALID_ARG;
     if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->head_dim <= 0 || s->block_size <= 0 ||
         s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->num_partitions < 0 ||
-        s->q_len < 0 || s->shared_prefix_blocks < 0)
+        s->q_len < 0 || s->shared_prefix_blocks < 0 || s->window < 0)
         return PA_ERR_INVALID_ARG;
     if (s->shared_prefix_blocks > s->max_blocks_per_seq) return PA_ERR_INVALID_ARG;
     if (s->num_q_heads % s->num_kv_heads != 0) return PA_ERR_INVALID_ARG;
@@ -125,6 +125,9 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
         if (query_len(s) > 1 || !use_mfma(s, kv) || s->batch < 1) return PA_ERR_UNSUPPORTED;
         if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens) return PA_ERR_INVALID_ARG;
     }
+    // sliding windows: matrix-core kernels only, and not together with a shared prefix
+    if (s->window > 0 && (!use_mfma(s, kv) || shared_tiles(s) > 0)) return PA_ERR_UNSUPPORTED;
+    if ((int64_t)s->window + kMaxQueryLen > INT32_MAX / 2) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
     // the global tile index and the launch grid are 32-bit
     const int64_t max_ctx = s->max_context_len > 0 ? s->max_context_len : (int64_t)s->max_blocks_per_seq * s->block_size;
@@ -140,9 +143,13 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     if (st != PA_OK) return st;
     plan->max_ctx = s->max_context_len > 0 ? s->max_context_len : s->max_blocks_per_seq * s->block_size;
     plan->skip_tiles = shared_tiles(s);
-    // tiles the per-sequence kernel can meet at most (those after a shared prefix)
-    const int64_t tile_bound =
-        (int64_t)s->batch * ((plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens - plan->skip_tiles);
+    // tiles the per-sequence kernel can meet at most (those after a shared prefix, those a sliding window reaches)
+    int64_t tiles_per_seq = (plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens - plan->skip_tiles;
+    if (s->window > 0) {
+        const int64_t reach_tiles = ((int64_t)s->window + query_len(s) - 1 + pa::kTileTokens - 1) / pa::kTileTokens + 1;
+        if (tiles_per_seq > reach_tiles) tiles_per_seq = reach_tiles;
+    }
+    const int64_t tile_bound = (int64_t)s->batch * tiles_per_seq;
     if (s->num_partitions > 0) {
         plan->P = s->num_partitions;
     } else {
@@ -310,6 +317,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.Q = query_len(shape);
     p.QH = p.Q * p.Hq;
     p.P = plan.P;
+    p.window = shape->window;
     p.skip_tiles = plan.skip_tiles;
     p.Pp = plan.Pp;
     if (plan.skip_tiles > 0) {
@@ -390,11 +398,13 @@ int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, const int32_t
     if (st != PA_OK) return -(int32_t)st;
     if (shape->batch > 0 && (!context_lens || !block_partition)) return -(int32_t)PA_ERR_INVALID_ARG;
     const int skip = plan.skip_tiles;
+    const int reach = shape->window > 0 ? shape->window + query_len(shape) - 1 : 0;
+    const pa::Span sp{skip, reach};
     int64_t T = 0;
     for (int32_t b = 0; b < shape->batch; ++b) {
         if (context_lens[b] > plan.max_ctx) return -(int32_t)PA_ERR_INVALID_ARG;
         if (context_lens[b] < skip * pa::kTileTokens) return -(int32_t)PA_ERR_INVALID_ARG;  // shorter than the shared prefix
-        T += pa::tiles_of(context_lens[b], skip);
+        T += pa::tiles_of(context_lens[b], sp);
     }
     const int32_t MB = shape->max_blocks_per_seq;
     int32_t k = 0;
@@ -408,9 +418,11 @@ int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, const int32_t
             block_partition[(int64_t)b * MB + 2 * pt] = -2 - kp;
             block_partition[(int64_t)b * MB + 2 * pt + 1] = -2 - kp;
         }
-        for (int32_t lt = skip; lt < skip + pa::tiles_of(L, skip); ++lt, ++t) {
+        const int32_t ft = pa::first_tile(L, sp);
+        for (int32_t lt = ft; lt < ft + pa::tiles_of(L, sp); ++lt, ++t) {
             while (k + 1 < plan.P && pa::part_begin(k + 1, (int)T, plan.P) <= t) ++k;
-            block_partition[(int64_t)b * MB + 2 * lt] = k;
+            // a block that lies entirely before the window is not read
+            if (!(reach > 0 && (2 * lt + 1) * pa::kBlockSize <= L - reach)) block_partition[(int64_t)b * MB + 2 * lt] = k;
             if (2 * lt + 1 < nblk) block_partition[(int64_t)b * MB + 2 * lt + 1] = k;
         }
     }

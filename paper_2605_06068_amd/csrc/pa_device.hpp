@@ -31,6 +31,7 @@ struct Params {
     int32_t Q;                    // query tokens per sequence (1 = plain decode)
     int32_t QH;                   // Q * Hq: output rows per sequence (q, out and the partials are [.., Q, Hq, D])
     int32_t P;                    // number of partitions of the global tile sequence
+    int32_t window;               // sliding window: a query at position t sees tokens t-window+1 .. t (0: everything before it)
     // shared-prefix calls only (skip_tiles > 0): the first skip_tiles tiles of every sequence are one
     // and the same physical blocks; a pass of its own reads them once for all sequences
     int32_t skip_tiles;           // tiles of the shared prefix (0: no shared prefix)

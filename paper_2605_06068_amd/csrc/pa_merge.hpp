@@ -26,15 +26,16 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
     const int lane = threadIdx.x;
     const int P = p.P;
 
-    const int T = total_tiles(p.context_lens, p.B, lane);
+    const Span sp{0, p.window > 0 ? p.window + p.Q - 1 : 0};  // the tiles the partition kernel covered
+    const int T = total_tiles(p.context_lens, p.B, lane, sp);
     if (T <= 0) return;
     const int bj = part_begin(j, T, P);
     if (bj <= 0 || bj >= T) return;
     int b, cum;
-    locate_tile(p.context_lens, p.B, bj, lane, b, cum);
+    locate_tile(p.context_lens, p.B, bj, lane, b, cum, sp);
     if (cum == bj) return;                             // the boundary falls between two sequences
     if (j > 1 && part_begin(j - 1, T, P) > cum) return;  // an earlier boundary inside b does the merge
-    const int end_b = cum + tiles_of(p.context_lens[b]);
+    const int end_b = cum + tiles_of(p.context_lens[b], sp);
 
     float acc[V], wsum = 0.f, mrun = kNegBig;
 #pragma unroll
@@ -122,20 +123,20 @@ __global__ __launch_bounds__(64) void merge_prefix_kernel(const Params p)
     const int h = blockIdx.x;
     const int b = blockIdx.y;
     const int lane = threadIdx.x;
-    const int skip = p.skip_tiles;
+    const Span sp{p.skip_tiles, 0};
     const int P = p.P;
     const int64_t rows = (int64_t)p.B * p.Hq;
     const int64_t row = (int64_t)b * p.Hq + h;
 
     // the sequence's own tiles (those after the prefix) inside the global tile sequence
-    const int T = total_tiles(p.context_lens, p.B, lane, skip);
+    const int T = total_tiles(p.context_lens, p.B, lane, sp);
     int before = 0;
     for (int b0 = 0; b0 < b; b0 += kWave) {
         const int bb = b0 + lane;
-        before += bb < b ? tiles_of(p.context_lens[bb], skip) : 0;
+        before += bb < b ? tiles_of(p.context_lens[bb], sp) : 0;
     }
     const int cum = wave_sum(before);
-    const int nb = tiles_of(p.context_lens[b], skip);
+    const int nb = tiles_of(p.context_lens[b], sp);
     int k_first = 0, nrest = 0;
     bool inside_one = false;
     if (nb > 0) {

@@ -108,20 +108,22 @@ __device__ __forceinline__ void wait_tile(int later_tiles)
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// Position inside the global tile sequence: sequence b, its length and tile count, local tile.
+// Position inside the global tile sequence: sequence b, its length, the first tile of it that the
+// plan covers, the number of tiles it covers, and the local tile (tile ft + lt of the sequence).
 struct Cursor {
-    int b, lt, nt, L;
+    int b, lt, nt, L, ft;
 };
 
-__device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, int B, int skip = 0)
+__device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, int B, Span sp = Span{0, 0})
 {
     if (++c.lt < c.nt) return;
     c.lt = 0;
     do {
         ++c.b;
         c.L = c.b < B ? uniform_load(context_lens, c.b) : 0;
-        c.nt = tiles_of(c.L, skip);
+        c.nt = tiles_of(c.L, sp);
     } while (c.nt == 0 && c.b < B);
+    c.ft = first_tile(c.L, sp);
 }
 
 template <int NSTAGE, int CPAD, int KV, bool TRACE>
@@ -150,12 +152,16 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     const int ncols = Q * G;   // real columns: (query token i, head h of the group) -> column i*G + h
     const int n = lane & 15;   // column of the tile / row-in-block, depending on the operand
     const int q4 = lane >> 4;  // 0..3
-    // shared-prefix calls: local tile lt of a sequence is its tile lt + skip; the tiles before belong
-    // to the prefix pass, and no row this kernel writes is final (the merge adds the prefix part)
+    // Tiles the plan leaves out at the head of every sequence.  Shared-prefix calls: the first
+    // skip tiles belong to the prefix pass, and no row this kernel writes is final (the merge adds
+    // the prefix part).  Sliding window: nothing further back than window + Q - 1 tokens from the
+    // end of a context is visible to any query, and blocks before that are never touched.
     const int skip = p.skip_tiles;
+    const int reach = p.window > 0 ? p.window + Q - 1 : 0;
+    const Span sp{skip, reach};
 
     // ---- this wave's range of the global tile sequence
-    const RangeStart rs = find_range(p.context_lens, B, k, p.P, lane, skip);
+    const RangeStart rs = find_range(p.context_lens, B, k, p.P, lane, sp);
     if (k == 0 && skip == 0) {  // empty contexts: their output rows are zero
         for (int b0 = 0; b0 < B; b0 += kWave) {
             const int b = b0 + lane;
@@ -174,7 +180,8 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     ic.b = first_b;
     ic.lt = rs.t_lo - rs.cum;
     ic.L = rs.L;
-    ic.nt = tiles_of(ic.L, skip);
+    ic.nt = tiles_of(ic.L, sp);
+    ic.ft = first_tile(ic.L, sp);
     Cursor cc = ic;  // compute side
 
     // ---- per-lane address pieces
@@ -245,31 +252,48 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         }
         const int nblk = (ic.L + kBlockSize - 1) / kBlockSize;
         const int32_t* table = p.block_tables + (int64_t)ic.b * p.MB;
-        const int j0 = 2 * (ic.lt + skip);
-        int phys[2], nvalid[2];
-        phys[0] = uniform_load(table, j0);
-        nvalid[0] = min(kBlockSize, ic.L - j0 * kBlockSize);
-        if (j0 + 1 < nblk) {
+        const int j0 = 2 * (ic.lt + ic.ft);
+        // Per block of the tile: its physical id and the rows [lo, hi) that hold tokens some query can
+        // see.  Every other row (past the context, before the earliest window) may hold anything,
+        // NaN patterns included, and is replaced on the way in by row lo of the same block; the
+        // softmax masks those positions.
+        int phys[2], lo[2], hi[2];
+        const int t_first = (reach > 0 && ic.L > reach) ? ic.L - reach : 0;  // first token any query sees
+        lo[0] = min(max(t_first - j0 * kBlockSize, 0), kBlockSize);
+        hi[0] = min(ic.L - j0 * kBlockSize, kBlockSize);
+        // a first block that lies entirely before the window may be gone: its table entry is not read
+        const bool first_gone = lo[0] >= kBlockSize;
+        const bool second = j0 + 1 < nblk;
+        if (second) {
             phys[1] = uniform_load(table, j0 + 1);
-            nvalid[1] = min(kBlockSize, ic.L - (j0 + 1) * kBlockSize);
-        } else {  // no second block: re-read row 0 of the first one, masked out of the softmax later
+            lo[1] = max(t_first - (j0 + 1) * kBlockSize, 0);
+            hi[1] = min(ic.L - (j0 + 1) * kBlockSize, kBlockSize);
+        }
+        if (!first_gone) {
+            phys[0] = uniform_load(table, j0);
+        } else {  // stand-in: the first visible row of the second block (which exists: it holds that token)
+            phys[0] = phys[1];
+            lo[0] = hi[0] = lo[1];
+        }
+        if (!second) {  // no second block: stand-in rows from the first one
             phys[1] = phys[0];
-            nvalid[1] = 1;
+            lo[1] = hi[1] = lo[0];
         }
         if (TRACE && lane == 0) {
             int32_t* v = p.trace_blocks + (((int64_t)ic.b * p.Hkv + g) * p.MB + j0) * 3;
-            v[0] = phys[0]; v[1] = phys[0]; v[2] = k;
-            if (j0 + 1 < nblk) { v[3] = phys[1]; v[4] = phys[1]; v[5] = k; }
+            if (!first_gone) { v[0] = phys[0]; v[1] = phys[0]; v[2] = k; }
+            if (second) { v[3] = phys[1]; v[4] = phys[1]; v[5] = k; }
         }
         const uint32_t ldst = lds0 + stage * kStageBytes;
-        // rows past the context hold garbage (possibly NaN patterns): load row 0 of the block instead
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const char* kb = kc + phys[sub] * head_stride;
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r) {
-                const bool live = r * Geo::kRowsPerDma + lane / Geo::kPieces < nvalid[sub];
-                dma16(ldst + sub * kSlabBytes + r * 1024, live ? dma_off[r] : (dma_off[r] & (Geo::kRow - 1)), kb);
+                const int row = r * Geo::kRowsPerDma + lane / Geo::kPieces;
+                const bool live = row >= lo[sub] && row < hi[sub];
+                dma16(ldst + sub * kSlabBytes + r * 1024,
+                      live ? dma_off[r] : lo[sub] * Geo::kRow + (dma_off[r] & (Geo::kRow - 1)), kb);
             }
         }
 #pragma unroll
@@ -277,11 +301,13 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             const char* vb = vc + phys[sub] * head_stride;
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r) {
-                const bool live = r * Geo::kRowsPerDma + lane / Geo::kPieces < nvalid[sub];
-                dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024, live ? dma_off[r] : (dma_off[r] & (Geo::kRow - 1)), vb);
+                const int row = r * Geo::kRowsPerDma + lane / Geo::kPieces;
+                const bool live = row >= lo[sub] && row < hi[sub];
+                dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024,
+                      live ? dma_off[r] : lo[sub] * Geo::kRow + (dma_off[r] & (Geo::kRow - 1)), vb);
             }
         }
-        advance(ic, p.context_lens, B, skip);
+        advance(ic, p.context_lens, B, sp);
     };
 
     // ---- online softmax state: lane = column n, tokens 4*q4+{0..3} of each block
@@ -348,14 +374,15 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         }
 
         // ---- online softmax (log2 domain); the column sees tokens t < L - col_back
-        const int t0 = (cc.lt + skip) * kTileTokens + 4 * q4;
+        const int t0 = (cc.lt + cc.ft) * kTileTokens + 4 * q4;
         const int lim = cc.L - col_back;
+        const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
         float x[8];
         bool ok[8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            ok[r] = t0 + r < lim;
-            ok[4 + r] = t0 + kBlockSize + r < lim;
+            ok[r] = t0 + r < lim && t0 + r >= low;
+            ok[4 + r] = t0 + kBlockSize + r < lim && t0 + kBlockSize + r >= low;
             x[r] = ok[r] ? s0[r] * qs : kNegBig;
             x[4 + r] = ok[4 + r] ? s1[r] * qs : kNegBig;
         }
@@ -425,7 +452,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                         make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
             }
         }
-        advance(cc, p.context_lens, B, skip);
+        advance(cc, p.context_lens, B, sp);
         stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
     }
 }

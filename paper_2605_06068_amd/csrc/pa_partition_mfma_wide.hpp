@@ -86,6 +86,9 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
     const int n = lane & 15;
     const int q4 = lane >> 4;
 
+    // sliding window (never together with a shared prefix): see the single-wave kernel
+    const int reach = (!PREFIX && p.window > 0) ? p.window + Q - 1 : 0;
+    const Span sp{0, reach};
     RangeStart rs;
     if (PREFIX) {
         rs.T = p.skip_tiles;
@@ -95,7 +98,7 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
         rs.cum = 0;
         rs.L = rs.T * kTileTokens;
     } else {
-        rs = find_range(p.context_lens, B, k, p.P, lane);
+        rs = find_range(p.context_lens, B, k, p.P, lane, sp);
     }
     if (!PREFIX && k == 0 && w == 0) {  // empty contexts: their output rows are zero
         for (int b0 = 0; b0 < B; b0 += kWave) {
@@ -115,7 +118,8 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
     ic.b = first_b;
     ic.lt = rs.t_lo - rs.cum;
     ic.L = rs.L;
-    ic.nt = tiles_of(ic.L);
+    ic.nt = tiles_of(ic.L, sp);
+    ic.ft = first_tile(ic.L, sp);
     Cursor cc = ic;
 
     // ---- this wave's share of a tile's loads: instructions w*PT .. w*PT+PT-1 of the tile's
@@ -190,32 +194,48 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
     auto issue = [&](int stage) {
         const int nblk = (ic.L + kBlockSize - 1) / kBlockSize;
         const int32_t* table = p.block_tables + (int64_t)ic.b * p.MB;
-        const int j0 = 2 * ic.lt;
-        int phys[2], nvalid[2];
-        phys[0] = uniform_load(table, j0);
-        nvalid[0] = min(kBlockSize, ic.L - j0 * kBlockSize);
-        if (j0 + 1 < nblk) {
+        const int j0 = 2 * (ic.lt + ic.ft);
+        // Per block of the tile: its physical id and the rows [lo, hi) that hold tokens some query can
+        // see.  Every other row (past the context, before the earliest window) may hold anything,
+        // NaN patterns included, and is replaced on the way in by row lo of the same block; the
+        // softmax masks those positions.
+        int phys[2], lo[2], hi[2];
+        const int t_first = (reach > 0 && ic.L > reach) ? ic.L - reach : 0;  // first token any query sees
+        lo[0] = min(max(t_first - j0 * kBlockSize, 0), kBlockSize);
+        hi[0] = min(ic.L - j0 * kBlockSize, kBlockSize);
+        // a first block that lies entirely before the window may be gone: its table entry is not read
+        const bool first_gone = lo[0] >= kBlockSize;
+        const bool second = j0 + 1 < nblk;
+        if (second) {
             phys[1] = uniform_load(table, j0 + 1);
-            nvalid[1] = min(kBlockSize, ic.L - (j0 + 1) * kBlockSize);
-        } else {  // no second block: re-read row 0 of the first one, masked out of the softmax later
+            lo[1] = max(t_first - (j0 + 1) * kBlockSize, 0);
+            hi[1] = min(ic.L - (j0 + 1) * kBlockSize, kBlockSize);
+        }
+        if (!first_gone) {
+            phys[0] = uniform_load(table, j0);
+        } else {  // stand-in: the first visible row of the second block (which exists: it holds that token)
+            phys[0] = phys[1];
+            lo[0] = hi[0] = lo[1];
+        }
+        if (!second) {  // no second block: stand-in rows from the first one
             phys[1] = phys[0];
-            nvalid[1] = 1;
+            lo[1] = hi[1] = lo[0];
         }
         if (TRACE && w == 0 && lane == 0) {
             int32_t* v = p.trace_blocks + (((int64_t)ic.b * p.Hkv + g) * p.MB + j0) * 3;
-            v[0] = phys[0]; v[1] = phys[0]; v[2] = k;
-            if (j0 + 1 < nblk) { v[3] = phys[1]; v[4] = phys[1]; v[5] = k; }
+            if (!first_gone) { v[0] = phys[0]; v[1] = phys[0]; v[2] = k; }
+            if (second) { v[3] = phys[1]; v[4] = phys[1]; v[5] = k; }
         }
         const uint32_t ldst = lds0 + stage * kStageBytes;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
             const int sub = my_slab[j] & 1;
             const char* base = (my_slab[j] >> 1 ? vc : kc) + (sub ? phys[1] : phys[0]) * head_stride;
-            // rows past the context hold garbage (possibly NaN patterns): load row 0 of the block instead
-            const bool live = my_tok[j] < (sub ? nvalid[1] : nvalid[0]);
-            dma16(ldst + my_dst[j], live ? my_off[j] : (my_off[j] & (Geo::kRow - 1)), base);
+            const int rlo = sub ? lo[1] : lo[0], rhi = sub ? hi[1] : hi[0];
+            const bool live = my_tok[j] >= rlo && my_tok[j] < rhi;
+            dma16(ldst + my_dst[j], live ? my_off[j] : rlo * Geo::kRow + (my_off[j] & (Geo::kRow - 1)), base);
         }
-        advance(ic, p.context_lens, B);
+        advance(ic, p.context_lens, B, sp);
     };
 
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;
@@ -255,7 +275,7 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
         const char* kbuf = smem + stage * kStageBytes;
         const char* vbuf = kbuf + 2 * kSlabBytes;
         if (!wave_active) {  // keeps loading and meeting the others at the barrier; nothing to compute
-            advance(cc, p.context_lens, B);
+            advance(cc, p.context_lens, B, sp);
             stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
             continue;
         }
@@ -307,14 +327,15 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
         bf16x8 pb, pb_lo;
         auto softmax = [&](auto masked_tag) {
             constexpr bool MASKED = decltype(masked_tag)::value;
-            const int t0 = cc.lt * kTileTokens + 4 * q4;
+            const int t0 = (cc.lt + cc.ft) * kTileTokens + 4 * q4;
             const int lim = cc.L - col_back;
+            const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
             float x[8];
             bool ok[8];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                ok[r] = !MASKED || t0 + r < lim;
-                ok[4 + r] = !MASKED || t0 + kBlockSize + r < lim;
+                ok[r] = !MASKED || (t0 + r < lim && t0 + r >= low);
+                ok[4 + r] = !MASKED || (t0 + kBlockSize + r < lim && t0 + kBlockSize + r >= low);
                 x[r] = ok[r] ? s0[r] * qs : kNegBig;
                 x[4 + r] = ok[4 + r] ? s1[r] * qs : kNegBig;
             }
@@ -341,7 +362,12 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
                 pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
             }
         };
-        if (PREFIX || (cc.lt + 1) * kTileTokens <= cc.L - (Q - 1))
+        // no mask needed: every column sees the whole tile (not at the end of a context, where the
+        // causal limits lie, nor in the tiles where the windows of the columns begin)
+        const int tile_first = (cc.lt + cc.ft) * kTileTokens;
+        const bool unmasked = PREFIX || (tile_first + kTileTokens <= cc.L - (Q - 1) &&
+                                         (reach == 0 || tile_first >= cc.L - p.window));
+        if (unmasked)
             softmax(std::false_type{});
         else
             softmax(std::true_type{});
@@ -388,7 +414,7 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
                         make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
             }
         }
-        advance(cc, p.context_lens, B);
+        advance(cc, p.context_lens, B, sp);
         stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
     }
 }

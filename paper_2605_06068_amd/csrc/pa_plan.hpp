@@ -21,12 +21,28 @@ namespace pa {
 
 constexpr int kTileTokens = 32;
 
-// Tiles of a context of L tokens that this plan covers.  `skip` leading tiles belong to someone
-// else (a prefix shared by the whole batch, handled by a pass of its own): they are left out.
-__host__ __device__ __forceinline__ int tiles_of(int L, int skip = 0)
+// Which tiles of a sequence the plan covers.  `skip` leading tiles belong to someone else (a prefix
+// shared by the whole batch, handled by a pass of its own).  `reach` > 0 bounds how far back from
+// the end of the context any query of the call can see (sliding window: window + q_len - 1
+// tokens); tiles that lie entirely before that are left out as well, and their blocks may be gone.
+struct Span {
+    int skip;
+    int reach;
+};
+
+// first tile of a context of L tokens that the plan covers
+__host__ __device__ __forceinline__ int first_tile(int L, Span sp)
+{
+    const int w = (sp.reach > 0 && L > sp.reach) ? (L - sp.reach) / kTileTokens : 0;
+    return w > sp.skip ? w : sp.skip;
+}
+
+// number of tiles it covers
+__host__ __device__ __forceinline__ int tiles_of(int L, Span sp = Span{0, 0})
 {
     const int n = L > 0 ? (L + kTileTokens - 1) / kTileTokens : 0;
-    return n > skip ? n - skip : 0;
+    const int f = first_tile(L, sp);
+    return n > f ? n - f : 0;
 }
 
 // first global tile of partition k
@@ -53,12 +69,12 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
 }
 
 // Total number of tiles of the batch.  All 64 lanes must call.
-__device__ __forceinline__ int total_tiles(const int32_t* context_lens, int B, int lane, int skip = 0)
+__device__ __forceinline__ int total_tiles(const int32_t* context_lens, int B, int lane, Span sp = Span{0, 0})
 {
     int sum = 0;
     for (int b0 = 0; b0 < B; b0 += kWave) {
         const int b = b0 + lane;
-        sum += b < B ? tiles_of(context_lens[b], skip) : 0;
+        sum += b < B ? tiles_of(context_lens[b], sp) : 0;
     }
     return wave_sum(sum);
 }
@@ -66,14 +82,14 @@ __device__ __forceinline__ int total_tiles(const int32_t* context_lens, int B, i
 // The sequence that contains global tile t (0 <= t < T) and the number of tiles before it.
 // All 64 lanes must call; results are wave-uniform.
 __device__ __forceinline__ void locate_tile(const int32_t* context_lens, int B, int t, int lane, int& b_out, int& cum_out,
-                                            int skip = 0)
+                                            Span sp = Span{0, 0})
 {
     int carry = 0;
     b_out = B - 1;
     cum_out = 0;
     for (int b0 = 0; b0 < B; b0 += kWave) {
         const int b = b0 + lane;
-        const int n = b < B ? tiles_of(context_lens[b], skip) : 0;
+        const int n = b < B ? tiles_of(context_lens[b], sp) : 0;
         const int incl = wave_inclusive_scan(n, lane) + carry;
         const unsigned long long hit = __ballot(incl > t);
         if (hit != 0ull) {
@@ -94,7 +110,7 @@ struct RangeStart {
     int T, t_lo, t_hi, b, cum, L;
 };
 
-__device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, int B, int k, int P, int lane, int skip = 0)
+__device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, int B, int k, int P, int lane, Span sp = Span{0, 0})
 {
     RangeStart r;
     r.b = 0;
@@ -102,7 +118,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     r.L = 0;
     if (B <= kWave) {
         const int L = lane < B ? context_lens[lane] : 0;
-        const int n = tiles_of(L, skip);
+        const int n = tiles_of(L, sp);
         const int incl = wave_inclusive_scan(n, lane);
         r.T = __builtin_amdgcn_readlane(incl, kWave - 1);
         r.t_lo = part_begin(k, r.T, P);
@@ -116,7 +132,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
         }
         return r;
     }
-    r.T = __builtin_amdgcn_readfirstlane(total_tiles(context_lens, B, lane, skip));
+    r.T = __builtin_amdgcn_readfirstlane(total_tiles(context_lens, B, lane, sp));
     r.t_lo = part_begin(k, r.T, P);
     r.t_hi = part_begin(k + 1, r.T, P);
     if (r.t_lo >= r.t_hi) return r;
@@ -124,7 +140,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     for (int b0 = 0; b0 < B; b0 += kWave) {
         const int b = b0 + lane;
         const int L = b < B ? context_lens[b] : 0;
-        const int n = tiles_of(L, skip);
+        const int n = tiles_of(L, sp);
         const int incl = wave_inclusive_scan(n, lane) + carry;
         const unsigned long long hit = __ballot(incl > r.t_lo);
         if (hit != 0ull) {

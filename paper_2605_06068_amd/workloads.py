@@ -64,6 +64,7 @@ class DecodeBatch:
     meta: dict = field(default_factory=dict)
     q_len: int = 1  # query tokens per sequence; > 1: q is [B, Q, Hq, D], the last Q tokens are the window
     shared_prefix_blocks: int = 0  # leading table entries that are the same physical blocks for every sequence
+    window: int = 0  # sliding window: a query at position t sees tokens t-window+1 .. t (0 = its whole past)
 
     @property
     def group(self) -> int:
@@ -88,6 +89,16 @@ class DecodeBatch:
         """The same with the shared prefix counted once: bytes of the distinct valid slots."""
         shared = self.shared_prefix_blocks * self.block_size
         tokens = self.total_tokens - (self.batch - 1) * shared if self.batch > 0 else 0
+        return tokens * self.num_kv_heads * self.head_dim * 2 * self.kv_elem_bytes
+
+    @property
+    def kv_bytes_visible(self) -> int:
+        """Bytes of K and V some query of the step can see: with a sliding window only the last
+        window + q_len - 1 tokens of every context."""
+        if self.window <= 0:
+            return self.kv_bytes
+        reach = self.window + self.q_len - 1
+        tokens = int(np.minimum(self.context_lens.astype(np.int64), reach).sum())
         return tokens * self.num_kv_heads * self.head_dim * 2 * self.kv_elem_bytes
 
 
@@ -214,15 +225,15 @@ def _normal_chunks(seed_seq: np.random.SeedSequence, n_elems: int, sigma: float,
             list(ex.map(work, range(n_chunks)))
 
 
-def _valid_slot_mask(tables: np.ndarray, context_lens: np.ndarray, block_size: int, num_blocks: int) -> np.ndarray:
-    """[NB, BS] bool: slot holds a token of some sequence."""
+def _valid_slot_mask(tables: np.ndarray, context_lens: np.ndarray, block_size: int, num_blocks: int,
+                     reach: int = 0) -> np.ndarray:
+    """[NB, BS] bool: slot holds a token of some sequence (with ``reach`` > 0: one of its last
+    ``reach`` tokens, the only ones a sliding-window call may look at)."""
     valid = np.zeros((num_blocks, block_size), dtype=bool)
     for b, L in enumerate(context_lens):
         L = int(L)
-        nfull, rem = divmod(L, block_size)
-        valid[tables[b, :nfull]] = True
-        if rem:
-            valid[tables[b, nfull], :rem] = True
+        t = np.arange(max(0, L - reach) if reach > 0 else 0, L)
+        valid[tables[b, t // block_size], t % block_size] = True
     return valid
 
 
@@ -230,12 +241,14 @@ def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: i
                head_dim: int, block_size: int = 16, kv_dtype: int = KV_BF16, sigma: float = 1.0,
                num_blocks: Optional[int] = None, max_blocks_per_seq: Optional[int] = None,
                table_kind: str = "permuted", poison: bool = True, q_len: int = 1,
-               shared_prefix_blocks: int = 0) -> DecodeBatch:
+               shared_prefix_blocks: int = 0, window: int = 0) -> DecodeBatch:
     """Draw one decode batch.  ``poison`` fills every slot no valid token owns with NaN patterns
     (parity runs); with ``poison=False`` those slots are zero (timing runs).  ``q_len`` > 1 draws a
     window of that many query tokens per sequence (q becomes [B, Q, Hq, D]); the cache contents do not
     depend on it.  ``shared_prefix_blocks`` > 0 makes that many leading blocks common to all sequences
-    (``table_kind`` is then ignored)."""
+    (``table_kind`` is then ignored).  ``window`` > 0 marks the batch for sliding-window attention:
+    everything before the earliest window of a sequence counts as evicted, i.e. its slots are
+    poisoned like other dead slots and its table entries are set to -1."""
     rng = np.random.default_rng(seed)
     lens = np.asarray(context_lens, dtype=np.int32)
     B = len(lens)
@@ -292,7 +305,11 @@ def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: i
     k_cache = k_cache.reshape(NB, num_kv_heads, block_size, head_dim)
     v_cache = v_cache.reshape(NB, num_kv_heads, block_size, head_dim)
 
-    valid = _valid_slot_mask(tables, lens, block_size, NB)
+    reach = window + q_len - 1 if window > 0 else 0
+    valid = _valid_slot_mask(tables, lens, block_size, NB, reach)
+    if reach > 0 and poison:
+        for b, L in enumerate(lens):
+            tables[b, :max(0, int(L) - reach) // block_size] = -1  # evicted blocks
     fill = nan_pat if poison else nan_pat.dtype.type(0)
     dead_blk, dead_slot = np.nonzero(~valid)
     if dead_blk.size:
@@ -304,7 +321,7 @@ def make_batch(name: str, seed: int, context_lens: Sequence[int], num_q_heads: i
                        block_size=block_size, max_blocks_per_seq=MB, num_blocks=NB, kv_dtype=kv_dtype, scale=scale,
                        q=q, k_cache=k_cache, v_cache=v_cache, block_tables=tables, context_lens=lens,
                        k_scale=k_scale, v_scale=v_scale, seed=seed, q_len=q_len,
-                       shared_prefix_blocks=shared_prefix_blocks,
+                       shared_prefix_blocks=shared_prefix_blocks, window=window,
                        meta={"sigma": sigma, "table_kind": table_kind, "poison": poison})
 
 
@@ -349,7 +366,7 @@ def config_context_lens(config: int, seed: int, length_scale: float = 1.0) -> np
 
 
 def make_config(config: int, seed: Optional[int] = None, poison: bool = True, length_scale: float = 1.0,
-                batch_limit: Optional[int] = None, q_len: int = 1) -> DecodeBatch:
+                batch_limit: Optional[int] = None, q_len: int = 1, window: int = 0) -> DecodeBatch:
     """Build named config 1..5.  Default seed is 1000+config.  ``batch_limit`` keeps only the first
     sequences (same lengths they would have in the full batch).  ``q_len`` > 1 turns the batch into a
     verification step over windows of that many tokens (same cache, more query rows)."""
@@ -359,15 +376,15 @@ def make_config(config: int, seed: Optional[int] = None, poison: bool = True, le
         lens = lens[:batch_limit]
     name = CONFIG_NAMES[config]
     if config == 1:
-        return make_batch(name, seed, lens, 4, 2, 64, 16, KV_BF16, 1.0, num_blocks=16, poison=poison, q_len=q_len)
+        return make_batch(name, seed, lens, 4, 2, 64, 16, KV_BF16, 1.0, num_blocks=16, poison=poison, q_len=q_len, window=window)
     if config == 2:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len)
+        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len, window=window)
     if config == 3:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len)
+        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len, window=window)
     if config == 4:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, table_kind="interleaved", poison=poison, q_len=q_len)
+        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, table_kind="interleaved", poison=poison, q_len=q_len, window=window)
     if config == 5:
-        return make_batch(name, seed, lens, 64, 8, 128, 16, KV_FP8_E4M3, 1.0, poison=poison, q_len=q_len)
+        return make_batch(name, seed, lens, 64, 8, 128, 16, KV_FP8_E4M3, 1.0, poison=poison, q_len=q_len, window=window)
     if config == 6:
         prefix_tokens = (max(1, int(round(32768 * length_scale))) // 32) * 32
         return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len,

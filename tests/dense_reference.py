@@ -24,7 +24,7 @@ def gather_dense(batch, b, g):
     L = int(batch.context_lens[b])
     BS = batch.block_size
     t = np.arange(L)
-    phys = batch.block_tables[b, t // BS]
+    phys = np.maximum(batch.block_tables[b, t // BS], 0)  # evicted entries (-1): any block, the caller masks them
     slot = t % BS
     kraw = batch.k_cache[phys, g, slot, :]
     vraw = batch.v_cache[phys, g, slot, :]
@@ -72,11 +72,12 @@ def torch_sdpa(batch):
     return out
 
 
-def dense_window_attention(batch):
+def dense_window_attention(batch, sliding=0):
     """Multi-token window, out [B,Q,Hq,D] float64: torch's scaled_dot_product_attention in float64 with
     an explicit boolean mask.  Query token i of the window may look at logical token t iff
-    t <= L - Q + i (the window is the last Q tokens of the context; each sees itself and the past).
-    Rows with nothing visible are zero."""
+    t <= L - Q + i (the window is the last Q tokens of the context; each sees itself and the past)
+    and, with ``sliding`` = W > 0, t > L - Q + i - W (the W most recent of those).  Rows with nothing
+    visible are zero.  K/V rows outside every mask may hold anything (they are zeroed first)."""
     import torch
     import torch.nn.functional as F
 
@@ -95,6 +96,13 @@ def dense_window_attention(batch):
         key_pos = torch.arange(L)[None, :]
         last_visible = (L - Q + torch.arange(Q))[:, None]
         mask = key_pos <= last_visible  # [Q, L]
+        if sliding > 0:
+            mask &= key_pos > last_visible - sliding
+            unseen = ~mask.any(dim=0)  # evicted / poisoned rows: keep NaN patterns out of the library call
+            K = K.clone()
+            V = V.clone()
+            K[:, unseen] = 0
+            V[:, unseen] = 0
         seen = mask.any(dim=1)
         safe = mask.clone()
         safe[~seen, 0] = True  # keep the library away from all-masked rows; they are zeroed below

@@ -28,6 +28,12 @@ def core_pins(oracle):
         r = oracle.decode_batch(w, want_f64=True)
         assert np.isfinite(r["out_f64"]).all()
         assert np.max(np.abs(r["out_f64"] - dense_window_attention(w))) <= 1e-12
+        # sliding window on top (band mask); nothing is evicted here, so a window that is too wide shows
+        sw = W.make_batch("s", 7, [2, 37, 100], 8, 2, 64, 16, kv, num_blocks=20, max_blocks_per_seq=9, q_len=3,
+                          window=7, poison=False)
+        r = oracle.decode_batch(sw, want_f64=True)
+        assert np.isfinite(r["out_f64"]).all()
+        assert np.max(np.abs(r["out_f64"] - dense_window_attention(sw, sliding=7))) <= 1e-12
 
 
 def main(so_path):
@@ -35,7 +41,7 @@ def main(so_path):
 
     good = pa_oracle.lib()
     other = ctypes.CDLL(so_path)
-    for fn in ("pa_oracle_decode", "pa_oracle_verify", "pa_oracle_e4m3_table"):
+    for fn in ("pa_oracle_decode", "pa_oracle_verify", "pa_oracle_window", "pa_oracle_e4m3_table"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     pa_oracle._lib = other

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def shape(**kw):
     base = dict(batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
-                num_blocks=1024, max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0)
+                num_blocks=1024, max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0)
     base.update(kw)
     return pa.make_shape(**base)
 
@@ -93,6 +93,21 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     assert pa.pa_kernel_variant(shape(num_q_heads=8, q_len=4), pa.PA_KV_BF16) == "mfma"
 
 
+@pytest.mark.parametrize("Q,window", [(1, 1), (1, 16), (1, 100), (4, 33), (16, 5), (1, 10 ** 6)])
+def test_sliding_window_split_plan_is_the_definition(oracle, Q, window):
+    rng = np.random.default_rng(window + Q)
+    for lens in ([0, 1, 4096, 33], [31, 32, 33, 64], rng.integers(1, 4097, 64).tolist()):
+        for forced in (0, 1, 3, 64):
+            s = shape(batch=len(lens), num_partitions=forced, q_len=Q, window=window)
+            P = pa.pa_num_partitions(s, pa.PA_KV_BF16)
+            T, plan = pa.pa_split_plan(s, pa.PA_KV_BF16, lens)
+            To, want = oracle.block_partition(np.asarray(lens, np.int32), 256, 16, P, reach=window + Q - 1)
+            assert T == To and np.array_equal(plan, want)
+    # a window bounds the tiles a sequence can contribute, hence the partition count
+    few = pa.pa_num_partitions(shape(batch=2, window=40), pa.PA_KV_BF16)
+    assert few <= 2 * 3
+
+
 def test_shared_prefix_plan_and_workspace():
     B, Hq, D, prefix_blocks = 4, 32, 128, 9          # 9 blocks: 4 whole tiles are shared, the 9th block is not
     lens = [144, 145, 400, 1000]
@@ -164,6 +179,10 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(shared_prefix_blocks=8, q_len=4), pa.PA_ERR_UNSUPPORTED),
     (dict(shared_prefix_blocks=8, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # groups of 2: no matrix-core pass
     (dict(shared_prefix_blocks=8, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
+    (dict(window=-1), pa.PA_ERR_INVALID_ARG),
+    (dict(window=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),             # groups of 2: no matrix-core kernel
+    (dict(window=64, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
+    (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected(bad, code):
     s = shape(**bad)

@@ -18,7 +18,8 @@ MUTATIONS = {
                          "p->block_tables[(int64_t)b * (p->MB - 1) + t / p->BS];\n        if"),
     "token to block by modulo": ("int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];\n        double w",
                                  "int64_t phys = p->block_tables[(int64_t)b * p->MB + t % p->BS];\n        double w"),
-    "last token dropped": ("for (int t = 0; t < L; ++t) {\n        scores[t] = exp", "for (int t = 0; t < L - 1; ++t) {\n        scores[t] = exp"),
+    "last token dropped": ("for (int t = t_first; t < L; ++t) {\n        scores[t] = exp",
+                           "for (int t = t_first; t < L - 1; ++t) {\n        scores[t] = exp"),
     "unnormalised": ("double w = scores[t] / denom;", "double w = scores[t];"),
     "v uses k scale": ("load_kv(p, p->v_cache, p->v_scale,", "load_kv(p, p->v_cache, p->k_scale,"),
     "e4m3 bias 8": ("(int)expo - 7);", "(int)expo - 8);"),
@@ -34,6 +35,12 @@ MUTATIONS = {
     "window: no causal mask": ("int visible = context_lens[b] - Q + 1 + i;", "int visible = context_lens[b];"),
     "window: order of the window reversed": ("int visible = context_lens[b] - Q + 1 + i;",
                                              "int visible = context_lens[b] - i;"),
+    "sliding window one token too wide": ("? visible - window : 0;", "? visible - window - 1 : 0;"),
+    "sliding window one token too narrow": ("? visible - window : 0;", "? visible - window + 1 : 0;"),
+    "sliding window counted from the end of the context": ("? visible - window : 0;",
+                                                           "? context_lens[b] - window : 0;"),
+    "sliding window ignored in the value pass": ("for (int t = t_first; t < L; ++t) {\n        int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];\n        double w",
+                                                 "for (int t = 0; t < L; ++t) {\n        int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];\n        double w"),
 }
 
 

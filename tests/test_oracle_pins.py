@@ -309,6 +309,90 @@ def test_window_row_selection_and_single_token_window(oracle):
     assert np.array_equal(one[:, 0], oracle.decode_batch(c)["out"])
 
 
+# ---------------------------------------------------------------- sliding window
+def test_sliding_window_of_one_returns_the_own_value_row(oracle):
+    b = tiny(60, [1, 16, 17, 100], Hq=4, Hkv=2, D=64, q_len=3, window=1, poison=False)
+    out = oracle.decode_batch(b, want_f64=True)["out_f64"]
+    for s, L in enumerate(b.context_lens):
+        for i in range(3):
+            t = L - 3 + i
+            for h in range(4):
+                want = widen_bf16(b.v_cache[b.block_tables[s, t // 16], h // 2, t % 16]) if t >= 0 else np.zeros(64)
+                assert np.array_equal(out[s, i, h], want)
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_sliding_window_wider_than_the_context_changes_nothing(oracle, kv):
+    b = tiny(61, [5, 37, 100], kv=kv, q_len=2)
+    free = oracle.decode_batch(b, want_f64=True, want_lse=True)
+    b.window = 100  # the latest query sits at position 99 and sees 0 .. 99
+    same = oracle.decode_batch(b, want_f64=True, want_lse=True)
+    assert np.array_equal(free["out_f64"], same["out_f64"]) and np.array_equal(free["lse"], same["lse"])
+    b.window = 99
+    cut = oracle.decode_batch(b, want_f64=True)
+    assert np.array_equal(cut["out_f64"][:2], free["out_f64"][:2])        # shorter contexts: still everything
+    assert np.array_equal(cut["out_f64"][2, 0], free["out_f64"][2, 0])    # position 98 sees 0 .. 98
+    assert not np.array_equal(cut["out_f64"][2, 1], free["out_f64"][2, 1])  # position 99 lost token 0
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=62, lens=[1, 16, 17, 33, 255], Hq=8, Hkv=2, D=128, q_len=1, window=20),
+    dict(seed=63, lens=[64, 7, 300], Hq=6, Hkv=6, D=64, q_len=5, window=33),
+    dict(seed=64, lens=[77, 130], Hq=16, Hkv=2, D=128, kv=W.KV_FP8_E4M3, q_len=3, window=16),
+])
+def test_sliding_window_matches_masked_library_attention(oracle, case):
+    """The generator evicts what lies before the earliest window (table entries -1, NaN patterns in
+    the slots): the result must be finite and equal the library's attention under the band mask."""
+    case = dict(case)
+    b = tiny(case.pop("seed"), case.pop("lens"), **case)
+    r = oracle.decode_batch(b, want_f64=True, want_probs=True)
+    assert np.isfinite(r["out_f64"]).all()
+    q4 = b.q if b.q.ndim == 4 else b.q[:, None]
+    view = type("V", (), dict(vars(b), q=q4))()
+    want = dense_window_attention(view, sliding=b.window)
+    got = r["out_f64"] if b.q.ndim == 4 else r["out_f64"][:, None]
+    assert np.max(np.abs(got - want)) <= 1e-10
+    probs = r["probs"] if b.q.ndim == 4 else r["probs"][:, None]
+    for s, L in enumerate(b.context_lens):
+        for i in range(b.q_len):
+            pos = L - b.q_len + i
+            lo = max(0, pos - b.window + 1)
+            if pos >= 0:
+                assert np.all(probs[s, i][:, :lo] == 0) and np.all(probs[s, i][:, pos + 1:] == 0)
+                assert np.all(probs[s, i][:, lo:pos + 1] > 0)
+
+
+def test_sliding_window_blocks_and_plan(oracle):
+    lens = np.array([100, 40, 3, 0, 1000, 31, 32, 33], np.int32)
+    tables = np.arange(8 * 64, dtype=np.int32).reshape(8, 64)
+    for reach in (1, 16, 17, 50, 2000):
+        for s, L in enumerate(lens):
+            first, ids = oracle.window_blocks(tables, lens, 16, s, reach)
+            t_first = max(0, int(L) - reach)
+            want = [tables[s, j] for j in range(64) if j * 16 < L and (j + 1) * 16 > t_first]
+            assert list(ids) == want and (not want or first == t_first // 16)
+        for P in (1, 3, 8):
+            T, owner = oracle.block_partition(lens, 64, 16, P, reach=reach)
+            tiles = [sum(1 for i in range(0, int(L), 32) if i + 32 > max(0, int(L) - reach)) for L in lens]
+            assert T == sum(tiles)
+            flat = []
+            for s, L in enumerate(lens):
+                t_first = max(0, int(L) - reach)
+                for j in range(64):
+                    live = j * 16 < L and (j + 1) * 16 > t_first
+                    assert (owner[s, j] >= 0) == live
+                    if live:
+                        flat.append(owner[s, j])
+            assert all(a <= b for a, b in zip(flat, flat[1:]))
+            counts = np.bincount([owner[s, 2 * i] if owner[s, 2 * i] >= 0 else owner[s, 2 * i + 1]
+                                  for s, L in enumerate(lens) for i in range(32)
+                                  if max(owner[s, 2 * i], owner[s, 2 * i + 1]) >= 0], minlength=P)
+            assert counts.max() - counts.min() <= 1
+    T0, owner0 = oracle.block_partition(lens, 64, 16, 5)
+    T1, owner1 = oracle.block_partition(lens, 64, 16, 5, reach=10 ** 6)
+    assert T0 == T1 and np.array_equal(owner0, owner1)
+
+
 # ---------------------------------------------------------------- fp8 table
 def test_e4m3_table_corner_values_and_torch_cast(oracle):
     t = oracle.e4m3_table()
