@@ -35,7 +35,7 @@
  *     block_tables  [batch, max_blocks_per_seq]                           int32
  *     context_lens  [batch]                                               int32
  *     k_scale, v_scale [num_kv_heads]                                     float32 (fp8 KV only)
- *     out           [batch, num_q_heads, head_dim]                        float32
+ *     out           [batch, num_q_heads, head_dim]                        float32 (bf16 if shape.out_dtype says so)
  *
  * Multi-token verification (shape.q_len = Q in 2 .. 16; the single forward pass over a window of
  * K proposed tokens in the paper's predicted-output speculative decoding, Appendix A, Scenario B):
@@ -89,6 +89,9 @@ typedef enum pa_status {
 
 typedef enum pa_kv_dtype { PA_KV_BF16 = 0, PA_KV_FP8_E4M3 = 1 } pa_kv_dtype;
 
+/* element type of `out` (pa_shape.out_dtype) */
+typedef enum pa_out_dtype { PA_OUT_F32 = 0, PA_OUT_BF16 = 1 } pa_out_dtype;
+
 /* Host-side description of one call.  Everything the launch plan depends on is here, so the
  * plan never needs the device-resident context_lens. */
 typedef struct pa_shape {
@@ -108,6 +111,8 @@ typedef struct pa_shape {
                                    every row of block_tables are the same physical blocks (a prompt prefix
                                    cached once for the whole batch) and every context is at least that long:
                                    those blocks are then read once for all sequences (see pa_decode) */
+    int32_t out_dtype;          /* PA_OUT_F32 (0), or PA_OUT_BF16: out holds bf16, every element the float32 result
+                                   rounded to nearest even (not with a shared prefix) */
     int32_t window;             /* 0 = every query sees its whole past; W > 0 = sliding window: the query at
                                    position t sees tokens t-W+1 .. t only (see pa_decode) */
 } pa_shape;
@@ -164,7 +169,7 @@ size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
  * The result is deterministic run to run (no floating-point atomics).
  */
 pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
-                    const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,
+                    const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,
                     const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
                     size_t workspace_bytes, void *stream);
 
@@ -200,7 +205,7 @@ pa_status pa_kv_append(const void *k_new, const void *v_new, void *k_cache, void
  * Shapes with a shared prefix are PA_ERR_UNSUPPORTED here.
  */
 pa_status pa_decode_trace(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
-                          const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,
+                          const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,
                           const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
                           size_t workspace_bytes, void *stream, int32_t *visited_blocks);
 
@@ -210,7 +215,7 @@ pa_status pa_decode_trace(const void *q, const void *k_cache, const void *v_cach
  * partition kernel and of the merge kernel (0 when no merge is launched).  HOST output pointers.
  */
 pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
-                            const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, float *out,
+                            const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,
                             const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
                             size_t workspace_bytes, void *stream, int32_t steps, float *partition_ms,
                             float *merge_ms);

@@ -23,6 +23,9 @@ PA_ERR_HIP = 4
 PA_KV_BF16 = 0
 PA_KV_FP8_E4M3 = 1
 
+PA_OUT_F32 = 0
+PA_OUT_BF16 = 1
+
 EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa_decode",
            "pa_kv_append", "pa_decode_trace", "pa_decode_profile", "pa_kernel_variant", "pa_status_string")
 
@@ -30,7 +33,7 @@ EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa
 class pa_shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_blocks",
-        "max_context_len", "num_partitions", "q_len", "shared_prefix_blocks", "window")]
+        "max_context_len", "num_partitions", "q_len", "shared_prefix_blocks", "out_dtype", "window")]
 
 
 class PaError(RuntimeError):
@@ -84,10 +87,13 @@ def status_string(status: int) -> str:
 
 
 def make_shape(batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks,
-               max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0) -> pa_shape:
-    return pa_shape(int(batch), int(num_q_heads), int(num_kv_heads), int(head_dim), int(block_size),
-                    int(max_blocks_per_seq), int(num_blocks), int(max_context_len), int(num_partitions),
-                    int(q_len), int(shared_prefix_blocks), int(window))
+               max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0,
+               out_dtype=PA_OUT_F32) -> pa_shape:
+    return pa_shape(batch=int(batch), num_q_heads=int(num_q_heads), num_kv_heads=int(num_kv_heads),
+                    head_dim=int(head_dim), block_size=int(block_size), max_blocks_per_seq=int(max_blocks_per_seq),
+                    num_blocks=int(num_blocks), max_context_len=int(max_context_len),
+                    num_partitions=int(num_partitions), q_len=int(q_len),
+                    shared_prefix_blocks=int(shared_prefix_blocks), out_dtype=int(out_dtype), window=int(window))
 
 
 def _neg_is_error(v: int, where: str) -> int:
@@ -194,7 +200,8 @@ def pa_decode_profile(q, k_cache, v_cache, block_tables, context_lens, scale, kv
 # --------------------------------------------------------------------------------------
 class DeviceBatch:
     def __init__(self, batch, device="cuda:0", max_context_len: Optional[int] = None, num_partitions: int = 0,
-                 shared_prefix_blocks: Optional[int] = None, window: Optional[int] = None):
+                 shared_prefix_blocks: Optional[int] = None, window: Optional[int] = None,
+                 out_dtype: int = PA_OUT_F32):
         import numpy as np
         import torch
 
@@ -216,14 +223,17 @@ class DeviceBatch:
         self.k_scale = up(batch.k_scale)
         self.v_scale = up(batch.v_scale)
         q_len = int(getattr(batch, "q_len", 1))
-        self.out = torch.full(tuple(batch.q.shape), float("nan"), dtype=torch.float32, device=dev)
+        # bf16 output travels as int16 storage (NaN pattern 0x7FC0 until the library writes it)
+        self.out = (torch.full(tuple(batch.q.shape), float("nan"), dtype=torch.float32, device=dev)
+                    if out_dtype == PA_OUT_F32 else
+                    torch.full(tuple(batch.q.shape), 0x7FC0, dtype=torch.int16, device=dev))
         if max_context_len is None:
             max_context_len = int(batch.context_lens.max(initial=0))
         self.shape = make_shape(batch.batch, batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.block_size,
                                 batch.max_blocks_per_seq, batch.num_blocks, max_context_len, num_partitions, q_len,
                                 int(getattr(batch, "shared_prefix_blocks", 0)) if shared_prefix_blocks is None
                                 else shared_prefix_blocks,
-                                int(getattr(batch, "window", 0)) if window is None else window)
+                                int(getattr(batch, "window", 0)) if window is None else window, out_dtype)
         nbytes = pa_decode_workspace_size(self.shape, self.kv_dtype)
         # NaN-filled so that a read of an entry this call did not write shows up in the output
         self.workspace = None if nbytes == 0 else torch.full((nbytes // 4,), float("nan"), dtype=torch.float32,

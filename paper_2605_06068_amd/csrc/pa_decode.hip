@@ -27,8 +27,10 @@ constexpr int kMaxColsMfma = 128;  // eight 16-column MFMA tiles, one per wave o
 constexpr int kMaxQueryLen = 16;
 constexpr int kMfmaStagesBf16 = 2;  // depth of the LDS tile ring of the matrix-core kernel, bf16 KV
 constexpr int kMfmaStagesFp8 = 4;   // same for fp8 KV (tiles are half the size)
-constexpr int kWideStagesBf16 = 4;  // ring depth of the multi-wave kernel (shared by the workgroup's waves)
-constexpr int kWideStagesFp8 = 4;
+// ring depth of the multi-wave kernel (the ring is shared by the workgroup's waves), by KV type
+// and waves per workgroup
+constexpr int kWideStagesBf16[3] = {4, 4, 4};  // 2, 4, 8 waves
+constexpr int kWideStagesFp8[3] = {4, 4, 4};
 constexpr int kWideWavesPerCu = 8;  // resident waves per compute unit the multi-wave plan aims at
 constexpr int kMfmaWavesPerCu = 4;  // one wave per SIMD measured best; more, thinner waves were slower
 constexpr int kLdsPerCu = 160 * 1024;
@@ -71,7 +73,11 @@ int mfma_stages(pa_kv_dtype kv) { return kv == PA_KV_BF16 ? kMfmaStagesBf16 : kM
 // waves per workgroup of the multi-wave kernel: one per 16 columns, rounded up to a power of two
 int wide_waves(int cols) { return cols <= 32 ? 2 : (cols <= 64 ? 4 : 8); }
 
-int wide_stages(pa_kv_dtype kv) { return kv == PA_KV_BF16 ? kWideStagesBf16 : kWideStagesFp8; }
+constexpr int wide_stages(int kv, int nw)
+{
+    const int i = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
+    return kv == PA_KV_BF16 ? kWideStagesBf16[i] : kWideStagesFp8[i];
+}
 
 // waves (one-wave kernel) or workgroups (multi-wave kernel) of the matrix-core path resident per compute unit
 int mfma_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
@@ -82,7 +88,7 @@ int mfma_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
         return fit < kMfmaWavesPerCu ? fit : kMfmaWavesPerCu;
     }
     const int nw = wide_waves(cols);
-    const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(nw, wide_stages(kv), (int)kv);
+    const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(nw, wide_stages((int)kv, nw), (int)kv);
     const int want = kWideWavesPerCu / nw;
     return fit < want ? fit : want;
 }
@@ -109,7 +115,8 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (kv != PA_KV_BF16 && kv != PA_KV_FP8_E4M3) return PA_ERR_INVALID_ARG;
     if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->head_dim <= 0 || s->block_size <= 0 ||
         s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->num_partitions < 0 ||
-        s->q_len < 0 || s->shared_prefix_blocks < 0 || s->window < 0)
+        s->q_len < 0 || s->shared_prefix_blocks < 0 || s->window < 0 ||
+        (s->out_dtype != PA_OUT_F32 && s->out_dtype != PA_OUT_BF16))
         return PA_ERR_INVALID_ARG;
     if (s->shared_prefix_blocks > s->max_blocks_per_seq) return PA_ERR_INVALID_ARG;
     if (s->num_q_heads % s->num_kv_heads != 0) return PA_ERR_INVALID_ARG;
@@ -123,6 +130,8 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (shared_tiles(s) > 0) {
         // the per-sequence pass runs on the one-wave matrix-core kernel, the prefix pass on the multi-wave one
         if (query_len(s) > 1 || !use_mfma(s, kv) || s->batch < 1) return PA_ERR_UNSUPPORTED;
+        // the merge of such calls reads rows of `out` back as float32
+        if (s->out_dtype != PA_OUT_F32) return PA_ERR_UNSUPPORTED;
         if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens) return PA_ERR_INVALID_ARG;
     }
     // sliding windows: matrix-core kernels only, and not together with a shared prefix
@@ -177,7 +186,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         const int group_cols = cols < kMaxColsMfma ? cols : kMaxColsMfma;
         plan->prefix_waves = wide_waves(group_cols);
         plan->prefix_groups = (cols + 16 * plan->prefix_waves - 1) / (16 * plan->prefix_waves);
-        const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(plan->prefix_waves, wide_stages(kv), (int)kv);
+        const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(plan->prefix_waves, wide_stages((int)kv, plan->prefix_waves), (int)kv);
         const int want = kWideWavesPerCu / plan->prefix_waves;
         const int per_cu = fit < want ? fit : want;
         int64_t Pp = (int64_t)compute_units() * per_cu / ((int64_t)s->num_kv_heads * plan->prefix_groups);
@@ -237,37 +246,38 @@ void launch_mfma_c(const Params& p, bool trace, dim3 grid, hipStream_t st)
         launch_mfma<NSTAGE, 16, KV>(p, trace, grid, st);
 }
 
-template <int NW, int NSTAGE, int KV>
+template <int NW, int KV>
 void launch_wide(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
+    constexpr int NSTAGE = wide_stages(KV, NW);
     if (trace)
         hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, true, false>), grid, dim3(NW * 64), 0, st, p);
     else
         hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
 }
 
-template <int NSTAGE, int KV>
+template <int KV>
 void launch_wide_w(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
     const int nw = wide_waves(p.Q * p.G);
     if (nw == 2)
-        launch_wide<2, NSTAGE, KV>(p, trace, grid, st);
+        launch_wide<2, KV>(p, trace, grid, st);
     else if (nw == 4)
-        launch_wide<4, NSTAGE, KV>(p, trace, grid, st);
+        launch_wide<4, KV>(p, trace, grid, st);
     else
-        launch_wide<8, NSTAGE, KV>(p, trace, grid, st);
+        launch_wide<8, KV>(p, trace, grid, st);
 }
 
 // the pass over the prefix all sequences share
-template <int NSTAGE, int KV>
+template <int KV>
 void launch_prefix(const Params& p, int nw, dim3 grid, hipStream_t st)
 {
     if (nw == 2)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<2, NSTAGE, KV, false, true>), grid, dim3(128), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<2, wide_stages(KV, 2), KV, false, true>), grid, dim3(128), 0, st, p);
     else if (nw == 4)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<4, NSTAGE, KV, false, true>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<4, wide_stages(KV, 4), KV, false, true>), grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<8, NSTAGE, KV, false, true>), grid, dim3(512), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<8, wide_stages(KV, 8), KV, false, true>), grid, dim3(512), 0, st, p);
 }
 
 struct Events {
@@ -275,7 +285,7 @@ struct Events {
 };
 
 pa_status run(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
-              const int32_t* context_lens, float scale, pa_kv_dtype kv, float* out, const float* k_scale,
+              const int32_t* context_lens, float scale, pa_kv_dtype kv, void* out, const float* k_scale,
               const float* v_scale, const pa_shape* shape, void* workspace, size_t workspace_bytes, void* stream,
               int32_t* trace_blocks, bool trace, const Events* ev)
 {
@@ -304,7 +314,8 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.context_lens = context_lens;
     p.k_scale = k_scale;
     p.v_scale = v_scale;
-    p.out = out;
+    p.out = static_cast<float*>(out);
+    p.out_bf16 = shape->out_dtype == PA_OUT_BF16 ? 1 : 0;
     p.part_o = plan.P > 1 ? static_cast<float*>(workspace) : nullptr;
     p.part_lse = plan.P > 1 ? reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.lse_offset) : nullptr;
     p.trace_blocks = trace ? trace_blocks : nullptr;
@@ -333,17 +344,17 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     if (plan.skip_tiles > 0) {
         const dim3 pgrid((uint32_t)plan.Pp * (uint32_t)p.Hkv * (uint32_t)plan.prefix_groups);
         if (kv == PA_KV_BF16)
-            launch_prefix<kWideStagesBf16, pa::KV_BF16>(p, plan.prefix_waves, pgrid, hs);
+            launch_prefix<pa::KV_BF16>(p, plan.prefix_waves, pgrid, hs);
         else
-            launch_prefix<kWideStagesFp8, pa::KV_FP8>(p, plan.prefix_waves, pgrid, hs);
+            launch_prefix<pa::KV_FP8>(p, plan.prefix_waves, pgrid, hs);
         if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
     }
     const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
     if (use_mfma(shape, kv) && columns(shape) > kMaxColsOneWave) {
         if (kv == PA_KV_BF16)
-            launch_wide_w<kWideStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
+            launch_wide_w<pa::KV_BF16>(p, trace, grid, hs);
         else
-            launch_wide_w<kWideStagesFp8, pa::KV_FP8>(p, trace, grid, hs);
+            launch_wide_w<pa::KV_FP8>(p, trace, grid, hs);
     } else if (use_mfma(shape, kv)) {
         if (kv == PA_KV_BF16)
             launch_mfma_c<kMfmaStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
@@ -436,7 +447,7 @@ size_t pa_decode_workspace_size(const pa_shape* shape, pa_kv_dtype kv_dtype)
 }
 
 pa_status pa_decode(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
-                    const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, float* out, const float* k_scale,
+                    const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, void* out, const float* k_scale,
                     const float* v_scale, const pa_shape* shape, void* workspace, size_t workspace_bytes, void* stream)
 {
     return run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
@@ -444,7 +455,7 @@ pa_status pa_decode(const void* q, const void* k_cache, const void* v_cache, con
 }
 
 pa_status pa_decode_trace(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
-                          const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, float* out,
+                          const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, void* out,
                           const float* k_scale, const float* v_scale, const pa_shape* shape, void* workspace,
                           size_t workspace_bytes, void* stream, int32_t* visited_blocks)
 {
@@ -453,7 +464,7 @@ pa_status pa_decode_trace(const void* q, const void* k_cache, const void* v_cach
 }
 
 pa_status pa_decode_profile(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
-                            const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, float* out,
+                            const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, void* out,
                             const float* k_scale, const float* v_scale, const pa_shape* shape, void* workspace,
                             size_t workspace_bytes, void* stream, int32_t steps, float* partition_ms, float* merge_ms)
 {

@@ -22,7 +22,7 @@ struct Params {
     const int32_t* context_lens;  // [B]
     const float* k_scale;         // [Hkv] or null
     const float* v_scale;
-    float* out;                   // [B, Hq, D]
+    float* out;                   // [B, Hq, D] float32, or the same shape in bf16 when out_bf16 is set
     float* part_o;                // [2P, Hq, D] normalised partial outputs (null when P == 1)
     float* part_lse;              // [2P, Hq]    log2-domain log-sum-exp of each partial
     int32_t* trace_blocks;        // [B, Hkv, MB, 3] or null
@@ -31,6 +31,7 @@ struct Params {
     int32_t Q;                    // query tokens per sequence (1 = plain decode)
     int32_t QH;                   // Q * Hq: output rows per sequence (q, out and the partials are [.., Q, Hq, D])
     int32_t P;                    // number of partitions of the global tile sequence
+    int32_t out_bf16;             // final rows are stored as bf16 (round to nearest even) instead of float32
     int32_t window;               // sliding window: a query at position t sees tokens t-window+1 .. t (0: everything before it)
     // shared-prefix calls only (skip_tiles > 0): the first skip_tiles tiles of every sequence are one
     // and the same physical blocks; a pass of its own reads them once for all sequences
@@ -98,6 +99,36 @@ __device__ __forceinline__ float rows_sum(float v)
     v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
     r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Stores of FINAL output rows (partials in the workspace are always float32).  `elem` is the
+// element index inside `out`, whatever its type.
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void store_out4(const Params& p, int64_t elem, float a, float b, float c, float d)
+{
+    if (p.out_bf16)
+        *reinterpret_cast<bf16x4_t*>(reinterpret_cast<uint16_t*>(p.out) + elem) =
+            bf16x4_t{(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+    else
+        *reinterpret_cast<float4*>(p.out + elem) = make_float4(a, b, c, d);
+}
+
+__device__ __forceinline__ void store_out2(const Params& p, int64_t elem, float a, float b)
+{
+    if (p.out_bf16)
+        *reinterpret_cast<bf16x2_t*>(reinterpret_cast<uint16_t*>(p.out) + elem) = bf16x2_t{(__bf16)a, (__bf16)b};
+    else
+        *reinterpret_cast<float2*>(p.out + elem) = make_float2(a, b);
+}
+
+__device__ __forceinline__ void store_out1(const Params& p, int64_t elem, float a)
+{
+    if (p.out_bf16)
+        reinterpret_cast<__bf16*>(p.out)[elem] = (__bf16)a;
+    else
+        p.out[elem] = a;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

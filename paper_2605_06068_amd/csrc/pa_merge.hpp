@@ -99,12 +99,11 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
         __syncthreads();
     }
     const float inv = 1.f / wsum;
-    float* dst = p.out + ((int64_t)b * p.QH + h) * D;
-    if (V == 2) {
-        *reinterpret_cast<float2*>(dst + lane * 2) = make_float2(acc[0] * inv, acc[V - 1] * inv);
-    } else {
-        dst[lane] = acc[0] * inv;
-    }
+    const int64_t row = ((int64_t)b * p.QH + h) * D;
+    if (V == 2)
+        store_out2(p, row + lane * 2, acc[0] * inv, acc[V - 1] * inv);
+    else
+        store_out1(p, row + lane, acc[0] * inv);
 }
 
 // Merge kernel of shared-prefix calls.  One wavefront per (query head h, sequence b) combines, by

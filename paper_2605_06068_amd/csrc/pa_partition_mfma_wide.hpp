@@ -105,8 +105,8 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
             const int b = b0 + lane;
             if (b < B && p.context_lens[b] <= 0) {
                 for (int i = 0; i < Q; ++i) {
-                    float* row = p.out + ((int64_t)b * p.QH + (int64_t)i * p.Hq + g * G) * D;
-                    for (int e = 0; e < G * D; ++e) row[e] = 0.f;
+                    const int64_t row = ((int64_t)b * p.QH + (int64_t)i * p.Hq + g * G) * D;
+                    for (int e = 0; e < G * D; ++e) store_out1(p, row + e, 0.f);
                 }
             }
         }
@@ -396,22 +396,28 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
                 // a column that saw no token (its query sits before this segment) leaves a zero row
                 // with an "empty" log-sum-exp
                 const float inv = l > 0.f ? vs / l : 0.f;
-                float* dst;
-                if (PREFIX) {
-                    const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row;
-                    dst = p.prefix_o + slot * D;
-                    if (q4 == 0) p.prefix_lse[slot] = m + fast_log2(l);
-                } else if (whole) {
-                    dst = p.out + ((int64_t)cc.b * p.QH + col_row) * D;
-                } else {
-                    const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
-                    dst = p.part_o + slot * D;
-                    if (q4 == 0) p.part_lse[slot] = l > 0.f ? m + fast_log2(l) : kNegBig;
-                }
+                if (!PREFIX && whole) {
+                    const int64_t row = ((int64_t)cc.b * p.QH + col_row) * D;
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt)
-                    *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
-                        make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
+                    for (int dt = 0; dt < 8; ++dt)
+                        store_out4(p, row + 16 * dt + 4 * q4, acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv,
+                                   acc[dt][3] * inv);
+                } else {
+                    float* dst;
+                    if (PREFIX) {
+                        const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row;
+                        dst = p.prefix_o + slot * D;
+                        if (q4 == 0) p.prefix_lse[slot] = m + fast_log2(l);
+                    } else {
+                        const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
+                        dst = p.part_o + slot * D;
+                        if (q4 == 0) p.part_lse[slot] = l > 0.f ? m + fast_log2(l) : kNegBig;
+                    }
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt)
+                        *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
+                            make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
+                }
             }
         }
         advance(cc, p.context_lens, B, sp);

@@ -54,8 +54,8 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
         for (int b0 = 0; b0 < B; b0 += kWave) {
             const int b = b0 + lane;
             if (b < B && p.context_lens[b] <= 0) {
-                float* orow = p.out + ((int64_t)b * p.Hq + g * G) * D;
-                for (int i = 0; i < G * D; ++i) orow[i] = 0.f;
+                const int64_t orow = ((int64_t)b * p.Hq + g * G) * D;
+                for (int i = 0; i < G * D; ++i) store_out1(p, orow + i, 0.f);
             }
         }
     }
@@ -157,16 +157,17 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
                     }
                     if (row == 0) {
                         const int hq = g * G + h;
-                        float* dst;
                         if (whole) {
-                            dst = p.out + ((int64_t)b * p.Hq + hq) * D + c * 8;
+                            const int64_t e0 = ((int64_t)b * p.Hq + hq) * D + c * 8;
+                            store_out4(p, e0, o8[0], o8[1], o8[2], o8[3]);
+                            store_out4(p, e0 + 4, o8[4], o8[5], o8[6], o8[7]);
                         } else {
                             const int64_t slot = ((int64_t)2 * k + (b != first_b ? 1 : 0)) * p.Hq + hq;
-                            dst = p.part_o + slot * D + c * 8;
+                            float* dst = p.part_o + slot * D + c * 8;
                             if (c == 0) p.part_lse[slot] = mt + fast_log2(lt_sum);
+                            *reinterpret_cast<float4*>(dst) = make_float4(o8[0], o8[1], o8[2], o8[3]);
+                            *reinterpret_cast<float4*>(dst + 4) = make_float4(o8[4], o8[5], o8[6], o8[7]);
                         }
-                        *reinterpret_cast<float4*>(dst) = make_float4(o8[0], o8[1], o8[2], o8[3]);
-                        *reinterpret_cast<float4*>(dst + 4) = make_float4(o8[4], o8[5], o8[6], o8[7]);
                     }
                 }
             }

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def shape(**kw):
     base = dict(batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
-                num_blocks=1024, max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0)
+                num_blocks=1024, max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0, out_dtype=0)
     base.update(kw)
     return pa.make_shape(**base)
 
@@ -183,6 +183,9 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(window=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),             # groups of 2: no matrix-core kernel
     (dict(window=64, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
     (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
+    (dict(out_dtype=2), pa.PA_ERR_INVALID_ARG),
+    (dict(out_dtype=-1), pa.PA_ERR_INVALID_ARG),
+    (dict(out_dtype=pa.PA_OUT_BF16, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected(bad, code):
     s = shape(**bad)
