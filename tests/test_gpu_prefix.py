@@ -142,3 +142,12 @@ def test_prompt_cache_workload_sampled_rows(pa, oracle):
     sel = np.stack([got[s, h] for s, h in rows])
     err = assert_parity(sel[:, None, :], want[:, None, :], b.kv_dtype, "prompt-cache workload")
     print(f"        {len(rows)} sampled rows max_abs={err[0]:.3e} worst row rel_l2={err[1]:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("B", [65, 130])
+def test_shared_prefix_many_sequences(pa, oracle, B):
+    """More sequences than lanes: several column groups in the prefix pass, chunked scans in the
+    per-sequence pass and in the merge."""
+    b = W.make_batch("prefix-many", 550 + B, suffix_lens(6, B, B), 8, 2, 128, 16, W.KV_BF16, shared_prefix_blocks=6)
+    for P in (0, 1, 9):
+        check(pa, oracle, b, f"shared-prefix many-sequences P={P}", num_partitions=P)

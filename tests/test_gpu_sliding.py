@@ -154,3 +154,16 @@ def test_sliding_window_full_size_sampled_rows(pa, oracle, config, Q, window):
     err = assert_parity(sel[:, None, :], want[:, None, :], b.kv_dtype, f"config{config} sliding Q={Q} W={window}")
     print(f"        {len(rows)} sampled rows max_abs={err[0]:.3e} worst row rel_l2={err[1]:.3e} "
           f"P={pa.pa_num_partitions(dev.shape, dev.kv_dtype)}", flush=True)
+
+
+@pytest.mark.parametrize("B", [65, 130])
+@pytest.mark.parametrize("Q", [1, 8])
+def test_sliding_window_many_short_sequences(pa, oracle, B, Q):
+    rng = np.random.default_rng(B + Q)
+    lens = rng.integers(1, 200, size=B)
+    lens[rng.random(B) < 0.2] = 0
+    lens[0] = 0
+    b = W.make_batch("sliding-many", 680 + B, lens.tolist(), 8, 2, 128, 16, W.KV_BF16, max_blocks_per_seq=13, q_len=Q,
+                     window=40)
+    for P in (0, 1, 7, 50):
+        check(pa, oracle, b, f"sliding many-sequences P={P}", num_partitions=P)

@@ -188,3 +188,16 @@ def test_window_repeated_calls_share_one_workspace(pa, oracle):
         assert_parity(flat(got), flat(want), b.kv_dtype, f"call {i}")
         first = got if first is None else first
         assert np.array_equal(got, first)
+
+
+@pytest.mark.parametrize("B", [65, 130])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 2), (16, 8, 2)])
+def test_window_many_short_sequences(pa, oracle, B, Q, Hq, Hkv):
+    """More sequences than lanes (the length scan runs in 64-sequence chunks), empty ones sprinkled in."""
+    rng = np.random.default_rng(B + Q)
+    lens = rng.integers(1, 120, size=B)
+    lens[rng.random(B) < 0.2] = 0
+    lens[0] = 0
+    b = W.make_batch("window-many", 380 + B, lens.tolist(), Hq, Hkv, 128, 16, W.KV_BF16, max_blocks_per_seq=8, q_len=Q)
+    for P in (0, 1, 7, 50):
+        check(pa, oracle, b, f"window many-sequences P={P}", num_partitions=P)
