@@ -147,7 +147,8 @@ int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, const int32_t
                       int32_t *block_partition);
 
 /* Bytes of device workspace pa_decode needs for this shape: two partial results (normalised
- * output row + log-sum-exp per query head and query token) per partition; with a shared prefix in
+ * output row + log-sum-exp per query head and query token) per partition, and 16 bytes per
+ * partition that tell the merge kernel where the partition's range starts; with a shared prefix in
  * addition one partial result per range of the prefix and one log-sum-exp per output row.  0 when P == 1.  Returns 0 as well for
  * an invalid shape (pa_decode then reports the error). */
 size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);

@@ -29,9 +29,12 @@ constexpr int kMfmaStagesBf16 = 2;  // depth of the LDS tile ring of the matrix-
 constexpr int kMfmaStagesFp8 = 4;   // same for fp8 KV (tiles are half the size)
 // ring depth of the multi-wave kernel (the ring is shared by the workgroup's waves), by KV type
 // and waves per workgroup
-constexpr int kWideStagesBf16[3] = {4, 4, 4};  // 2, 4, 8 waves
+constexpr int kWideStagesBf16[3] = {4, 4, 3};  // 2, 4, 8 waves (8 waves: 3 stages leave room for two workgroups per CU)
 constexpr int kWideStagesFp8[3] = {4, 4, 4};
-constexpr int kWideWavesPerCu = 8;  // resident waves per compute unit the multi-wave plan aims at
+// resident waves per compute unit the multi-wave plan aims at, LDS permitting: two workgroups of
+// up to 4 waves; two of 8 waves pay off for bf16 only (measured: fp8 with 128 columns is bound by
+// instruction issue, and more partitions only lengthen the merge)
+constexpr int wide_waves_per_cu(int kv, int nw) { return (nw == 8 && kv == PA_KV_BF16) ? 16 : 8; }
 constexpr int kMfmaWavesPerCu = 4;  // one wave per SIMD measured best; more, thinner waves were slower
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kValuWavesPerCu = 8;
@@ -42,6 +45,7 @@ struct Plan {
     int32_t P;          // partitions of the global tile sequence
     int32_t max_ctx;    // resolved max context length
     size_t lse_offset;  // byte offset of the lse array inside the workspace
+    size_t desc_offset; // byte offset of the merge descriptors
     size_t ws_bytes;
     // shared-prefix calls
     int32_t skip_tiles;       // tiles of the shared prefix (0: none)
@@ -89,7 +93,7 @@ int mfma_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
     }
     const int nw = wide_waves(cols);
     const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(nw, wide_stages((int)kv, nw), (int)kv);
-    const int want = kWideWavesPerCu / nw;
+    const int want = wide_waves_per_cu((int)kv, nw) / nw;
     return fit < want ? fit : want;
 }
 
@@ -175,7 +179,8 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     const size_t o_bytes = plan->P == 1 ? 0 : rows * s->head_dim * sizeof(float);
     const auto pad = [](size_t n) { return (n + 255) / 256 * 256; };
     plan->lse_offset = pad(o_bytes);
-    plan->ws_bytes = plan->P == 1 ? 0 : plan->lse_offset + pad(rows * sizeof(float));
+    plan->desc_offset = plan->lse_offset + pad(rows * sizeof(float));
+    plan->ws_bytes = plan->P == 1 ? 0 : plan->desc_offset + pad((size_t)plan->P * 4 * sizeof(int32_t));
     plan->Pp = 0;
     plan->prefix_waves = plan->prefix_groups = 0;
     plan->seq_lse_offset = plan->prefix_o_offset = plan->prefix_lse_offset = 0;
@@ -187,7 +192,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         plan->prefix_waves = wide_waves(group_cols);
         plan->prefix_groups = (cols + 16 * plan->prefix_waves - 1) / (16 * plan->prefix_waves);
         const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(plan->prefix_waves, wide_stages((int)kv, plan->prefix_waves), (int)kv);
-        const int want = kWideWavesPerCu / plan->prefix_waves;
+        const int want = wide_waves_per_cu((int)kv, plan->prefix_waves) / plan->prefix_waves;
         const int per_cu = fit < want ? fit : want;
         int64_t Pp = (int64_t)compute_units() * per_cu / ((int64_t)s->num_kv_heads * plan->prefix_groups);
         if (s->num_partitions > 0) Pp = s->num_partitions;  // tests force both counts with one knob
@@ -318,6 +323,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.out_bf16 = shape->out_dtype == PA_OUT_BF16 ? 1 : 0;
     p.part_o = plan.P > 1 ? static_cast<float*>(workspace) : nullptr;
     p.part_lse = plan.P > 1 ? reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.lse_offset) : nullptr;
+    p.merge_desc = plan.P > 1 ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.desc_offset) : nullptr;
     p.trace_blocks = trace ? trace_blocks : nullptr;
     p.scale_log2 = scale * pa::kLog2e;
     p.B = shape->batch;
@@ -376,7 +382,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
 
     if (plan.skip_tiles > 0) {
         const dim3 mgrid(p.Hq, p.B);
-        hipLaunchKernelGGL((pa::merge_prefix_kernel<128>), mgrid, dim3(64), 0, hs, p);
+        hipLaunchKernelGGL((pa::merge_prefix_kernel<128>), mgrid, dim3(pa::kMergePrefixWaves * pa::kWave), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
     } else if (plan.P > 1) {
         const dim3 mgrid(p.QH, plan.P - 1);

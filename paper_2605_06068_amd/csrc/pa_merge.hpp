@@ -5,7 +5,8 @@
 // One wavefront per (partition boundary j in [1, P), output row h of a sequence: query head, or
 // (query token, query head) pair of a multi-token call).  Boundary j sits at global
 // tile part_begin(j).  The wave whose boundary is the FIRST one strictly inside a sequence b
-// merges that sequence; all other waves exit.  The partials of b come from the partitions
+// merges that sequence; all other waves exit.  Which boundaries those are, and the sequence's
+// place in the tile sequence, comes from the descriptors the partition kernel wrote.  The partials of b come from the partitions
 // k = j-1, j, j+1, ... whose ranges intersect b: slot 2k when b holds partition k's first tile,
 // slot 2k+1 otherwise (only possible for k = j-1).  Only slots written by the partition kernel
 // of the same call are read.
@@ -26,16 +27,11 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
     const int lane = threadIdx.x;
     const int P = p.P;
 
-    const Span sp{0, p.window > 0 ? p.window + p.Q - 1 : 0};  // the tiles the partition kernel covered
-    const int T = total_tiles(p.context_lens, p.B, lane, sp);
-    if (T <= 0) return;
-    const int bj = part_begin(j, T, P);
-    if (bj <= 0 || bj >= T) return;
-    int b, cum;
-    locate_tile(p.context_lens, p.B, bj, lane, b, cum, sp);
-    if (cum == bj) return;                             // the boundary falls between two sequences
-    if (j > 1 && part_begin(j - 1, T, P) > cum) return;  // an earlier boundary inside b does the merge
-    const int end_b = cum + tiles_of(p.context_lens[b], sp);
+    // the partition kernel left what there is to know about boundary j: see write_merge_desc
+    const int T = uniform_load(p.merge_desc, 4 * j + 3);
+    if (T == 0) return;  // nothing to merge at this boundary
+    const int b = uniform_load(p.merge_desc, 4 * j), cum = uniform_load(p.merge_desc, 4 * j + 1),
+              end_b = uniform_load(p.merge_desc, 4 * j + 2);
 
     float acc[V], wsum = 0.f, mrun = kNegBig;
 #pragma unroll
@@ -106,28 +102,38 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
         store_out1(p, row + lane, acc[0] * inv);
 }
 
-// Merge kernel of shared-prefix calls.  One wavefront per (query head h, sequence b) combines, by
-// their log-sum-exps, every piece of that output row:
+// Merge kernel of shared-prefix calls.  One workgroup of four wavefronts per (query head h,
+// sequence b) combines, by their log-sum-exps, every piece of that output row:
 //   - the Pp partials of the prefix pass (slot kp of prefix_o / prefix_lse), and
 //   - what the per-sequence pass produced over the rest of the context: nothing (the context ends
 //     with the prefix), or the row already in `out` with its log-sum-exp in seq_lse (the rest lies
 //     inside one partition), or the partials of the partitions that cut it (slots as above).
-// The row in `out` is read before it is overwritten by the same wave.
+// The pieces are taken 256 at a time: thread t looks at piece t (address, log-sum-exp), the
+// workgroup agrees on the maximum and the weights, then wave w sums pieces w, w+4, ... with eight
+// row loads in flight, and the four sums are added through LDS.  The row in `out` is read by all
+// before it is overwritten.
+constexpr int kMergePrefixWaves = 4;
+
 template <int D>
-__global__ __launch_bounds__(64) void merge_prefix_kernel(const Params p)
+__global__ __launch_bounds__(kMergePrefixWaves * kWave) void merge_prefix_kernel(const Params p)
 {
     constexpr int V = D / kWave;
-    __shared__ const float* s_row[kWave];
-    __shared__ float s_w[kWave];
+    constexpr int NT = kMergePrefixWaves * kWave;
+    __shared__ const float* s_row[NT];
+    __shared__ float s_w[NT];
+    __shared__ float s_red[2][kMergePrefixWaves];
+    __shared__ float s_acc[kMergePrefixWaves][D];
     const int h = blockIdx.x;
     const int b = blockIdx.y;
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = tid >> 6;
     const Span sp{p.skip_tiles, 0};
     const int P = p.P;
     const int64_t rows = (int64_t)p.B * p.Hq;
     const int64_t row = (int64_t)b * p.Hq + h;
 
-    // the sequence's own tiles (those after the prefix) inside the global tile sequence
+    // the sequence's own tiles (those after the prefix) inside the global tile sequence (every wave computes this)
     const int T = total_tiles(p.context_lens, p.B, lane, sp);
     int before = 0;
     for (int b0 = 0; b0 < b; b0 += kWave) {
@@ -145,15 +151,16 @@ __global__ __launch_bounds__(64) void merge_prefix_kernel(const Params p)
         nrest = inside_one ? 1 : k_last - k_first + 1;
     }
     const int nsrc = p.Pp + nrest;
+    const float* safe_row = p.prefix_o + row * D;  // prefix range 0 of this row: always written, finite
 
     float acc[V], wsum = 0.f, mrun = kNegBig;
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
 
-    for (int base = 0; base < nsrc; base += kWave) {
-        const int s = base + lane;
+    for (int base = 0; base < nsrc; base += NT) {
+        const int s = base + tid;
         bool valid = s < nsrc;
-        const float* src = p.out;
+        const float* src = safe_row;
         float lse = kNegBig;
         if (valid) {
             if (s < p.Pp) {
@@ -166,40 +173,45 @@ __global__ __launch_bounds__(64) void merge_prefix_kernel(const Params p)
                 const int kk = k_first + (s - p.Pp);
                 const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
                 valid = hi > lo;  // partitions without tiles wrote nothing
-                const int64_t slot = (int64_t)(2 * kk + ((kk == k_first && lo != cum) ? 1 : 0)) * p.Hq + h;
-                src = p.part_o + slot * D;
-                if (valid) lse = p.part_lse[slot];
+                if (valid) {
+                    const int64_t slot = (int64_t)(2 * kk + ((kk == k_first && lo != cum) ? 1 : 0)) * p.Hq + h;
+                    src = p.part_o + slot * D;
+                    lse = p.part_lse[slot];
+                }
             }
         }
+        // workgroup-wide maximum of the log-sum-exps
         float cm = lse;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) cm = fmaxf(cm, __shfl_xor(cm, o, kWave));
+        if (lane == 0) s_red[0][w] = cm;
+        __syncthreads();
+        cm = fmaxf(fmaxf(s_red[0][0], s_red[0][1]), fmaxf(s_red[0][2], s_red[0][3]));
         const float m_new = fmaxf(mrun, cm);
         const float rescale = fast_exp2(mrun - m_new);
-        const float w = valid ? fast_exp2(lse - m_new) : 0.f;
-        float ws = w;
+        const float wt = valid ? fast_exp2(lse - m_new) : 0.f;
+        float ws = wt;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) ws += __shfl_xor(ws, o, kWave);
-        wsum = wsum * rescale + ws;
+        if (lane == 0) s_red[1][w] = ws;
+        s_row[tid] = src;
+        s_w[tid] = wt;
+        __syncthreads();
+        wsum = wsum * rescale + (s_red[1][0] + s_red[1][1]) + (s_red[1][2] + s_red[1][3]);
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] *= rescale;
         mrun = m_new;
 
-        const unsigned long long vmask = __ballot(valid);
-        const int pos = __popcll(vmask & ((1ull << lane) - 1ull));
-        const int cnt = __popcll(vmask);
-        if (valid) {
-            s_row[pos] = src;
-            s_w[pos] = w;
-        }
-        __syncthreads();
-        for (int i0 = 0; i0 < cnt; i0 += 8) {
+        // wave w sums pieces w, w + 4, ... of this batch, eight row loads in flight
+        const int cnt = min(NT, nsrc - base);
+        const int mine = cnt > w ? (cnt - w + kMergePrefixWaves - 1) / kMergePrefixWaves : 0;
+        for (int i0 = 0; i0 < mine; i0 += 8) {
             float wv[8];
             float2 xv[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int idx = min(i0 + u, cnt - 1);
-                wv[u] = (i0 + u < cnt) ? s_w[idx] : 0.f;
+                const int idx = w + kMergePrefixWaves * min(i0 + u, mine - 1);
+                wv[u] = (i0 + u < mine) ? s_w[idx] : 0.f;
                 const float* r = s_row[idx];
                 if (V == 2) {
                     xv[u] = *reinterpret_cast<const float2*>(r + lane * 2);
@@ -214,14 +226,24 @@ __global__ __launch_bounds__(64) void merge_prefix_kernel(const Params p)
                 if (V == 2) acc[V - 1] = fmaf(wv[u], xv[u].y, acc[V - 1]);
             }
         }
-        __syncthreads();
+        __syncthreads();  // s_row / s_w / s_red are reused by the next batch
     }
-    const float inv = 1.f / wsum;
-    float* dst = p.out + row * D;
-    if (V == 2) {
-        *reinterpret_cast<float2*>(dst + lane * 2) = make_float2(acc[0] * inv, acc[V - 1] * inv);
-    } else {
-        dst[lane] = acc[0] * inv;
+    // add the four waves' sums; every read of the row in `out` has been consumed by now
+#pragma unroll
+    for (int i = 0; i < V; ++i) s_acc[w][lane * V + i] = acc[i];
+    __syncthreads();
+    if (w == 0) {
+        const float inv = 1.f / wsum;
+        float o[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+            o[i] = ((s_acc[0][lane * V + i] + s_acc[1][lane * V + i]) + (s_acc[2][lane * V + i] + s_acc[3][lane * V + i])) * inv;
+        float* dst = p.out + row * D;
+        if (V == 2) {
+            *reinterpret_cast<float2*>(dst + lane * 2) = make_float2(o[0], o[V - 1]);
+        } else {
+            dst[lane] = o[0];
+        }
     }
 }
 

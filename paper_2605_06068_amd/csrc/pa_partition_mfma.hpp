@@ -173,6 +173,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             }
         }
     }
+    if (g == 0 && k > 0 && skip == 0) write_merge_desc(p.merge_desc, p.context_lens, B, k, p.P, rs, lane, sp);
     if (rs.t_lo >= rs.t_hi) return;
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;

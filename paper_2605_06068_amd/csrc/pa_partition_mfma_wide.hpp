@@ -111,6 +111,7 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
             }
         }
     }
+    if (!PREFIX && g == 0 && k > 0 && w == 0) write_merge_desc(p.merge_desc, p.context_lens, B, k, p.P, rs, lane, sp);
     if (rs.t_lo >= rs.t_hi) return;  // the same for every wave of the workgroup
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;

@@ -59,6 +59,7 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
             }
         }
     }
+    if (g == 0 && k > 0) write_merge_desc(p.merge_desc, p.context_lens, B, k, p.P, rs, lane, Span{0, 0});
     if (rs.t_lo >= rs.t_hi) return;
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;

@@ -155,6 +155,34 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     return r;
 }
 
+// What the merge kernel needs to know about partition boundary k (the start of partition k's
+// range, k >= 1), written by the partition kernel's wave (k, KV head 0) so that the merge waves
+// neither scan the context lengths nor locate the boundary again: {b, cum, end, T} = the
+// sequence holding the boundary tile, the tiles before it, its last tile + 1 and the total tile
+// count, with T = 0 when this boundary triggers no merge (it falls between two sequences or
+// outside the tile sequence, or an earlier boundary lies inside the same sequence).
+// All 64 lanes must call.
+__device__ __forceinline__ void write_merge_desc(int32_t* desc, const int32_t* context_lens, int B, int k, int P,
+                                                 const RangeStart& rs, int lane, Span sp)
+{
+    const int bj = rs.t_lo;
+    const bool in_range = bj > 0 && bj < rs.T;
+    int b = rs.b, cum = rs.cum, L = rs.L;
+    if (in_range && rs.t_lo >= rs.t_hi) {  // a partition without tiles: find_range did not locate its start
+        locate_tile(context_lens, B, bj, lane, b, cum, sp);
+        L = context_lens[b];
+    }
+    const bool merges = in_range && cum != bj && !(k > 1 && part_begin(k - 1, rs.T, P) > cum);
+    if (lane == 0) {
+        int4 d;
+        d.x = b;
+        d.y = cum;
+        d.z = cum + tiles_of(L, sp);
+        d.w = merges ? rs.T : 0;
+        *reinterpret_cast<int4*>(desc + 4 * k) = d;
+    }
+}
+
 // Uniform (scalar-cache) load of a 32-bit word: keeps table and length lookups off the
 // vector-memory counter that the hand-scheduled LDS-DMA ring relies on.
 __device__ __forceinline__ int32_t uniform_load(const int32_t* p, int64_t idx)
