@@ -180,15 +180,20 @@ pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, con
  * and value rows of the token generated in this step into the cache, at logical position
  * context_lens[b] - 1 of sequence b (the lengths already count the new token; sequences with
  * context_lens[b] <= 0 are skipped), i.e. into block block_tables[b][(L-1) / block_size], slot
- * (L-1) % block_size.
+ * (L-1) % block_size.  With shape.q_len = Q > 1 (the window of proposed tokens a verification
+ * call is about to look at, Appendix A, Scenario B) it stores Q rows per sequence, token i at
+ * position context_lens[b] - Q + i (tokens whose position would be negative are skipped).
  *
- *   k_new, v_new   device bf16 [batch, num_kv_heads, head_dim], 16-byte aligned
+ *   k_new, v_new   device bf16 [batch, num_kv_heads, head_dim] ([batch, Q, num_kv_heads, head_dim]
+ *                  for Q > 1), 16-byte aligned
  *   k_cache, v_cache, block_tables, context_lens   device, layouts above (caches are written)
  *   kv_dtype       PA_KV_BF16: rows are copied.  PA_KV_FP8_E4M3: every element is divided by its
  *                  KV head's scale (k_scale / v_scale, float32 division) and rounded to the nearest
  *                  e4m3 value, ties to even, saturating at +-448.  Inputs must be finite.
  *
- * One kernel on `stream`; no workspace; can be captured into a HIP graph together with pa_decode.
+ * Only batch, num_kv_heads, head_dim, block_size, max_blocks_per_seq and q_len of the shape matter
+ * here (the shape must be valid as a whole).  One kernel on `stream`; no workspace; can be
+ * captured into a HIP graph together with pa_decode.
  */
 pa_status pa_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                        const int32_t *block_tables, const int32_t *context_lens, pa_kv_dtype kv_dtype,

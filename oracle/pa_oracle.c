@@ -409,31 +409,33 @@ unsigned pa_oracle_e4m3_encode(float x)
 }
 
 /*
- * KV append by its definition: for every sequence with L_b > 0 the new token's key and value
- * rows (bf16, [B, Hkv, D]) go to logical position L_b - 1, i.e. block block_tables[b][(L_b-1)/BS],
- * slot (L_b-1) % BS.  bf16 caches receive the bit patterns unchanged; e4m3 caches receive
+ * KV append by its definition: the key and value rows of the Q tokens added in this step (bf16,
+ * [B, Q, Hkv, D]; Q = 1 is the ordinary decode step) go to the last Q logical positions of each
+ * context, token i to position t = L_b - Q + i (skipped when t < 0), i.e. block
+ * block_tables[b][t/BS], slot t % BS.  bf16 caches receive the bit patterns unchanged; e4m3 caches receive
  * encode(float(x) / scale[g]) with the division in float32 (the precision the product states for
  * this decision).  Returns 0, -1 bad argument, -2 block id outside the pool.
  */
 int pa_oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, void *k_cache, void *v_cache,
                         const int32_t *block_tables, const int32_t *context_lens, int kv_dtype, const float *k_scale,
-                        const float *v_scale, int32_t B, int32_t Hkv, int32_t D, int32_t BS, int32_t MB, int32_t NB)
+                        const float *v_scale, int32_t B, int32_t Q, int32_t Hkv, int32_t D, int32_t BS, int32_t MB,
+                        int32_t NB)
 {
-    if (!k_new || !v_new || !k_cache || !v_cache || !block_tables || !context_lens)
+    if (!k_new || !v_new || !k_cache || !v_cache || !block_tables || !context_lens || Q < 1)
         return -1;
     if (kv_dtype == PA_ORACLE_KV_FP8_E4M3 && (!k_scale || !v_scale))
         return -1;
-    for (int32_t b = 0; b < B; ++b) {
-        int32_t L = context_lens[b];
-        if (L <= 0)
+    for (int64_t bi = 0; bi < (int64_t)B * Q; ++bi) {
+        int32_t b = (int32_t)(bi / Q), i = (int32_t)(bi % Q);
+        int32_t t = context_lens[b] - Q + i;
+        if (t < 0)
             continue;
-        int32_t t = L - 1;
         int64_t phys = block_tables[(int64_t)b * MB + t / BS];
         if (phys < 0 || phys >= NB)
             return -2;
         for (int32_t g = 0; g < Hkv; ++g)
             for (int32_t d = 0; d < D; ++d) {
-                int64_t src = ((int64_t)b * Hkv + g) * D + d;
+                int64_t src = (((int64_t)b * Q + i) * Hkv + g) * D + d;
                 int64_t dst = ((phys * Hkv + g) * BS + t % BS) * (int64_t)D + d;
                 if (kv_dtype == PA_ORACLE_KV_BF16) {
                     ((uint16_t *)k_cache)[dst] = k_new[src];

@@ -61,7 +61,7 @@ def lib() -> ctypes.CDLL:
         L.pa_oracle_e4m3_encode.restype = ctypes.c_uint
         L.pa_oracle_e4m3_encode.argtypes = [ctypes.c_float]
         L.pa_oracle_kv_append.restype = ctypes.c_int
-        L.pa_oracle_kv_append.argtypes = [p, p, p, p, p, p, ctypes.c_int, p, p, i32, i32, i32, i32, i32, i32]
+        L.pa_oracle_kv_append.argtypes = [p, p, p, p, p, p, ctypes.c_int, p, p, i32, i32, i32, i32, i32, i32, i32]
         L.pa_oracle_num_threads.restype = ctypes.c_int
         L.pa_oracle_num_threads.argtypes = []
         _lib = L
@@ -243,7 +243,8 @@ def e4m3_encode(x: float) -> int:
 def kv_append(k_new: np.ndarray, v_new: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
               block_tables: np.ndarray, context_lens: np.ndarray, kv_dtype: int = KV_BF16,
               k_scale: Optional[np.ndarray] = None, v_scale: Optional[np.ndarray] = None) -> None:
-    """Append in place: k_new/v_new are bf16 bit patterns [B, Hkv, D]; caches are modified."""
+    """Append in place: k_new/v_new are bf16 bit patterns [B, Hkv, D], or [B, Q, Hkv, D] for the Q
+    last tokens of every context; caches are modified."""
     k_new = _c(k_new, np.uint16)
     v_new = _c(v_new, np.uint16)
     kv_np = np.uint16 if kv_dtype == KV_BF16 else np.uint8
@@ -251,14 +252,16 @@ def kv_append(k_new: np.ndarray, v_new: np.ndarray, k_cache: np.ndarray, v_cache
     assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
     block_tables = _c(block_tables, np.int32)
     context_lens = _c(context_lens, np.int32)
-    B, Hkv, D = k_new.shape
+    Q = 1 if k_new.ndim == 3 else k_new.shape[1]
+    B, Hkv, D = k_new.shape[0], k_new.shape[-2], k_new.shape[-1]
+    assert v_new.shape == k_new.shape
     NB, Hkv2, BS, D2 = k_cache.shape
     assert (Hkv2, D2) == (Hkv, D) and block_tables.shape[0] == B
     if kv_dtype == KV_FP8_E4M3:
         k_scale = _c(k_scale, np.float32)
         v_scale = _c(v_scale, np.float32)
     rc = lib().pa_oracle_kv_append(_ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
-                                   _ptr(context_lens), int(kv_dtype), _ptr(k_scale), _ptr(v_scale), B, Hkv, D, BS,
+                                   _ptr(context_lens), int(kv_dtype), _ptr(k_scale), _ptr(v_scale), B, Q, Hkv, D, BS,
                                    block_tables.shape[1], NB)
     if rc != 0:
         raise RuntimeError(f"pa_oracle_kv_append failed with code {rc}")

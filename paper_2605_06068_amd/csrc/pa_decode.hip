@@ -525,7 +525,8 @@ pa_status pa_kv_append(const void* k_new, const void* v_new, void* k_cache, void
         !aligned(block_tables, 4) || !aligned(context_lens, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 4))
         return PA_ERR_INVALID_ARG;
     if (shape->batch == 0) return PA_OK;
-    const int64_t threads = (int64_t)shape->batch * shape->num_kv_heads * (shape->head_dim / 8);
+    const int Q = query_len(shape);
+    const int64_t threads = (int64_t)shape->batch * Q * shape->num_kv_heads * (shape->head_dim / 8);
     if ((threads + 255) / 256 > INT32_MAX) return PA_ERR_UNSUPPORTED;
     const dim3 grid((uint32_t)((threads + 255) / 256));
     hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -535,17 +536,17 @@ pa_status pa_kv_append(const void* k_new, const void* v_new, void* k_cache, void
     if (shape->head_dim == 128) {
         if (kv_dtype == PA_KV_BF16)
             hipLaunchKernelGGL((pa::kv_append_kernel<128, pa::KV_BF16>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
-                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+                               block_tables, context_lens, k_scale, v_scale, B, Q, Hkv, MB);
         else
             hipLaunchKernelGGL((pa::kv_append_kernel<128, pa::KV_FP8>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
-                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+                               block_tables, context_lens, k_scale, v_scale, B, Q, Hkv, MB);
     } else {
         if (kv_dtype == PA_KV_BF16)
             hipLaunchKernelGGL((pa::kv_append_kernel<64, pa::KV_BF16>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
-                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+                               block_tables, context_lens, k_scale, v_scale, B, Q, Hkv, MB);
         else
             hipLaunchKernelGGL((pa::kv_append_kernel<64, pa::KV_FP8>), grid, dim3(256), 0, hs, kn, vn, k_cache, v_cache,
-                               block_tables, context_lens, k_scale, v_scale, B, Hkv, MB);
+                               block_tables, context_lens, k_scale, v_scale, B, Q, Hkv, MB);
     }
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }

@@ -1,7 +1,8 @@
-// KV append: stores the key and value rows of the token generated in this step into the paged
-// cache, at logical position context_lens[b] - 1 of every sequence (the lengths already count
-// the new token), quantising to e4m3 with the KV head's scale when the cache is fp8.
-// One thread per 8 consecutive elements of one (sequence, KV head) row.
+// KV append: stores the key and value rows of the Q tokens added in this step (Q = 1: the token
+// just generated; Q > 1: a window of proposed tokens about to be verified) into the paged cache,
+// at logical positions context_lens[b] - Q .. context_lens[b] - 1 of every sequence (the lengths
+// already count the new tokens), quantising to e4m3 with the KV head's scale when the cache is
+// fp8.  One thread per 8 consecutive elements of one (sequence, token, KV head) row.
 #pragma once
 #include "pa_device.hpp"
 
@@ -21,20 +22,21 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const uint16_t* __restri
                                                          void* v_cache, const int32_t* __restrict__ block_tables,
                                                          const int32_t* __restrict__ context_lens,
                                                          const float* __restrict__ k_scale,
-                                                         const float* __restrict__ v_scale, int B, int Hkv, int MB)
+                                                         const float* __restrict__ v_scale, int B, int Q, int Hkv,
+                                                         int MB)
 {
     constexpr int CH = D / 8;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (int64_t)B * Hkv * CH) return;
+    if (i >= (int64_t)B * Q * Hkv * CH) return;
     const int c = (int)(i % CH);
     const int g = (int)((i / CH) % Hkv);
-    const int b = (int)(i / ((int64_t)CH * Hkv));
-    const int L = context_lens[b];
-    if (L <= 0) return;  // nothing was generated for an empty sequence
-    const int t = L - 1;
+    const int tok = (int)((i / ((int64_t)CH * Hkv)) % Q);
+    const int b = (int)(i / ((int64_t)CH * Hkv * Q));
+    const int t = context_lens[b] - Q + tok;
+    if (t < 0) return;  // an empty sequence, or a window that starts before the sequence does
     const int64_t phys = block_tables[(int64_t)b * MB + t / kBlockSize];
     const int64_t dst = ((phys * Hkv + g) * kBlockSize + t % kBlockSize) * D + c * 8;
-    const int64_t src = ((int64_t)b * Hkv + g) * D + c * 8;
+    const int64_t src = (((int64_t)b * Q + tok) * Hkv + g) * D + c * 8;
     const uint4 kw = *reinterpret_cast<const uint4*>(k_new + src);
     const uint4 vw = *reinterpret_cast<const uint4*>(v_new + src);
     if (KV == KV_BF16) {

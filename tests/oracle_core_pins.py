@@ -34,6 +34,18 @@ def core_pins(oracle):
         r = oracle.decode_batch(sw, want_f64=True)
         assert np.isfinite(r["out_f64"]).all()
         assert np.max(np.abs(r["out_f64"] - dense_window_attention(sw, sliding=7))) <= 1e-12
+    # appending a window of Q tokens and then attending over it: token i of the window must be what
+    # query i sees last (one-token windows, so each output is exactly that token's value row)
+    rng = np.random.default_rng(3)
+    a = W.make_batch("a", 8, [9, 40], 4, 2, 64, 16, W.KV_BF16, num_blocks=8, q_len=3, window=1, poison=False)
+    k_new = W.f32_to_bf16_bits(rng.standard_normal((2, 3, 2, 64)).astype(np.float32))
+    v_new = W.f32_to_bf16_bits(rng.standard_normal((2, 3, 2, 64)).astype(np.float32))
+    oracle.kv_append(k_new, v_new, a.k_cache, a.v_cache, a.block_tables, a.context_lens, W.KV_BF16)
+    out = oracle.decode_batch(a)["out"]
+    for s in range(2):
+        for i in range(3):
+            for h in range(4):
+                assert np.array_equal(out[s, i, h], W.bf16_bits_to_f32(v_new[s, i, h // 2]))
 
 
 def main(so_path):
@@ -41,7 +53,8 @@ def main(so_path):
 
     good = pa_oracle.lib()
     other = ctypes.CDLL(so_path)
-    for fn in ("pa_oracle_decode", "pa_oracle_verify", "pa_oracle_window", "pa_oracle_e4m3_table"):
+    for fn in ("pa_oracle_decode", "pa_oracle_verify", "pa_oracle_window", "pa_oracle_e4m3_table",
+               "pa_oracle_kv_append"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     pa_oracle._lib = other

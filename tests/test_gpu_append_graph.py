@@ -61,6 +61,35 @@ def test_append_is_byte_exact(pa, oracle, kv, Hq, Hkv, D):
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 2), (16, 8, 2), (16, 8, 1)])
+def test_window_append_is_byte_exact_and_feeds_verification(pa, oracle, kv, Q, Hq, Hkv):
+    """Q proposed tokens per sequence are appended in one call (byte-exact against the oracle, contexts
+    shorter than the window included) and the verification call then attends over them."""
+    import torch
+
+    rng = np.random.default_rng(17 + Q + Hkv)
+    lens = [17, 0, 32, 3, 100, 16, 33, 255, Q, Q - 1, Q + 1]
+    b = W.make_batch("append-window", 75 + Q, lens, Hq, Hkv, 128, 16, kv, poison=False, q_len=Q)
+    k_new = np.stack([new_rows(rng, len(lens), Hkv, 128, edge=(i == 0)) for i in range(Q)], axis=1)
+    v_new = np.stack([new_rows(rng, len(lens), Hkv, 128, scale=0.5) for i in range(Q)], axis=1)
+    dev = pa.DeviceBatch(b)
+    dk = torch.from_numpy(np.ascontiguousarray(k_new).view(np.int16)).cuda()
+    dv = torch.from_numpy(np.ascontiguousarray(v_new).view(np.int16)).cuda()
+    pa.pa_kv_append(dk, dv, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens, dev.kv_dtype, dev.k_scale,
+                    dev.v_scale, shape=dev.shape)
+    torch.cuda.synchronize()
+    oracle.kv_append(np.ascontiguousarray(k_new), np.ascontiguousarray(v_new), b.k_cache, b.v_cache, b.block_tables,
+                     b.context_lens, kv, b.k_scale, b.v_scale)
+    view = np.int16 if kv == W.KV_BF16 else np.uint8
+    assert np.array_equal(dev.k_cache.cpu().numpy(), b.k_cache.view(view))
+    assert np.array_equal(dev.v_cache.cpu().numpy(), b.v_cache.view(view))
+    got = dev.decode().cpu().numpy()
+    want = oracle.decode_batch(b)["out"]
+    flat = lambda a: a.reshape(a.shape[0], -1, a.shape[-1])
+    assert_parity(flat(got), flat(want), kv, "verification after the window append")
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
 def test_append_and_decode_in_a_hip_graph(pa, oracle, kv):
     """Five decode steps: append the new token's K/V, attend over the grown context.  The two
     library calls are captured once into a HIP graph and replayed with the inputs updated in

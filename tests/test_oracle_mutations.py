@@ -41,6 +41,10 @@ MUTATIONS = {
                                                            "? context_lens[b] - window : 0;"),
     "sliding window ignored in the value pass": ("for (int t = t_first; t < L; ++t) {\n        int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];\n        double w",
                                                  "for (int t = 0; t < L; ++t) {\n        int64_t phys = p->block_tables[(int64_t)b * p->MB + t / p->BS];\n        double w"),
+    "append: window written from the wrong end": ("int32_t t = context_lens[b] - Q + i;",
+                                                   "int32_t t = context_lens[b] - 1 - i;"),
+    "append: token and head axes of the new rows swapped": ("int64_t src = (((int64_t)b * Q + i) * Hkv + g) * D + d;",
+                                                            "int64_t src = (((int64_t)b * Hkv + g) * Q + i) * D + d;"),
 }
 
 

@@ -473,6 +473,33 @@ def test_kv_append_writes_exactly_the_last_slot(oracle, kv):
     assert np.isfinite(out["out"]).all()
 
 
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_kv_append_of_a_window_equals_token_by_token_appends(oracle, kv):
+    """Appending Q tokens at once writes exactly what Q single-token appends write while the context
+    grows to the same length; tokens that would land before position 0 are dropped."""
+    rng = np.random.default_rng(52)
+    Q = 5
+    lens = np.array([17, 0, 32, 3, 100, 5], dtype=np.int32)  # one context shorter than the window
+    b = tiny(52, lens.tolist(), Hq=4, Hkv=2, D=64, kv=kv, poison=False)
+    k_new = bf16(rng.standard_normal((6, Q, 2, 64)))
+    v_new = bf16(rng.standard_normal((6, Q, 2, 64)))
+    k0, v0 = b.k_cache.copy(), b.v_cache.copy()
+    oracle.kv_append(k_new, v_new, b.k_cache, b.v_cache, b.block_tables, b.context_lens, kv, b.k_scale, b.v_scale)
+    k1, v1 = k0.copy(), v0.copy()
+    for i in range(Q):
+        step_lens = lens - (Q - 1 - i)            # the context after token i of the window
+        oracle.kv_append(np.ascontiguousarray(k_new[:, i]), np.ascontiguousarray(v_new[:, i]), k1, v1, b.block_tables,
+                         np.maximum(step_lens, 0).astype(np.int32), kv, b.k_scale, b.v_scale)
+    assert np.array_equal(b.k_cache, k1) and np.array_equal(b.v_cache, v1)
+    # sequence 3 (3 tokens, window of 5): only the last 3 window tokens exist, at positions 0..2
+    phys = b.block_tables[3, 0]
+    if kv == W.KV_BF16:
+        assert np.array_equal(b.k_cache[phys, :, :3], np.swapaxes(k_new[3, 2:], 0, 1))
+    assert np.array_equal(b.k_cache[phys, :, 3:], k0[phys, :, 3:])
+    # the empty sequence got nothing
+    assert (b.k_cache != k0).any() and np.array_equal(b.block_tables[1], np.full_like(b.block_tables[1], -1))
+
+
 # ---------------------------------------------------------------- indexing helpers
 def test_visited_blocks_follow_the_table(oracle):
     b = W.make_config(1)
