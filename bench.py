@@ -72,7 +72,7 @@ def recorded_traffic(workload_name: str):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no sharding or collectives are part of it); "
+        print("bench.py: this library runs on exactly one GPU (no sharding or collectives are part of it); "
               "use --gpus 1", file=sys.stderr)
         return 2
 

@@ -65,7 +65,7 @@
  * stale.  Supported on the matrix-core kernels (head_dim 128, 4 <= Q * G <= 128), not together
  * with a shared prefix.
  *
- * Supported: head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
+ * Supported: batch <= 65535; head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
  * 1 <= G <= 16 (G <= 8 for head_dim 64); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
  * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
  */
@@ -148,7 +148,7 @@ int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, const int32_t
 
 /* Bytes of device workspace pa_decode needs for this shape: two partial results (normalised
  * output row + log-sum-exp per query head and query token) per partition, and 16 bytes per
- * partition that tell the merge kernel where the partition's range starts; with a shared prefix in
+ * sequence that tell the merge kernel whether and where the sequence was cut; with a shared prefix in
  * addition one partial result per range of the prefix and one log-sum-exp per output row.  0 when P == 1.  Returns 0 as well for
  * an invalid shape (pa_decode then reports the error). */
 size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);

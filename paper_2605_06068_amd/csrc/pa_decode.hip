@@ -40,6 +40,10 @@ constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kValuWavesPerCu = 8;
 constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
 constexpr int kMaxPartitions = 65535;
+constexpr int kMaxBatch = 65535;
+constexpr int kMinTilesOneWave = 2;  // tiles a partition should at least have: one-wave kernels
+constexpr int kMinTilesWide = 4;     // multi-wave kernel
+constexpr int kMergeManyPerSeq = 8;  // partitions per sequence from which the multi-wave merge kernel is used
 
 struct Plan {
     int32_t P;          // partitions of the global tile sequence
@@ -131,6 +135,7 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->num_q_heads / s->num_kv_heads > (use_mfma(s, kv) ? kMaxGroupMfma : kMaxGroupValu)) return PA_ERR_UNSUPPORTED;
     if (!use_mfma(s, kv) && query_len(s) > 1) return PA_ERR_UNSUPPORTED;  // multi-token calls: matrix-core kernel only
     if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
+    if (s->batch > kMaxBatch) return PA_ERR_UNSUPPORTED;  // the merge kernels index sequences by blockIdx.y
     if (shared_tiles(s) > 0) {
         // the per-sequence pass runs on the one-wave matrix-core kernel, the prefix pass on the multi-wave one
         if (query_len(s) > 1 || !use_mfma(s, kv) || s->batch < 1) return PA_ERR_UNSUPPORTED;
@@ -170,7 +175,10 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         // but never more than there can be tiles
         const int groups_per_cu = use_mfma(s, kv) ? mfma_groups_per_cu(s, kv) : kValuWavesPerCu;
         int64_t P = (int64_t)compute_units() * groups_per_cu / s->num_kv_heads;
-        if (P > tile_bound) P = tile_bound;
+        // small calls: a partition should have a few tiles to amortise its start-up, and every extra
+        // partition is one more piece per row for the merge (measured on single-sequence calls)
+        const int min_tiles = (use_mfma(s, kv) && columns(s) > kMaxColsOneWave) ? kMinTilesWide : kMinTilesOneWave;
+        if (P > tile_bound / min_tiles) P = tile_bound / min_tiles;
         if (P > kMaxPartitions) P = kMaxPartitions;
         if (P < 1) P = 1;
         plan->P = (int32_t)P;
@@ -180,7 +188,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     const auto pad = [](size_t n) { return (n + 255) / 256 * 256; };
     plan->lse_offset = pad(o_bytes);
     plan->desc_offset = plan->lse_offset + pad(rows * sizeof(float));
-    plan->ws_bytes = plan->P == 1 ? 0 : plan->desc_offset + pad((size_t)plan->P * 4 * sizeof(int32_t));
+    plan->ws_bytes = plan->P == 1 ? 0 : plan->desc_offset + pad((size_t)s->batch * 4 * sizeof(int32_t));
     plan->Pp = 0;
     plan->prefix_waves = plan->prefix_groups = 0;
     plan->seq_lse_offset = plan->prefix_o_offset = plan->prefix_lse_offset = 0;
@@ -382,12 +390,18 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
 
     if (plan.skip_tiles > 0) {
         const dim3 mgrid(p.Hq, p.B);
-        hipLaunchKernelGGL((pa::merge_prefix_kernel<128>), mgrid, dim3(pa::kMergePrefixWaves * pa::kWave), 0, hs, p);
+        hipLaunchKernelGGL((pa::merge_prefix_kernel<128>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
     } else if (plan.P > 1) {
-        const dim3 mgrid(p.QH, plan.P - 1);
-        if (shape->head_dim == 128)
+        const dim3 mgrid(p.QH, p.B);
+        // few sequences cut many times each: split a row's pieces over the waves of a workgroup
+        const bool many = plan.P >= kMergeManyPerSeq * (int64_t)p.B;
+        if (shape->head_dim == 128 && many)
+            hipLaunchKernelGGL((pa::merge_many_kernel<128>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
+        else if (shape->head_dim == 128)
             hipLaunchKernelGGL((pa::merge_kernel<128>), mgrid, dim3(64), 0, hs, p);
+        else if (many)
+            hipLaunchKernelGGL((pa::merge_many_kernel<64>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
         else
             hipLaunchKernelGGL((pa::merge_kernel<64>), mgrid, dim3(64), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;

@@ -25,7 +25,7 @@ struct Params {
     float* out;                   // [B, Hq, D] float32, or the same shape in bf16 when out_bf16 is set
     float* part_o;                // [2P, Hq, D] normalised partial outputs (null when P == 1)
     float* part_lse;              // [2P, Hq]    log2-domain log-sum-exp of each partial
-    int32_t* merge_desc;          // [P, 4] what the merge kernel needs per partition boundary (null when P == 1)
+    int32_t* merge_desc;          // [B, 4] what the merge kernel needs to know per sequence (null when P == 1)
     int32_t* trace_blocks;        // [B, Hkv, MB, 3] or null
     float scale_log2;             // softmax scale * log2(e)
     int32_t B, Hq, Hkv, G, MB;

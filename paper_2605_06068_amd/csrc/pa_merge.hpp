@@ -2,11 +2,11 @@
 // (see pa_plan.hpp).  With lse_s = log2(sum_t 2^(score_t)) over segment s and o_s the segment's
 // normalised output, out = sum_s w_s o_s / sum_s w_s with w_s = 2^(lse_s - max_s lse_s).
 //
-// One wavefront per (partition boundary j in [1, P), output row h of a sequence: query head, or
-// (query token, query head) pair of a multi-token call).  Boundary j sits at global
-// tile part_begin(j).  The wave whose boundary is the FIRST one strictly inside a sequence b
-// merges that sequence; all other waves exit.  Which boundaries those are, and the sequence's
-// place in the tile sequence, comes from the descriptors the partition kernel wrote.  The partials of b come from the partitions
+// One wavefront per (sequence b, output row h of a sequence: query head, or (query token, query
+// head) pair of a multi-token call).  The descriptor the partition kernel wrote for b (see
+// write_seq_desc) says whether b was cut and, if so, names the first boundary j strictly inside
+// it (the start of partition j) and b's place in the tile sequence; waves of uncut sequences
+// exit.  The partials of b come from the partitions
 // k = j-1, j, j+1, ... whose ranges intersect b: slot 2k when b holds partition k's first tile,
 // slot 2k+1 otherwise (only possible for k = j-1).  Only slots written by the partition kernel
 // of the same call are read.
@@ -23,15 +23,15 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
     __shared__ int s_slot[kWave];
     __shared__ float s_w[kWave];
     const int h = blockIdx.x;
-    const int j = blockIdx.y + 1;
+    const int b = blockIdx.y;
     const int lane = threadIdx.x;
     const int P = p.P;
 
-    // the partition kernel left what there is to know about boundary j: see write_merge_desc
-    const int T = uniform_load(p.merge_desc, 4 * j + 3);
-    if (T == 0) return;  // nothing to merge at this boundary
-    const int b = uniform_load(p.merge_desc, 4 * j), cum = uniform_load(p.merge_desc, 4 * j + 1),
-              end_b = uniform_load(p.merge_desc, 4 * j + 2);
+    // what the partition kernel left about sequence b: see write_seq_desc
+    const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
+    if (j == 0) return;  // empty, or finished inside one partition
+    const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),
+              T = uniform_load(p.merge_desc, 4 * (int64_t)b + 3);
 
     float acc[V], wsum = 0.f, mrun = kNegBig;
 #pragma unroll
@@ -102,56 +102,31 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
         store_out1(p, row + lane, acc[0] * inv);
 }
 
-// Merge kernel of shared-prefix calls.  One workgroup of four wavefronts per (query head h,
-// sequence b) combines, by their log-sum-exps, every piece of that output row:
-//   - the Pp partials of the prefix pass (slot kp of prefix_o / prefix_lse), and
-//   - what the per-sequence pass produced over the rest of the context: nothing (the context ends
-//     with the prefix), or the row already in `out` with its log-sum-exp in seq_lse (the rest lies
-//     inside one partition), or the partials of the partitions that cut it (slots as above).
-// The pieces are taken 256 at a time: thread t looks at piece t (address, log-sum-exp), the
-// workgroup agrees on the maximum and the weights, then wave w sums pieces w, w+4, ... with eight
-// row loads in flight, and the four sums are added through LDS.  The row in `out` is read by all
-// before it is overwritten.
-constexpr int kMergePrefixWaves = 4;
+// ---------------------------------------------------------------------------------------------
+// Rows with many pieces: a workgroup of kMergeWaves wavefronts per output row.
+//
+// combine_pieces() combines, by their log-sum-exps, `nsrc` pieces of one output row and stores
+// the row.  piece(s, row_ptr, lse) describes piece s (false: it does not exist).  The pieces are
+// taken 256 at a time: thread t looks at piece t (address, log-sum-exp), the workgroup agrees on
+// the maximum and the weights, then wave w sums pieces w, w+4, ... with eight row loads in
+// flight, and the four sums are added through LDS.  `safe_row` is any row that is certainly
+// written (it stands in, with weight 0, for pieces that do not exist).  A piece may be the
+// row in `out` itself: every read has been consumed before the row is stored.
+constexpr int kMergeWaves = 4;
 
-template <int D>
-__global__ __launch_bounds__(kMergePrefixWaves * kWave) void merge_prefix_kernel(const Params p)
+template <int D, class Piece>
+__device__ __forceinline__ void combine_pieces(const Params& p, int64_t out_elem, int nsrc, const float* safe_row,
+                                               Piece piece)
 {
     constexpr int V = D / kWave;
-    constexpr int NT = kMergePrefixWaves * kWave;
+    constexpr int NT = kMergeWaves * kWave;
     __shared__ const float* s_row[NT];
     __shared__ float s_w[NT];
-    __shared__ float s_red[2][kMergePrefixWaves];
-    __shared__ float s_acc[kMergePrefixWaves][D];
-    const int h = blockIdx.x;
-    const int b = blockIdx.y;
+    __shared__ float s_red[2][kMergeWaves];
+    __shared__ float s_acc[kMergeWaves][D];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = tid >> 6;
-    const Span sp{p.skip_tiles, 0};
-    const int P = p.P;
-    const int64_t rows = (int64_t)p.B * p.Hq;
-    const int64_t row = (int64_t)b * p.Hq + h;
-
-    // the sequence's own tiles (those after the prefix) inside the global tile sequence (every wave computes this)
-    const int T = total_tiles(p.context_lens, p.B, lane, sp);
-    int before = 0;
-    for (int b0 = 0; b0 < b; b0 += kWave) {
-        const int bb = b0 + lane;
-        before += bb < b ? tiles_of(p.context_lens[bb], sp) : 0;
-    }
-    const int cum = wave_sum(before);
-    const int nb = tiles_of(p.context_lens[b], sp);
-    int k_first = 0, nrest = 0;
-    bool inside_one = false;
-    if (nb > 0) {
-        k_first = part_of(cum, T, P);
-        const int k_last = part_of(cum + nb - 1, T, P);
-        inside_one = k_first == k_last;
-        nrest = inside_one ? 1 : k_last - k_first + 1;
-    }
-    const int nsrc = p.Pp + nrest;
-    const float* safe_row = p.prefix_o + row * D;  // prefix range 0 of this row: always written, finite
 
     float acc[V], wsum = 0.f, mrun = kNegBig;
 #pragma unroll
@@ -159,26 +134,12 @@ __global__ __launch_bounds__(kMergePrefixWaves * kWave) void merge_prefix_kernel
 
     for (int base = 0; base < nsrc; base += NT) {
         const int s = base + tid;
-        bool valid = s < nsrc;
         const float* src = safe_row;
         float lse = kNegBig;
-        if (valid) {
-            if (s < p.Pp) {
-                src = p.prefix_o + ((int64_t)s * rows + row) * D;
-                lse = p.prefix_lse[(int64_t)s * rows + row];
-            } else if (inside_one) {
-                src = p.out + row * D;
-                lse = p.seq_lse[row];
-            } else {
-                const int kk = k_first + (s - p.Pp);
-                const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
-                valid = hi > lo;  // partitions without tiles wrote nothing
-                if (valid) {
-                    const int64_t slot = (int64_t)(2 * kk + ((kk == k_first && lo != cum) ? 1 : 0)) * p.Hq + h;
-                    src = p.part_o + slot * D;
-                    lse = p.part_lse[slot];
-                }
-            }
+        const bool valid = s < nsrc && piece(s, src, lse);
+        if (!valid) {
+            src = safe_row;
+            lse = kNegBig;
         }
         // workgroup-wide maximum of the log-sum-exps
         float cm = lse;
@@ -204,13 +165,13 @@ __global__ __launch_bounds__(kMergePrefixWaves * kWave) void merge_prefix_kernel
 
         // wave w sums pieces w, w + 4, ... of this batch, eight row loads in flight
         const int cnt = min(NT, nsrc - base);
-        const int mine = cnt > w ? (cnt - w + kMergePrefixWaves - 1) / kMergePrefixWaves : 0;
+        const int mine = cnt > w ? (cnt - w + kMergeWaves - 1) / kMergeWaves : 0;
         for (int i0 = 0; i0 < mine; i0 += 8) {
             float wv[8];
             float2 xv[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int idx = w + kMergePrefixWaves * min(i0 + u, mine - 1);
+                const int idx = w + kMergeWaves * min(i0 + u, mine - 1);
                 wv[u] = (i0 + u < mine) ? s_w[idx] : 0.f;
                 const float* r = s_row[idx];
                 if (V == 2) {
@@ -228,7 +189,7 @@ __global__ __launch_bounds__(kMergePrefixWaves * kWave) void merge_prefix_kernel
         }
         __syncthreads();  // s_row / s_w / s_red are reused by the next batch
     }
-    // add the four waves' sums; every read of the row in `out` has been consumed by now
+    // add the four waves' sums; every read of a row in `out` has been consumed by now
 #pragma unroll
     for (int i = 0; i < V; ++i) s_acc[w][lane * V + i] = acc[i];
     __syncthreads();
@@ -238,13 +199,96 @@ __global__ __launch_bounds__(kMergePrefixWaves * kWave) void merge_prefix_kernel
 #pragma unroll
         for (int i = 0; i < V; ++i)
             o[i] = ((s_acc[0][lane * V + i] + s_acc[1][lane * V + i]) + (s_acc[2][lane * V + i] + s_acc[3][lane * V + i])) * inv;
-        float* dst = p.out + row * D;
-        if (V == 2) {
-            *reinterpret_cast<float2*>(dst + lane * 2) = make_float2(o[0], o[V - 1]);
-        } else {
-            dst[lane] = o[0];
-        }
+        if (V == 2)
+            store_out2(p, out_elem + lane * 2, o[0], o[V - 1]);
+        else
+            store_out1(p, out_elem + lane, o[0]);
     }
+}
+
+// The merge of merge_kernel above for calls whose sequences are cut many times (few sequences,
+// many partitions: a single long context is cut by every partition): same descriptors, same
+// slots, but a workgroup per (sequence, output row) that splits the pieces over its waves.
+template <int D>
+__global__ __launch_bounds__(kMergeWaves * kWave) void merge_many_kernel(const Params p)
+{
+    const int h = blockIdx.x;
+    const int b = blockIdx.y;
+    const int P = p.P;
+    const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
+    if (j == 0) return;  // empty, or finished inside one partition (the same for every thread)
+    const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),
+              T = uniform_load(p.merge_desc, 4 * (int64_t)b + 3);
+    const int k_last = part_of(end_b - 1, T, P);
+    const int nsrc = k_last - (j - 1) + 1;
+    // partition j-1 holds the tile before the boundary, a tile of b: its piece exists
+    const int lo_first = part_begin(j - 1, T, P);
+    const float* safe_row = p.part_o + ((int64_t)(2 * (j - 1) + (lo_first != cum ? 1 : 0)) * p.QH + h) * D;
+    combine_pieces<D>(p, ((int64_t)b * p.QH + h) * D, nsrc, safe_row, [&](int s, const float*& src, float& lse) {
+        const int kk = j - 1 + s;
+        const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
+        if (hi <= lo) return false;  // partitions without tiles wrote nothing
+        const int64_t slot = (int64_t)(2 * kk + ((kk == j - 1 && lo != cum) ? 1 : 0)) * p.QH + h;
+        src = p.part_o + slot * D;
+        lse = p.part_lse[slot];
+        return true;
+    });
+}
+
+// Merge kernel of shared-prefix calls.  One workgroup per (query head h, sequence b) combines
+// every piece of that output row:
+//   - the Pp partials of the prefix pass (slot kp of prefix_o / prefix_lse), and
+//   - what the per-sequence pass produced over the rest of the context: nothing (the context ends
+//     with the prefix), or the row already in `out` with its log-sum-exp in seq_lse (the rest lies
+//     inside one partition), or the partials of the partitions that cut it (slots as above).
+template <int D>
+__global__ __launch_bounds__(kMergeWaves * kWave) void merge_prefix_kernel(const Params p)
+{
+    const int h = blockIdx.x;
+    const int b = blockIdx.y;
+    const int lane = threadIdx.x & (kWave - 1);
+    const Span sp{p.skip_tiles, 0};
+    const int P = p.P;
+    const int64_t rows = (int64_t)p.B * p.Hq;
+    const int64_t row = (int64_t)b * p.Hq + h;
+
+    // the sequence's own tiles (those after the prefix) inside the global tile sequence (every wave computes this)
+    const int T = total_tiles(p.context_lens, p.B, lane, sp);
+    int before = 0;
+    for (int b0 = 0; b0 < b; b0 += kWave) {
+        const int bb = b0 + lane;
+        before += bb < b ? tiles_of(p.context_lens[bb], sp) : 0;
+    }
+    const int cum = wave_sum(before);
+    const int nb = tiles_of(p.context_lens[b], sp);
+    int k_first = 0, nrest = 0;
+    bool inside_one = false;
+    if (nb > 0) {
+        k_first = part_of(cum, T, P);
+        const int k_last = part_of(cum + nb - 1, T, P);
+        inside_one = k_first == k_last;
+        nrest = inside_one ? 1 : k_last - k_first + 1;
+    }
+    // prefix range 0 of this row is always written and finite
+    combine_pieces<D>(p, row * D, p.Pp + nrest, p.prefix_o + row * D, [&](int s, const float*& src, float& lse) {
+        if (s < p.Pp) {
+            src = p.prefix_o + ((int64_t)s * rows + row) * D;
+            lse = p.prefix_lse[(int64_t)s * rows + row];
+            return true;
+        }
+        if (inside_one) {
+            src = p.out + row * D;
+            lse = p.seq_lse[row];
+            return true;
+        }
+        const int kk = k_first + (s - p.Pp);
+        const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
+        if (hi <= lo) return false;  // partitions without tiles wrote nothing
+        const int64_t slot = (int64_t)(2 * kk + ((kk == k_first && lo != cum) ? 1 : 0)) * p.Hq + h;
+        src = p.part_o + slot * D;
+        lse = p.part_lse[slot];
+        return true;
+    });
 }
 
 }  // namespace pa

@@ -170,10 +170,11 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                     const int64_t row = ((int64_t)b * p.QH + (int64_t)i * p.Hq + g * G) * D;
                     for (int e = 0; e < G * D; ++e) store_out1(p, row + e, 0.f);
                 }
+                if (g == 0 && p.merge_desc != nullptr) write_seq_desc(p.merge_desc, b, 0, 0, 0, 0);
             }
         }
     }
-    if (g == 0 && k > 0 && skip == 0) write_merge_desc(p.merge_desc, p.context_lens, B, k, p.P, rs, lane, sp);
+    const bool describes = g == 0 && skip == 0 && p.merge_desc != nullptr;  // this wave tells the merge about its sequences
     if (rs.t_lo >= rs.t_hi) return;
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;
@@ -342,6 +343,10 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         wait_tile<kDmaPerTile / 2, NSTAGE, kDmaPerTile>(later);  // K of this tile (and its segment's query rows) landed
         if (tile == 0 || cc.lt == 0) {  // segment start
             seg_first_lt = cc.lt;
+            if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is mine
+                const int cum = rs.t_lo + tile, end = cum + cc.nt;
+                write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
+            }
             const char* qsl = qslots + q_comp * kQSlot;
             m = kNegBig;
             lsum = 0.f;

@@ -108,10 +108,11 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
                     const int64_t row = ((int64_t)b * p.QH + (int64_t)i * p.Hq + g * G) * D;
                     for (int e = 0; e < G * D; ++e) store_out1(p, row + e, 0.f);
                 }
+                if (g == 0 && p.merge_desc != nullptr) write_seq_desc(p.merge_desc, b, 0, 0, 0, 0);
             }
         }
     }
-    if (!PREFIX && g == 0 && k > 0 && w == 0) write_merge_desc(p.merge_desc, p.context_lens, B, k, p.P, rs, lane, sp);
+    const bool describes = !PREFIX && g == 0 && w == 0 && p.merge_desc != nullptr;  // tells the merge about its sequences
     if (rs.t_lo >= rs.t_hi) return;  // the same for every wave of the workgroup
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;
@@ -283,6 +284,10 @@ __global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const P
 
         if (seg_start) {
             seg_first_lt = cc.lt;
+            if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is this workgroup's
+                const int cum = rs.t_lo + tile, end = cum + cc.nt;
+                write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
+            }
             m = kNegBig;
             lsum = 0.f;
 #pragma unroll

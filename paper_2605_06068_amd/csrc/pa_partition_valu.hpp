@@ -56,10 +56,11 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
             if (b < B && p.context_lens[b] <= 0) {
                 const int64_t orow = ((int64_t)b * p.Hq + g * G) * D;
                 for (int i = 0; i < G * D; ++i) store_out1(p, orow + i, 0.f);
+                if (g == 0 && p.merge_desc != nullptr) write_seq_desc(p.merge_desc, b, 0, 0, 0, 0);
             }
         }
     }
-    if (g == 0 && k > 0) write_merge_desc(p.merge_desc, p.context_lens, B, k, p.P, rs, lane, Span{0, 0});
+    const bool describes = g == 0 && p.merge_desc != nullptr;  // this wave tells the merge about its sequences
     if (rs.t_lo >= rs.t_hi) return;
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;
@@ -78,6 +79,10 @@ __global__ __launch_bounds__(64) void partition_valu_kernel(const Params p)
     for (int tile = 0; tile < ntiles; ++tile) {
         if (tile == 0 || lt == 0) {  // segment start: this lane's slice of the G query rows, fresh state
             seg_first_lt = lt;
+            if (describes && lt == 0 && lane == 0) {  // the sequence's first tile is mine
+                const int cum = rs.t_lo + tile, end = cum + nt;
+                write_seq_desc(p.merge_desc, b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
+            }
 #pragma unroll
             for (int h = 0; h < GMAX; ++h) {
                 m[h] = kNegBig;

@@ -155,32 +155,22 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     return r;
 }
 
-// What the merge kernel needs to know about partition boundary k (the start of partition k's
-// range, k >= 1), written by the partition kernel's wave (k, KV head 0) so that the merge waves
-// neither scan the context lengths nor locate the boundary again: {b, cum, end, T} = the
-// sequence holding the boundary tile, the tiles before it, its last tile + 1 and the total tile
-// count, with T = 0 when this boundary triggers no merge (it falls between two sequences or
-// outside the tile sequence, or an earlier boundary lies inside the same sequence).
-// All 64 lanes must call.
-__device__ __forceinline__ void write_merge_desc(int32_t* desc, const int32_t* context_lens, int B, int k, int P,
-                                                 const RangeStart& rs, int lane, Span sp)
+// What the merge kernel needs to know about sequence b, written by the partition kernel so that
+// the merge neither scans the context lengths nor searches for boundaries: {j, cum, end, T}.
+// j = 0: nothing to merge (the sequence is empty, or lies inside one partition).  Otherwise j is
+// the first partition boundary strictly inside the sequence (the start of partition j), cum and
+// end are the sequence's first tile and last tile + 1 in the global tile sequence, T the total.
+// The writer is the wave (KV head 0) that processes the sequence's FIRST tile: it is the one that
+// sees whether the sequence runs past the end of its own range.  Empty sequences are covered by
+// the wave that zero-fills their output rows.
+__device__ __forceinline__ void write_seq_desc(int32_t* desc, int b, int j, int cum, int end, int T)
 {
-    const int bj = rs.t_lo;
-    const bool in_range = bj > 0 && bj < rs.T;
-    int b = rs.b, cum = rs.cum, L = rs.L;
-    if (in_range && rs.t_lo >= rs.t_hi) {  // a partition without tiles: find_range did not locate its start
-        locate_tile(context_lens, B, bj, lane, b, cum, sp);
-        L = context_lens[b];
-    }
-    const bool merges = in_range && cum != bj && !(k > 1 && part_begin(k - 1, rs.T, P) > cum);
-    if (lane == 0) {
-        int4 d;
-        d.x = b;
-        d.y = cum;
-        d.z = cum + tiles_of(L, sp);
-        d.w = merges ? rs.T : 0;
-        *reinterpret_cast<int4*>(desc + 4 * k) = d;
-    }
+    int4 d;
+    d.x = j;
+    d.y = cum;
+    d.z = end;
+    d.w = T;
+    *reinterpret_cast<int4*>(desc + 4 * (int64_t)b) = d;
 }
 
 // Uniform (scalar-cache) load of a 32-bit word: keeps table and length lookups off the

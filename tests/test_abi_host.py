@@ -71,7 +71,7 @@ def test_partition_count_depends_on_host_shape_only():
 
 def test_workspace_size_covers_partials():
     s = shape(num_partitions=16)
-    need = 2 * 16 * 32 * (128 + 1) * 4 + 16 * 16  # partials + 16 bytes per partition boundary for the merge
+    need = 2 * 16 * 32 * (128 + 1) * 4 + 4 * 16  # partials + 16 bytes per sequence for the merge
     got = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
     assert need <= got <= need + 3 * 256
 
@@ -82,7 +82,7 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     for Q in (2, 4, 16):
         win = shape(num_partitions=16, q_len=Q)
         assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == "mfma"
-        need = 2 * 16 * Q * 32 * (128 + 1) * 4 + 16 * 16
+        need = 2 * 16 * Q * 32 * (128 + 1) * 4 + 4 * 16
         assert need <= pa.pa_decode_workspace_size(win, pa.PA_KV_BF16) <= need + 3 * 256
         lens = [100, 4096, 1, 33]
         assert pa.pa_split_plan(win, pa.PA_KV_BF16, lens)[0] == pa.pa_split_plan(one, pa.PA_KV_BF16, lens)[0]
@@ -134,9 +134,9 @@ def test_shared_prefix_plan_and_workspace():
                     assert plan[b, 2 * lt + 1] == k
                 t += 1
             assert np.all(plan[b, nblk:] == -1)
-        # partials of the rest (+ 16 bytes per partition boundary for the merge) + one log-sum-exp per row
+        # partials of the rest (+ 16 bytes per sequence for the merge) + one log-sum-exp per row
         # + Pp partial results over the prefix
-        need = (0 if P == 1 else 2 * P * Hq * (D + 1) * 4 + P * 16) + B * Hq * 4 + Pp * B * Hq * (D + 1) * 4
+        need = (0 if P == 1 else 2 * P * Hq * (D + 1) * 4 + B * 16) + B * Hq * 4 + Pp * B * Hq * (D + 1) * 4
         got = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
         assert need <= got <= need + 6 * 256
     with pytest.raises(pa.PaError):  # a context that ends inside the shared prefix
@@ -166,6 +166,7 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(max_context_len=256 * 16 + 1), pa.PA_ERR_INVALID_ARG),
     (dict(num_partitions=-3), pa.PA_ERR_INVALID_ARG),
     (dict(num_partitions=70000), pa.PA_ERR_UNSUPPORTED),
+    (dict(batch=70000, max_context_len=64), pa.PA_ERR_UNSUPPORTED),
     (dict(head_dim=96), pa.PA_ERR_UNSUPPORTED),
     (dict(block_size=32), pa.PA_ERR_UNSUPPORTED),
     (dict(num_q_heads=8 * 32), pa.PA_ERR_UNSUPPORTED),

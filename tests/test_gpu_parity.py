@@ -100,6 +100,18 @@ def test_one_sequence_cut_by_every_partition(pa, oracle):
         check(pa, oracle, b, f"single-sequence P={P}", num_partitions=P)
 
 
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 2, 64), (8, 2, 128), (2, 2, 128), (16, 1, 128)])
+@pytest.mark.parametrize("P", [16, 40, 300])
+def test_few_sequences_cut_many_times(pa, oracle, kv, Hq, Hkv, D, P):
+    """Eight or more partitions per sequence: the merge runs as a workgroup of waves per output row
+    (both head sizes, both partition kernels, empty partitions when P exceeds the tile count)."""
+    b = W.make_batch("fewlong", 65 + P, [3000, 0, 1500], Hq, Hkv, D, 16, kv)
+    got, want = check(pa, oracle, b, f"few-long P={P}", num_partitions=P)
+    ref, _ = run_gpu(pa, b, num_partitions=1)
+    assert_parity(got, ref, kv, "against the unsplit run")
+
+
 @pytest.mark.parametrize("B", [63, 64, 65, 130, 300])
 @pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2)])
 def test_many_short_sequences_with_gaps(pa, oracle, B, Hq, Hkv):
