@@ -55,8 +55,12 @@ __device__ __forceinline__ void wait_loads(int tiles)
     }
 }
 
+// The second launch bound (two waves per SIMD, where the workgroup's LDS lets that happen at all)
+// caps the register budget at 256, which makes the compiler keep the MFMA accumulators in ordinary
+// VGPRs: with more it parks them in AGPRs and moves all 32 to VGPRs and back in every tile around
+// the rarely taken rescale branch.
 template <int NW, int NSTAGE, int KV, bool TRACE, bool PREFIX>
-__global__ __launch_bounds__(NW * 64, 2) void partition_mfma_wide_kernel(const Params p)
+__global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_kernel(const Params p)
 {
     constexpr int D = 128;
     static_assert(NW == 2 || NW == 4 || NW == 8, "waves per workgroup");
