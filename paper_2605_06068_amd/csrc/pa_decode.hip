@@ -393,7 +393,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         hipLaunchKernelGGL((pa::merge_prefix_kernel<128>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
     } else if (plan.P > 1) {
-        const dim3 mgrid(p.QH, p.B);
+        const dim3 mgrid(p.QH, p.B < plan.P - 1 ? p.B : plan.P - 1);  // at most P - 1 sequences are cut
         // few sequences cut many times each: split a row's pieces over the waves of a workgroup
         const bool many = plan.P >= kMergeManyPerSeq * (int64_t)p.B;
         if (shape->head_dim == 128 && many)

@@ -2,11 +2,11 @@
 // (see pa_plan.hpp).  With lse_s = log2(sum_t 2^(score_t)) over segment s and o_s the segment's
 // normalised output, out = sum_s w_s o_s / sum_s w_s with w_s = 2^(lse_s - max_s lse_s).
 //
-// One wavefront per (sequence b, output row h of a sequence: query head, or (query token, query
-// head) pair of a multi-token call).  The descriptor the partition kernel wrote for b (see
+// One wavefront per (cut sequence b, output row h of a sequence: query head, or (query token,
+// query head) pair of a multi-token call).  The descriptor the partition kernel wrote for b (see
 // write_seq_desc) says whether b was cut and, if so, names the first boundary j strictly inside
-// it (the start of partition j) and b's place in the tile sequence; waves of uncut sequences
-// exit.  The partials of b come from the partitions
+// it (the start of partition j) and b's place in the tile sequence.  The grid has room for
+// min(B, P - 1) cut sequences; slot y takes the y-th sequence that was cut, the rest exit.  The partials of b come from the partitions
 // k = j-1, j, j+1, ... whose ranges intersect b: slot 2k when b holds partition k's first tile,
 // slot 2k+1 otherwise (only possible for k = j-1).  Only slots written by the partition kernel
 // of the same call are read.
@@ -16,6 +16,26 @@
 
 namespace pa {
 
+// The y-th sequence (in batch order) whose descriptor says it was cut, or -1 if there are fewer:
+// the merge grids have one slot per sequence that CAN be cut (at most P - 1 of them are), and
+// slot y takes the y-th one that was.  All 64 lanes must call; the result is wave-uniform.
+__device__ __forceinline__ int nth_cut_sequence(const int32_t* desc, int B, int y, int lane)
+{
+    int seen = 0;
+    for (int b0 = 0; b0 < B; b0 += kWave) {
+        const int b = b0 + lane;
+        const bool cut = b < B && desc[4 * (int64_t)b] != 0;
+        const unsigned long long mask = __ballot(cut);
+        const int c = __popcll(mask);
+        if (y < seen + c) {
+            const bool hit = cut && (int)__popcll(mask & ((1ull << lane) - 1ull)) == y - seen;
+            return b0 + __ffsll((long long)__ballot(hit)) - 1;
+        }
+        seen += c;
+    }
+    return -1;
+}
+
 template <int D>
 __global__ __launch_bounds__(64) void merge_kernel(const Params p)
 {
@@ -23,13 +43,13 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
     __shared__ int s_slot[kWave];
     __shared__ float s_w[kWave];
     const int h = blockIdx.x;
-    const int b = blockIdx.y;
     const int lane = threadIdx.x;
     const int P = p.P;
 
-    // what the partition kernel left about sequence b: see write_seq_desc
+    // what the partition kernel left about the sequences: see write_seq_desc
+    const int b = nth_cut_sequence(p.merge_desc, p.B, blockIdx.y, lane);
+    if (b < 0) return;  // fewer sequences were cut than the grid has room for
     const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
-    if (j == 0) return;  // empty, or finished inside one partition
     const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),
               T = uniform_load(p.merge_desc, 4 * (int64_t)b + 3);
 
@@ -213,10 +233,10 @@ template <int D>
 __global__ __launch_bounds__(kMergeWaves * kWave) void merge_many_kernel(const Params p)
 {
     const int h = blockIdx.x;
-    const int b = blockIdx.y;
     const int P = p.P;
+    const int b = nth_cut_sequence(p.merge_desc, p.B, blockIdx.y, threadIdx.x & (kWave - 1));
+    if (b < 0) return;  // fewer sequences were cut than the grid has room for (the same for every thread)
     const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
-    if (j == 0) return;  // empty, or finished inside one partition (the same for every thread)
     const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),
               T = uniform_load(p.merge_desc, 4 * (int64_t)b + 3);
     const int k_last = part_of(end_b - 1, T, P);

@@ -1,0 +1,331 @@
+// Pieces shared by the two matrix-core partition kernels (pa_partition_mfma.hpp: one wavefront per
+// (partition, KV head), up to 16 columns; pa_partition_mfma_wide.hpp: a workgroup of wavefronts,
+// 16 columns each): the geometry of a tile in LDS, the LDS-DMA load, the cursor over the global
+// tile sequence, and what one wavefront does with one tile of 32 tokens and 16 columns --
+// which blocks and rows to load, scores, online softmax, PV.  head_dim is 128 throughout.
+//
+// LDS tile layout: row t (one token, 256 B bf16 / 128 B fp8) at byte t*rowbytes; the 16-byte
+// piece holding dims [8c, 8c+8) (fp8: [16c, 16c+16)) sits at piece position c ^ (t mod pieces).
+// The XOR swizzle is applied on the *global* side of the LDS-DMA load (the LDS side of such a
+// load is always lane-linear), which keeps every 16-lane group on one contiguous row, and makes
+// both the operand reads (16 different rows per 16 lanes) and the transposing reads
+// bank-conflict free.
+//
+// The P^T operand needs no data movement: the score tile comes out of the MFMA with lane l
+// holding column l%16 and tokens 4*(l/16)+{0..3}; declaring MFMA k-index 8*(l/16)+e to mean
+// token 4*(l/16)+e of the first block (e<4) or of the second block (e>=4) makes the score
+// registers, once exponentiated and packed to bf16, the B operand of the PV product as they
+// stand.  The V^T operand is read with the same k-index convention.
+#pragma once
+#include <type_traits>
+
+#include "pa_device.hpp"
+#include "pa_plan.hpp"
+
+namespace pa {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kQRowBytes = 256;  // one query row: 128 bf16
+
+// Storage geometry of one (block, head) slab of the KV cache, head_dim 128.
+template <int KV>
+struct KvGeom {
+    static constexpr int kRow = KV == KV_BF16 ? 256 : 128;  // bytes per token row
+    static constexpr int kSlab = kBlockSize * kRow;          // 16 rows
+    static constexpr int kPieces = kRow / 16;                // 16-byte pieces per row
+    static constexpr int kRowsPerDma = kWave / kPieces;      // rows one 1 KB wave-wide load covers
+    static constexpr int kDmaPerSlab = kSlab / 1024;
+    static constexpr int kStage = 4 * kSlab;                 // K block 0, K block 1, V block 0, V block 1
+    static constexpr int kDmaPerTile = 4 * kDmaPerSlab;
+};
+
+// eight e4m3 bytes -> eight bf16 (exact), in byte order
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi)
+{
+    const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)lo, 1.0f, false);
+    const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)lo, 1.0f, true);
+    const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)hi, 1.0f, false);
+    const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)hi, 1.0f, true);
+    return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
+// 16-byte-per-lane load from global memory straight into LDS.  LDS destination is
+// lds_addr + lane*16 (wave-uniform lds_addr goes through M0); the global source is
+// base (wave-uniform) + voff (per lane).  Completion is tracked by vmcnt.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const void* base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Position inside the global tile sequence: sequence b, its length, the first tile of it that the
+// plan covers, the number of tiles it covers, and the local tile (tile ft + lt of the sequence).
+struct Cursor {
+    int b, lt, nt, L, ft;
+};
+
+__device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, int B, Span sp = Span{0, 0})
+{
+    if (++c.lt < c.nt) return;
+    c.lt = 0;
+    do {
+        ++c.b;
+        c.L = c.b < B ? uniform_load(context_lens, c.b) : 0;
+        c.nt = tiles_of(c.L, sp);
+    } while (c.nt == 0 && c.b < B);
+    c.ft = first_tile(c.L, sp);
+}
+
+// ---- one tile (two KV blocks) of a sequence: what to load ---------------------------------------
+// Per block of the tile: its physical id and the rows [lo, hi) that hold tokens some query can
+// see.  Every other row (past the context, before the earliest sliding window) may hold anything,
+// NaN patterns included, and is replaced on the way in by row lo of the same block; the softmax
+// masks those positions.  A first block that lies entirely before the window may be gone: its
+// table entry is not read, and the first visible row of the second block (which exists: it
+// holds that token) stands in.  Without a second block, rows of the first one stand in.
+struct TileBlocks {
+    int j0;         // logical index of the tile's first block
+    int phys[2];
+    int lo[2], hi[2];
+    bool first_gone, second;
+};
+
+// `reach` > 0: sliding window, nothing further back than `reach` tokens from the end is visible.
+__device__ __forceinline__ TileBlocks tile_blocks(const int32_t* block_tables, int MB, const Cursor& c, int reach)
+{
+    TileBlocks t;
+    const int nblk = (c.L + kBlockSize - 1) / kBlockSize;
+    const int32_t* table = block_tables + (int64_t)c.b * MB;
+    t.j0 = 2 * (c.lt + c.ft);
+    const int t_first = (reach > 0 && c.L > reach) ? c.L - reach : 0;  // first token any query sees
+    t.lo[0] = min(max(t_first - t.j0 * kBlockSize, 0), kBlockSize);
+    t.hi[0] = min(c.L - t.j0 * kBlockSize, kBlockSize);
+    t.first_gone = t.lo[0] >= kBlockSize;
+    t.second = t.j0 + 1 < nblk;
+    if (t.second) {
+        t.phys[1] = uniform_load(table, t.j0 + 1);
+        t.lo[1] = max(t_first - (t.j0 + 1) * kBlockSize, 0);
+        t.hi[1] = min(c.L - (t.j0 + 1) * kBlockSize, kBlockSize);
+    }
+    if (!t.first_gone) {
+        t.phys[0] = uniform_load(table, t.j0);
+    } else {
+        t.phys[0] = t.phys[1];
+        t.lo[0] = t.hi[0] = t.lo[1];
+    }
+    if (!t.second) {
+        t.phys[1] = t.phys[0];
+        t.lo[1] = t.hi[1] = t.lo[0];
+    }
+    return t;
+}
+
+// instrumented runs: which physical block was loaded for which logical block, and by which partition
+__device__ __forceinline__ void trace_tile_blocks(int32_t* trace, const TileBlocks& t, int b, int g, int k, int Hkv, int MB)
+{
+    int32_t* v = trace + (((int64_t)b * Hkv + g) * MB + t.j0) * 3;
+    if (!t.first_gone) { v[0] = t.phys[0]; v[1] = t.phys[0]; v[2] = k; }
+    if (t.second) { v[3] = t.phys[1]; v[4] = t.phys[1]; v[5] = k; }
+}
+
+// this lane's global byte offset for LDS-DMA instruction r of a slab (rows r*kRowsPerDma ..)
+template <int KV>
+__device__ __forceinline__ uint32_t slab_dma_offset(int r, int lane)
+{
+    using Geo = KvGeom<KV>;
+    const int t = r * Geo::kRowsPerDma + lane / Geo::kPieces;
+    return t * Geo::kRow + (((lane % Geo::kPieces) ^ (t & (Geo::kPieces - 1))) << 4);
+}
+
+// the same with the stand-in rule applied: rows outside [lo, hi) load row lo instead
+template <int KV>
+__device__ __forceinline__ uint32_t live_or_stand_in(uint32_t off, int row, int lo, int hi)
+{
+    using Geo = KvGeom<KV>;
+    return (row >= lo && row < hi) ? off : lo * Geo::kRow + (off & (Geo::kRow - 1));
+}
+
+// ---- one tile: what a wavefront computes on it ---------------------------------------------------
+// Per-lane LDS read offsets of the MFMA operands (lane = 16*q4 + n).
+template <int KV>
+struct OperandOffsets {
+    uint32_t kread[4];  // inside a K slab: this lane's operand piece for k-step kk (token n, dims 32kk + 8q4 + [0,8))
+    uint32_t vread[8];  // inside the V half of a stage: this lane's transposing-read source for dim tile dt
+
+    __device__ __forceinline__ void init(int n, int q4)
+    {
+        using Geo = KvGeom<KV>;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (KV == KV_BF16)  // 16 bytes
+                kread[kk] = n * Geo::kRow + (((4 * kk + q4) ^ n) << 4);
+            else                // 8 bytes: half of 16-byte piece 2kk + q4/2
+                kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & 7)) << 4) + ((q4 & 1) << 3);
+        }
+        // bf16: one read per block, rows = tokens 4q4 + n/4, 8 bytes = 4 dims.  fp8: one read for both blocks,
+        // rows n/2 = 0..3 -> tokens 4q4.. of block 0, rows 4..7 -> the same tokens of block 1, 8 bytes = 8 dims.
+        if (KV == KV_BF16) {
+            const int row = 4 * q4 + (n >> 2);
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+                vread[dt] = row * Geo::kRow + ((n & 1) << 3) + (((2 * dt + ((n >> 1) & 1)) ^ row) << 4);
+        } else {
+            const int r = n >> 1;
+            const int tok = 4 * q4 + (r & 3);
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+                vread[dt] = (r >> 2) * Geo::kSlab + tok * Geo::kRow + ((dt ^ (tok & 7)) << 4) + ((n & 1) << 3);
+        }
+    }
+};
+
+// The 16 columns' query rows from an LDS slot (row c at c*256 B, swizzled like a K row) into MFMA
+// B-operand registers; a padding column gets zeros.
+__device__ __forceinline__ void load_query_operand(const char* slot, int n, int q4, bool col_ok, bf16x8 (&qreg)[4])
+{
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        uint4 w = *reinterpret_cast<const uint4*>(slot + (col_ok ? n : 0) * kQRowBytes + (((4 * kk + q4) ^ n) << 4));
+        if (!col_ok) w = make_uint4(0, 0, 0, 0);
+        qreg[kk] = as_bf16x8(w);
+    }
+}
+
+// S^T[token, column] = K . Q^T for the two blocks of the tile
+template <int KV>
+__device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets<KV>& of, const bf16x8 (&qreg)[4],
+                                          f32x4& s0, f32x4& s1)
+{
+    constexpr int kSlabBytes = KvGeom<KV>::kSlab;
+    s0 = f32x4{0.f, 0.f, 0.f, 0.f};
+    s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 a0, a1;
+        if (KV == KV_BF16) {
+            a0 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + of.kread[kk]));
+            a1 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kSlabBytes + of.kread[kk]));
+        } else {
+            const uint2 w0 = *reinterpret_cast<const uint2*>(kbuf + of.kread[kk]);
+            const uint2 w1 = *reinterpret_cast<const uint2*>(kbuf + kSlabBytes + of.kread[kk]);
+            a0 = fp8x8_to_bf16x8(w0.x, w0.y);
+            a1 = fp8x8_to_bf16x8(w1.x, w1.y);
+        }
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[kk], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[kk], s1, 0, 0, 0);
+    }
+}
+
+// Online softmax state of one column (replicated over the four lanes that hold its tokens) and
+// the unnormalised output accumulators out^T[dim, column].
+struct ColumnState {
+    float m, lsum;
+    f32x4 acc[8];
+
+    __device__ __forceinline__ void reset()
+    {
+        m = kNegBig;
+        lsum = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+};
+
+// Online softmax step (log2 domain) on the tile's scores.  The lane's tokens are t0 + {0..3} and
+// t0 + 16 + {0..3}; with MASKED the column sees only tokens low <= t < lim (the end of the context,
+// the causal limit of a multi-token call, the start of a sliding window); without it the whole tile.
+// Leaves the P^T operand as a bf16 pair (high part + rounding remainder: 16 significant bits, so
+// the weights lose nothing that matters against the fp32 accumulation).
+template <bool MASKED>
+__device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1, float qs, int t0, int lim, int low,
+                                               ColumnState& st, bf16x8& pb, bf16x8& pb_lo)
+{
+    float x[8];
+    bool ok[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        ok[r] = !MASKED || (t0 + r < lim && t0 + r >= low);
+        ok[4 + r] = !MASKED || (t0 + kBlockSize + r < lim && t0 + kBlockSize + r >= low);
+        x[r] = ok[r] ? s0[r] * qs : kNegBig;
+        x[4 + r] = ok[4 + r] ? s1[r] * qs : kNegBig;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = rows_max(mx);
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = fast_exp2(st.m - m_new);
+    float ps = 0.f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        x[r] = ok[r] ? fast_exp2(x[r] - m_new) : 0.f;  // a column may see nothing of a tile
+        ps += x[r];
+    }
+    st.lsum = st.lsum * alpha + ps;
+    st.m = m_new;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) st.acc[dt] *= alpha;
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        pb[r] = (__bf16)x[r];
+        pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
+    }
+}
+
+// out^T[dim, column] += V^T . P^T
+template <int KV>
+__device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOffsets<KV>& of, const bf16x8& pb,
+                                              const bf16x8& pb_lo, ColumnState& st)
+{
+    constexpr int kSlabBytes = KvGeom<KV>::kSlab;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        bf16x8 va;
+        if (KV == KV_BF16) {
+            const i16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + of.vread[dt]));
+            const i16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + kSlabBytes + of.vread[dt]));
+            va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+        } else {
+            const i32x2 v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(vbuf + of.vread[dt]));
+            va = fp8x8_to_bf16x8((uint32_t)v[0], (uint32_t)v[1]);
+        }
+        st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, st.acc[dt], 0, 0, 0);
+        st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo, st.acc[dt], 0, 0, 0);
+    }
+}
+
+// One column's 128 output values times `inv`, as float32 to `dst` (a partial row in the workspace)
+__device__ __forceinline__ void store_partial_row(float* dst, const ColumnState& st, float inv, int q4)
+{
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+        *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
+            make_float4(st.acc[dt][0] * inv, st.acc[dt][1] * inv, st.acc[dt][2] * inv, st.acc[dt][3] * inv);
+}
+
+// ... or as a final row of `out` (element index `row`), in the output's type
+__device__ __forceinline__ void store_final_row(const Params& p, int64_t row, const ColumnState& st, float inv, int q4)
+{
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+        store_out4(p, row + 16 * dt + 4 * q4, st.acc[dt][0] * inv, st.acc[dt][1] * inv, st.acc[dt][2] * inv,
+                   st.acc[dt][3] * inv);
+}
+
+}  // namespace pa

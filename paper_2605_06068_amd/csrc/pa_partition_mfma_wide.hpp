@@ -3,7 +3,8 @@
 // wavefronts serves one (partition, KV head): the waves share ONE ring of K/V tiles in LDS, so
 // the cache is read from HBM once for all columns, and each wave computes its own tile of 16
 // columns (columns 16w .. 16w+15) exactly as the single-wave kernel does: same operand
-// layouts, same swizzle, same online softmax (see pa_partition_mfma.hpp).
+// layouts, same swizzle, same online softmax (pa_mfma_tile.hpp; wait-count discipline as
+// described in pa_partition_mfma.hpp).
 //
 // Per tile, every wave loads 1/NW of the tile's LDS-DMA instructions and the workgroup meets at
 // one barrier:
@@ -30,7 +31,7 @@
 #include <type_traits>
 
 #include "pa_device.hpp"
-#include "pa_partition_mfma.hpp"
+#include "pa_mfma_tile.hpp"
 #include "pa_plan.hpp"
 
 namespace pa {
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         const int r = d % Geo::kDmaPerSlab;
         my_dst[j] = my_slab[j] * kSlabBytes + r * 1024;
         my_tok[j] = r * Geo::kRowsPerDma + lane / Geo::kPieces;
-        my_off[j] = my_tok[j] * Geo::kRow + (((lane % Geo::kPieces) ^ (my_tok[j] & (Geo::kPieces - 1))) << 4);
+        my_off[j] = slab_dma_offset<KV>(r, lane);
     }
     // query rows of this wave's columns: LDS row r4*4 + q4 holds column c = 16w + that row
     uint32_t qdma_off[4];
@@ -152,14 +153,8 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * kQRowBytes : 0;
         qdma_off[r] = src + ((n ^ lc) << 4);
     }
-    uint32_t kread[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        if (KV == KV_BF16)
-            kread[kk] = n * Geo::kRow + (((4 * kk + q4) ^ n) << 4);
-        else
-            kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & 7)) << 4) + ((q4 & 1) << 3);
-    }
+    OperandOffsets<KV> of;
+    of.init(n, q4);
     // this lane's column
     const int col = col0 + 16 * w + n;
     const bool col_ok = col < ncols;
@@ -168,22 +163,6 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     // tokens at the end of the context the column must not see (prefix pass: every column sees all of it)
     const int col_back = col_ok ? (PREFIX ? 0 : Q - 1 - col_i) : (1 << 30);
     const int col_row = col_i * p.Hq + g * G + col_h;          // output row inside its sequence
-    uint32_t qpiece[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) qpiece[kk] = n * kQRowBytes + (((4 * kk + q4) ^ n) << 4);
-    uint32_t vread[8];
-    if (KV == KV_BF16) {
-        const int row = 4 * q4 + (n >> 2);
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-            vread[dt] = row * Geo::kRow + ((n & 1) << 3) + (((2 * dt + ((n >> 1) & 1)) ^ row) << 4);
-    } else {
-        const int r = n >> 1;
-        const int tok = 4 * q4 + (r & 3);
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-            vread[dt] = (r >> 2) * kSlabBytes + tok * Geo::kRow + ((dt ^ (tok & 7)) << 4) + ((n & 1) << 3);
-    }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t ldsq = lds0 + NSTAGE * kStageBytes + w * kQSlotBytesWide;
     const char* qslot = smem + NSTAGE * kStageBytes + w * kQSlotBytesWide;
@@ -198,56 +177,23 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         for (int r = 0; r < 4; ++r) dma16(ldsq + r * 1024, qdma_off[r], qb);
     };
     auto issue = [&](int stage) {
-        const int nblk = (ic.L + kBlockSize - 1) / kBlockSize;
-        const int32_t* table = p.block_tables + (int64_t)ic.b * p.MB;
-        const int j0 = 2 * (ic.lt + ic.ft);
-        // Per block of the tile: its physical id and the rows [lo, hi) that hold tokens some query can
-        // see.  Every other row (past the context, before the earliest window) may hold anything,
-        // NaN patterns included, and is replaced on the way in by row lo of the same block; the
-        // softmax masks those positions.
-        int phys[2], lo[2], hi[2];
-        const int t_first = (reach > 0 && ic.L > reach) ? ic.L - reach : 0;  // first token any query sees
-        lo[0] = min(max(t_first - j0 * kBlockSize, 0), kBlockSize);
-        hi[0] = min(ic.L - j0 * kBlockSize, kBlockSize);
-        // a first block that lies entirely before the window may be gone: its table entry is not read
-        const bool first_gone = lo[0] >= kBlockSize;
-        const bool second = j0 + 1 < nblk;
-        if (second) {
-            phys[1] = uniform_load(table, j0 + 1);
-            lo[1] = max(t_first - (j0 + 1) * kBlockSize, 0);
-            hi[1] = min(ic.L - (j0 + 1) * kBlockSize, kBlockSize);
-        }
-        if (!first_gone) {
-            phys[0] = uniform_load(table, j0);
-        } else {  // stand-in: the first visible row of the second block (which exists: it holds that token)
-            phys[0] = phys[1];
-            lo[0] = hi[0] = lo[1];
-        }
-        if (!second) {  // no second block: stand-in rows from the first one
-            phys[1] = phys[0];
-            lo[1] = hi[1] = lo[0];
-        }
-        if (TRACE && w == 0 && lane == 0) {
-            int32_t* v = p.trace_blocks + (((int64_t)ic.b * p.Hkv + g) * p.MB + j0) * 3;
-            if (!first_gone) { v[0] = phys[0]; v[1] = phys[0]; v[2] = k; }
-            if (second) { v[3] = phys[1]; v[4] = phys[1]; v[5] = k; }
-        }
+        const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
+        if (TRACE && w == 0 && lane == 0) trace_tile_blocks(p.trace_blocks, tb, ic.b, g, k, p.Hkv, p.MB);
         const uint32_t ldst = lds0 + stage * kStageBytes;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
             const int sub = my_slab[j] & 1;
-            const char* base = (my_slab[j] >> 1 ? vc : kc) + (sub ? phys[1] : phys[0]) * head_stride;
-            const int rlo = sub ? lo[1] : lo[0], rhi = sub ? hi[1] : hi[0];
-            const bool live = my_tok[j] >= rlo && my_tok[j] < rhi;
-            dma16(ldst + my_dst[j], live ? my_off[j] : rlo * Geo::kRow + (my_off[j] & (Geo::kRow - 1)), base);
+            const char* base = (my_slab[j] >> 1 ? vc : kc) + (sub ? tb.phys[1] : tb.phys[0]) * head_stride;
+            dma16(ldst + my_dst[j],
+                  live_or_stand_in<KV>(my_off[j], my_tok[j], sub ? tb.lo[1] : tb.lo[0], sub ? tb.hi[1] : tb.hi[0]), base);
         }
         advance(ic, p.context_lens, B, sp);
     };
 
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    float m = kNegBig, lsum = 0.f;
-    f32x4 acc[8];
+    ColumnState st;
+    st.reset();
     bf16x8 qreg[4];
     int seg_first_lt = 0;
 
@@ -273,9 +219,9 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         __builtin_amdgcn_s_barrier();
         const int ahead = tile + NSTAGE - 1;
         if (ahead < ntiles) {
-            int st = stage + NSTAGE - 1;
-            if (st >= NSTAGE) st -= NSTAGE;
-            issue(st);
+            int stg = stage + NSTAGE - 1;
+            if (stg >= NSTAGE) stg -= NSTAGE;
+            issue(stg);
             ++q_age;
         }
         const char* kbuf = smem + stage * kStageBytes;
@@ -292,16 +238,8 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
                 const int cum = rs.t_lo + tile, end = cum + cc.nt;
                 write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
             }
-            m = kNegBig;
-            lsum = 0.f;
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                uint4 v = *reinterpret_cast<const uint4*>(qslot + qpiece[kk]);
-                if (!col_ok) v = make_uint4(0, 0, 0, 0);
-                qreg[kk] = as_bf16x8(v);
-            }
+            st.reset();
+            load_query_operand(qslot, n, q4, col_ok, qreg);
             // refill the slot with the rows of the next segment of this range, if there is one
             if (tile + (cc.nt - cc.lt) < ntiles) {
                 int nb = cc.b;
@@ -314,119 +252,45 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
             }
         }
 
-        // ---- scores: S^T[token, column] for the two blocks of the tile
-        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 a0, a1;
-            if (KV == KV_BF16) {
-                a0 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kread[kk]));
-                a1 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kSlabBytes + kread[kk]));
-            } else {
-                const uint2 w0 = *reinterpret_cast<const uint2*>(kbuf + kread[kk]);
-                const uint2 w1 = *reinterpret_cast<const uint2*>(kbuf + kSlabBytes + kread[kk]);
-                a0 = fp8x8_to_bf16x8(w0.x, w0.y);
-                a1 = fp8x8_to_bf16x8(w1.x, w1.y);
-            }
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[kk], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[kk], s1, 0, 0, 0);
-        }
+        f32x4 s0, s1;
+        qk_scores<KV>(kbuf, of, qreg, s0, s1);
 
-        // ---- online softmax (log2 domain); the column sees tokens t < L - col_back.  Only the last
-        // tiles of a sequence need the mask: everywhere else every column sees the whole tile.
-        bf16x8 pb, pb_lo;
-        auto softmax = [&](auto masked_tag) {
-            constexpr bool MASKED = decltype(masked_tag)::value;
-            const int t0 = (cc.lt + cc.ft) * kTileTokens + 4 * q4;
-            const int lim = cc.L - col_back;
-            const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
-            float x[8];
-            bool ok[8];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                ok[r] = !MASKED || (t0 + r < lim && t0 + r >= low);
-                ok[4 + r] = !MASKED || (t0 + kBlockSize + r < lim && t0 + kBlockSize + r >= low);
-                x[r] = ok[r] ? s0[r] * qs : kNegBig;
-                x[4 + r] = ok[4 + r] ? s1[r] * qs : kNegBig;
-            }
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            mx = rows_max(mx);
-            const float m_new = fmaxf(m, mx);
-            const float alpha = fast_exp2(m - m_new);
-            float ps = 0.f;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                x[r] = ok[r] ? fast_exp2(x[r] - m_new) : 0.f;  // a column may see nothing of a tile
-                ps += x[r];
-            }
-            lsum = lsum * alpha + ps;
-            m = m_new;
-            if (__any(alpha != 1.f)) {
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;
-            }
-            // P^T operand as a bf16 pair (high part + rounding remainder)
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                pb[r] = (__bf16)x[r];
-                pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
-            }
-        };
-        // no mask needed: every column sees the whole tile (not at the end of a context, where the
-        // causal limits lie, nor in the tiles where the windows of the columns begin)
+        // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (where the causal
+        // limits lie) and the tiles where the columns' sliding windows begin need the mask:
+        // everywhere else every column sees the whole tile.
         const int tile_first = (cc.lt + cc.ft) * kTileTokens;
+        const int t0 = tile_first + 4 * q4;
+        const int lim = cc.L - col_back;
+        const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
         const bool unmasked = PREFIX || (tile_first + kTileTokens <= cc.L - (Q - 1) &&
                                          (reach == 0 || tile_first >= cc.L - p.window));
+        bf16x8 pb, pb_lo;
         if (unmasked)
-            softmax(std::false_type{});
+            online_softmax<false>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
         else
-            softmax(std::true_type{});
+            online_softmax<true>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
 
-        // ---- out^T[dim, column] += V^T . P^T
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            bf16x8 va;
-            if (KV == KV_BF16) {
-                const i16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + vread[dt]));
-                const i16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + kSlabBytes + vread[dt]));
-                va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
-            } else {
-                const i32x2 v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(vbuf + vread[dt]));
-                va = fp8x8_to_bf16x8((uint32_t)v[0], (uint32_t)v[1]);
-            }
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, acc[dt], 0, 0, 0);
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo, acc[dt], 0, 0, 0);
-        }
+        pv_accumulate<KV>(vbuf, of, pb, pb_lo, st);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
             const bool whole = seg_first_lt == 0 && cc.lt == cc.nt - 1;
-            const float l = rows_sum(lsum);
+            const float l = rows_sum(st.lsum);
             if (col_ok) {
                 // a column that saw no token (its query sits before this segment) leaves a zero row
                 // with an "empty" log-sum-exp
                 const float inv = l > 0.f ? vs / l : 0.f;
-                if (!PREFIX && whole) {
-                    const int64_t row = ((int64_t)cc.b * p.QH + col_row) * D;
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt)
-                        store_out4(p, row + 16 * dt + 4 * q4, acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv,
-                                   acc[dt][3] * inv);
+                const float lse = l > 0.f ? st.m + fast_log2(l) : kNegBig;
+                if (PREFIX) {
+                    const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row;
+                    if (q4 == 0) p.prefix_lse[slot] = lse;
+                    store_partial_row(p.prefix_o + slot * D, st, inv, q4);
+                } else if (whole) {
+                    store_final_row(p, ((int64_t)cc.b * p.QH + col_row) * D, st, inv, q4);
                 } else {
-                    float* dst;
-                    if (PREFIX) {
-                        const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row;
-                        dst = p.prefix_o + slot * D;
-                        if (q4 == 0) p.prefix_lse[slot] = m + fast_log2(l);
-                    } else {
-                        const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
-                        dst = p.part_o + slot * D;
-                        if (q4 == 0) p.part_lse[slot] = l > 0.f ? m + fast_log2(l) : kNegBig;
-                    }
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt)
-                        *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
-                            make_float4(acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv);
+                    const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
+                    if (q4 == 0) p.part_lse[slot] = lse;
+                    store_partial_row(p.part_o + slot * D, st, inv, q4);
                 }
             }
         }
