@@ -21,7 +21,6 @@ using pa::Params;
 
 constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds in registers
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
-constexpr int kMinColsMfma = 4;    // fewer (query token, head) columns than this: vector-ALU kernel
 constexpr int kMaxColsOneWave = 16; // up to here one wave per (partition, KV head); above, a workgroup of waves
 constexpr int kMaxColsMfma = 128;  // eight 16-column MFMA tiles, one per wave of the widest workgroup
 constexpr int kMaxQueryLen = 16;
@@ -67,11 +66,13 @@ int shared_tiles(const pa_shape* s) { return s->shared_prefix_blocks / 2; }
 // columns of the score matrix per KV head: (query token, query head of the group) pairs
 int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
 
-// The matrix-core kernels cover head_dim 128, groups of up to 16 query heads and 4..128 columns.
+// The matrix-core kernels cover head_dim 128, groups of up to 16 query heads and up to 128 columns
+// (narrow groups are padded inside the 16-column tile: the kernel is bound by the KV traffic, and
+// runs at the same speed for 1 column as for 16).
 bool use_mfma(const pa_shape* s, pa_kv_dtype kv)
 {
     const int G = s->num_q_heads / s->num_kv_heads;
-    return s->head_dim == 128 && G <= kMaxGroupMfma && columns(s) >= kMinColsMfma && columns(s) <= kMaxColsMfma;
+    return s->head_dim == 128 && G <= kMaxGroupMfma && columns(s) <= kMaxColsMfma;
 }
 
 int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : 16); }

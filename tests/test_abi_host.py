@@ -89,8 +89,10 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
         assert np.array_equal(pa.pa_split_plan(win, pa.PA_KV_BF16, lens)[1], pa.pa_split_plan(one, pa.PA_KV_BF16, lens)[1])
     # q_len 0 and 1 are the same call
     assert pa.pa_decode_workspace_size(shape(q_len=1), pa.PA_KV_BF16) == pa.pa_decode_workspace_size(shape(), pa.PA_KV_BF16)
-    # windows over single-head groups reach the matrix-core path once they have 4 rows
-    assert pa.pa_kernel_variant(shape(num_q_heads=8, q_len=4), pa.PA_KV_BF16) == "mfma"
+    # narrow groups run on the matrix-core path too (head_dim 128); head_dim 64 is the vector-ALU kernel's
+    assert pa.pa_kernel_variant(shape(num_q_heads=8, q_len=2), pa.PA_KV_BF16) == "mfma"
+    assert pa.pa_kernel_variant(shape(num_q_heads=8), pa.PA_KV_BF16) == "mfma"
+    assert pa.pa_kernel_variant(shape(num_q_heads=16, head_dim=64), pa.PA_KV_BF16) == "valu"
 
 
 @pytest.mark.parametrize("Q,window", [(1, 1), (1, 16), (1, 100), (4, 33), (16, 5), (1, 10 ** 6)])
@@ -173,16 +175,13 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(q_len=-1), pa.PA_ERR_INVALID_ARG),
     (dict(q_len=17), pa.PA_ERR_UNSUPPORTED),
     (dict(q_len=16, num_q_heads=128), pa.PA_ERR_UNSUPPORTED),           # 16 tokens x 16 heads > 128 rows per KV head
-    (dict(q_len=2, num_q_heads=8), pa.PA_ERR_UNSUPPORTED),              # 2 rows per KV head: below the matrix-core path
     (dict(q_len=4, head_dim=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # windows need head_dim 128
     (dict(shared_prefix_blocks=-2), pa.PA_ERR_INVALID_ARG),
     (dict(shared_prefix_blocks=257), pa.PA_ERR_INVALID_ARG),              # more than a table row holds
     (dict(shared_prefix_blocks=8, max_context_len=100), pa.PA_ERR_INVALID_ARG),  # contexts shorter than the prefix
     (dict(shared_prefix_blocks=8, q_len=4), pa.PA_ERR_UNSUPPORTED),
-    (dict(shared_prefix_blocks=8, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # groups of 2: no matrix-core pass
     (dict(shared_prefix_blocks=8, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
     (dict(window=-1), pa.PA_ERR_INVALID_ARG),
-    (dict(window=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),             # groups of 2: no matrix-core kernel
     (dict(window=64, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
     (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
     (dict(out_dtype=2), pa.PA_ERR_INVALID_ARG),

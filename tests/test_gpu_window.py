@@ -48,11 +48,11 @@ def check(pa, oracle, batch, what, **kw):
     return got, want
 
 
-# (Q, Hq, Hkv): columns per KV head Q*G = 4 .. 128: up to 16 one wave (padded to 4 / 8 / 16), above that a
+# (Q, Hq, Hkv): columns per KV head Q*G = 2 .. 128: up to 16 one wave (padded to 4 / 8 / 16), above that a
 # workgroup of 2 / 4 / 8 waves with 16 columns each
 WINDOW_SHAPES = [(4, 4, 4), (2, 8, 2), (2, 4, 1), (3, 6, 2), (2, 16, 2), (16, 2, 2), (7, 3, 1), (2, 16, 1),
                  (16, 4, 2), (5, 16, 2), (16, 4, 1), (4, 16, 1), (9, 7, 1), (16, 8, 1), (16, 16, 2), (8, 16, 1),
-                 (13, 9, 1), (5, 13, 1)]
+                 (13, 9, 1), (5, 13, 1), (2, 1, 1), (3, 2, 2), (2, 4, 2)]
 
 
 @pytest.mark.parametrize("Q,Hq,Hkv", WINDOW_SHAPES)
