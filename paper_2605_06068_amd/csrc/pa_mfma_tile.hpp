@@ -7,9 +7,12 @@
 // LDS tile layout: row t (one token, 256 B bf16 / 128 B fp8) at byte t*rowbytes; the 16-byte
 // piece holding dims [8c, 8c+8) (fp8: [16c, 16c+16)) sits at piece position c ^ (t mod pieces).
 // The XOR swizzle is applied on the *global* side of the LDS-DMA load (the LDS side of such a
-// load is always lane-linear), which keeps every 16-lane group on one contiguous row, and makes
-// both the operand reads (16 different rows per 16 lanes) and the transposing reads
-// bank-conflict free.
+// load is always lane-linear), which keeps every 16-lane group on one contiguous row and spreads
+// the operand reads (16 different rows per 16 lanes) and the transposing reads over the banks.
+// Measured with the SQ counters on the decode workload: LDS busy 4.0 cycles per LDS instruction
+// against 2.7 for conflict-free 1 KB / 512 B reads (fp8 rows are half as long, so rows t and t+8
+// still share banks there: twice the minimum); waves wait on LDS for under 1 % of their time
+// either way, so this was left alone.
 //
 // The P^T operand needs no data movement: the score tile comes out of the MFMA with lane l
 // holding column l%16 and tokens 4*(l/16)+{0..3}; declaring MFMA k-index 8*(l/16)+e to mean
