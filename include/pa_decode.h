@@ -44,7 +44,7 @@
  *     q   [batch, Q, num_q_heads, head_dim]      out [batch, Q, num_q_heads, head_dim]
  * and query token i attends causally, to t in [0, context_lens[b] - Q + i]; a query token with no
  * visible token yields a zero row.  The KV cache is read once for all Q tokens.  Supported for
- * head_dim 128 with Q * G <= 128 (matrix-core kernels only).
+ * Q * G <= 128.
  *
  * Shared prefix (shape.shared_prefix_blocks > 0; the long common prompt prefix of the paper's
  * prompt-caching workload, Appendix A, Scenario C: many concurrent requests over one cached
@@ -54,7 +54,7 @@
  * of once per sequence; the rest of every context is processed per sequence as usual and a merge
  * kernel joins the two by their log-sum-exps.  The promise is not checked on the device: block
  * ids of the prefix are taken from row 0 of block_tables.  Supported for plain decode
- * (q_len <= 1), head_dim 128 and G <= 16.
+ * (q_len <= 1).
  *
  * Sliding window (shape.window = W > 0; attention over the last W positions only, as in the
  * streaming encoder of the paper's Appendix A, Scenario D, whose per-stream cache is evicted in
@@ -62,11 +62,10 @@
  * position (context_lens[b] - 1 for plain decode, context_lens[b] - Q + i for query token i of a
  * multi-token call).  Blocks that lie entirely before the earliest window of a sequence
  * (before token context_lens[b] - Q - W + 1) are never dereferenced: their table entries may be
- * stale.  Supported on the matrix-core kernels (head_dim 128, Q * G <= 128), not together
- * with a shared prefix.
+ * stale.  Not supported together with a shared prefix.
  *
  * Supported: batch <= 65535; head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
- * 1 <= G <= 16 (G <= 8 for head_dim 64); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
+ * 1 <= G <= 16 and Q * G <= 128; PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
  * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
  */
 #ifndef PA_DECODE_H
@@ -226,9 +225,9 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
                             size_t workspace_bytes, void *stream, int32_t steps, float *partition_ms,
                             float *merge_ms);
 
-/* Name of the partition kernel variant pa_decode picks for this shape ("mfma": matrix cores, for
- * head_dim 128 and up to 128 query rows (Q * G) per KV head; "valu": head_dim 64); NULL for an invalid
- * or unsupported shape.  Static storage. */
+/* Name of the partition kernel variant pa_decode picks for this shape ("mfma": one wavefront per
+ * (partition, KV head), up to 16 query rows (Q * G) per KV head; "mfma-wide": a workgroup of 2, 4 or 8
+ * wavefronts, up to 128); NULL for an invalid or unsupported shape.  Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
 /* Human-readable name of a status code.  Static storage. */

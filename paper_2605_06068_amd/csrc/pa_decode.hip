@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
 #include <vector>
 
 #include "pa_device.hpp"
@@ -12,31 +13,33 @@
 #include "pa_merge.hpp"
 #include "pa_partition_mfma.hpp"
 #include "pa_partition_mfma_wide.hpp"
-#include "pa_partition_valu.hpp"
 #include "pa_plan.hpp"
 
 namespace {
 
 using pa::Params;
 
-constexpr int kMaxGroupValu = 8;   // widest group the vector-ALU kernel holds in registers
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
 constexpr int kMaxColsOneWave = 16; // up to here one wave per (partition, KV head); above, a workgroup of waves
 constexpr int kMaxColsMfma = 128;  // eight 16-column MFMA tiles, one per wave of the widest workgroup
 constexpr int kMaxQueryLen = 16;
-constexpr int kMfmaStagesBf16 = 2;  // depth of the LDS tile ring of the matrix-core kernel, bf16 KV
-constexpr int kMfmaStagesFp8 = 4;   // same for fp8 KV (tiles are half the size)
+// depth of the LDS tile ring of the one-wave kernel.  head_dim 128: 2 tiles of 16 KB (bf16) or 4
+// of 8 KB (fp8), one wave per SIMD.  head_dim 64: tiles are half that, and what pays is more
+// resident waves rather than deeper rings (measured on 64 sequences of 1k-8k tokens, fp8: 2 tiles
+// and 8 waves per compute unit 67 us, 8 tiles and 4 waves 85 us; bf16 within 2 % either way)
+constexpr int mfma_stages(int d, int kv) { return d == 128 ? (kv == PA_KV_BF16 ? 2 : 4) : 2; }
+constexpr int mfma_waves_per_cu(int d) { return d == 128 ? 4 : 8; }
 // ring depth of the multi-wave kernel (the ring is shared by the workgroup's waves), by KV type
 // and waves per workgroup
 constexpr int kWideStagesBf16[3] = {4, 4, 3};  // 2, 4, 8 waves (8 waves: 3 stages leave room for two workgroups per CU)
 constexpr int kWideStagesFp8[3] = {4, 4, 4};
+constexpr int kWideStages64Bf16 = 4;  // head_dim 64: half the bytes per tile
+constexpr int kWideStages64Fp8 = 6;
 // resident waves per compute unit the multi-wave plan aims at, LDS permitting: two workgroups of
 // up to 4 waves; two of 8 waves pay off for bf16 only (measured: fp8 with 128 columns is bound by
 // instruction issue, and more partitions only lengthen the merge)
 constexpr int wide_waves_per_cu(int kv, int nw) { return (nw == 8 && kv == PA_KV_BF16) ? 16 : 8; }
-constexpr int kMfmaWavesPerCu = 4;  // one wave per SIMD measured best; more, thinner waves were slower
 constexpr int kLdsPerCu = 160 * 1024;
-constexpr int kValuWavesPerCu = 8;
 constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
 constexpr int kMaxPartitions = 65535;
 constexpr int kMaxBatch = 65535;
@@ -66,40 +69,38 @@ int shared_tiles(const pa_shape* s) { return s->shared_prefix_blocks / 2; }
 // columns of the score matrix per KV head: (query token, query head of the group) pairs
 int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
 
-// The matrix-core kernels cover head_dim 128, groups of up to 16 query heads and up to 128 columns
+// The kernels cover head_dim 64 and 128, groups of up to 16 query heads and up to 128 columns
 // (narrow groups are padded inside the 16-column tile: the kernel is bound by the KV traffic, and
 // runs at the same speed for 1 column as for 16).
-bool use_mfma(const pa_shape* s, pa_kv_dtype kv)
-{
-    const int G = s->num_q_heads / s->num_kv_heads;
-    return s->head_dim == 128 && G <= kMaxGroupMfma && columns(s) <= kMaxColsMfma;
-}
-
 int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : 16); }
-
-int mfma_stages(pa_kv_dtype kv) { return kv == PA_KV_BF16 ? kMfmaStagesBf16 : kMfmaStagesFp8; }
 
 // waves per workgroup of the multi-wave kernel: one per 16 columns, rounded up to a power of two
 int wide_waves(int cols) { return cols <= 32 ? 2 : (cols <= 64 ? 4 : 8); }
 
-constexpr int wide_stages(int kv, int nw)
+constexpr int wide_stages(int d, int kv, int nw)
 {
+    if (d == 64) return kv == PA_KV_BF16 ? kWideStages64Bf16 : kWideStages64Fp8;
     const int i = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
     return kv == PA_KV_BF16 ? kWideStagesBf16[i] : kWideStagesFp8[i];
 }
 
-// waves (one-wave kernel) or workgroups (multi-wave kernel) of the matrix-core path resident per compute unit
-int mfma_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
+// workgroups of the multi-wave kernel resident per compute unit
+int wide_groups_per_cu(int d, int kv, int nw)
+{
+    const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(d, nw, wide_stages(d, kv, nw), kv);
+    const int want = wide_waves_per_cu(kv, nw) / nw;
+    return fit < want ? fit : want;
+}
+
+// waves (one-wave kernel) or workgroups (multi-wave kernel) resident per compute unit
+int groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
 {
     const int cols = columns(s);
     if (cols <= kMaxColsOneWave) {
-        const int fit = kLdsPerCu / pa::mfma_lds_bytes(mfma_stages(kv), mfma_col_pad(cols), (int)kv);
-        return fit < kMfmaWavesPerCu ? fit : kMfmaWavesPerCu;
+        const int fit = kLdsPerCu / pa::mfma_lds_bytes(s->head_dim, mfma_stages(s->head_dim, (int)kv), mfma_col_pad(cols), (int)kv);
+        return fit < mfma_waves_per_cu(s->head_dim) ? fit : mfma_waves_per_cu(s->head_dim);
     }
-    const int nw = wide_waves(cols);
-    const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(nw, wide_stages((int)kv, nw), (int)kv);
-    const int want = wide_waves_per_cu((int)kv, nw) / nw;
-    return fit < want ? fit : want;
+    return wide_groups_per_cu(s->head_dim, (int)kv, wide_waves(cols));
 }
 
 // Compute units of the current device (cached per process; 256 when there is no device).
@@ -133,19 +134,18 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return PA_ERR_UNSUPPORTED;
     if (s->q_len > kMaxQueryLen) return PA_ERR_UNSUPPORTED;
-    if (s->num_q_heads / s->num_kv_heads > (use_mfma(s, kv) ? kMaxGroupMfma : kMaxGroupValu)) return PA_ERR_UNSUPPORTED;
-    if (!use_mfma(s, kv) && query_len(s) > 1) return PA_ERR_UNSUPPORTED;  // multi-token calls: matrix-core kernel only
+    if (s->num_q_heads / s->num_kv_heads > kMaxGroupMfma || columns(s) > kMaxColsMfma) return PA_ERR_UNSUPPORTED;
     if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
     if (s->batch > kMaxBatch) return PA_ERR_UNSUPPORTED;  // the merge kernels index sequences by blockIdx.y
     if (shared_tiles(s) > 0) {
-        // the per-sequence pass runs on the one-wave matrix-core kernel, the prefix pass on the multi-wave one
-        if (query_len(s) > 1 || !use_mfma(s, kv) || s->batch < 1) return PA_ERR_UNSUPPORTED;
+        // the per-sequence pass runs on the one-wave kernel, the prefix pass on the multi-wave one
+        if (query_len(s) > 1 || s->batch < 1) return PA_ERR_UNSUPPORTED;
         // the merge of such calls reads rows of `out` back as float32
         if (s->out_dtype != PA_OUT_F32) return PA_ERR_UNSUPPORTED;
         if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens) return PA_ERR_INVALID_ARG;
     }
-    // sliding windows: matrix-core kernels only, and not together with a shared prefix
-    if (s->window > 0 && (!use_mfma(s, kv) || shared_tiles(s) > 0)) return PA_ERR_UNSUPPORTED;
+    // sliding windows: not together with a shared prefix
+    if (s->window > 0 && shared_tiles(s) > 0) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->window + kMaxQueryLen > INT32_MAX / 2) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
     // the global tile index and the launch grid are 32-bit
@@ -174,11 +174,10 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     } else {
         // one resident wave (or workgroup) per (partition, KV head): as many partitions as the device holds at once,
         // but never more than there can be tiles
-        const int groups_per_cu = use_mfma(s, kv) ? mfma_groups_per_cu(s, kv) : kValuWavesPerCu;
-        int64_t P = (int64_t)compute_units() * groups_per_cu / s->num_kv_heads;
+        int64_t P = (int64_t)compute_units() * groups_per_cu(s, kv) / s->num_kv_heads;
         // small calls: a partition should have a few tiles to amortise its start-up, and every extra
         // partition is one more piece per row for the merge (measured on single-sequence calls)
-        const int min_tiles = (use_mfma(s, kv) && columns(s) > kMaxColsOneWave) ? kMinTilesWide : kMinTilesOneWave;
+        const int min_tiles = columns(s) > kMaxColsOneWave ? kMinTilesWide : kMinTilesOneWave;
         if (P > tile_bound / min_tiles) P = tile_bound / min_tiles;
         if (P > kMaxPartitions) P = kMaxPartitions;
         if (P < 1) P = 1;
@@ -200,9 +199,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         const int group_cols = cols < kMaxColsMfma ? cols : kMaxColsMfma;
         plan->prefix_waves = wide_waves(group_cols);
         plan->prefix_groups = (cols + 16 * plan->prefix_waves - 1) / (16 * plan->prefix_waves);
-        const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(plan->prefix_waves, wide_stages((int)kv, plan->prefix_waves), (int)kv);
-        const int want = wide_waves_per_cu((int)kv, plan->prefix_waves) / plan->prefix_waves;
-        const int per_cu = fit < want ? fit : want;
+        const int per_cu = wide_groups_per_cu(s->head_dim, (int)kv, plan->prefix_waves);
         int64_t Pp = (int64_t)compute_units() * per_cu / ((int64_t)s->num_kv_heads * plan->prefix_groups);
         if (s->num_partitions > 0) Pp = s->num_partitions;  // tests force both counts with one knob
         if (Pp > plan->skip_tiles) Pp = plan->skip_tiles;
@@ -219,79 +216,66 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-template <int D, int GMAX, int KV>
-void launch_valu(const Params& p, bool trace, dim3 grid, hipStream_t st)
-{
-    if (trace)
-        hipLaunchKernelGGL((pa::partition_valu_kernel<D, GMAX, KV, true>), grid, dim3(64), 0, st, p);
-    else
-        hipLaunchKernelGGL((pa::partition_valu_kernel<D, GMAX, KV, false>), grid, dim3(64), 0, st, p);
-}
-
-template <int D, int KV>
-void launch_valu_g(const Params& p, bool trace, dim3 grid, hipStream_t st)
-{
-    if (p.G <= 2)
-        launch_valu<D, 2, KV>(p, trace, grid, st);
-    else if (p.G <= 4)
-        launch_valu<D, 4, KV>(p, trace, grid, st);
-    else
-        launch_valu<D, 8, KV>(p, trace, grid, st);
-}
-
-template <int NSTAGE, int GPAD, int KV>
+template <int D, int CPAD, int KV>
 void launch_mfma(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
+    constexpr int NSTAGE = mfma_stages(D, KV);
     if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_kernel<NSTAGE, GPAD, KV, true>), grid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, true>), grid, dim3(64), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_kernel<NSTAGE, GPAD, KV, false>), grid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, false>), grid, dim3(64), 0, st, p);
 }
 
-template <int NSTAGE, int KV>
-void launch_mfma_c(const Params& p, bool trace, dim3 grid, hipStream_t st)
-{
-    const int cpad = mfma_col_pad(p.Q * p.G);
-    if (cpad == 4)
-        launch_mfma<NSTAGE, 4, KV>(p, trace, grid, st);
-    else if (cpad == 8)
-        launch_mfma<NSTAGE, 8, KV>(p, trace, grid, st);
-    else
-        launch_mfma<NSTAGE, 16, KV>(p, trace, grid, st);
-}
-
-template <int NW, int KV>
+template <int D, int NW, int KV>
 void launch_wide(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
-    constexpr int NSTAGE = wide_stages(KV, NW);
+    constexpr int NSTAGE = wide_stages(D, KV, NW);
     if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, true, false>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NSTAGE, KV, true, false>), grid, dim3(NW * 64), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<NW, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
 }
 
-template <int KV>
-void launch_wide_w(const Params& p, bool trace, dim3 grid, hipStream_t st)
+// the per-sequence pass: one wave per (partition, KV head) up to 16 columns, a workgroup of waves above
+template <int D, int KV>
+void launch_partition(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
-    const int nw = wide_waves(p.Q * p.G);
-    if (nw == 2)
-        launch_wide<2, KV>(p, trace, grid, st);
-    else if (nw == 4)
-        launch_wide<4, KV>(p, trace, grid, st);
+    const int cols = p.Q * p.G;
+    if (cols <= 4)
+        launch_mfma<D, 4, KV>(p, trace, grid, st);
+    else if (cols <= 8)
+        launch_mfma<D, 8, KV>(p, trace, grid, st);
+    else if (cols <= kMaxColsOneWave)
+        launch_mfma<D, 16, KV>(p, trace, grid, st);
+    else if (wide_waves(cols) == 2)
+        launch_wide<D, 2, KV>(p, trace, grid, st);
+    else if (wide_waves(cols) == 4)
+        launch_wide<D, 4, KV>(p, trace, grid, st);
     else
-        launch_wide<8, KV>(p, trace, grid, st);
+        launch_wide<D, 8, KV>(p, trace, grid, st);
 }
 
 // the pass over the prefix all sequences share
-template <int KV>
+template <int D, int KV>
 void launch_prefix(const Params& p, int nw, dim3 grid, hipStream_t st)
 {
     if (nw == 2)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<2, wide_stages(KV, 2), KV, false, true>), grid, dim3(128), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 2, wide_stages(D, KV, 2), KV, false, true>), grid, dim3(128), 0, st, p);
     else if (nw == 4)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<4, wide_stages(KV, 4), KV, false, true>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 4, wide_stages(D, KV, 4), KV, false, true>), grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<8, wide_stages(KV, 8), KV, false, true>), grid, dim3(512), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 8, wide_stages(D, KV, 8), KV, false, true>), grid, dim3(512), 0, st, p);
+}
+
+// calls f with head_dim and the KV type as compile-time constants
+template <typename F>
+void with_head_dim_and_kv(int d, pa_kv_dtype kv, F&& f)
+{
+    using std::integral_constant;
+    if (d == 128 && kv == PA_KV_BF16) f(integral_constant<int, 128>{}, integral_constant<int, pa::KV_BF16>{});
+    else if (d == 128) f(integral_constant<int, 128>{}, integral_constant<int, pa::KV_FP8>{});
+    else if (kv == PA_KV_BF16) f(integral_constant<int, 64>{}, integral_constant<int, pa::KV_BF16>{});
+    else f(integral_constant<int, 64>{}, integral_constant<int, pa::KV_FP8>{});
 }
 
 struct Events {
@@ -356,57 +340,33 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (ev && hipEventRecord(ev->before, hs) != hipSuccess) return PA_ERR_HIP;
 
-    if (plan.skip_tiles > 0) {
-        const dim3 pgrid((uint32_t)plan.Pp * (uint32_t)p.Hkv * (uint32_t)plan.prefix_groups);
-        if (kv == PA_KV_BF16)
-            launch_prefix<pa::KV_BF16>(p, plan.prefix_waves, pgrid, hs);
-        else
-            launch_prefix<pa::KV_FP8>(p, plan.prefix_waves, pgrid, hs);
-        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
-    }
-    const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
-    if (use_mfma(shape, kv) && columns(shape) > kMaxColsOneWave) {
-        if (kv == PA_KV_BF16)
-            launch_wide_w<pa::KV_BF16>(p, trace, grid, hs);
-        else
-            launch_wide_w<pa::KV_FP8>(p, trace, grid, hs);
-    } else if (use_mfma(shape, kv)) {
-        if (kv == PA_KV_BF16)
-            launch_mfma_c<kMfmaStagesBf16, pa::KV_BF16>(p, trace, grid, hs);
-        else
-            launch_mfma_c<kMfmaStagesFp8, pa::KV_FP8>(p, trace, grid, hs);
-    } else if (shape->head_dim == 128) {
-        if (kv == PA_KV_BF16)
-            launch_valu_g<128, pa::KV_BF16>(p, trace, grid, hs);
-        else
-            launch_valu_g<128, pa::KV_FP8>(p, trace, grid, hs);
-    } else {
-        if (kv == PA_KV_BF16)
-            launch_valu_g<64, pa::KV_BF16>(p, trace, grid, hs);
-        else
-            launch_valu_g<64, pa::KV_FP8>(p, trace, grid, hs);
-    }
-    if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
-    if (ev && hipEventRecord(ev->between, hs) != hipSuccess) return PA_ERR_HIP;
+    bool launched = true;
+    with_head_dim_and_kv(shape->head_dim, kv, [&](auto d, auto kvt) {
+        constexpr int D = decltype(d)::value, KV = decltype(kvt)::value;
+        if (plan.skip_tiles > 0) {
+            const dim3 pgrid((uint32_t)plan.Pp * (uint32_t)p.Hkv * (uint32_t)plan.prefix_groups);
+            launch_prefix<D, KV>(p, plan.prefix_waves, pgrid, hs);
+            if (hipGetLastError() != hipSuccess) { launched = false; return; }
+        }
+        const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
+        launch_partition<D, KV>(p, trace, grid, hs);
+        if (hipGetLastError() != hipSuccess) { launched = false; return; }
+        if (ev && hipEventRecord(ev->between, hs) != hipSuccess) { launched = false; return; }
 
-    if (plan.skip_tiles > 0) {
-        const dim3 mgrid(p.Hq, p.B);
-        hipLaunchKernelGGL((pa::merge_prefix_kernel<128>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
-        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
-    } else if (plan.P > 1) {
-        const dim3 mgrid(p.QH, p.B < plan.P - 1 ? p.B : plan.P - 1);  // at most P - 1 sequences are cut
-        // few sequences cut many times each: split a row's pieces over the waves of a workgroup
-        const bool many = plan.P >= kMergeManyPerSeq * (int64_t)p.B;
-        if (shape->head_dim == 128 && many)
-            hipLaunchKernelGGL((pa::merge_many_kernel<128>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
-        else if (shape->head_dim == 128)
-            hipLaunchKernelGGL((pa::merge_kernel<128>), mgrid, dim3(64), 0, hs, p);
-        else if (many)
-            hipLaunchKernelGGL((pa::merge_many_kernel<64>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
-        else
-            hipLaunchKernelGGL((pa::merge_kernel<64>), mgrid, dim3(64), 0, hs, p);
-        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
-    }
+        if (plan.skip_tiles > 0) {
+            const dim3 mgrid(p.Hq, p.B);
+            hipLaunchKernelGGL((pa::merge_prefix_kernel<D>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
+        } else if (plan.P > 1) {
+            const dim3 mgrid(p.QH, p.B < plan.P - 1 ? p.B : plan.P - 1);  // at most P - 1 sequences are cut
+            // few sequences cut many times each: split a row's pieces over the waves of a workgroup
+            if (plan.P >= kMergeManyPerSeq * (int64_t)p.B)
+                hipLaunchKernelGGL((pa::merge_many_kernel<D>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
+            else
+                hipLaunchKernelGGL((pa::merge_kernel<D>), mgrid, dim3(64), 0, hs, p);
+        }
+        if (hipGetLastError() != hipSuccess) launched = false;
+    });
+    if (!launched) return PA_ERR_HIP;
     if (ev && hipEventRecord(ev->after, hs) != hipSuccess) return PA_ERR_HIP;
     return PA_OK;
 }
@@ -569,7 +529,7 @@ pa_status pa_kv_append(const void* k_new, const void* v_new, void* k_cache, void
 const char* pa_kernel_variant(const pa_shape* shape, pa_kv_dtype kv_dtype)
 {
     if (check_shape(shape, kv_dtype) != PA_OK) return nullptr;
-    return use_mfma(shape, kv_dtype) ? "mfma" : "valu";
+    return columns(shape) <= kMaxColsOneWave ? "mfma" : "mfma-wide";
 }
 
 const char* pa_status_string(pa_status status)

@@ -2,17 +2,17 @@
 // (partition, KV head), up to 16 columns; pa_partition_mfma_wide.hpp: a workgroup of wavefronts,
 // 16 columns each): the geometry of a tile in LDS, the LDS-DMA load, the cursor over the global
 // tile sequence, and what one wavefront does with one tile of 32 tokens and 16 columns --
-// which blocks and rows to load, scores, online softmax, PV.  head_dim is 128 throughout.
+// which blocks and rows to load, scores, online softmax, PV.  D = head_dim is 128 or 64.
 //
-// LDS tile layout: row t (one token, 256 B bf16 / 128 B fp8) at byte t*rowbytes; the 16-byte
+// LDS tile layout: row t (one token, 2 D bytes bf16 / D bytes fp8) at byte t*rowbytes; the 16-byte
 // piece holding dims [8c, 8c+8) (fp8: [16c, 16c+16)) sits at piece position c ^ (t mod pieces).
 // The XOR swizzle is applied on the *global* side of the LDS-DMA load (the LDS side of such a
 // load is always lane-linear), which keeps every 16-lane group on one contiguous row and spreads
 // the operand reads (16 different rows per 16 lanes) and the transposing reads over the banks.
-// Measured with the SQ counters on the decode workload: LDS busy 4.0 cycles per LDS instruction
-// against 2.7 for conflict-free 1 KB / 512 B reads (fp8 rows are half as long, so rows t and t+8
-// still share banks there: twice the minimum); waves wait on LDS for under 1 % of their time
-// either way, so this was left alone.
+// Measured with the SQ counters on the decode workload (head_dim 128): LDS busy 4.0 cycles per LDS
+// instruction against 2.7 for conflict-free 1 KB / 512 B reads (rows of 128 B or less repeat their
+// banks every few rows: twice the minimum and more); waves wait on LDS for under 1 % of their
+// time either way, so this was left alone.
 //
 // The P^T operand needs no data movement: the score tile comes out of the MFMA with lane l
 // holding column l%16 and tokens 4*(l/16)+{0..3}; declaring MFMA k-index 8*(l/16)+e to mean
@@ -36,12 +36,19 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kQRowBytes = 256;  // one query row: 128 bf16
+// One query row (always bf16) and how the 1 KB wave-wide LDS-DMA load covers such rows.
+template <int D>
+struct QGeom {
+    static constexpr int kRow = 2 * D;                     // bytes
+    static constexpr int kPieces = kRow / 16;              // 16-byte pieces per row
+    static constexpr int kRowsPerDma = kWave / kPieces;    // 4 (head_dim 128) or 8 (64)
+};
 
-// Storage geometry of one (block, head) slab of the KV cache, head_dim 128.
-template <int KV>
+// Storage geometry of one (block, head) slab of the KV cache.
+template <int D, int KV>
 struct KvGeom {
-    static constexpr int kRow = KV == KV_BF16 ? 256 : 128;  // bytes per token row
+    static_assert(D == 64 || D == 128, "head_dim");
+    static constexpr int kRow = KV == KV_BF16 ? 2 * D : D;  // bytes per token row
     static constexpr int kSlab = kBlockSize * kRow;          // 16 rows
     static constexpr int kPieces = kRow / 16;                // 16-byte pieces per row
     static constexpr int kRowsPerDma = kWave / kPieces;      // rows one 1 KB wave-wide load covers
@@ -148,78 +155,82 @@ __device__ __forceinline__ void trace_tile_blocks(int32_t* trace, const TileBloc
 }
 
 // this lane's global byte offset for LDS-DMA instruction r of a slab (rows r*kRowsPerDma ..)
-template <int KV>
+template <int D, int KV>
 __device__ __forceinline__ uint32_t slab_dma_offset(int r, int lane)
 {
-    using Geo = KvGeom<KV>;
+    using Geo = KvGeom<D, KV>;
     const int t = r * Geo::kRowsPerDma + lane / Geo::kPieces;
     return t * Geo::kRow + (((lane % Geo::kPieces) ^ (t & (Geo::kPieces - 1))) << 4);
 }
 
 // the same with the stand-in rule applied: rows outside [lo, hi) load row lo instead
-template <int KV>
+template <int D, int KV>
 __device__ __forceinline__ uint32_t live_or_stand_in(uint32_t off, int row, int lo, int hi)
 {
-    using Geo = KvGeom<KV>;
+    using Geo = KvGeom<D, KV>;
     return (row >= lo && row < hi) ? off : lo * Geo::kRow + (off & (Geo::kRow - 1));
 }
 
 // ---- one tile: what a wavefront computes on it ---------------------------------------------------
 // Per-lane LDS read offsets of the MFMA operands (lane = 16*q4 + n).
-template <int KV>
+template <int D, int KV>
 struct OperandOffsets {
-    uint32_t kread[4];  // inside a K slab: this lane's operand piece for k-step kk (token n, dims 32kk + 8q4 + [0,8))
-    uint32_t vread[8];  // inside the V half of a stage: this lane's transposing-read source for dim tile dt
+    uint32_t kread[D / 32];  // inside a K slab: this lane's operand piece for k-step kk (token n, dims 32kk + 8q4 + [0,8))
+    uint32_t vread[D / 16];  // inside the V half of a stage: this lane's transposing-read source for dim tile dt
 
     __device__ __forceinline__ void init(int n, int q4)
     {
-        using Geo = KvGeom<KV>;
+        using Geo = KvGeom<D, KV>;
+        constexpr int kMask = Geo::kPieces - 1;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < D / 32; ++kk) {
             if (KV == KV_BF16)  // 16 bytes
-                kread[kk] = n * Geo::kRow + (((4 * kk + q4) ^ n) << 4);
+                kread[kk] = n * Geo::kRow + (((4 * kk + q4) ^ (n & kMask)) << 4);
             else                // 8 bytes: half of 16-byte piece 2kk + q4/2
-                kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & 7)) << 4) + ((q4 & 1) << 3);
+                kread[kk] = n * Geo::kRow + (((2 * kk + (q4 >> 1)) ^ (n & kMask)) << 4) + ((q4 & 1) << 3);
         }
         // bf16: one read per block, rows = tokens 4q4 + n/4, 8 bytes = 4 dims.  fp8: one read for both blocks,
         // rows n/2 = 0..3 -> tokens 4q4.. of block 0, rows 4..7 -> the same tokens of block 1, 8 bytes = 8 dims.
         if (KV == KV_BF16) {
             const int row = 4 * q4 + (n >> 2);
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                vread[dt] = row * Geo::kRow + ((n & 1) << 3) + (((2 * dt + ((n >> 1) & 1)) ^ row) << 4);
+            for (int dt = 0; dt < D / 16; ++dt)
+                vread[dt] = row * Geo::kRow + ((n & 1) << 3) + (((2 * dt + ((n >> 1) & 1)) ^ (row & kMask)) << 4);
         } else {
             const int r = n >> 1;
             const int tok = 4 * q4 + (r & 3);
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                vread[dt] = (r >> 2) * Geo::kSlab + tok * Geo::kRow + ((dt ^ (tok & 7)) << 4) + ((n & 1) << 3);
+            for (int dt = 0; dt < D / 16; ++dt)
+                vread[dt] = (r >> 2) * Geo::kSlab + tok * Geo::kRow + ((dt ^ (tok & kMask)) << 4) + ((n & 1) << 3);
         }
     }
 };
 
-// The 16 columns' query rows from an LDS slot (row c at c*256 B, swizzled like a K row) into MFMA
-// B-operand registers; a padding column gets zeros.
-__device__ __forceinline__ void load_query_operand(const char* slot, int n, int q4, bool col_ok, bf16x8 (&qreg)[4])
+// The 16 columns' query rows from an LDS slot (row c at c * 2 D bytes, swizzled like a bf16 K row)
+// into MFMA B-operand registers; a padding column gets zeros.
+template <int D>
+__device__ __forceinline__ void load_query_operand(const char* slot, int n, int q4, bool col_ok, bf16x8 (&qreg)[D / 32])
 {
+    using QG = QGeom<D>;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        uint4 w = *reinterpret_cast<const uint4*>(slot + (col_ok ? n : 0) * kQRowBytes + (((4 * kk + q4) ^ n) << 4));
+    for (int kk = 0; kk < D / 32; ++kk) {
+        uint4 w = *reinterpret_cast<const uint4*>(slot + (col_ok ? n : 0) * QG::kRow +
+                                                  (((4 * kk + q4) ^ (n & (QG::kPieces - 1))) << 4));
         if (!col_ok) w = make_uint4(0, 0, 0, 0);
         qreg[kk] = as_bf16x8(w);
     }
 }
 
 // S^T[token, column] = K . Q^T for the two blocks of the tile
-template <int KV>
-__device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets<KV>& of, const bf16x8 (&qreg)[4],
+template <int D, int KV>
+__device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets<D, KV>& of, const bf16x8 (&qreg)[D / 32],
                                           f32x4& s0, f32x4& s1)
 {
-    constexpr int kSlabBytes = KvGeom<KV>::kSlab;
+    constexpr int kSlabBytes = KvGeom<D, KV>::kSlab;
     s0 = f32x4{0.f, 0.f, 0.f, 0.f};
     s1 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < D / 32; ++kk) {
         bf16x8 a0, a1;
         if (KV == KV_BF16) {
             a0 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + of.kread[kk]));
@@ -237,16 +248,17 @@ __device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets
 
 // Online softmax state of one column (replicated over the four lanes that hold its tokens) and
 // the unnormalised output accumulators out^T[dim, column].
+template <int D>
 struct ColumnState {
     float m, lsum;
-    f32x4 acc[8];
+    f32x4 acc[D / 16];
 
     __device__ __forceinline__ void reset()
     {
         m = kNegBig;
         lsum = 0.f;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int dt = 0; dt < D / 16; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 };
 
@@ -255,9 +267,9 @@ struct ColumnState {
 // the causal limit of a multi-token call, the start of a sliding window); without it the whole tile.
 // Leaves the P^T operand as a bf16 pair (high part + rounding remainder: 16 significant bits, so
 // the weights lose nothing that matters against the fp32 accumulation).
-template <bool MASKED>
+template <bool MASKED, int D>
 __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1, float qs, int t0, int lim, int low,
-                                               ColumnState& st, bf16x8& pb, bf16x8& pb_lo)
+                                               ColumnState<D>& st, bf16x8& pb, bf16x8& pb_lo)
 {
     float x[8];
     bool ok[8];
@@ -282,7 +294,7 @@ __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1,
     st.m = m_new;
     if (__any(alpha != 1.f)) {
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) st.acc[dt] *= alpha;
+        for (int dt = 0; dt < D / 16; ++dt) st.acc[dt] *= alpha;
     }
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -292,13 +304,13 @@ __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1,
 }
 
 // out^T[dim, column] += V^T . P^T
-template <int KV>
-__device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOffsets<KV>& of, const bf16x8& pb,
-                                              const bf16x8& pb_lo, ColumnState& st)
+template <int D, int KV>
+__device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOffsets<D, KV>& of, const bf16x8& pb,
+                                              const bf16x8& pb_lo, ColumnState<D>& st)
 {
-    constexpr int kSlabBytes = KvGeom<KV>::kSlab;
+    constexpr int kSlabBytes = KvGeom<D, KV>::kSlab;
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) {
+    for (int dt = 0; dt < D / 16; ++dt) {
         bf16x8 va;
         if (KV == KV_BF16) {
             const i16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vbuf + of.vread[dt]));
@@ -313,20 +325,22 @@ __device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOff
     }
 }
 
-// One column's 128 output values times `inv`, as float32 to `dst` (a partial row in the workspace)
-__device__ __forceinline__ void store_partial_row(float* dst, const ColumnState& st, float inv, int q4)
+// One column's D output values times `inv`, as float32 to `dst` (a partial row in the workspace)
+template <int D>
+__device__ __forceinline__ void store_partial_row(float* dst, const ColumnState<D>& st, float inv, int q4)
 {
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
+    for (int dt = 0; dt < D / 16; ++dt)
         *reinterpret_cast<float4*>(dst + 16 * dt + 4 * q4) =
             make_float4(st.acc[dt][0] * inv, st.acc[dt][1] * inv, st.acc[dt][2] * inv, st.acc[dt][3] * inv);
 }
 
 // ... or as a final row of `out` (element index `row`), in the output's type
-__device__ __forceinline__ void store_final_row(const Params& p, int64_t row, const ColumnState& st, float inv, int q4)
+template <int D>
+__device__ __forceinline__ void store_final_row(const Params& p, int64_t row, const ColumnState<D>& st, float inv, int q4)
 {
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
+    for (int dt = 0; dt < D / 16; ++dt)
         store_out4(p, row + 16 * dt + 4 * q4, st.acc[dt][0] * inv, st.acc[dt][1] * inv, st.acc[dt][2] * inv,
                    st.acc[dt][3] * inv);
 }

@@ -1,4 +1,4 @@
-// Partition kernel, matrix-core variant (head_dim 128, bf16 or fp8 KV) for up to 16 columns.
+// Partition kernel, matrix-core variant (head_dim 128 or 64, bf16 or fp8 KV) for up to 16 columns.
 // The columns of its matrix tile are the (query token, query head) pairs that share one KV
 // head: q_len * G of them (plain decode: the G heads of the group), padded to CPAD = 4, 8 or
 // 16 inside one 16-column MFMA tile.  One wavefront per (partition, KV head) walks its balanced
@@ -31,36 +31,53 @@
 
 namespace pa {
 
-// LDS bytes one workgroup (one wave) of the kernel uses: tile ring + query-row ring.
-constexpr int mfma_lds_bytes(int nstage, int cpad, int kv)
+// bytes of one tile (K block 0, K block 1, V block 0, V block 1) in LDS
+constexpr int mfma_stage_bytes(int d, int kv)
 {
-    return nstage * ((kv == KV_BF16 ? KvGeom<KV_BF16>::kStage : KvGeom<KV_FP8>::kStage) + cpad * kQRowBytes);
+    return d == 128 ? (kv == KV_BF16 ? KvGeom<128, KV_BF16>::kStage : KvGeom<128, KV_FP8>::kStage)
+                    : (kv == KV_BF16 ? KvGeom<64, KV_BF16>::kStage : KvGeom<64, KV_FP8>::kStage);
 }
 
-// wait until at most `later_tiles` whole tiles (PER_TILE loads each) plus EXTRA loads are still in flight
-template <int EXTRA, int NSTAGE, int PER_TILE>
+// LDS-DMA loads that bring in the query rows of `cpad` columns, 1 KB each
+constexpr int mfma_q_loads(int d, int cpad)
+{
+    return (cpad * 2 * d + 1023) / 1024;
+}
+
+// LDS bytes one workgroup (one wave) of the kernel uses: tile ring + query-row ring.
+constexpr int mfma_lds_bytes(int d, int nstage, int cpad, int kv)
+{
+    return nstage * (mfma_stage_bytes(d, kv) + mfma_q_loads(d, cpad) * 1024);
+}
+
+// wait until at most `later_tiles` whole tiles (PER_TILE loads each, at most MAXT tiles) plus EXTRA
+// loads are still in flight
+template <int EXTRA, int PER_TILE, int MAXT>
 __device__ __forceinline__ void wait_tile(int later_tiles)
 {
-    static_assert(3 * PER_TILE + EXTRA <= 63, "vmcnt is a 6-bit counter");
-    if (NSTAGE >= 4 && later_tiles >= 3) wait_vmcnt<3 * PER_TILE + EXTRA>();
-    else if (NSTAGE >= 3 && later_tiles == 2) wait_vmcnt<2 * PER_TILE + EXTRA>();
-    else if (later_tiles == 1) wait_vmcnt<1 * PER_TILE + EXTRA>();
-    else wait_vmcnt<EXTRA>();
+    static_assert(MAXT * PER_TILE + EXTRA <= 63, "vmcnt is a 6-bit counter");
+    if constexpr (MAXT == 0) {
+        wait_vmcnt<EXTRA>();
+    } else {
+        if (later_tiles >= MAXT) wait_vmcnt<MAXT * PER_TILE + EXTRA>();
+        else wait_tile<EXTRA, PER_TILE, MAXT - 1>(later_tiles);
+    }
 }
 
-template <int NSTAGE, int CPAD, int KV, bool TRACE>
+template <int D, int NSTAGE, int CPAD, int KV, bool TRACE>
 __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 {
-    constexpr int D = 128;
-    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring depth");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 8, "ring depth");
     static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16, "padded column count");
-    using Geo = KvGeom<KV>;
+    using Geo = KvGeom<D, KV>;
+    using QG = QGeom<D>;
     constexpr int kSlabBytes = Geo::kSlab;
     constexpr int kStageBytes = Geo::kStage;
     constexpr int kDmaPerTile = Geo::kDmaPerTile;
-    constexpr int kQSlot = CPAD * kQRowBytes;
-    static_assert(mfma_lds_bytes(NSTAGE, CPAD, KV) <= 65536, "static LDS limit");
-    __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(NSTAGE, CPAD, KV)];
+    constexpr int kQLoads = mfma_q_loads(D, CPAD);
+    constexpr int kQSlot = kQLoads * 1024;
+    static_assert(mfma_lds_bytes(D, NSTAGE, CPAD, KV) <= 65536, "static LDS limit");
+    __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(D, NSTAGE, CPAD, KV)];
 
     const int lane = threadIdx.x;
     // partition index fastest: workgroups go to the chip's eight dies round-robin, so (with P a
@@ -113,19 +130,19 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     int dma_row[Geo::kDmaPerSlab];       // the token row of the block it loads
 #pragma unroll
     for (int r = 0; r < Geo::kDmaPerSlab; ++r) {
-        dma_off[r] = slab_dma_offset<KV>(r, lane);
+        dma_off[r] = slab_dma_offset<D, KV>(r, lane);
         dma_row[r] = r * Geo::kRowsPerDma + lane / Geo::kPieces;
     }
-    // LDS-DMA of the query rows (always bf16: 4 rows of 256 B per instruction).  LDS row c holds
-    // column c, i.e. query token c / G, head c % G of this group; padding rows re-read column 0.
-    uint32_t qdma_off[CPAD / 4];
+    // LDS-DMA of the query rows (always bf16: 1 KB, i.e. 4 or 8 rows, per instruction).  LDS row c
+    // holds column c, i.e. query token c / G, head c % G of this group; padding rows re-read column 0.
+    uint32_t qdma_off[kQLoads];
 #pragma unroll
-    for (int r = 0; r < CPAD / 4; ++r) {
-        const int c = 4 * r + q4;
-        const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * kQRowBytes : 0;
-        qdma_off[r] = src + ((n ^ (c & 15)) << 4);
+    for (int r = 0; r < kQLoads; ++r) {
+        const int c = r * QG::kRowsPerDma + lane / QG::kPieces;
+        const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * QG::kRow : 0;
+        qdma_off[r] = src + (((lane % QG::kPieces) ^ (c & (QG::kPieces - 1))) << 4);
     }
-    OperandOffsets<KV> of;
+    OperandOffsets<D, KV> of;
     of.init(n, q4);
     // this lane's column n
     const bool col_ok = n < ncols;                                 // a real column
@@ -143,9 +160,9 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     int q_issue = 0;  // query slot the issue side fills next
     auto issue = [&](int i, int stage) {
         if (i == 0 || ic.lt == 0) {  // a new segment starts: send its query rows ahead of its first tile
-            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.QH + g * G) * kQRowBytes;
+            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.QH + g * G) * QG::kRow;
 #pragma unroll
-            for (int r = 0; r < CPAD / 4; ++r) dma16(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
+            for (int r = 0; r < kQLoads; ++r) dma16(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
             q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
         }
         const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
@@ -157,7 +174,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r)
                 dma16(ldst + sub * kSlabBytes + r * 1024,
-                      live_or_stand_in<KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), kb);
+                      live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), kb);
         }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
@@ -165,7 +182,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r)
                 dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024,
-                      live_or_stand_in<KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), vb);
+                      live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), vb);
         }
         advance(ic, p.context_lens, B, sp);
     };
@@ -173,9 +190,9 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     // ---- online softmax state: lane = column n, tokens 4*q4+{0..3} of each block
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;  // K scale folded in
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    ColumnState st;
+    ColumnState<D> st;
     st.reset();
-    bf16x8 qreg[4];
+    bf16x8 qreg[D / 32];
     int q_comp = 0;       // query slot of the segment being computed
     int seg_first_lt = 0;
 
@@ -198,7 +215,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         const char* kbuf = smem + stage * kStageBytes;
         const char* vbuf = kbuf + 2 * kSlabBytes;
 
-        wait_tile<kDmaPerTile / 2, NSTAGE, kDmaPerTile>(later);  // K of this tile (and its segment's query rows) landed
+        wait_tile<kDmaPerTile / 2, kDmaPerTile, NSTAGE - 1>(later);  // K of this tile (and its segment's query rows) landed
         if (tile == 0 || cc.lt == 0) {  // segment start
             seg_first_lt = cc.lt;
             if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is mine
@@ -206,12 +223,12 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                 write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
             }
             st.reset();
-            load_query_operand(qslots + q_comp * kQSlot, n, q4, col_ok, qreg);
+            load_query_operand<D>(qslots + q_comp * kQSlot, n, q4, col_ok, qreg);
             q_comp = (q_comp + 1 == NSTAGE) ? 0 : q_comp + 1;
         }
 
         f32x4 s0, s1;
-        qk_scores<KV>(kbuf, of, qreg, s0, s1);
+        qk_scores<D, KV>(kbuf, of, qreg, s0, s1);
 
         // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (the end of the
         // context, the causal limits of a multi-token call) and the tiles where sliding windows begin
@@ -227,8 +244,8 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         else
             online_softmax<true>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
 
-        wait_tile<0, NSTAGE, kDmaPerTile>(later);  // V of this tile landed
-        pv_accumulate<KV>(vbuf, of, pb, pb_lo, st);
+        wait_tile<0, kDmaPerTile, NSTAGE - 1>(later);  // V of this tile landed
+        pv_accumulate<D, KV>(vbuf, of, pb, pb_lo, st);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {

@@ -15,7 +15,7 @@
 //     scores, online softmax, PV for my 16 columns on tile t
 // All waves of a workgroup walk the same range, so they execute the same number of barriers.
 //
-// Query rows: every wave keeps ONE private LDS slot (16 rows of 256 B) for the rows of its own
+// Query rows: every wave keeps ONE private LDS slot (16 rows) for the rows of its own
 // columns.  At the start of a segment it moves the slot into registers and at once refills the
 // slot with the rows of the next segment in its range, so the rows are there long before that
 // segment's first tile; after a short segment (fewer tiles than the ring is deep) the wait at
@@ -36,11 +36,12 @@
 
 namespace pa {
 
-constexpr int kQSlotBytesWide = 16 * kQRowBytes;  // one wave's query rows
+// one wave's query rows: 16 columns
+constexpr int wide_q_slot_bytes(int d) { return 16 * 2 * d; }
 
-constexpr int mfma_wide_lds_bytes(int nw, int nstage, int kv)
+constexpr int mfma_wide_lds_bytes(int d, int nw, int nstage, int kv)
 {
-    return nstage * (kv == KV_BF16 ? KvGeom<KV_BF16>::kStage : KvGeom<KV_FP8>::kStage) + nw * kQSlotBytesWide;
+    return nstage * mfma_stage_bytes(d, kv) + nw * wide_q_slot_bytes(d);
 }
 
 // wait until at most `tiles` * PER_TILE of this wave's loads are still in flight (tiles clamped to MAXT)
@@ -60,20 +61,25 @@ __device__ __forceinline__ void wait_loads(int tiles)
 // caps the register budget at 256, which makes the compiler keep the MFMA accumulators in ordinary
 // VGPRs: with more it parks them in AGPRs and moves all 32 to VGPRs and back in every tile around
 // the rarely taken rescale branch.
-template <int NW, int NSTAGE, int KV, bool TRACE, bool PREFIX>
+template <int D, int NW, int NSTAGE, int KV, bool TRACE, bool PREFIX>
 __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_kernel(const Params p)
 {
-    constexpr int D = 128;
     static_assert(NW == 2 || NW == 4 || NW == 8, "waves per workgroup");
     static_assert(NSTAGE >= 3, "the ring holds the tile in use, the one being refilled and at least one in flight");
-    using Geo = KvGeom<KV>;
+    using Geo = KvGeom<D, KV>;
+    using QG = QGeom<D>;
     constexpr int kSlabBytes = Geo::kSlab;
     constexpr int kStageBytes = Geo::kStage;
-    constexpr int PT = Geo::kDmaPerTile / NW;  // LDS-DMA instructions per tile and wave
-    static_assert(PT >= 1 && PT * NW == Geo::kDmaPerTile, "the tile's loads divide evenly over the waves");
+    // LDS-DMA instructions per tile and loading wave: the tile's loads divide evenly over the
+    // waves, or (small tiles) over the first of them and the others load only their query rows
+    constexpr int PT = Geo::kDmaPerTile >= NW ? Geo::kDmaPerTile / NW : 1;
+    static_assert(Geo::kDmaPerTile % PT == 0 && (Geo::kDmaPerTile >= NW ? PT * NW == Geo::kDmaPerTile : true),
+                  "shares of a tile's loads");
     constexpr int kMaxLater = NSTAGE - 2;      // tiles in flight behind the one a wave waits for
-    static_assert(mfma_wide_lds_bytes(NW, NSTAGE, KV) <= 160 * 1024, "LDS of one compute unit");
-    __shared__ __attribute__((aligned(1024))) char smem[mfma_wide_lds_bytes(NW, NSTAGE, KV)];
+    constexpr int kQSlotBytes = wide_q_slot_bytes(D);
+    constexpr int kQLoads = kQSlotBytes / 1024;
+    static_assert(mfma_wide_lds_bytes(D, NW, NSTAGE, KV) <= 160 * 1024, "LDS of one compute unit");
+    __shared__ __attribute__((aligned(1024))) char smem[mfma_wide_lds_bytes(D, NW, NSTAGE, KV)];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -135,25 +141,26 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     uint32_t my_dst[PT];   // LDS byte offset inside a stage
     uint32_t my_off[PT];   // this lane's global byte offset inside the slab (swizzled piece)
     int my_tok[PT];        // token row of the block this lane loads
+    const bool loader = w * PT < Geo::kDmaPerTile;
 #pragma unroll
     for (int j = 0; j < PT; ++j) {
-        const int d = w * PT + j;
+        const int d = loader ? w * PT + j : 0;
         my_slab[j] = d / Geo::kDmaPerSlab;
         const int r = d % Geo::kDmaPerSlab;
         my_dst[j] = my_slab[j] * kSlabBytes + r * 1024;
         my_tok[j] = r * Geo::kRowsPerDma + lane / Geo::kPieces;
-        my_off[j] = slab_dma_offset<KV>(r, lane);
+        my_off[j] = slab_dma_offset<D, KV>(r, lane);
     }
-    // query rows of this wave's columns: LDS row r4*4 + q4 holds column c = 16w + that row
-    uint32_t qdma_off[4];
+    // query rows of this wave's columns: LDS row lc holds column c = 16w + lc
+    uint32_t qdma_off[kQLoads];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int lc = 4 * r + q4;
+    for (int r = 0; r < kQLoads; ++r) {
+        const int lc = r * QG::kRowsPerDma + lane / QG::kPieces;
         const int c = col0 + 16 * w + lc;
-        const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * kQRowBytes : 0;
-        qdma_off[r] = src + ((n ^ lc) << 4);
+        const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * QG::kRow : 0;
+        qdma_off[r] = src + (((lane % QG::kPieces) ^ (lc & (QG::kPieces - 1))) << 4);
     }
-    OperandOffsets<KV> of;
+    OperandOffsets<D, KV> of;
     of.init(n, q4);
     // this lane's column
     const int col = col0 + 16 * w + n;
@@ -164,48 +171,50 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     const int col_back = col_ok ? (PREFIX ? 0 : Q - 1 - col_i) : (1 << 30);
     const int col_row = col_i * p.Hq + g * G + col_h;          // output row inside its sequence
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    const uint32_t ldsq = lds0 + NSTAGE * kStageBytes + w * kQSlotBytesWide;
-    const char* qslot = smem + NSTAGE * kStageBytes + w * kQSlotBytesWide;
+    const uint32_t ldsq = lds0 + NSTAGE * kStageBytes + w * kQSlotBytes;
+    const char* qslot = smem + NSTAGE * kStageBytes + w * kQSlotBytes;
 
     const int64_t head_stride = (int64_t)p.Hkv * kSlabBytes;
     const char* kc = static_cast<const char*>(p.k_cache) + (int64_t)g * kSlabBytes;
     const char* vc = static_cast<const char*>(p.v_cache) + (int64_t)g * kSlabBytes;
 
     auto issue_q = [&](int b) {
-        const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)b * (Q * p.Hq) + g * G) * kQRowBytes;
+        const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)b * (Q * p.Hq) + g * G) * QG::kRow;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) dma16(ldsq + r * 1024, qdma_off[r], qb);
+        for (int r = 0; r < kQLoads; ++r) dma16(ldsq + r * 1024, qdma_off[r], qb);
     };
+    // returns whether this wave put loads in flight
     auto issue = [&](int stage) {
         const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
         if (TRACE && w == 0 && lane == 0) trace_tile_blocks(p.trace_blocks, tb, ic.b, g, k, p.Hkv, p.MB);
         const uint32_t ldst = lds0 + stage * kStageBytes;
+        if (loader) {
 #pragma unroll
-        for (int j = 0; j < PT; ++j) {
-            const int sub = my_slab[j] & 1;
-            const char* base = (my_slab[j] >> 1 ? vc : kc) + (sub ? tb.phys[1] : tb.phys[0]) * head_stride;
-            dma16(ldst + my_dst[j],
-                  live_or_stand_in<KV>(my_off[j], my_tok[j], sub ? tb.lo[1] : tb.lo[0], sub ? tb.hi[1] : tb.hi[0]), base);
+            for (int j = 0; j < PT; ++j) {
+                const int sub = my_slab[j] & 1;
+                const char* base = (my_slab[j] >> 1 ? vc : kc) + (sub ? tb.phys[1] : tb.phys[0]) * head_stride;
+                dma16(ldst + my_dst[j],
+                      live_or_stand_in<D, KV>(my_off[j], my_tok[j], sub ? tb.lo[1] : tb.lo[0], sub ? tb.hi[1] : tb.hi[0]),
+                      base);
+            }
         }
         advance(ic, p.context_lens, B, sp);
+        return loader;
     };
 
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    ColumnState st;
+    ColumnState<D> st;
     st.reset();
-    bf16x8 qreg[4];
+    bf16x8 qreg[D / 32];
     int seg_first_lt = 0;
 
     // ---- prologue: the first segment's query rows, then the ring
     issue_q(first_b);
-    int q_age = 0;  // tiles this wave has issued since it last issued query rows
+    int q_age = 0;  // tiles this wave has put loads in flight for since it last issued query rows
 #pragma unroll
     for (int t = 0; t < NSTAGE - 1; ++t)
-        if (t < ntiles) {
-            issue(t);
-            ++q_age;
-        }
+        if (t < ntiles && issue(t)) ++q_age;
 
     int stage = 0;
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -221,8 +230,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         if (ahead < ntiles) {
             int stg = stage + NSTAGE - 1;
             if (stg >= NSTAGE) stg -= NSTAGE;
-            issue(stg);
-            ++q_age;
+            if (issue(stg)) ++q_age;
         }
         const char* kbuf = smem + stage * kStageBytes;
         const char* vbuf = kbuf + 2 * kSlabBytes;
@@ -239,7 +247,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
                 write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
             }
             st.reset();
-            load_query_operand(qslot, n, q4, col_ok, qreg);
+            load_query_operand<D>(qslot, n, q4, col_ok, qreg);
             // refill the slot with the rows of the next segment of this range, if there is one
             if (tile + (cc.nt - cc.lt) < ntiles) {
                 int nb = cc.b;
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         }
 
         f32x4 s0, s1;
-        qk_scores<KV>(kbuf, of, qreg, s0, s1);
+        qk_scores<D, KV>(kbuf, of, qreg, s0, s1);
 
         // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (where the causal
         // limits lie) and the tiles where the columns' sliding windows begin need the mask:
@@ -270,7 +278,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         else
             online_softmax<true>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
 
-        pv_accumulate<KV>(vbuf, of, pb, pb_lo, st);
+        pv_accumulate<D, KV>(vbuf, of, pb, pb_lo, st);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {

@@ -78,10 +78,10 @@ def test_workspace_size_covers_partials():
 
 def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     one = shape(num_partitions=16)
-    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_BF16) == "mfma"  # 128 rows per KV head
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_BF16) == "mfma-wide"  # 128 columns per KV head
     for Q in (2, 4, 16):
         win = shape(num_partitions=16, q_len=Q)
-        assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == "mfma"
+        assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == ("mfma" if Q * 4 <= 16 else "mfma-wide")
         need = 2 * 16 * Q * 32 * (128 + 1) * 4 + 4 * 16
         assert need <= pa.pa_decode_workspace_size(win, pa.PA_KV_BF16) <= need + 3 * 256
         lens = [100, 4096, 1, 33]
@@ -89,10 +89,11 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
         assert np.array_equal(pa.pa_split_plan(win, pa.PA_KV_BF16, lens)[1], pa.pa_split_plan(one, pa.PA_KV_BF16, lens)[1])
     # q_len 0 and 1 are the same call
     assert pa.pa_decode_workspace_size(shape(q_len=1), pa.PA_KV_BF16) == pa.pa_decode_workspace_size(shape(), pa.PA_KV_BF16)
-    # narrow groups run on the matrix-core path too (head_dim 128); head_dim 64 is the vector-ALU kernel's
+    # up to 16 columns per KV head: one wave per (partition, KV head), narrow groups and head_dim 64 included
     assert pa.pa_kernel_variant(shape(num_q_heads=8, q_len=2), pa.PA_KV_BF16) == "mfma"
     assert pa.pa_kernel_variant(shape(num_q_heads=8), pa.PA_KV_BF16) == "mfma"
-    assert pa.pa_kernel_variant(shape(num_q_heads=16, head_dim=64), pa.PA_KV_BF16) == "valu"
+    assert pa.pa_kernel_variant(shape(num_q_heads=16, head_dim=64), pa.PA_KV_BF16) == "mfma"
+    assert pa.pa_kernel_variant(shape(num_q_heads=16, head_dim=64, q_len=16), pa.PA_KV_FP8_E4M3) == "mfma-wide"
 
 
 @pytest.mark.parametrize("Q,window", [(1, 1), (1, 16), (1, 100), (4, 33), (16, 5), (1, 10 ** 6)])
@@ -175,14 +176,11 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(q_len=-1), pa.PA_ERR_INVALID_ARG),
     (dict(q_len=17), pa.PA_ERR_UNSUPPORTED),
     (dict(q_len=16, num_q_heads=128), pa.PA_ERR_UNSUPPORTED),           # 16 tokens x 16 heads > 128 rows per KV head
-    (dict(q_len=4, head_dim=64, num_q_heads=16), pa.PA_ERR_UNSUPPORTED),  # windows need head_dim 128
     (dict(shared_prefix_blocks=-2), pa.PA_ERR_INVALID_ARG),
     (dict(shared_prefix_blocks=257), pa.PA_ERR_INVALID_ARG),              # more than a table row holds
     (dict(shared_prefix_blocks=8, max_context_len=100), pa.PA_ERR_INVALID_ARG),  # contexts shorter than the prefix
     (dict(shared_prefix_blocks=8, q_len=4), pa.PA_ERR_UNSUPPORTED),
-    (dict(shared_prefix_blocks=8, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
     (dict(window=-1), pa.PA_ERR_INVALID_ARG),
-    (dict(window=64, head_dim=64, num_q_heads=64), pa.PA_ERR_UNSUPPORTED),
     (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
     (dict(out_dtype=2), pa.PA_ERR_INVALID_ARG),
     (dict(out_dtype=-1), pa.PA_ERR_INVALID_ARG),
@@ -229,3 +227,12 @@ def test_binding_refuses_host_tensors():
     t = torch.zeros(16)
     with pytest.raises(ValueError):
         pa.pa_decode(t, t, t, t, t, 0.1, pa.PA_KV_BF16, t, shape=s)
+
+
+@pytest.mark.parametrize("extra", [dict(q_len=4, num_q_heads=16), dict(shared_prefix_blocks=8, num_q_heads=64),
+                                   dict(window=64, num_q_heads=64), dict(q_len=16, num_q_heads=64)])
+@pytest.mark.parametrize("kv", [pa.PA_KV_BF16, pa.PA_KV_FP8_E4M3])
+def test_head_dim_64_takes_every_kind_of_call(extra, kv):
+    s = shape(head_dim=64, **extra)
+    assert pa.pa_num_partitions(s, kv) >= 1
+    assert pa.pa_kernel_variant(s, kv) in ("mfma", "mfma-wide")

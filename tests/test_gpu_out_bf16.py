@@ -32,8 +32,8 @@ def run_gpu(pa, batch, **kw):
 
 
 CASES = {
-    "vector-ALU kernel, head_dim 64": lambda: W.make_config(1),
-    "vector-ALU kernel, groups of 8": lambda: W.make_batch("o0", 699, [0, 1, 33, 700, 16], 16, 2, 64, 16, W.KV_FP8_E4M3),
+    "head_dim 64": lambda: W.make_config(1),
+    "head_dim 64, groups of 8, fp8": lambda: W.make_batch("o0", 699, [0, 1, 33, 700, 16], 16, 2, 64, 16, W.KV_FP8_E4M3),
     "matrix-core kernel, groups of 2": lambda: W.make_batch("o1", 700, [0, 1, 33, 700, 16], 4, 2, 128, 16, W.KV_BF16),
     "matrix-core kernel": lambda: W.make_batch("o2", 701, [0, 1, 33, 700, 16, 2000], 16, 4, 128, 16, W.KV_BF16),
     "matrix-core kernel, fp8": lambda: W.make_batch("o3", 702, [513, 40, 0], 16, 2, 128, 16, W.KV_FP8_E4M3),
