@@ -162,7 +162,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         if (i == 0 || ic.lt == 0) {  // a new segment starts: send its query rows ahead of its first tile
             const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.QH + g * G) * QG::kRow;
 #pragma unroll
-            for (int r = 0; r < kQLoads; ++r) dma16(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
+            for (int r = 0; r < kQLoads; ++r) dma16<false>(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
             q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
         }
         const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             const char* kb = kc + tb.phys[sub] * head_stride;
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r)
-                dma16(ldst + sub * kSlabBytes + r * 1024,
+                dma16<true>(ldst + sub * kSlabBytes + r * 1024,
                       live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), kb);
         }
 #pragma unroll
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             const char* vb = vc + tb.phys[sub] * head_stride;
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r)
-                dma16(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024,
+                dma16<true>(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024,
                       live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), vb);
         }
         advance(ic, p.context_lens, B, sp);
