@@ -41,6 +41,11 @@ def parse_args():
                     help="query tokens per sequence (default 1: plain decode, the metric's workload; 2..16 times "
                          "the multi-token verification call over the same KV cache instead)")
     ap.add_argument("--window", type=int, default=0, help="sliding window in tokens (default 0: none)")
+    ap.add_argument("--num-q-heads", type=int, default=None, help="override the workload's query heads")
+    ap.add_argument("--num-kv-heads", type=int, default=None, help="override the workload's KV heads")
+    ap.add_argument("--head-dim", type=int, default=None, choices=[64, 128], help="override the workload's head_dim")
+    ap.add_argument("--kv-dtype", default=None, choices=["bf16", "fp8"], help="override the workload's KV type")
+    ap.add_argument("--length-scale", type=float, default=1.0, help="scale every context length of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -89,7 +94,10 @@ def main():
     torch.cuda.set_device(0)
 
     t0 = time.time()
-    batch = W.make_config(args.workload, seed=args.seed, poison=False, q_len=args.q_len, window=args.window)
+    kv_override = None if args.kv_dtype is None else (W.KV_BF16 if args.kv_dtype == "bf16" else W.KV_FP8_E4M3)
+    batch = W.make_config(args.workload, seed=args.seed, poison=False, q_len=args.q_len, window=args.window,
+                          length_scale=args.length_scale, num_q_heads=args.num_q_heads,
+                          num_kv_heads=args.num_kv_heads, head_dim=args.head_dim, kv_dtype=kv_override)
     gen_s = time.time() - t0
     shared_blocks = 0 if args.no_shared_prefix else batch.shared_prefix_blocks
     # bytes the step has to read: every valid K/V slot once per sequence that owns it, a declared shared prefix once

@@ -365,28 +365,49 @@ def config_context_lens(config: int, seed: int, length_scale: float = 1.0) -> np
     raise ValueError(f"unknown config {config}")
 
 
+# head shape, KV type and value scale of the named configs: (num_q_heads, num_kv_heads, head_dim, kv_dtype, sigma)
+CONFIG_SHAPES = {
+    1: (4, 2, 64, KV_BF16, 1.0),
+    2: (32, 8, 128, KV_BF16, 0.5),
+    3: (32, 8, 128, KV_BF16, 0.5),
+    4: (32, 8, 128, KV_BF16, 0.5),
+    5: (64, 8, 128, KV_FP8_E4M3, 1.0),
+    6: (32, 8, 128, KV_BF16, 0.5),
+}
+
+
 def make_config(config: int, seed: Optional[int] = None, poison: bool = True, length_scale: float = 1.0,
-                batch_limit: Optional[int] = None, q_len: int = 1, window: int = 0) -> DecodeBatch:
-    """Build named config 1..5.  Default seed is 1000+config.  ``batch_limit`` keeps only the first
+                batch_limit: Optional[int] = None, q_len: int = 1, window: int = 0,
+                num_q_heads: Optional[int] = None, num_kv_heads: Optional[int] = None,
+                head_dim: Optional[int] = None, kv_dtype: Optional[int] = None) -> DecodeBatch:
+    """Build named config 1..6.  Default seed is 1000+config.  ``batch_limit`` keeps only the first
     sequences (same lengths they would have in the full batch).  ``q_len`` > 1 turns the batch into a
-    verification step over windows of that many tokens (same cache, more query rows)."""
+    verification step over windows of that many tokens (same cache, more query rows).  The head
+    shape and KV type can be overridden (same lengths and tables, another model shape); the name of
+    the batch then says so."""
     seed = 1000 + config if seed is None else seed
     lens = config_context_lens(config, seed, length_scale)
     if batch_limit is not None:
         lens = lens[:batch_limit]
+    Hq, Hkv, D, kv, sigma = CONFIG_SHAPES[config]
     name = CONFIG_NAMES[config]
+    if (num_q_heads, num_kv_heads, head_dim, kv_dtype) != (None, None, None, None):
+        Hq = Hq if num_q_heads is None else num_q_heads
+        Hkv = Hkv if num_kv_heads is None else num_kv_heads
+        D = D if head_dim is None else head_dim
+        kv = kv if kv_dtype is None else kv_dtype
+        name += f"_hq{Hq}_hkv{Hkv}_d{D}_{'bf16' if kv == KV_BF16 else 'fp8'}"
+    if length_scale != 1.0:
+        name += f"_lenx{length_scale:g}"
     if config == 1:
-        return make_batch(name, seed, lens, 4, 2, 64, 16, KV_BF16, 1.0, num_blocks=16, poison=poison, q_len=q_len, window=window)
-    if config == 2:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len, window=window)
-    if config == 3:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len, window=window)
+        return make_batch(name, seed, lens, Hq, Hkv, D, 16, kv, sigma, num_blocks=16, poison=poison, q_len=q_len, window=window)
     if config == 4:
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, table_kind="interleaved", poison=poison, q_len=q_len, window=window)
-    if config == 5:
-        return make_batch(name, seed, lens, 64, 8, 128, 16, KV_FP8_E4M3, 1.0, poison=poison, q_len=q_len, window=window)
+        return make_batch(name, seed, lens, Hq, Hkv, D, 16, kv, sigma, table_kind="interleaved", poison=poison,
+                          q_len=q_len, window=window)
     if config == 6:
         prefix_tokens = (max(1, int(round(32768 * length_scale))) // 32) * 32
-        return make_batch(name, seed, lens, 32, 8, 128, 16, KV_BF16, 0.5, poison=poison, q_len=q_len,
+        return make_batch(name, seed, lens, Hq, Hkv, D, 16, kv, sigma, poison=poison, q_len=q_len,
                           shared_prefix_blocks=prefix_tokens // 16)
+    if config in (2, 3, 5):
+        return make_batch(name, seed, lens, Hq, Hkv, D, 16, kv, sigma, poison=poison, q_len=q_len, window=window)
     raise ValueError(config)
