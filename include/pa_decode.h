@@ -226,8 +226,8 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
                             float *merge_ms);
 
 /* Name of the partition kernel variant pa_decode picks for this shape ("mfma": one wavefront per
- * (partition, KV head), up to 16 query rows (Q * G) per KV head; "mfma-wide": a workgroup of 2, 4 or 8
- * wavefronts, up to 128); NULL for an invalid or unsupported shape.  Static storage. */
+ * (partition, KV head), up to 32 query rows (Q * G) per KV head (16 for fp8 at head_dim 128); "mfma-wide":
+ * a workgroup of 2, 4 or 8 wavefronts, up to 128); NULL for an invalid or unsupported shape.  Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
 /* Human-readable name of a status code.  Static storage. */

@@ -20,14 +20,20 @@ namespace {
 using pa::Params;
 
 constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
-constexpr int kMaxColsOneWave = 16; // up to here one wave per (partition, KV head); above, a workgroup of waves
+// Up to here one wave per (partition, KV head), with one or two MFMA column tiles; above, a
+// workgroup of waves.  Two column tiles per wave beat two waves with one tile each (8B-shaped
+// batch, 5 / 8 query tokens: 118 / 125 us against 130 / 137 us; long-context batch, 8 tokens: 380
+// against 427 us) except for fp8 at head_dim 128, where the second tile's arithmetic no longer
+// hides behind the loads (70B-head-shaped batch, 4 tokens: 540 against 523 us).
+constexpr int max_cols_one_wave(int d, int kv) { return (kv == PA_KV_FP8_E4M3 && d == 128) ? 16 : 32; }
 constexpr int kMaxColsMfma = 128;  // eight 16-column MFMA tiles, one per wave of the widest workgroup
 constexpr int kMaxQueryLen = 16;
-// depth of the LDS tile ring of the one-wave kernel.  head_dim 128: 2 tiles of 16 KB (bf16) or 4
-// of 8 KB (fp8), one wave per SIMD.  head_dim 64: tiles are half that, and what pays is more
-// resident waves rather than deeper rings (measured on 64 sequences of 1k-8k tokens, fp8: 2 tiles
-// and 8 waves per compute unit 67 us, 8 tiles and 4 waves 85 us; bf16 within 2 % either way)
-constexpr int mfma_stages(int d, int kv) { return d == 128 ? (kv == PA_KV_BF16 ? 2 : 4) : 2; }
+// Depth of the LDS tile ring of the one-wave kernel: two tiles for every head_dim and KV type.
+// What pays is resident waves (head_dim 128: one per SIMD; head_dim 64, whose tiles are half the
+// size: two), not deeper rings.  Measured: head_dim 64 fp8, 64 sequences of 1k-8k tokens: 2 tiles
+// and 8 waves per compute unit 67 us, 8 tiles and 4 waves 85 us; head_dim 128 fp8 with 16 padded
+// columns, where 4 tiles leave room for 3 waves only: 477 us against 381 us with 2 tiles.
+constexpr int mfma_stages(int, int) { return 2; }
 constexpr int mfma_waves_per_cu(int d) { return d == 128 ? 4 : 8; }
 // ring depth of the multi-wave kernel (the ring is shared by the workgroup's waves), by KV type
 // and waves per workgroup
@@ -45,10 +51,12 @@ constexpr int kMaxPartitions = 65535;
 constexpr int kMaxBatch = 65535;
 constexpr int kMinTilesOneWave = 2;  // tiles a partition should at least have: one-wave kernels
 constexpr int kMinTilesWide = 4;     // multi-wave kernel
+constexpr int kMinTilesTwoColumnTiles = 16;  // tiles per partition from which one wave takes two column tiles
 constexpr int kMergeManyPerSeq = 8;  // partitions per sequence from which the multi-wave merge kernel is used
 
 struct Plan {
     int32_t P;          // partitions of the global tile sequence
+    bool one_wave;      // the per-sequence pass runs on the one-wave kernel
     int32_t max_ctx;    // resolved max context length
     size_t lse_offset;  // byte offset of the lse array inside the workspace
     size_t desc_offset; // byte offset of the merge descriptors
@@ -72,7 +80,7 @@ int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_
 // The kernels cover head_dim 64 and 128, groups of up to 16 query heads and up to 128 columns
 // (narrow groups are padded inside the 16-column tile: the kernel is bound by the KV traffic, and
 // runs at the same speed for 1 column as for 16).
-int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : 16); }
+int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : (cols <= 16 ? 16 : 32)); }
 
 // waves per workgroup of the multi-wave kernel: one per 16 columns, rounded up to a power of two
 int wide_waves(int cols) { return cols <= 32 ? 2 : (cols <= 64 ? 4 : 8); }
@@ -92,17 +100,6 @@ int wide_groups_per_cu(int d, int kv, int nw)
     return fit < want ? fit : want;
 }
 
-// waves (one-wave kernel) or workgroups (multi-wave kernel) resident per compute unit
-int groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
-{
-    const int cols = columns(s);
-    if (cols <= kMaxColsOneWave) {
-        const int fit = kLdsPerCu / pa::mfma_lds_bytes(s->head_dim, mfma_stages(s->head_dim, (int)kv), mfma_col_pad(cols), (int)kv);
-        return fit < mfma_waves_per_cu(s->head_dim) ? fit : mfma_waves_per_cu(s->head_dim);
-    }
-    return wide_groups_per_cu(s->head_dim, (int)kv, wide_waves(cols));
-}
-
 // Compute units of the current device (cached per process; 256 when there is no device).
 int compute_units()
 {
@@ -117,6 +114,47 @@ int compute_units()
         return kDefaultCus;
     }();
     return cached;
+}
+
+// tiles the per-sequence kernel can meet at most (those after a shared prefix, those a sliding
+// window reaches), from what the host knows
+int64_t tile_bound(const pa_shape* s)
+{
+    const int64_t max_ctx = s->max_context_len > 0 ? s->max_context_len : (int64_t)s->max_blocks_per_seq * s->block_size;
+    int64_t tiles_per_seq = (max_ctx + pa::kTileTokens - 1) / pa::kTileTokens - shared_tiles(s);
+    if (s->window > 0) {
+        const int64_t reach_tiles = ((int64_t)s->window + query_len(s) - 1 + pa::kTileTokens - 1) / pa::kTileTokens + 1;
+        if (tiles_per_seq > reach_tiles) tiles_per_seq = reach_tiles;
+    }
+    return (int64_t)s->batch * tiles_per_seq;
+}
+
+// resident waves of the one-wave kernel per compute unit
+int one_wave_per_cu(const pa_shape* s, pa_kv_dtype kv)
+{
+    const int fit = kLdsPerCu / pa::mfma_lds_bytes(s->head_dim, mfma_stages(s->head_dim, (int)kv), mfma_col_pad(columns(s)), (int)kv);
+    return fit < mfma_waves_per_cu(s->head_dim) ? fit : mfma_waves_per_cu(s->head_dim);
+}
+
+// Which kernel runs the per-sequence pass.  Up to 16 columns: one wave.  17 .. 32 columns, where
+// both kernels apply: two column tiles in one wave once every partition has a long run of
+// tiles, the two-wave workgroup for small calls, which are bound by the per-tile latency chain
+// (one sequence, 64 query / 8 KV heads, 4 tokens: 16k context 33.4 against 27.5 us, 64k equal,
+// 256k 188 against 208 us).
+bool one_wave(const pa_shape* s, pa_kv_dtype kv)
+{
+    const int cols = columns(s);
+    if (cols <= 16) return true;
+    if (cols > max_cols_one_wave(s->head_dim, (int)kv)) return false;
+    const int64_t P = s->num_partitions > 0 ? s->num_partitions
+                                            : (int64_t)compute_units() * one_wave_per_cu(s, kv) / s->num_kv_heads;
+    return tile_bound(s) >= kMinTilesTwoColumnTiles * (P < 1 ? 1 : P);
+}
+
+// waves (one-wave kernel) or workgroups (multi-wave kernel) resident per compute unit
+int groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
+{
+    return one_wave(s, kv) ? one_wave_per_cu(s, kv) : wide_groups_per_cu(s->head_dim, (int)kv, wide_waves(columns(s)));
 }
 
 pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
@@ -162,13 +200,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     if (st != PA_OK) return st;
     plan->max_ctx = s->max_context_len > 0 ? s->max_context_len : s->max_blocks_per_seq * s->block_size;
     plan->skip_tiles = shared_tiles(s);
-    // tiles the per-sequence kernel can meet at most (those after a shared prefix, those a sliding window reaches)
-    int64_t tiles_per_seq = (plan->max_ctx + pa::kTileTokens - 1) / pa::kTileTokens - plan->skip_tiles;
-    if (s->window > 0) {
-        const int64_t reach_tiles = ((int64_t)s->window + query_len(s) - 1 + pa::kTileTokens - 1) / pa::kTileTokens + 1;
-        if (tiles_per_seq > reach_tiles) tiles_per_seq = reach_tiles;
-    }
-    const int64_t tile_bound = (int64_t)s->batch * tiles_per_seq;
+    plan->one_wave = one_wave(s, kv);
     if (s->num_partitions > 0) {
         plan->P = s->num_partitions;
     } else {
@@ -177,8 +209,8 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         int64_t P = (int64_t)compute_units() * groups_per_cu(s, kv) / s->num_kv_heads;
         // small calls: a partition should have a few tiles to amortise its start-up, and every extra
         // partition is one more piece per row for the merge (measured on single-sequence calls)
-        const int min_tiles = columns(s) > kMaxColsOneWave ? kMinTilesWide : kMinTilesOneWave;
-        if (P > tile_bound / min_tiles) P = tile_bound / min_tiles;
+        const int min_tiles = plan->one_wave ? kMinTilesOneWave : kMinTilesWide;
+        if (P > tile_bound(s) / min_tiles) P = tile_bound(s) / min_tiles;
         if (P > kMaxPartitions) P = kMaxPartitions;
         if (P < 1) P = 1;
         plan->P = (int32_t)P;
@@ -236,17 +268,19 @@ void launch_wide(const Params& p, bool trace, dim3 grid, hipStream_t st)
         hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
 }
 
-// the per-sequence pass: one wave per (partition, KV head) up to 16 columns, a workgroup of waves above
+// the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2, 4 or 8 waves above
 template <int D, int KV>
-void launch_partition(const Params& p, bool trace, dim3 grid, hipStream_t st)
+void launch_partition(const Params& p, bool one_wave, bool trace, dim3 grid, hipStream_t st)
 {
     const int cols = p.Q * p.G;
     if (cols <= 4)
         launch_mfma<D, 4, KV>(p, trace, grid, st);
     else if (cols <= 8)
         launch_mfma<D, 8, KV>(p, trace, grid, st);
-    else if (cols <= kMaxColsOneWave)
+    else if (cols <= 16)
         launch_mfma<D, 16, KV>(p, trace, grid, st);
+    else if (one_wave)
+        launch_mfma<D, 32, KV>(p, trace, grid, st);
     else if (wide_waves(cols) == 2)
         launch_wide<D, 2, KV>(p, trace, grid, st);
     else if (wide_waves(cols) == 4)
@@ -349,7 +383,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
             if (hipGetLastError() != hipSuccess) { launched = false; return; }
         }
         const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
-        launch_partition<D, KV>(p, trace, grid, hs);
+        launch_partition<D, KV>(p, plan.one_wave, trace, grid, hs);
         if (hipGetLastError() != hipSuccess) { launched = false; return; }
         if (ev && hipEventRecord(ev->between, hs) != hipSuccess) { launched = false; return; }
 
@@ -529,7 +563,7 @@ pa_status pa_kv_append(const void* k_new, const void* v_new, void* k_cache, void
 const char* pa_kernel_variant(const pa_shape* shape, pa_kv_dtype kv_dtype)
 {
     if (check_shape(shape, kv_dtype) != PA_OK) return nullptr;
-    return columns(shape) <= kMaxColsOneWave ? "mfma" : "mfma-wide";
+    return one_wave(shape, kv_dtype) ? "mfma" : "mfma-wide";
 }
 
 const char* pa_status_string(pa_status status)

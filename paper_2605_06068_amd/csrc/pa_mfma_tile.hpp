@@ -229,28 +229,42 @@ __device__ __forceinline__ void load_query_operand(const char* slot, int n, int 
     }
 }
 
-// S^T[token, column] = K . Q^T for the two blocks of the tile
+// The K operand of k-step kk for the two blocks of the tile (token n, dims 32 kk + 8 q4 + [0, 8))
 template <int D, int KV>
-__device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets<D, KV>& of, const bf16x8 (&qreg)[D / 32],
-                                          f32x4& s0, f32x4& s1)
+__device__ __forceinline__ void load_k_operand(const char* kbuf, const OperandOffsets<D, KV>& of, int kk, bf16x8& a0, bf16x8& a1)
 {
     constexpr int kSlabBytes = KvGeom<D, KV>::kSlab;
-    s0 = f32x4{0.f, 0.f, 0.f, 0.f};
-    s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (KV == KV_BF16) {
+        a0 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + of.kread[kk]));
+        a1 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kSlabBytes + of.kread[kk]));
+    } else {
+        const uint2 w0 = *reinterpret_cast<const uint2*>(kbuf + of.kread[kk]);
+        const uint2 w1 = *reinterpret_cast<const uint2*>(kbuf + kSlabBytes + of.kread[kk]);
+        a0 = fp8x8_to_bf16x8(w0.x, w0.y);
+        a1 = fp8x8_to_bf16x8(w1.x, w1.y);
+    }
+}
+
+// S^T[token, column] = K . Q^T for the two blocks of the tile and NCT tiles of 16 columns; the K
+// operand is read (and, fp8, converted) once for all of them
+template <int D, int KV, int NCT>
+__device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets<D, KV>& of,
+                                          const bf16x8 (&qreg)[NCT][D / 32], f32x4 (&s0)[NCT], f32x4 (&s1)[NCT])
+{
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        s0[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+        s1[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) {
         bf16x8 a0, a1;
-        if (KV == KV_BF16) {
-            a0 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + of.kread[kk]));
-            a1 = as_bf16x8(*reinterpret_cast<const uint4*>(kbuf + kSlabBytes + of.kread[kk]));
-        } else {
-            const uint2 w0 = *reinterpret_cast<const uint2*>(kbuf + of.kread[kk]);
-            const uint2 w1 = *reinterpret_cast<const uint2*>(kbuf + kSlabBytes + of.kread[kk]);
-            a0 = fp8x8_to_bf16x8(w0.x, w0.y);
-            a1 = fp8x8_to_bf16x8(w1.x, w1.y);
+        load_k_operand<D, KV>(kbuf, of, kk, a0, a1);
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            s0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[ct][kk], s0[ct], 0, 0, 0);
+            s1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[ct][kk], s1[ct], 0, 0, 0);
         }
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qreg[kk], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qreg[kk], s1, 0, 0, 0);
     }
 }
 
@@ -311,10 +325,11 @@ __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1,
     }
 }
 
-// out^T[dim, column] += V^T . P^T
-template <int D, int KV>
-__device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOffsets<D, KV>& of, const bf16x8& pb,
-                                              const bf16x8& pb_lo, ColumnState<D>& st)
+// out^T[dim, column] += V^T . P^T for NCT tiles of 16 columns; the V^T operand is read (and, fp8,
+// converted) once for all of them
+template <int D, int KV, int NCT>
+__device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOffsets<D, KV>& of, const bf16x8 (&pb)[NCT],
+                                              const bf16x8 (&pb_lo)[NCT], ColumnState<D> (&st)[NCT])
 {
     constexpr int kSlabBytes = KvGeom<D, KV>::kSlab;
 #pragma unroll
@@ -328,8 +343,11 @@ __device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOff
             const i32x2 v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(vbuf + of.vread[dt]));
             va = fp8x8_to_bf16x8((uint32_t)v[0], (uint32_t)v[1]);
         }
-        st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, st.acc[dt], 0, 0, 0);
-        st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo, st.acc[dt], 0, 0, 0);
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            st[ct].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[ct], st[ct].acc[dt], 0, 0, 0);
+            st[ct].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo[ct], st[ct].acc[dt], 0, 0, 0);
+        }
     }
 }
 

@@ -1,9 +1,10 @@
-// Partition kernel, matrix-core variant (head_dim 128 or 64, bf16 or fp8 KV) for up to 16 columns.
+// Partition kernel, matrix-core variant (head_dim 128 or 64, bf16 or fp8 KV) for up to 32 columns.
 // The columns of its matrix tile are the (query token, query head) pairs that share one KV
 // head: q_len * G of them (plain decode: the G heads of the group), padded to CPAD = 4, 8 or
-// 16 inside one 16-column MFMA tile.  One wavefront per (partition, KV head) walks its balanced
-// range of the batch's global tile sequence (see pa_plan.hpp); no workgroup barriers, no
-// atomics.  More columns than 16 go to the multi-wave kernel in pa_partition_mfma_wide.hpp.
+// 16 inside one 16-column MFMA tile, or to 32 = two such tiles that share every K and V operand
+// read.  One wavefront per (partition, KV head) walks its balanced range of the batch's global
+// tile sequence (see pa_plan.hpp); no workgroup barriers, no atomics.  More columns than 32 go
+// to the multi-wave kernel in pa_partition_mfma_wide.hpp.
 //
 // Data path per 32-token tile (two KV blocks; layouts and the per-tile arithmetic are in
 // pa_mfma_tile.hpp):
@@ -44,10 +45,15 @@ constexpr int mfma_q_loads(int d, int cpad)
     return (cpad * 2 * d + 1023) / 1024;
 }
 
-// LDS bytes one workgroup (one wave) of the kernel uses: tile ring + query-row ring.
+// Two column tiles keep ONE slot of query rows and refill it with the rows of the next segment
+// as soon as the current ones are in registers (as the multi-wave kernel does); one column tile
+// keeps a ring of NSTAGE slots filled just ahead of each segment's first tile.
+constexpr bool mfma_one_q_slot(int cpad) { return cpad > 16; }
+
+// LDS bytes one workgroup (one wave) of the kernel uses: tile ring + query-row slots.
 constexpr int mfma_lds_bytes(int d, int nstage, int cpad, int kv)
 {
-    return nstage * (mfma_stage_bytes(d, kv) + mfma_q_loads(d, cpad) * 1024);
+    return nstage * mfma_stage_bytes(d, kv) + (mfma_one_q_slot(cpad) ? 1 : nstage) * mfma_q_loads(d, cpad) * 1024;
 }
 
 // wait until at most `later_tiles` whole tiles (PER_TILE loads each, at most MAXT tiles) plus EXTRA
@@ -68,7 +74,8 @@ template <int D, int NSTAGE, int CPAD, int KV, bool TRACE>
 __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 {
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "ring depth");
-    static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16, "padded column count");
+    static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16 || CPAD == 32, "padded column count");
+    constexpr int NCT = CPAD > 16 ? CPAD / 16 : 1;  // MFMA column tiles
     using Geo = KvGeom<D, KV>;
     using QG = QGeom<D>;
     constexpr int kSlabBytes = Geo::kSlab;
@@ -76,6 +83,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     constexpr int kDmaPerTile = Geo::kDmaPerTile;
     constexpr int kQLoads = mfma_q_loads(D, CPAD);
     constexpr int kQSlot = kQLoads * 1024;
+    constexpr bool ONE_SLOT = mfma_one_q_slot(CPAD);
     static_assert(mfma_lds_bytes(D, NSTAGE, CPAD, KV) <= 65536, "static LDS limit");
     __shared__ __attribute__((aligned(1024))) char smem[mfma_lds_bytes(D, NSTAGE, CPAD, KV)];
 
@@ -144,11 +152,18 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     }
     OperandOffsets<D, KV> of;
     of.init(n, q4);
-    // this lane's column n
-    const bool col_ok = n < ncols;                                 // a real column
-    const int col_i = col_ok ? n / G : 0, col_h = col_ok ? n % G : 0;
-    const int col_back = col_ok ? Q - 1 - col_i : (1 << 30);       // tokens at the end of the context its query must not see
-    const int col_row = col_i * p.Hq + g * G + col_h;              // its output row inside its sequence
+    // this lane's columns: 16 ct + n of column tile ct
+    bool col_ok[NCT];   // a real column
+    int col_back[NCT];  // tokens at the end of the context its query must not see
+    int col_row[NCT];   // its output row inside its sequence
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int c = 16 * ct + n;
+        col_ok[ct] = c < ncols;
+        const int col_i = col_ok[ct] ? c / G : 0, col_h = col_ok[ct] ? c % G : 0;
+        col_back[ct] = col_ok[ct] ? Q - 1 - col_i : (1 << 30);
+        col_row[ct] = col_i * p.Hq + g * G + col_h;
+    }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t ldsq = lds0 + NSTAGE * kStageBytes;
     const char* qslots = smem + NSTAGE * kStageBytes;
@@ -158,13 +173,15 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     const char* vc = static_cast<const char*>(p.v_cache) + (int64_t)g * kSlabBytes;
 
     int q_issue = 0;  // query slot the issue side fills next
-    auto issue = [&](int i, int stage) {
-        if (i == 0 || ic.lt == 0) {  // a new segment starts: send its query rows ahead of its first tile
-            const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)ic.b * p.QH + g * G) * QG::kRow;
+    auto issue_q = [&](int b) {
+        const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)b * p.QH + g * G) * QG::kRow;
 #pragma unroll
-            for (int r = 0; r < kQLoads; ++r) dma16<false>(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
-            q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
-        }
+        for (int r = 0; r < kQLoads; ++r) dma16<false>(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
+        if (!ONE_SLOT) q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
+    };
+    auto issue = [&](int i, int stage) {
+        // ring of slots: a new segment starts, send its query rows ahead of its first tile
+        if (!ONE_SLOT && (i == 0 || ic.lt == 0)) issue_q(ic.b);
         const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
         if (TRACE && lane == 0) trace_tile_blocks(p.trace_blocks, tb, ic.b, g, k, p.Hkv, p.MB);
         const uint32_t ldst = lds0 + stage * kStageBytes;
@@ -190,16 +207,22 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     // ---- online softmax state: lane = column n, tokens 4*q4+{0..3} of each block
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;  // K scale folded in
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    ColumnState<D> st;
-    st.reset();
-    bf16x8 qreg[D / 32];
+    ColumnState<D> st[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) st[ct].reset();
+    bf16x8 qreg[NCT][D / 32];
     int q_comp = 0;       // query slot of the segment being computed
     int seg_first_lt = 0;
 
-    // ---- prologue: fill the ring
+    // ---- prologue: (one slot: the first segment's query rows,) fill the ring
+    if (ONE_SLOT) issue_q(first_b);
+    int q_age = 0;  // one slot: tiles issued since the slot was last refilled
 #pragma unroll
     for (int t = 0; t < NSTAGE - 1; ++t)
-        if (t < ntiles) issue(t, t);
+        if (t < ntiles) {
+            issue(t, t);
+            ++q_age;
+        }
 
     int stage = 0;
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -210,59 +233,93 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             int stg = stage + NSTAGE - 1;
             if (stg >= NSTAGE) stg -= NSTAGE;
             issue(ahead, stg);
+            ++q_age;
         }
         const int later = min(NSTAGE - 1, ntiles - 1 - tile);
         const char* kbuf = smem + stage * kStageBytes;
         const char* vbuf = kbuf + 2 * kSlabBytes;
 
-        wait_tile<kDmaPerTile / 2, kDmaPerTile, NSTAGE - 1>(later);  // K of this tile (and its segment's query rows) landed
+        // K of this tile and its segment's query rows have landed.  Ring of slots: the rows were
+        // issued just before the K loads.  One slot: they were issued q_age tiles ago, which after a
+        // segment shorter than the ring is later than this tile's loads; then nothing but the tiles
+        // issued after the rows may still be in flight.
+        if (ONE_SLOT && (tile == 0 || cc.lt == 0) && q_age <= later)
+            wait_tile<0, kDmaPerTile, NSTAGE - 1>(q_age);
+        else
+            wait_tile<kDmaPerTile / 2, kDmaPerTile, NSTAGE - 1>(later);
+        bool refilled = false;  // one slot: query rows of the next segment were issued in this iteration
         if (tile == 0 || cc.lt == 0) {  // segment start
             seg_first_lt = cc.lt;
             if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is mine
                 const int cum = rs.t_lo + tile, end = cum + cc.nt;
                 write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
             }
-            st.reset();
-            load_query_operand<D>(qslots + q_comp * kQSlot, n, q4, col_ok, qreg);
-            q_comp = (q_comp + 1 == NSTAGE) ? 0 : q_comp + 1;
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                st[ct].reset();
+                load_query_operand<D>(qslots + q_comp * kQSlot + ct * 16 * QG::kRow, n, q4, col_ok[ct], qreg[ct]);
+            }
+            if (!ONE_SLOT) {
+                q_comp = (q_comp + 1 == NSTAGE) ? 0 : q_comp + 1;
+            } else if (tile + (cc.nt - cc.lt) < ntiles) {
+                // refill the slot with the rows of the next segment of this range
+                int nb = cc.b;
+                do {
+                    ++nb;
+                } while (nb < B - 1 && tiles_of(uniform_load(p.context_lens, nb), sp) == 0);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the slot has been read
+                issue_q(nb);
+                q_age = 0;
+                refilled = true;
+            }
         }
 
-        f32x4 s0, s1;
-        qk_scores<D, KV>(kbuf, of, qreg, s0, s1);
+        f32x4 s0[NCT], s1[NCT];
+        qk_scores<D, KV, NCT>(kbuf, of, qreg, s0, s1);
 
         // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (the end of the
         // context, the causal limits of a multi-token call) and the tiles where sliding windows begin
         // need the mask: everywhere else every column sees the whole tile.
         const int tile_first = (cc.lt + cc.ft) * kTileTokens;
         const int t0 = tile_first + 4 * q4;
-        const int lim = cc.L - col_back;
-        const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
         const bool unmasked = tile_first + kTileTokens <= cc.L - (Q - 1) && (reach == 0 || tile_first >= cc.L - p.window);
-        bf16x8 pb, pb_lo;
-        if (unmasked)
-            online_softmax<false>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
-        else
-            online_softmax<true>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
+        bf16x8 pb[NCT], pb_lo[NCT];
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            const int lim = cc.L - col_back[ct];
+            const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
+            if (unmasked)
+                online_softmax<false>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+            else
+                online_softmax<true>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+        }
 
-        wait_tile<0, kDmaPerTile, NSTAGE - 1>(later);  // V of this tile landed
-        pv_accumulate<D, KV>(vbuf, of, pb, pb_lo, st);
+        // V of this tile landed (query rows just issued are newer and may stay in flight)
+        if (ONE_SLOT && refilled)
+            wait_tile<kQLoads, kDmaPerTile, NSTAGE - 1>(later);
+        else
+            wait_tile<0, kDmaPerTile, NSTAGE - 1>(later);
+        pv_accumulate<D, KV, NCT>(vbuf, of, pb, pb_lo, st);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
             const bool whole = seg_first_lt == 0 && cc.lt == cc.nt - 1;  // the entire sequence: final result
-            const float l = rows_sum(st.lsum);
-            if (col_ok) {
-                // a column that saw no token (its query sits before this segment) leaves a zero
-                // row with an "empty" log-sum-exp
-                const float inv = l > 0.f ? vs / l : 0.f;
-                const float lse = l > 0.f ? st.m + fast_log2(l) : kNegBig;
-                if (whole) {
-                    if (skip > 0 && q4 == 0) p.seq_lse[(int64_t)cc.b * p.QH + col_row] = lse;
-                    store_final_row(p, ((int64_t)cc.b * p.QH + col_row) * D, st, inv, q4);
-                } else {
-                    const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
-                    if (q4 == 0) p.part_lse[slot] = lse;
-                    store_partial_row(p.part_o + slot * D, st, inv, q4);
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const float l = rows_sum(st[ct].lsum);
+                if (col_ok[ct]) {
+                    // a column that saw no token (its query sits before this segment) leaves a zero
+                    // row with an "empty" log-sum-exp
+                    const float inv = l > 0.f ? vs / l : 0.f;
+                    const float lse = l > 0.f ? st[ct].m + fast_log2(l) : kNegBig;
+                    if (whole) {
+                        if (skip > 0 && q4 == 0) p.seq_lse[(int64_t)cc.b * p.QH + col_row[ct]] = lse;
+                        store_final_row(p, ((int64_t)cc.b * p.QH + col_row[ct]) * D, st[ct], inv, q4);
+                    } else {
+                        const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row[ct];
+                        if (q4 == 0) p.part_lse[slot] = lse;
+                        store_partial_row(p.part_o + slot * D, st[ct], inv, q4);
+                    }
                 }
             }
         }

@@ -204,9 +204,11 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
 
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    ColumnState<D> st;
+    ColumnState<D> sts[1];  // one tile of 16 columns per wave
+    ColumnState<D>& st = sts[0];
     st.reset();
-    bf16x8 qreg[D / 32];
+    bf16x8 qregs[1][D / 32];
+    bf16x8 (&qreg)[D / 32] = qregs[0];
     int seg_first_lt = 0;
 
     // ---- prologue: the first segment's query rows, then the ring
@@ -260,8 +262,9 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
             }
         }
 
-        f32x4 s0, s1;
-        qk_scores<D, KV>(kbuf, of, qreg, s0, s1);
+        f32x4 s0s[1], s1s[1];
+        qk_scores<D, KV, 1>(kbuf, of, qregs, s0s, s1s);
+        const f32x4 &s0 = s0s[0], &s1 = s1s[0];
 
         // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (where the causal
         // limits lie) and the tiles where the columns' sliding windows begin need the mask:
@@ -272,13 +275,14 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
         const bool unmasked = PREFIX || (tile_first + kTileTokens <= cc.L - (Q - 1) &&
                                          (reach == 0 || tile_first >= cc.L - p.window));
-        bf16x8 pb, pb_lo;
+        bf16x8 pbs[1], pbs_lo[1];
+        bf16x8 &pb = pbs[0], &pb_lo = pbs_lo[0];
         if (unmasked)
             online_softmax<false>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
         else
             online_softmax<true>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
 
-        pv_accumulate<D, KV>(vbuf, of, pb, pb_lo, st);
+        pv_accumulate<D, KV, 1>(vbuf, of, pbs, pbs_lo, sts);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {

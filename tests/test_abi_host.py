@@ -81,7 +81,7 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_BF16) == "mfma-wide"  # 128 columns per KV head
     for Q in (2, 4, 16):
         win = shape(num_partitions=16, q_len=Q)
-        assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == ("mfma" if Q * 4 <= 16 else "mfma-wide")
+        assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == ("mfma" if Q * 4 <= 32 else "mfma-wide")  # 512 tiles, 16 partitions
         need = 2 * 16 * Q * 32 * (128 + 1) * 4 + 4 * 16
         assert need <= pa.pa_decode_workspace_size(win, pa.PA_KV_BF16) <= need + 3 * 256
         lens = [100, 4096, 1, 33]
@@ -89,11 +89,19 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
         assert np.array_equal(pa.pa_split_plan(win, pa.PA_KV_BF16, lens)[1], pa.pa_split_plan(one, pa.PA_KV_BF16, lens)[1])
     # q_len 0 and 1 are the same call
     assert pa.pa_decode_workspace_size(shape(q_len=1), pa.PA_KV_BF16) == pa.pa_decode_workspace_size(shape(), pa.PA_KV_BF16)
-    # up to 16 columns per KV head: one wave per (partition, KV head), narrow groups and head_dim 64 included
+    # up to 32 columns per KV head: one wave per (partition, KV head), narrow groups and head_dim 64 included
     assert pa.pa_kernel_variant(shape(num_q_heads=8, q_len=2), pa.PA_KV_BF16) == "mfma"
     assert pa.pa_kernel_variant(shape(num_q_heads=8), pa.PA_KV_BF16) == "mfma"
     assert pa.pa_kernel_variant(shape(num_q_heads=16, head_dim=64), pa.PA_KV_BF16) == "mfma"
-    assert pa.pa_kernel_variant(shape(num_q_heads=16, head_dim=64, q_len=16), pa.PA_KV_FP8_E4M3) == "mfma-wide"
+    # 17 .. 32 columns: two column tiles in one wave when every partition has a long run of tiles (here: at
+    # most 128 tiles per sequence and 256 partitions of the full device), else the two-wave workgroup
+    big = dict(batch=64, num_q_heads=16, head_dim=64, q_len=16)
+    assert pa.pa_kernel_variant(shape(**big), pa.PA_KV_FP8_E4M3) == "mfma"
+    assert pa.pa_kernel_variant(shape(**dict(big, batch=4)), pa.PA_KV_FP8_E4M3) == "mfma-wide"
+    assert pa.pa_kernel_variant(shape(**dict(big, batch=4, num_partitions=8)), pa.PA_KV_FP8_E4M3) == "mfma"
+    assert pa.pa_kernel_variant(shape(**dict(big, head_dim=128)), pa.PA_KV_FP8_E4M3) == "mfma-wide"  # fp8 at head_dim 128
+    assert pa.pa_kernel_variant(shape(**dict(big, head_dim=128)), pa.PA_KV_BF16) == "mfma"
+    assert pa.pa_kernel_variant(shape(num_q_heads=24, head_dim=64, q_len=16), pa.PA_KV_FP8_E4M3) == "mfma-wide"  # 48
 
 
 @pytest.mark.parametrize("Q,window", [(1, 1), (1, 16), (1, 100), (4, 33), (16, 5), (1, 10 ** 6)])

@@ -61,10 +61,11 @@ def test_decode_groups(pa, oracle, kv, Hq, Hkv):
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
 @pytest.mark.parametrize("Q,Hq,Hkv", [(2, 8, 2), (4, 4, 4), (16, 1, 1), (3, 6, 2), (2, 16, 2), (16, 2, 2), (16, 4, 2),
-                                      (5, 16, 2), (16, 4, 1), (9, 7, 1), (16, 8, 1), (16, 16, 2), (13, 9, 1)])
+                                      (5, 16, 2), (16, 4, 1), (9, 7, 1), (16, 8, 1), (16, 16, 2), (13, 9, 1), (5, 4, 1),
+                                      (2, 9, 1), (16, 2, 1), (6, 5, 1), (8, 8, 2)])
 def test_verification_shapes(pa, oracle, kv, Q, Hq, Hkv):
-    """2 .. 128 columns per KV head: one wave, and 2, 4 and 8 waves per workgroup (with fp8 rows a tile
-    is four loads, so only four of eight waves load)."""
+    """2 .. 128 columns per KV head: one wave with one or two column tiles, and 4 and 8 waves per
+    workgroup (with fp8 rows a tile is four loads, so only four of eight waves load)."""
     b = W.make_batch("d64-verify", 910 + 17 * Q + Hq, EDGE_LENS, Hq, Hkv, 64, 16, kv, q_len=Q)
     got, _ = check(pa, oracle, b, "head_dim 64 verify")
     for s, L in enumerate(EDGE_LENS):
@@ -86,7 +87,7 @@ def test_partition_sweep(pa, oracle, kv, Q, Hq, Hkv, P):
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("Q,Hq,Hkv", [(1, 4, 1), (4, 8, 2), (16, 4, 1), (16, 8, 1)])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(1, 4, 1), (4, 8, 2), (16, 4, 1), (16, 8, 1), (8, 4, 1), (6, 5, 1)])
 def test_every_dim_and_token_lands_in_its_place(pa, kv, Q, Hq, Hkv):
     """Query token i of a sequence sees, with all its weight, its own position (key 16 (i + 1) e_0
     against a query of 128 e_0: the others underflow); the value row of position t holds t's base-16
@@ -172,7 +173,7 @@ def test_shared_prefix(pa, oracle, kv, Hq, Hkv, B, prefix_blocks):
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("Q,Hq,Hkv", [(1, 8, 2), (1, 16, 1), (4, 8, 2), (16, 4, 1), (16, 8, 1), (1, 2, 2)])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(1, 8, 2), (1, 16, 1), (4, 8, 2), (16, 4, 1), (16, 8, 1), (1, 2, 2), (8, 4, 1), (5, 5, 1)])
 @pytest.mark.parametrize("window", [1, 16, 33, 100, 5000])
 def test_sliding_window(pa, oracle, kv, Q, Hq, Hkv, window):
     b = W.make_batch("d64-sliding", 960 + 13 * Q + Hq + window, EDGE_LENS, Hq, Hkv, 64, 16, kv, q_len=Q, window=window)

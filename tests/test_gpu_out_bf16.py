@@ -38,6 +38,7 @@ CASES = {
     "matrix-core kernel": lambda: W.make_batch("o2", 701, [0, 1, 33, 700, 16, 2000], 16, 4, 128, 16, W.KV_BF16),
     "matrix-core kernel, fp8": lambda: W.make_batch("o3", 702, [513, 40, 0], 16, 2, 128, 16, W.KV_FP8_E4M3),
     "verification, one wave": lambda: W.make_batch("o4", 703, [600, 2, 90], 8, 2, 128, 16, W.KV_BF16, q_len=4),
+    "verification, one wave, two column tiles": lambda: W.make_batch("o7", 706, [600, 2, 90, 33], 8, 2, 128, 16, W.KV_BF16, q_len=7),
     "verification, multi-wave": lambda: W.make_batch("o5", 704, [600, 3, 90, 0], 8, 2, 128, 16, W.KV_BF16, q_len=16),
     "sliding window": lambda: W.make_batch("o6", 705, [700, 50, 1], 8, 2, 128, 16, W.KV_BF16, window=100),
     "reduced 8B-shaped batch": lambda: W.make_config(2, length_scale=0.25),
