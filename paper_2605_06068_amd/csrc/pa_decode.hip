@@ -36,14 +36,14 @@ constexpr int kMaxQueryLen = 16;
 constexpr int mfma_stages(int, int) { return 2; }
 constexpr int mfma_waves_per_cu(int d) { return d == 128 ? 4 : 8; }
 // ring depth of the multi-wave kernel (the ring is shared by the workgroup's waves), by KV type
-// and waves per workgroup
-constexpr int kWideStagesBf16[3] = {4, 4, 3};  // 2, 4, 8 waves (8 waves: 3 stages leave room for two workgroups per CU)
+// and the workgroup's columns (32, 64 or 128): with 128 columns 3 stages leave room for two
+// workgroups per CU
+constexpr int kWideStagesBf16[3] = {4, 4, 3};
 constexpr int kWideStagesFp8[3] = {4, 4, 4};
 constexpr int kWideStages64Bf16 = 4;  // head_dim 64: half the bytes per tile
 constexpr int kWideStages64Fp8 = 6;
 // resident waves per compute unit the multi-wave plan aims at, LDS permitting: two workgroups of
-// up to 4 waves; two of 8 waves pay off for bf16 only (measured: fp8 with 128 columns is bound by
-// instruction issue, and more partitions only lengthen the merge)
+// up to 4 waves; two of 8 waves (the prefix pass) pay off for bf16 only
 constexpr int wide_waves_per_cu(int kv, int nw) { return (nw == 8 && kv == PA_KV_BF16) ? 16 : 8; }
 constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
@@ -82,21 +82,37 @@ int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_
 // runs at the same speed for 1 column as for 16).
 int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : (cols <= 16 ? 16 : 32)); }
 
-// waves per workgroup of the multi-wave kernel: one per 16 columns, rounded up to a power of two
-int wide_waves(int cols) { return cols <= 32 ? 2 : (cols <= 64 ? 4 : 8); }
+// Shape of a workgroup of the multi-wave kernel: waves, and MFMA column tiles (16 columns) per
+// wave.  Up to 64 columns one tile per wave (2 or 4 waves); above, in the per-sequence pass, 4
+// waves with two tiles each, which share every operand read and fp8 conversion (16 tokens on
+// 64 query / 8 KV heads = 128 columns, against 8 waves with one tile: 8B-shaped lengths bf16
+// 268 -> 247 us, fp8 258 -> 224 us, 70B-head-shaped fp8 batch 1614 -> 1216 us; with 64 columns
+// two waves of two tiles are slower than four of one, 186 against 152 us).  The prefix pass
+// keeps one tile per wave, up to 8 waves (two tiles measured 58.7 against 54.9 us per step).
+struct WideShape {
+    int nw, nct;
+};
 
-constexpr int wide_stages(int d, int kv, int nw)
+constexpr WideShape wide_shape(int cols, bool prefix)
+{
+    if (cols <= 32) return {2, 1};
+    if (cols <= 64) return {4, 1};
+    return prefix ? WideShape{8, 1} : WideShape{4, 2};
+}
+
+constexpr int wide_stages(int d, int kv, WideShape ws)
 {
     if (d == 64) return kv == PA_KV_BF16 ? kWideStages64Bf16 : kWideStages64Fp8;
-    const int i = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
+    const int cols = 16 * ws.nw * ws.nct;
+    const int i = cols <= 32 ? 0 : (cols <= 64 ? 1 : 2);
     return kv == PA_KV_BF16 ? kWideStagesBf16[i] : kWideStagesFp8[i];
 }
 
 // workgroups of the multi-wave kernel resident per compute unit
-int wide_groups_per_cu(int d, int kv, int nw)
+int wide_groups_per_cu(int d, int kv, WideShape ws)
 {
-    const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(d, nw, wide_stages(d, kv, nw), kv);
-    const int want = wide_waves_per_cu(kv, nw) / nw;
+    const int fit = kLdsPerCu / pa::mfma_wide_lds_bytes(d, ws.nw, ws.nct, wide_stages(d, kv, ws), kv);
+    const int want = wide_waves_per_cu(kv, ws.nw) / ws.nw;
     return fit < want ? fit : want;
 }
 
@@ -154,7 +170,7 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
 // waves (one-wave kernel) or workgroups (multi-wave kernel) resident per compute unit
 int groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
 {
-    return one_wave(s, kv) ? one_wave_per_cu(s, kv) : wide_groups_per_cu(s->head_dim, (int)kv, wide_waves(columns(s)));
+    return one_wave(s, kv) ? one_wave_per_cu(s, kv) : wide_groups_per_cu(s->head_dim, (int)kv, wide_shape(columns(s), false));
 }
 
 pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
@@ -229,9 +245,10 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         // kMaxColsMfma per workgroup, further column groups beyond that
         const int cols = s->batch * (s->num_q_heads / s->num_kv_heads);
         const int group_cols = cols < kMaxColsMfma ? cols : kMaxColsMfma;
-        plan->prefix_waves = wide_waves(group_cols);
-        plan->prefix_groups = (cols + 16 * plan->prefix_waves - 1) / (16 * plan->prefix_waves);
-        const int per_cu = wide_groups_per_cu(s->head_dim, (int)kv, plan->prefix_waves);
+        const WideShape ws = wide_shape(group_cols, true);
+        plan->prefix_waves = ws.nw;
+        plan->prefix_groups = (cols + 16 * ws.nw - 1) / (16 * ws.nw);
+        const int per_cu = wide_groups_per_cu(s->head_dim, (int)kv, ws);
         int64_t Pp = (int64_t)compute_units() * per_cu / ((int64_t)s->num_kv_heads * plan->prefix_groups);
         if (s->num_partitions > 0) Pp = s->num_partitions;  // tests force both counts with one knob
         if (Pp > plan->skip_tiles) Pp = plan->skip_tiles;
@@ -258,17 +275,17 @@ void launch_mfma(const Params& p, bool trace, dim3 grid, hipStream_t st)
         hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, false>), grid, dim3(64), 0, st, p);
 }
 
-template <int D, int NW, int KV>
+template <int D, int NW, int NCT, int KV>
 void launch_wide(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
-    constexpr int NSTAGE = wide_stages(D, KV, NW);
+    constexpr int NSTAGE = wide_stages(D, KV, WideShape{NW, NCT});
     if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NSTAGE, KV, true, false>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, true, false>), grid, dim3(NW * 64), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
 }
 
-// the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2, 4 or 8 waves above
+// the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2 or 4 waves above
 template <int D, int KV>
 void launch_partition(const Params& p, bool one_wave, bool trace, dim3 grid, hipStream_t st)
 {
@@ -281,12 +298,13 @@ void launch_partition(const Params& p, bool one_wave, bool trace, dim3 grid, hip
         launch_mfma<D, 16, KV>(p, trace, grid, st);
     else if (one_wave)
         launch_mfma<D, 32, KV>(p, trace, grid, st);
-    else if (wide_waves(cols) == 2)
-        launch_wide<D, 2, KV>(p, trace, grid, st);
-    else if (wide_waves(cols) == 4)
-        launch_wide<D, 4, KV>(p, trace, grid, st);
+    else if (cols <= 32)
+        launch_wide<D, 2, 1, KV>(p, trace, grid, st);
+    else if (cols <= 64)
+        launch_wide<D, 4, 1, KV>(p, trace, grid, st);
     else
-        launch_wide<D, 8, KV>(p, trace, grid, st);
+        launch_wide<D, 4, 2, KV>(p, trace, grid, st);
+    static_assert(wide_shape(32, false).nw == 2 && wide_shape(64, false).nw == 4 && wide_shape(128, false).nct == 2, "as launched");
 }
 
 // the pass over the prefix all sequences share
@@ -294,11 +312,11 @@ template <int D, int KV>
 void launch_prefix(const Params& p, int nw, dim3 grid, hipStream_t st)
 {
     if (nw == 2)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 2, wide_stages(D, KV, 2), KV, false, true>), grid, dim3(128), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 2, 1, wide_stages(D, KV, WideShape{2, 1}), KV, false, true>), grid, dim3(128), 0, st, p);
     else if (nw == 4)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 4, wide_stages(D, KV, 4), KV, false, true>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 4, 1, wide_stages(D, KV, WideShape{4, 1}), KV, false, true>), grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 8, wide_stages(D, KV, 8), KV, false, true>), grid, dim3(512), 0, st, p);
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 8, 1, wide_stages(D, KV, WideShape{8, 1}), KV, false, true>), grid, dim3(512), 0, st, p);
 }
 
 // calls f with head_dim and the KV type as compile-time constants

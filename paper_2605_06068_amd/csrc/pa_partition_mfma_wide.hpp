@@ -1,10 +1,11 @@
 // Partition kernel, matrix-core variant for more than 16 columns per KV head (multi-token
 // verification: q_len * G = 17 .. 128 (query token, query head) pairs).  A workgroup of NW
 // wavefronts serves one (partition, KV head): the waves share ONE ring of K/V tiles in LDS, so
-// the cache is read from HBM once for all columns, and each wave computes its own tile of 16
-// columns (columns 16w .. 16w+15) exactly as the single-wave kernel does: same operand
-// layouts, same swizzle, same online softmax (pa_mfma_tile.hpp; wait-count discipline as
-// described in pa_partition_mfma.hpp).
+// the cache is read from HBM once for all columns, and each wave computes its own NCT = 1 or 2
+// tiles of 16 columns (columns 16 NCT w .. 16 NCT (w + 1) - 1) exactly as the single-wave kernel
+// does: same operand layouts, same swizzle, same online softmax (pa_mfma_tile.hpp; wait-count
+// discipline as described in pa_partition_mfma.hpp).  Two tiles share every K and V operand read
+// and every fp8 conversion.
 //
 // Per tile, every wave loads 1/NW of the tile's LDS-DMA instructions and the workgroup meets at
 // one barrier:
@@ -12,7 +13,7 @@
 //     s_barrier                                (all parts of tile t are in LDS; everyone is done
 //                                               reading tile t-1, whose buffer is refilled next)
 //     issue my part of tile t + NSTAGE - 1
-//     scores, online softmax, PV for my 16 columns on tile t
+//     scores, online softmax, PV for my columns on tile t
 // All waves of a workgroup walk the same range, so they execute the same number of barriers.
 //
 // Query rows: every wave keeps ONE private LDS slot (16 rows) for the rows of its own
@@ -36,12 +37,12 @@
 
 namespace pa {
 
-// one wave's query rows: 16 columns
-constexpr int wide_q_slot_bytes(int d) { return 16 * 2 * d; }
+// one wave's query rows: nct tiles of 16 columns
+constexpr int wide_q_slot_bytes(int d, int nct) { return nct * 16 * 2 * d; }
 
-constexpr int mfma_wide_lds_bytes(int d, int nw, int nstage, int kv)
+constexpr int mfma_wide_lds_bytes(int d, int nw, int nct, int nstage, int kv)
 {
-    return nstage * mfma_stage_bytes(d, kv) + nw * wide_q_slot_bytes(d);
+    return nstage * mfma_stage_bytes(d, kv) + nw * wide_q_slot_bytes(d, nct);
 }
 
 // wait until at most `tiles` * PER_TILE of this wave's loads are still in flight (tiles clamped to MAXT)
@@ -61,10 +62,12 @@ __device__ __forceinline__ void wait_loads(int tiles)
 // caps the register budget at 256, which makes the compiler keep the MFMA accumulators in ordinary
 // VGPRs: with more it parks them in AGPRs and moves all 32 to VGPRs and back in every tile around
 // the rarely taken rescale branch.
-template <int D, int NW, int NSTAGE, int KV, bool TRACE, bool PREFIX>
+template <int D, int NW, int NCT, int NSTAGE, int KV, bool TRACE, bool PREFIX>
 __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_kernel(const Params p)
 {
     static_assert(NW == 2 || NW == 4 || NW == 8, "waves per workgroup");
+    static_assert(NCT == 1 || NCT == 2, "MFMA column tiles per wave");
+    constexpr int kWaveCols = 16 * NCT;  // columns one wave computes
     static_assert(NSTAGE >= 3, "the ring holds the tile in use, the one being refilled and at least one in flight");
     using Geo = KvGeom<D, KV>;
     using QG = QGeom<D>;
@@ -76,10 +79,10 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     static_assert(Geo::kDmaPerTile % PT == 0 && (Geo::kDmaPerTile >= NW ? PT * NW == Geo::kDmaPerTile : true),
                   "shares of a tile's loads");
     constexpr int kMaxLater = NSTAGE - 2;      // tiles in flight behind the one a wave waits for
-    constexpr int kQSlotBytes = wide_q_slot_bytes(D);
+    constexpr int kQSlotBytes = wide_q_slot_bytes(D, NCT);
     constexpr int kQLoads = kQSlotBytes / 1024;
-    static_assert(mfma_wide_lds_bytes(D, NW, NSTAGE, KV) <= 160 * 1024, "LDS of one compute unit");
-    __shared__ __attribute__((aligned(1024))) char smem[mfma_wide_lds_bytes(D, NW, NSTAGE, KV)];
+    static_assert(mfma_wide_lds_bytes(D, NW, NCT, NSTAGE, KV) <= 160 * 1024, "LDS of one compute unit");
+    __shared__ __attribute__((aligned(1024))) char smem[mfma_wide_lds_bytes(D, NW, NCT, NSTAGE, KV)];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -89,7 +92,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     const int nparts = PREFIX ? p.Pp : p.P;
     const int k = blockIdx.x % nparts;
     const int g = (blockIdx.x / nparts) % p.Hkv;
-    const int col0 = (blockIdx.x / nparts / p.Hkv) * (16 * NW);
+    const int col0 = (blockIdx.x / nparts / p.Hkv) * (kWaveCols * NW);
     const int G = p.G;
     const int B = PREFIX ? 1 : p.B;      // sequences as this kernel sees them
     const int Q = PREFIX ? p.B : p.Q;    // query tokens per such sequence
@@ -151,25 +154,30 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         my_tok[j] = r * Geo::kRowsPerDma + lane / Geo::kPieces;
         my_off[j] = slab_dma_offset<D, KV>(r, lane);
     }
-    // query rows of this wave's columns: LDS row lc holds column c = 16w + lc
+    // query rows of this wave's columns: LDS row lc holds column c = kWaveCols w + lc
     uint32_t qdma_off[kQLoads];
 #pragma unroll
     for (int r = 0; r < kQLoads; ++r) {
         const int lc = r * QG::kRowsPerDma + lane / QG::kPieces;
-        const int c = col0 + 16 * w + lc;
+        const int c = col0 + kWaveCols * w + lc;
         const int src = c < ncols ? ((c / G) * p.Hq + (c % G)) * QG::kRow : 0;
         qdma_off[r] = src + (((lane % QG::kPieces) ^ (lc & (QG::kPieces - 1))) << 4);
     }
     OperandOffsets<D, KV> of;
     of.init(n, q4);
-    // this lane's column
-    const int col = col0 + 16 * w + n;
-    const bool col_ok = col < ncols;
-    const bool wave_active = col0 + 16 * w < ncols;  // a wave without real columns only loads its share of the tiles
-    const int col_i = col_ok ? col / G : 0, col_h = col_ok ? col % G : 0;
-    // tokens at the end of the context the column must not see (prefix pass: every column sees all of it)
-    const int col_back = col_ok ? (PREFIX ? 0 : Q - 1 - col_i) : (1 << 30);
-    const int col_row = col_i * p.Hq + g * G + col_h;          // output row inside its sequence
+    // this lane's columns: kWaveCols w + 16 ct + n of column tile ct
+    const bool wave_active = col0 + kWaveCols * w < ncols;  // a wave without real columns only loads its share of the tiles
+    bool col_ok[NCT];
+    int col_back[NCT];  // tokens at the end of the context the column must not see (prefix pass: every column sees all of it)
+    int col_row[NCT];   // output row inside its sequence
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int col = col0 + kWaveCols * w + 16 * ct + n;
+        col_ok[ct] = col < ncols;
+        const int col_i = col_ok[ct] ? col / G : 0, col_h = col_ok[ct] ? col % G : 0;
+        col_back[ct] = col_ok[ct] ? (PREFIX ? 0 : Q - 1 - col_i) : (1 << 30);
+        col_row[ct] = col_i * p.Hq + g * G + col_h;
+    }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t ldsq = lds0 + NSTAGE * kStageBytes + w * kQSlotBytes;
     const char* qslot = smem + NSTAGE * kStageBytes + w * kQSlotBytes;
@@ -204,11 +212,10 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
 
     const float qs = KV == KV_FP8 ? p.scale_log2 * p.k_scale[g] : p.scale_log2;
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
-    ColumnState<D> sts[1];  // one tile of 16 columns per wave
-    ColumnState<D>& st = sts[0];
-    st.reset();
-    bf16x8 qregs[1][D / 32];
-    bf16x8 (&qreg)[D / 32] = qregs[0];
+    ColumnState<D> st[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) st[ct].reset();
+    bf16x8 qreg[NCT][D / 32];
     int seg_first_lt = 0;
 
     // ---- prologue: the first segment's query rows, then the ring
@@ -248,8 +255,11 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
                 const int cum = rs.t_lo + tile, end = cum + cc.nt;
                 write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
             }
-            st.reset();
-            load_query_operand<D>(qslot, n, q4, col_ok, qreg);
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                st[ct].reset();
+                load_query_operand<D>(qslot + ct * 16 * QG::kRow, n, q4, col_ok[ct], qreg[ct]);
+            }
             // refill the slot with the rows of the next segment of this range, if there is one
             if (tile + (cc.nt - cc.lt) < ntiles) {
                 int nb = cc.b;
@@ -262,47 +272,51 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
             }
         }
 
-        f32x4 s0s[1], s1s[1];
-        qk_scores<D, KV, 1>(kbuf, of, qregs, s0s, s1s);
-        const f32x4 &s0 = s0s[0], &s1 = s1s[0];
+        f32x4 s0[NCT], s1[NCT];
+        qk_scores<D, KV, NCT>(kbuf, of, qreg, s0, s1);
 
         // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (where the causal
         // limits lie) and the tiles where the columns' sliding windows begin need the mask:
         // everywhere else every column sees the whole tile.
         const int tile_first = (cc.lt + cc.ft) * kTileTokens;
         const int t0 = tile_first + 4 * q4;
-        const int lim = cc.L - col_back;
-        const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
         const bool unmasked = PREFIX || (tile_first + kTileTokens <= cc.L - (Q - 1) &&
                                          (reach == 0 || tile_first >= cc.L - p.window));
-        bf16x8 pbs[1], pbs_lo[1];
-        bf16x8 &pb = pbs[0], &pb_lo = pbs_lo[0];
-        if (unmasked)
-            online_softmax<false>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
-        else
-            online_softmax<true>(s0, s1, qs, t0, lim, low, st, pb, pb_lo);
+        bf16x8 pb[NCT], pb_lo[NCT];
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            const int lim = cc.L - col_back[ct];
+            const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
+            if (unmasked)
+                online_softmax<false>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+            else
+                online_softmax<true>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+        }
 
-        pv_accumulate<D, KV, 1>(vbuf, of, pbs, pbs_lo, sts);
+        pv_accumulate<D, KV, NCT>(vbuf, of, pb, pb_lo, st);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
             const bool whole = seg_first_lt == 0 && cc.lt == cc.nt - 1;
-            const float l = rows_sum(st.lsum);
-            if (col_ok) {
-                // a column that saw no token (its query sits before this segment) leaves a zero row
-                // with an "empty" log-sum-exp
-                const float inv = l > 0.f ? vs / l : 0.f;
-                const float lse = l > 0.f ? st.m + fast_log2(l) : kNegBig;
-                if (PREFIX) {
-                    const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row;
-                    if (q4 == 0) p.prefix_lse[slot] = lse;
-                    store_partial_row(p.prefix_o + slot * D, st, inv, q4);
-                } else if (whole) {
-                    store_final_row(p, ((int64_t)cc.b * p.QH + col_row) * D, st, inv, q4);
-                } else {
-                    const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row;
-                    if (q4 == 0) p.part_lse[slot] = lse;
-                    store_partial_row(p.part_o + slot * D, st, inv, q4);
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const float l = rows_sum(st[ct].lsum);
+                if (col_ok[ct]) {
+                    // a column that saw no token (its query sits before this segment) leaves a zero row
+                    // with an "empty" log-sum-exp
+                    const float inv = l > 0.f ? vs / l : 0.f;
+                    const float lse = l > 0.f ? st[ct].m + fast_log2(l) : kNegBig;
+                    if (PREFIX) {
+                        const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row[ct];
+                        if (q4 == 0) p.prefix_lse[slot] = lse;
+                        store_partial_row(p.prefix_o + slot * D, st[ct], inv, q4);
+                    } else if (whole) {
+                        store_final_row(p, ((int64_t)cc.b * p.QH + col_row[ct]) * D, st[ct], inv, q4);
+                    } else {
+                        const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row[ct];
+                        if (q4 == 0) p.part_lse[slot] = lse;
+                        store_partial_row(p.part_o + slot * D, st[ct], inv, q4);
+                    }
                 }
             }
         }
