@@ -288,7 +288,8 @@ struct ColumnState {
 // t0 + 16 + {0..3}; with MASKED the column sees only tokens low <= t < lim (the end of the context,
 // the causal limit of a multi-token call, the start of a sliding window); without it the whole tile.
 // Leaves the P^T operand as a bf16 pair (high part + rounding remainder: 16 significant bits, so
-// the weights lose nothing that matters against the fp32 accumulation).
+// the weights lose nothing that matters against the fp32 accumulation); the PV product uses the
+// remainder only for bf16 KV.
 template <bool MASKED, int D>
 __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1, float qs, int t0, int lim, int low,
                                                ColumnState<D>& st, bf16x8& pb, bf16x8& pb_lo)
@@ -346,7 +347,9 @@ __device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOff
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) {
             st[ct].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[ct], st[ct].acc[dt], 0, 0, 0);
-            st[ct].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo[ct], st[ct].acc[dt], 0, 0, 0);
+            // fp8 KV: the weights stay at bf16 precision (8 bits against the 4 of the values they multiply)
+            if (KV == KV_BF16)
+                st[ct].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo[ct], st[ct].acc[dt], 0, 0, 0);
         }
     }
 }

@@ -58,7 +58,10 @@ def test_bf16_output_is_the_rounded_float32_output(pa, oracle, name, P):
     want = oracle.decode_batch(b)["out"]
     flat = lambda a: a.reshape(a.shape[0], -1, a.shape[-1])
     assert np.isfinite(got).all()
-    assert np.all(np.abs(got.astype(np.float64) - want) <= np.abs(want) / 256 + 1e-5)
+    # half a bf16 ulp of the value on top of what the float32 result of the same path may be off by
+    # (bf16 KV: next to nothing; fp8 KV: its softmax weights enter the PV product at bf16 precision)
+    slack = 1e-5 if b.kv_dtype == W.KV_BF16 else 1e-2
+    assert np.all(np.abs(got.astype(np.float64) - want) <= np.abs(want) / 256 + slack)
     err = errors(flat(got), flat(want))
     assert err[1] <= BF16_REL_L2
     print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e}", flush=True)
