@@ -123,6 +123,99 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same merge for calls with many output rows per sequence (multi-token calls, wide models):
+// one wavefront merges FOUR rows of one cut sequence, 16 lanes per row, D / 16 floats per lane.
+// The rows of a sequence share its pieces, so control flow stays wave-uniform; every lane walks
+// the pieces itself (no cross-lane traffic), four pieces at a time with all their loads in
+// flight together.  Against one wave per row this cuts the number of waves, and with it the
+// rounds of dependent round trips the grid needs, by four (8B-shaped batch, 16 query tokens =
+// 512 rows x 63 cut sequences: 16.9 -> 12.3 us); with few rows per sequence one wave per row is
+// as fast or faster, and the host keeps it there.
+constexpr int kMergeRowsPerWave = 4;
+
+template <int D>
+__global__ __launch_bounds__(64) void merge_rows_kernel(const Params p)
+{
+    constexpr int kLanesPerRow = kWave / kMergeRowsPerWave;  // 16
+    constexpr int V4 = D / kLanesPerRow / 4;                  // float4s per lane: 2 (head_dim 128) or 1 (64)
+    const int lane = threadIdx.x;
+    const int P = p.P;
+    const int b = nth_cut_sequence(p.merge_desc, p.B, blockIdx.y, lane);
+    if (b < 0) return;  // fewer sequences were cut than the grid has room for
+    const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
+    const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),
+              T = uniform_load(p.merge_desc, 4 * (int64_t)b + 3);
+
+    const int h = blockIdx.x * kMergeRowsPerWave + lane / kLanesPerRow;
+    const bool row_ok = h < p.QH;
+    const int hr = row_ok ? h : p.QH - 1;  // lanes past the last row follow along on the last one and store nothing
+    const int sub = lane % kLanesPerRow;
+
+    // partition j-1 holds the tile before the boundary, a tile of b: its piece exists and stands
+    // in (with weight 0) for partitions of the walk that have no tiles
+    const int lo_first = part_begin(j - 1, T, P);
+    const int64_t safe = (int64_t)(2 * (j - 1) + (lo_first != cum ? 1 : 0)) * p.QH + hr;
+
+    float4 acc[V4];
+#pragma unroll
+    for (int i = 0; i < V4; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    float wsum = 0.f, m = kNegBig;
+    for (int kk0 = j - 1; kk0 < P; kk0 += 4) {
+        if (part_begin(kk0, T, P) >= end_b) break;  // past the sequence's last tile
+        float lse[4];
+        float4 x[4][V4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int kk = kk0 + u;
+            ok[u] = false;
+            int64_t r = safe;
+            if (kk < P) {
+                const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
+                ok[u] = hi > lo && lo < end_b && hi > cum;
+                if (ok[u]) r = (int64_t)(2 * kk + ((kk == j - 1 && lo != cum) ? 1 : 0)) * p.QH + hr;
+            }
+            lse[u] = p.part_lse[r];
+            const float4* src = reinterpret_cast<const float4*>(p.part_o + r * D) + sub * V4;
+#pragma unroll
+            for (int i = 0; i < V4; ++i) x[u][i] = src[i];
+        }
+        float cm = kNegBig;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cm = ok[u] ? fmaxf(cm, lse[u]) : cm;
+        const float m_new = fmaxf(m, cm);
+        const float rescale = fast_exp2(m - m_new);
+        wsum *= rescale;
+#pragma unroll
+        for (int i = 0; i < V4; ++i) {
+            acc[i].x *= rescale;
+            acc[i].y *= rescale;
+            acc[i].z *= rescale;
+            acc[i].w *= rescale;
+        }
+        m = m_new;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = ok[u] ? fast_exp2(lse[u] - m_new) : 0.f;
+            wsum += w;
+#pragma unroll
+            for (int i = 0; i < V4; ++i) {
+                acc[i].x = fmaf(w, x[u][i].x, acc[i].x);
+                acc[i].y = fmaf(w, x[u][i].y, acc[i].y);
+                acc[i].z = fmaf(w, x[u][i].z, acc[i].z);
+                acc[i].w = fmaf(w, x[u][i].w, acc[i].w);
+            }
+        }
+    }
+    if (!row_ok) return;
+    const float inv = 1.f / wsum;
+    const int64_t row = ((int64_t)b * p.QH + h) * D + sub * (4 * V4);
+#pragma unroll
+    for (int i = 0; i < V4; ++i)
+        store_out4(p, row + 4 * i, acc[i].x * inv, acc[i].y * inv, acc[i].z * inv, acc[i].w * inv);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Rows with many pieces: a workgroup of kMergeWaves wavefronts per output row.
 //
 // combine_pieces() combines, by their log-sum-exps, `nsrc` pieces of one output row and stores
