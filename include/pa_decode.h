@@ -54,7 +54,7 @@
  * of once per sequence; the rest of every context is processed per sequence as usual and a merge
  * kernel joins the two by their log-sum-exps.  The promise is not checked on the device: block
  * ids of the prefix are taken from row 0 of block_tables.  Supported for plain decode
- * (q_len <= 1).
+ * (q_len <= 1) with G <= 32.
  *
  * Sliding window (shape.window = W > 0; attention over the last W positions only, as in the
  * streaming encoder of the paper's Appendix A, Scenario D, whose per-stream cache is evicted in
@@ -65,7 +65,7 @@
  * stale.  Not supported together with a shared prefix.
  *
  * Supported: batch <= 65535; head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
- * 1 <= G <= 16 and Q * G <= 128; PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
+ * Q * G <= 128 (G up to 128 for plain decode); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
  * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
  */
 #ifndef PA_DECODE_H

@@ -19,7 +19,6 @@ namespace {
 
 using pa::Params;
 
-constexpr int kMaxGroupMfma = 16;  // columns of one MFMA tile
 // Up to here one wave per (partition, KV head), with one or two MFMA column tiles; above, a
 // workgroup of waves.  Two column tiles per wave beat two waves with one tile each (8B-shaped
 // batch, 5 / 8 query tokens: 118 / 125 us against 130 / 137 us; long-context batch, 8 tokens: 380
@@ -80,7 +79,7 @@ int shared_tiles(const pa_shape* s) { return s->shared_prefix_blocks / 2; }
 // columns of the score matrix per KV head: (query token, query head of the group) pairs
 int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
 
-// The kernels cover head_dim 64 and 128, groups of up to 16 query heads and up to 128 columns
+// The kernels cover head_dim 64 and 128 and up to 128 columns (query tokens x heads of a group)
 // (narrow groups are padded inside the 16-column tile: the kernel is bound by the KV traffic, and
 // runs at the same speed for 1 column as for 16).
 int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : (cols <= 16 ? 16 : 32)); }
@@ -164,6 +163,7 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
 {
     const int cols = columns(s);
     if (cols <= 16) return true;
+    if (shared_tiles(s) > 0) return true;  // only the one-wave kernel leaves a prefix out of its plan (groups of up to 32)
     if (cols > max_cols_one_wave(s->head_dim, (int)kv)) return false;
     const int64_t P = s->num_partitions > 0 ? s->num_partitions
                                             : (int64_t)compute_units() * one_wave_per_cu(s, kv) / s->num_kv_heads;
@@ -191,12 +191,12 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return PA_ERR_UNSUPPORTED;
     if (s->q_len > kMaxQueryLen) return PA_ERR_UNSUPPORTED;
-    if (s->num_q_heads / s->num_kv_heads > kMaxGroupMfma || columns(s) > kMaxColsMfma) return PA_ERR_UNSUPPORTED;
+    if (columns(s) > kMaxColsMfma) return PA_ERR_UNSUPPORTED;
     if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
     if (s->batch > kMaxBatch) return PA_ERR_UNSUPPORTED;  // the merge kernels index sequences by blockIdx.y
     if (shared_tiles(s) > 0) {
-        // the per-sequence pass runs on the one-wave kernel, the prefix pass on the multi-wave one
-        if (query_len(s) > 1 || s->batch < 1) return PA_ERR_UNSUPPORTED;
+        // the per-sequence pass runs on the one-wave kernel (up to 32 columns), the prefix pass on the multi-wave one
+        if (query_len(s) > 1 || s->batch < 1 || columns(s) > 32) return PA_ERR_UNSUPPORTED;
         // the merge of such calls reads rows of `out` back as float32
         if (s->out_dtype != PA_OUT_F32) return PA_ERR_UNSUPPORTED;
         if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens) return PA_ERR_INVALID_ARG;

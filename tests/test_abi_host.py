@@ -180,14 +180,16 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(batch=70000, max_context_len=64), pa.PA_ERR_UNSUPPORTED),
     (dict(head_dim=96), pa.PA_ERR_UNSUPPORTED),
     (dict(block_size=32), pa.PA_ERR_UNSUPPORTED),
-    (dict(num_q_heads=8 * 32), pa.PA_ERR_UNSUPPORTED),
+    (dict(num_q_heads=8 * 129), pa.PA_ERR_UNSUPPORTED),                  # more than 128 query heads per KV head
     (dict(q_len=-1), pa.PA_ERR_INVALID_ARG),
     (dict(q_len=17), pa.PA_ERR_UNSUPPORTED),
     (dict(q_len=16, num_q_heads=128), pa.PA_ERR_UNSUPPORTED),           # 16 tokens x 16 heads > 128 rows per KV head
+    (dict(q_len=2, num_q_heads=8 * 65), pa.PA_ERR_UNSUPPORTED),
     (dict(shared_prefix_blocks=-2), pa.PA_ERR_INVALID_ARG),
     (dict(shared_prefix_blocks=257), pa.PA_ERR_INVALID_ARG),              # more than a table row holds
     (dict(shared_prefix_blocks=8, max_context_len=100), pa.PA_ERR_INVALID_ARG),  # contexts shorter than the prefix
     (dict(shared_prefix_blocks=8, q_len=4), pa.PA_ERR_UNSUPPORTED),
+    (dict(shared_prefix_blocks=8, num_q_heads=8 * 40), pa.PA_ERR_UNSUPPORTED),  # groups wider than 32
     (dict(window=-1), pa.PA_ERR_INVALID_ARG),
     (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
     (dict(out_dtype=2), pa.PA_ERR_INVALID_ARG),

@@ -71,11 +71,10 @@ def test_configs_full_size(pa, oracle, config):
 
 # ------------------------------------------------------------------ shapes and edges
 @pytest.mark.parametrize("Hq,Hkv,D", [(1, 1, 64), (1, 1, 128), (4, 4, 128), (2, 1, 64), (6, 2, 128), (8, 1, 128),
-                                      (16, 2, 64), (5, 1, 128), (12, 4, 64), (16, 1, 128), (24, 2, 128), (4, 1, 128)])
+                                      (16, 2, 64), (5, 1, 128), (12, 4, 64), (16, 1, 128), (24, 2, 128), (4, 1, 128),
+                                      (32, 1, 128), (64, 1, 64), (128, 1, 128), (64, 2, 128), (40, 1, 64), (17, 1, 128)])
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
 def test_head_shapes(pa, oracle, Hq, Hkv, D, kv):
-    if Hq // Hkv > 8 and D == 64:
-        pytest.skip("groups wider than 8 are supported for head_dim 128 only")
     b = W.make_batch("shapes", 50 + Hq + D, [1, 15, 16, 17, 300, 257, 512, 31, 32, 33], Hq, Hkv, D, 16, kv,
                      num_blocks=100, max_blocks_per_seq=40)
     check(pa, oracle, b, "head-shapes")

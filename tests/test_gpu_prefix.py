@@ -52,7 +52,7 @@ def suffix_lens(prefix_blocks, B, seed):
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 2), (16, 1), (5, 1), (2, 2), (4, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 2), (16, 1), (5, 1), (2, 2), (4, 2), (32, 1), (40, 2), (17, 1)])
 @pytest.mark.parametrize("B,prefix_blocks", [(1, 8), (3, 2), (5, 3), (20, 64), (16, 9), (40, 10)])
 def test_shared_prefix_shapes(pa, oracle, kv, Hq, Hkv, B, prefix_blocks):
     """Column counts B*G from 1 to 640: 2, 4 and 8 waves per workgroup, padded and idle waves, several
