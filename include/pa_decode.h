@@ -37,7 +37,7 @@
  *     k_scale, v_scale [num_kv_heads]                                     float32 (fp8 KV only)
  *     out           [batch, num_q_heads, head_dim]                        float32 (bf16 if shape.out_dtype says so)
  *
- * Multi-token verification (shape.q_len = Q in 2 .. 16; the single forward pass over a window of
+ * Multi-token verification (shape.q_len = Q >= 2 with Q * G <= 128; the single forward pass over a window of
  * K proposed tokens in the paper's predicted-output speculative decoding, Appendix A, Scenario B):
  * the Q window tokens are already in the cache as the LAST Q tokens of every context
  * (context_lens counts them), q and out gain a query-token axis,
@@ -104,8 +104,8 @@ typedef struct pa_shape {
     int32_t max_context_len;    /* host-known upper bound on context_lens; 0 = max_blocks_per_seq * block_size */
     int32_t num_partitions;     /* 0 = library heuristic; otherwise the number P of partitions of the
                                    split plan below (1 .. 65535; tests force values) */
-    int32_t q_len;              /* query tokens per sequence: 0 or 1 = plain decode; 2 .. 16 = multi-token
-                                   verification (see pa_decode) */
+    int32_t q_len;              /* query tokens per sequence: 0 or 1 = plain decode; 2 .. 128 = multi-token
+                                   verification (see pa_decode; q_len * G <= 128) */
     int32_t shared_prefix_blocks; /* 0, or the caller's promise that the first shared_prefix_blocks entries of
                                    every row of block_tables are the same physical blocks (a prompt prefix
                                    cached once for the whole batch) and every context is at least that long:

@@ -26,7 +26,7 @@ using pa::Params;
 // hides behind the loads (70B-head-shaped batch, 4 tokens: 540 against 523 us).
 constexpr int max_cols_one_wave(int d, int kv) { return (kv == PA_KV_FP8_E4M3 && d == 128) ? 16 : 32; }
 constexpr int kMaxColsMfma = 128;  // eight 16-column MFMA tiles, one per wave of the widest workgroup
-constexpr int kMaxQueryLen = 16;
+constexpr int kMaxQueryLen = 128;  // with one query head per KV head; in general q_len * G <= kMaxColsMfma
 // Depth of the LDS tile ring of the one-wave kernel: two tiles for every head_dim and KV type.
 // What pays is resident waves (head_dim 128: one per SIMD; head_dim 64, whose tiles are half the
 // size: two), not deeper rings.  Measured: head_dim 64 fp8, 64 sequences of 1k-8k tokens: 2 tiles

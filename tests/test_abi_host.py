@@ -182,7 +182,8 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(block_size=32), pa.PA_ERR_UNSUPPORTED),
     (dict(num_q_heads=8 * 129), pa.PA_ERR_UNSUPPORTED),                  # more than 128 query heads per KV head
     (dict(q_len=-1), pa.PA_ERR_INVALID_ARG),
-    (dict(q_len=17), pa.PA_ERR_UNSUPPORTED),
+    (dict(q_len=129, num_q_heads=8), pa.PA_ERR_UNSUPPORTED),
+    (dict(q_len=33), pa.PA_ERR_UNSUPPORTED),                             # 33 tokens x 4 heads > 128 columns
     (dict(q_len=16, num_q_heads=128), pa.PA_ERR_UNSUPPORTED),           # 16 tokens x 16 heads > 128 rows per KV head
     (dict(q_len=2, num_q_heads=8 * 65), pa.PA_ERR_UNSUPPORTED),
     (dict(shared_prefix_blocks=-2), pa.PA_ERR_INVALID_ARG),

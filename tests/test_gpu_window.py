@@ -53,7 +53,7 @@ def check(pa, oracle, batch, what, **kw):
 WINDOW_SHAPES = [(4, 4, 4), (2, 8, 2), (2, 4, 1), (3, 6, 2), (2, 16, 2), (16, 2, 2), (7, 3, 1), (2, 16, 1),
                  (16, 4, 2), (5, 16, 2), (16, 4, 1), (4, 16, 1), (9, 7, 1), (16, 8, 1), (16, 16, 2), (8, 16, 1),
                  (13, 9, 1), (5, 13, 1), (2, 1, 1), (3, 2, 2), (2, 4, 2), (5, 4, 1), (2, 9, 1), (3, 8, 1), (16, 2, 1),
-                 (6, 5, 1), (3, 11, 1), (16, 4, 2), (4, 32, 1), (2, 40, 1), (3, 17, 1)]
+                 (6, 5, 1), (3, 11, 1), (16, 4, 2), (4, 32, 1), (2, 40, 1), (3, 17, 1), (32, 4, 1), (128, 1, 1), (64, 2, 1), (24, 5, 1), (17, 2, 2), (40, 3, 1)]
 
 
 @pytest.mark.parametrize("Q,Hq,Hkv", WINDOW_SHAPES)
