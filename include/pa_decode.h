@@ -37,14 +37,14 @@
  *     k_scale, v_scale [num_kv_heads]                                     float32 (fp8 KV only)
  *     out           [batch, num_q_heads, head_dim]                        float32 (bf16 if shape.out_dtype says so)
  *
- * Multi-token verification (shape.q_len = Q >= 2 with Q * G <= 128; the single forward pass over a window of
+ * Multi-token verification (shape.q_len = Q >= 2 with Q * G <= 512; the single forward pass over a window of
  * K proposed tokens in the paper's predicted-output speculative decoding, Appendix A, Scenario B):
  * the Q window tokens are already in the cache as the LAST Q tokens of every context
  * (context_lens counts them), q and out gain a query-token axis,
  *     q   [batch, Q, num_q_heads, head_dim]      out [batch, Q, num_q_heads, head_dim]
  * and query token i attends causally, to t in [0, context_lens[b] - Q + i]; a query token with no
- * visible token yields a zero row.  The KV cache is read once for all Q tokens.  Supported for
- * Q * G <= 128.
+ * visible token yields a zero row.  The KV cache is read once for all Q tokens up to Q * G = 128
+ * (query token, head) pairs per KV head, once per 128 of them above that (Q * G <= 512).
  *
  * Shared prefix (shape.shared_prefix_blocks > 0; the long common prompt prefix of the paper's
  * prompt-caching workload, Appendix A, Scenario C: many concurrent requests over one cached
@@ -65,7 +65,7 @@
  * stale.  Not supported together with a shared prefix.
  *
  * Supported: batch <= 65535; head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
- * Q * G <= 128 (G up to 128 for plain decode); PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
+ * Q * G <= 512; PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
  * infinities, 0x7F/0xFF NaN) with one float32 scale per KV head for K and one for V.
  */
 #ifndef PA_DECODE_H
@@ -104,8 +104,8 @@ typedef struct pa_shape {
     int32_t max_context_len;    /* host-known upper bound on context_lens; 0 = max_blocks_per_seq * block_size */
     int32_t num_partitions;     /* 0 = library heuristic; otherwise the number P of partitions of the
                                    split plan below (1 .. 65535; tests force values) */
-    int32_t q_len;              /* query tokens per sequence: 0 or 1 = plain decode; 2 .. 128 = multi-token
-                                   verification (see pa_decode; q_len * G <= 128) */
+    int32_t q_len;              /* query tokens per sequence: 0 or 1 = plain decode; 2 .. 512 = multi-token
+                                   verification (see pa_decode; q_len * G <= 512) */
     int32_t shared_prefix_blocks; /* 0, or the caller's promise that the first shared_prefix_blocks entries of
                                    every row of block_tables are the same physical blocks (a prompt prefix
                                    cached once for the whole batch) and every context is at least that long:

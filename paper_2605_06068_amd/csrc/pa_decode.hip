@@ -25,8 +25,10 @@ using pa::Params;
 // against 427 us) except for fp8 at head_dim 128, where the second tile's arithmetic no longer
 // hides behind the loads (70B-head-shaped batch, 4 tokens: 540 against 523 us).
 constexpr int max_cols_one_wave(int d, int kv) { return (kv == PA_KV_FP8_E4M3 && d == 128) ? 16 : 32; }
-constexpr int kMaxColsMfma = 128;  // eight 16-column MFMA tiles, one per wave of the widest workgroup
-constexpr int kMaxQueryLen = 128;  // with one query head per KV head; in general q_len * G <= kMaxColsMfma
+constexpr int kMaxColsMfma = 128;  // columns of the widest workgroup: eight 16-column MFMA tiles
+constexpr int kMaxColGroups = 4;   // workgroups side by side on one (partition, KV head), each reading the tiles for its own columns
+constexpr int kMaxCols = kMaxColsMfma * kMaxColGroups;
+constexpr int kMaxQueryLen = kMaxCols;  // with one query head per KV head; in general q_len * G <= kMaxCols
 // Depth of the LDS tile ring of the one-wave kernel: two tiles for every head_dim and KV type.
 // What pays is resident waves (head_dim 128: one per SIMD; head_dim 64, whose tiles are half the
 // size: two), not deeper rings.  Measured: head_dim 64 fp8, 64 sequences of 1k-8k tokens: 2 tiles
@@ -170,10 +172,14 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
     return tile_bound(s) >= kMinTilesTwoColumnTiles * (P < 1 ? 1 : P);
 }
 
+// workgroups of up to 128 columns a call needs side by side (more than one: the cache is read once per group)
+int column_groups(const pa_shape* s) { return (columns(s) + kMaxColsMfma - 1) / kMaxColsMfma; }
+
 // waves (one-wave kernel) or workgroups (multi-wave kernel) resident per compute unit
 int groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
 {
-    return one_wave(s, kv) ? one_wave_per_cu(s, kv) : wide_groups_per_cu(s->head_dim, (int)kv, wide_shape(columns(s), false));
+    const int cols = columns(s) < kMaxColsMfma ? columns(s) : kMaxColsMfma;
+    return one_wave(s, kv) ? one_wave_per_cu(s, kv) : wide_groups_per_cu(s->head_dim, (int)kv, wide_shape(cols, false));
 }
 
 pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
@@ -191,7 +197,7 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->block_size != pa::kBlockSize) return PA_ERR_UNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return PA_ERR_UNSUPPORTED;
     if (s->q_len > kMaxQueryLen) return PA_ERR_UNSUPPORTED;
-    if (columns(s) > kMaxColsMfma) return PA_ERR_UNSUPPORTED;
+    if (columns(s) > kMaxCols) return PA_ERR_UNSUPPORTED;
     if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
     if (s->batch > kMaxBatch) return PA_ERR_UNSUPPORTED;  // the merge kernels index sequences by blockIdx.y
     if (shared_tiles(s) > 0) {
@@ -225,7 +231,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     } else {
         // one resident wave (or workgroup) per (partition, KV head): as many partitions as the device holds at once,
         // but never more than there can be tiles
-        int64_t P = (int64_t)compute_units() * groups_per_cu(s, kv) / s->num_kv_heads;
+        int64_t P = (int64_t)compute_units() * groups_per_cu(s, kv) / ((int64_t)s->num_kv_heads * column_groups(s));
         // small calls: a partition should have a few tiles to amortise its start-up, and every extra
         // partition is one more piece per row for the merge (measured on single-sequence calls)
         const int min_tiles = plan->one_wave ? kMinTilesOneWave : kMinTilesWide;
@@ -403,7 +409,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
             launch_prefix<D, KV>(p, plan.prefix_waves, pgrid, hs);
             if (hipGetLastError() != hipSuccess) { launched = false; return; }
         }
-        const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv);
+        const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv * (uint32_t)column_groups(shape));
         launch_partition<D, KV>(p, plan.one_wave, trace, grid, hs);
         if (hipGetLastError() != hipSuccess) { launched = false; return; }
         if (ev && hipEventRecord(ev->between, hs) != hipSuccess) { launched = false; return; }

@@ -114,7 +114,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     } else {
         rs = find_range(p.context_lens, B, k, p.P, lane, sp);
     }
-    if (!PREFIX && k == 0 && w == 0) {  // empty contexts: their output rows are zero
+    if (!PREFIX && k == 0 && w == 0 && col0 == 0) {  // empty contexts: their output rows are zero
         for (int b0 = 0; b0 < B; b0 += kWave) {
             const int b = b0 + lane;
             if (b < B && p.context_lens[b] <= 0) {
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
             }
         }
     }
-    const bool describes = !PREFIX && g == 0 && w == 0 && p.merge_desc != nullptr;  // tells the merge about its sequences
+    const bool describes = !PREFIX && g == 0 && w == 0 && col0 == 0 && p.merge_desc != nullptr;  // tells the merge about its sequences
     if (rs.t_lo >= rs.t_hi) return;  // the same for every wave of the workgroup
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     // returns whether this wave put loads in flight
     auto issue = [&](int stage) {
         const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
-        if (TRACE && w == 0 && lane == 0) trace_tile_blocks(p.trace_blocks, tb, ic.b, g, k, p.Hkv, p.MB);
+        if (TRACE && w == 0 && lane == 0 && col0 == 0) trace_tile_blocks(p.trace_blocks, tb, ic.b, g, k, p.Hkv, p.MB);
         const uint32_t ldst = lds0 + stage * kStageBytes;
         if (loader) {
 #pragma unroll

@@ -180,12 +180,12 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(batch=70000, max_context_len=64), pa.PA_ERR_UNSUPPORTED),
     (dict(head_dim=96), pa.PA_ERR_UNSUPPORTED),
     (dict(block_size=32), pa.PA_ERR_UNSUPPORTED),
-    (dict(num_q_heads=8 * 129), pa.PA_ERR_UNSUPPORTED),                  # more than 128 query heads per KV head
+    (dict(num_q_heads=8 * 513), pa.PA_ERR_UNSUPPORTED),                  # more than 512 query heads per KV head
     (dict(q_len=-1), pa.PA_ERR_INVALID_ARG),
-    (dict(q_len=129, num_q_heads=8), pa.PA_ERR_UNSUPPORTED),
-    (dict(q_len=33), pa.PA_ERR_UNSUPPORTED),                             # 33 tokens x 4 heads > 128 columns
-    (dict(q_len=16, num_q_heads=128), pa.PA_ERR_UNSUPPORTED),           # 16 tokens x 16 heads > 128 rows per KV head
-    (dict(q_len=2, num_q_heads=8 * 65), pa.PA_ERR_UNSUPPORTED),
+    (dict(q_len=513, num_q_heads=8), pa.PA_ERR_UNSUPPORTED),
+    (dict(q_len=129), pa.PA_ERR_UNSUPPORTED),                            # 129 tokens x 4 heads > 512 columns
+    (dict(q_len=16, num_q_heads=8 * 33), pa.PA_ERR_UNSUPPORTED),        # 16 tokens x 33 heads > 512 columns per KV head
+    (dict(q_len=2, num_q_heads=8 * 257), pa.PA_ERR_UNSUPPORTED),
     (dict(shared_prefix_blocks=-2), pa.PA_ERR_INVALID_ARG),
     (dict(shared_prefix_blocks=257), pa.PA_ERR_INVALID_ARG),              # more than a table row holds
     (dict(shared_prefix_blocks=8, max_context_len=100), pa.PA_ERR_INVALID_ARG),  # contexts shorter than the prefix

@@ -62,7 +62,7 @@ def test_decode_groups(pa, oracle, kv, Hq, Hkv):
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
 @pytest.mark.parametrize("Q,Hq,Hkv", [(2, 8, 2), (4, 4, 4), (16, 1, 1), (3, 6, 2), (2, 16, 2), (16, 2, 2), (16, 4, 2),
                                       (5, 16, 2), (16, 4, 1), (9, 7, 1), (16, 8, 1), (16, 16, 2), (13, 9, 1), (5, 4, 1),
-                                      (2, 9, 1), (16, 2, 1), (6, 5, 1), (8, 8, 2)])
+                                      (2, 9, 1), (16, 2, 1), (6, 5, 1), (8, 8, 2), (16, 16, 1), (40, 8, 1)])
 def test_verification_shapes(pa, oracle, kv, Q, Hq, Hkv):
     """2 .. 128 columns per KV head: one wave with one or two column tiles, and 4 and 8 waves per
     workgroup (with fp8 rows a tile is four loads, so only four of eight waves load)."""

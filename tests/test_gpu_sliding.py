@@ -50,7 +50,7 @@ def check(pa, oracle, batch, what, **kw):
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
 @pytest.mark.parametrize("Q,Hq,Hkv", [(1, 8, 2), (1, 16, 1), (4, 8, 2), (16, 4, 1), (16, 8, 1), (3, 5, 1), (1, 2, 2),
-                                      (1, 4, 2), (2, 1, 1), (8, 4, 1), (5, 5, 1), (16, 2, 1), (1, 32, 1), (2, 48, 2)])
+                                      (1, 4, 2), (2, 1, 1), (8, 4, 1), (5, 5, 1), (16, 2, 1), (1, 32, 1), (2, 48, 2), (16, 10, 1)])
 @pytest.mark.parametrize("window", [1, 5, 16, 31, 32, 33, 100, 5000])
 def test_sliding_window_shapes(pa, oracle, kv, Q, Hq, Hkv, window):
     b = W.make_batch("sliding", 600 + 13 * Q + Hq + window, EDGE_LENS, Hq, Hkv, 128, 16, kv, q_len=Q, window=window)

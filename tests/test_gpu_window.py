@@ -53,7 +53,8 @@ def check(pa, oracle, batch, what, **kw):
 WINDOW_SHAPES = [(4, 4, 4), (2, 8, 2), (2, 4, 1), (3, 6, 2), (2, 16, 2), (16, 2, 2), (7, 3, 1), (2, 16, 1),
                  (16, 4, 2), (5, 16, 2), (16, 4, 1), (4, 16, 1), (9, 7, 1), (16, 8, 1), (16, 16, 2), (8, 16, 1),
                  (13, 9, 1), (5, 13, 1), (2, 1, 1), (3, 2, 2), (2, 4, 2), (5, 4, 1), (2, 9, 1), (3, 8, 1), (16, 2, 1),
-                 (6, 5, 1), (3, 11, 1), (16, 4, 2), (4, 32, 1), (2, 40, 1), (3, 17, 1), (32, 4, 1), (128, 1, 1), (64, 2, 1), (24, 5, 1), (17, 2, 2), (40, 3, 1)]
+                 (6, 5, 1), (3, 11, 1), (16, 4, 2), (4, 32, 1), (2, 40, 1), (3, 17, 1), (32, 4, 1), (128, 1, 1), (64, 2, 1), (24, 5, 1), (17, 2, 2), (40, 3, 1), (16, 16, 1), (32, 5, 1), (128, 4, 1),
+                 (16, 32, 2), (9, 16, 1), (3, 43, 1)]
 
 
 @pytest.mark.parametrize("Q,Hq,Hkv", WINDOW_SHAPES)
@@ -71,7 +72,7 @@ def test_window_shapes(pa, oracle, Q, Hq, Hkv, kv):
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 2), (16, 8, 2), (6, 10, 2), (16, 16, 2), (5, 8, 2), (8, 8, 2)])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 2), (16, 8, 2), (6, 10, 2), (16, 16, 2), (5, 8, 2), (8, 8, 2), (20, 16, 2)])
 @pytest.mark.parametrize("P", [2, 3, 7, 64, 1000])
 def test_window_partition_sweep(pa, oracle, kv, Q, Hq, Hkv, P):
     """Boundaries anywhere, including ones that leave a partition only the last tile of a sequence,
@@ -90,7 +91,7 @@ def test_window_one_sequence_cut_by_every_partition(pa, oracle):
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 2), (16, 4, 1), (16, 1, 1), (6, 10, 2), (16, 8, 1), (8, 4, 1), (5, 8, 2)])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 2), (16, 4, 1), (16, 1, 1), (6, 10, 2), (16, 8, 1), (8, 4, 1), (5, 8, 2), (16, 12, 1)])
 @pytest.mark.parametrize("P", [0, 1, 6])
 def test_window_mask_is_exact(pa, kv, Q, Hq, Hkv, P):
     """Window token j (logical position L - Q + j) has the key 16 (j + 1) e_0, every other token the
