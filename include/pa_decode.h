@@ -53,8 +53,9 @@
  * are read once for the whole batch, with the (sequence, head) pairs as matrix columns, instead
  * of once per sequence; the rest of every context is processed per sequence as usual and a merge
  * kernel joins the two by their log-sum-exps.  The promise is not checked on the device: block
- * ids of the prefix are taken from row 0 of block_tables.  Supported for plain decode
- * (q_len <= 1) with G <= 32.
+ * ids of the prefix are taken from row 0 of block_tables.  Supported for Q * G <= 32; in a
+ * multi-token call every query token must lie after the prefix (context_lens[b] >= prefix tokens
+ * + Q - 1).
  *
  * Sliding window (shape.window = W > 0; attention over the last W positions only, as in the
  * streaming encoder of the paper's Appendix A, Scenario D, whose per-stream cache is evicted in

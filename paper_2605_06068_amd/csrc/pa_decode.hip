@@ -202,10 +202,11 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->batch > kMaxBatch) return PA_ERR_UNSUPPORTED;  // the merge kernels index sequences by blockIdx.y
     if (shared_tiles(s) > 0) {
         // the per-sequence pass runs on the one-wave kernel (up to 32 columns), the prefix pass on the multi-wave one
-        if (query_len(s) > 1 || s->batch < 1 || columns(s) > 32) return PA_ERR_UNSUPPORTED;
+        if (s->batch < 1 || columns(s) > 32) return PA_ERR_UNSUPPORTED;
         // the merge of such calls reads rows of `out` back as float32
         if (s->out_dtype != PA_OUT_F32) return PA_ERR_UNSUPPORTED;
-        if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens) return PA_ERR_INVALID_ARG;
+        // every query token lies after the prefix
+        if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens + query_len(s) - 1) return PA_ERR_INVALID_ARG;
     }
     // sliding windows: not together with a shared prefix
     if (s->window > 0 && shared_tiles(s) > 0) return PA_ERR_UNSUPPORTED;
@@ -252,7 +253,9 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     if (plan->skip_tiles > 0) {
         // the prefix pass: columns are the (sequence, head of the group) pairs, 16 per wave, at most
         // kMaxColsMfma per workgroup, further column groups beyond that
-        const int cols = s->batch * (s->num_q_heads / s->num_kv_heads);
+        const int64_t cols64 = (int64_t)s->batch * columns(s);  // (sequence, query token, head of the group)
+        if (cols64 > INT32_MAX / 2) return PA_ERR_UNSUPPORTED;
+        const int cols = (int)cols64;
         const int group_cols = cols < kMaxColsMfma ? cols : kMaxColsMfma;
         const WideShape ws = wide_shape(group_cols, true);
         plan->prefix_waves = ws.nw;
@@ -263,7 +266,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         if (Pp > plan->skip_tiles) Pp = plan->skip_tiles;
         if (Pp < 1) Pp = 1;
         plan->Pp = (int32_t)Pp;
-        const size_t out_rows = (size_t)s->batch * s->num_q_heads;
+        const size_t out_rows = (size_t)s->batch * s->num_q_heads * query_len(s);
         plan->seq_lse_offset = plan->ws_bytes;
         plan->prefix_o_offset = plan->seq_lse_offset + pad(out_rows * sizeof(float));
         plan->prefix_lse_offset = plan->prefix_o_offset + pad((size_t)plan->Pp * out_rows * s->head_dim * sizeof(float));
@@ -415,7 +418,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         if (ev && hipEventRecord(ev->between, hs) != hipSuccess) { launched = false; return; }
 
         if (plan.skip_tiles > 0) {
-            const dim3 mgrid(p.Hq, p.B);
+            const dim3 mgrid(p.QH, p.B);
             hipLaunchKernelGGL((pa::merge_prefix_kernel<D>), mgrid, dim3(pa::kMergeWaves * pa::kWave), 0, hs, p);
         } else if (plan.P > 1) {
             const dim3 mgrid(p.QH, p.B < plan.P - 1 ? p.B : plan.P - 1);  // at most P - 1 sequences are cut
@@ -461,7 +464,8 @@ int32_t pa_split_plan(const pa_shape* shape, pa_kv_dtype kv_dtype, const int32_t
     int64_t T = 0;
     for (int32_t b = 0; b < shape->batch; ++b) {
         if (context_lens[b] > plan.max_ctx) return -(int32_t)PA_ERR_INVALID_ARG;
-        if (context_lens[b] < skip * pa::kTileTokens) return -(int32_t)PA_ERR_INVALID_ARG;  // shorter than the shared prefix
+        if (skip > 0 && context_lens[b] < skip * pa::kTileTokens + query_len(shape) - 1)
+            return -(int32_t)PA_ERR_INVALID_ARG;  // a query token inside the shared prefix
         T += pa::tiles_of(context_lens[b], sp);
     }
     const int32_t MB = shape->max_blocks_per_seq;

@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_many_kernel(const P
     });
 }
 
-// Merge kernel of shared-prefix calls.  One workgroup per (query head h, sequence b) combines
+// Merge kernel of shared-prefix calls.  One workgroup per (output row h of a sequence, sequence b) combines
 // every piece of that output row:
 //   - the Pp partials of the prefix pass (slot kp of prefix_o / prefix_lse), and
 //   - what the per-sequence pass produced over the rest of the context: nothing (the context ends
@@ -362,8 +362,8 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_prefix_kernel(const
     const int lane = threadIdx.x & (kWave - 1);
     const Span sp{p.skip_tiles, 0};
     const int P = p.P;
-    const int64_t rows = (int64_t)p.B * p.Hq;
-    const int64_t row = (int64_t)b * p.Hq + h;
+    const int64_t rows = (int64_t)p.B * p.QH;
+    const int64_t row = (int64_t)b * p.QH + h;
 
     // the sequence's own tiles (those after the prefix) inside the global tile sequence (every wave computes this)
     const int T = total_tiles(p.context_lens, p.B, lane, sp);
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_prefix_kernel(const
         const int kk = k_first + (s - p.Pp);
         const int lo = part_begin(kk, T, P), hi = part_begin(kk + 1, T, P);
         if (hi <= lo) return false;  // partitions without tiles wrote nothing
-        const int64_t slot = (int64_t)(2 * kk + ((kk == k_first && lo != cum) ? 1 : 0)) * p.Hq + h;
+        const int64_t slot = (int64_t)(2 * kk + ((kk == k_first && lo != cum) ? 1 : 0)) * p.QH + h;
         src = p.part_o + slot * D;
         lse = p.part_lse[slot];
         return true;

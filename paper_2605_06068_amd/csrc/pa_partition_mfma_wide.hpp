@@ -25,7 +25,8 @@
 // PREFIX mode is the pass over a prefix that every sequence of a decode batch shares (the same
 // physical blocks at the head of every block table).  The columns are then the (sequence, head)
 // pairs: to this kernel the batch is ONE sequence, the prefix, with one "query token" per real
-// sequence and no causal mask.  The prefix tiles are cut into Pp ranges, workgroup
+// sequence (or Q of them in a multi-token call: every query token lies after the prefix and sees
+// all of it) and no causal mask.  The prefix tiles are cut into Pp ranges, workgroup
 // (column group, KV head, range) leaves one partial result per column, and the prefix merge
 // kernel adds them to what the per-sequence pass computed over the rest of each context.
 #pragma once
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     const int col0 = (blockIdx.x / nparts / p.Hkv) * (kWaveCols * NW);
     const int G = p.G;
     const int B = PREFIX ? 1 : p.B;      // sequences as this kernel sees them
-    const int Q = PREFIX ? p.B : p.Q;    // query tokens per such sequence
+    const int Q = PREFIX ? p.B * p.Q : p.Q;  // query tokens per such sequence (prefix pass: those of all real sequences)
     const int ncols = Q * G;
     const int n = lane & 15;
     const int q4 = lane >> 4;
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
                     const float inv = l > 0.f ? vs / l : 0.f;
                     const float lse = l > 0.f ? st[ct].m + fast_log2(l) : kNegBig;
                     if (PREFIX) {
-                        const int64_t slot = (int64_t)k * ((int64_t)p.B * p.Hq) + col_row[ct];
+                        const int64_t slot = (int64_t)k * ((int64_t)p.B * p.QH) + col_row[ct];
                         if (q4 == 0) p.prefix_lse[slot] = lse;
                         store_partial_row(p.prefix_o + slot * D, st[ct], inv, q4);
                     } else if (whole) {

@@ -151,3 +151,25 @@ def test_shared_prefix_many_sequences(pa, oracle, B):
     b = W.make_batch("prefix-many", 550 + B, suffix_lens(6, B, B), 8, 2, 128, 16, W.KV_BF16, shared_prefix_blocks=6)
     for P in (0, 1, 9):
         check(pa, oracle, b, f"shared-prefix many-sequences P={P}", num_partitions=P)
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("D", [128, 64])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 2), (8, 4, 1), (2, 16, 1), (16, 2, 1), (3, 5, 1), (2, 2, 2), (16, 4, 2)])
+@pytest.mark.parametrize("B,prefix_blocks", [(1, 8), (5, 3), (20, 64), (9, 10)])
+def test_multi_token_calls_over_a_shared_prefix(pa, oracle, kv, D, Q, Hq, Hkv, B, prefix_blocks):
+    """Verification windows whose tokens all lie after the shared prefix (the shortest context ends
+    Q - 1 tokens after it): the prefix pass sees B * Q * G columns, the per-sequence pass is causal
+    inside the window, the merge joins them row by row."""
+    lens = [L + Q - 1 for L in suffix_lens(prefix_blocks, B, B + Q)]
+    b = W.make_batch("prefix-verify", 560 + 7 * B + Hq + Q, lens, Hq, Hkv, D, 16, kv, q_len=Q,
+                     shared_prefix_blocks=prefix_blocks)
+    print(f"[case] Q={Q} D={D}", flush=True)
+    got, dev = run_gpu(pa, b)
+    want = oracle.decode_batch(b)["out"]
+    flat = lambda a: a.reshape(a.shape[0], -1, a.shape[-1])
+    assert_parity(flat(got), flat(want), kv, "shared prefix, multi-token")
+    got3, _ = run_gpu(pa, b, num_partitions=3)
+    assert_parity(flat(got3), flat(want), kv, "shared prefix, multi-token, P=3")
+    plain, _ = run_gpu(pa, b, shared_prefix_blocks=0)
+    assert_parity(flat(got), flat(plain), kv, "against the call without a shared prefix")
