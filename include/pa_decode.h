@@ -112,7 +112,7 @@ typedef struct pa_shape {
                                    cached once for the whole batch) and every context is at least that long:
                                    those blocks are then read once for all sequences (see pa_decode) */
     int32_t out_dtype;          /* PA_OUT_F32 (0), or PA_OUT_BF16: out holds bf16, every element the float32 result
-                                   rounded to nearest even (not with a shared prefix) */
+                                   rounded to nearest even */
     int32_t window;             /* 0 = every query sees its whole past; W > 0 = sliding window: the query at
                                    position t sees tokens t-W+1 .. t only (see pa_decode) */
 } pa_shape;
@@ -149,7 +149,7 @@ int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, const int32_t
 /* Bytes of device workspace pa_decode needs for this shape: two partial results (normalised
  * output row + log-sum-exp per query head and query token) per partition, and 16 bytes per
  * sequence that tell the merge kernel whether and where the sequence was cut; with a shared prefix in
- * addition one partial result per range of the prefix and one log-sum-exp per output row.  0 when P == 1.  Returns 0 as well for
+ * addition one partial result per range of the prefix and one more per output row.  0 when P == 1.  Returns 0 as well for
  * an invalid shape (pa_decode then reports the error). */
 size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
 

@@ -70,7 +70,7 @@ struct Plan {
     int32_t Pp;               // partitions of the prefix tiles
     int32_t prefix_waves;     // waves per workgroup of the prefix pass
     int32_t prefix_groups;    // column groups of the prefix pass (16 * prefix_waves columns each)
-    size_t seq_lse_offset, prefix_o_offset, prefix_lse_offset;
+    size_t seq_o_offset, seq_lse_offset, prefix_o_offset, prefix_lse_offset;
 };
 
 int query_len(const pa_shape* s) { return s->q_len > 0 ? s->q_len : 1; }
@@ -203,8 +203,6 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (shared_tiles(s) > 0) {
         // the per-sequence pass runs on the one-wave kernel (up to 32 columns), the prefix pass on the multi-wave one
         if (s->batch < 1 || columns(s) > 32) return PA_ERR_UNSUPPORTED;
-        // the merge of such calls reads rows of `out` back as float32
-        if (s->out_dtype != PA_OUT_F32) return PA_ERR_UNSUPPORTED;
         // every query token lies after the prefix
         if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens + query_len(s) - 1) return PA_ERR_INVALID_ARG;
     }
@@ -249,7 +247,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     plan->ws_bytes = plan->P == 1 ? 0 : plan->desc_offset + pad((size_t)s->batch * 4 * sizeof(int32_t));
     plan->Pp = 0;
     plan->prefix_waves = plan->prefix_groups = 0;
-    plan->seq_lse_offset = plan->prefix_o_offset = plan->prefix_lse_offset = 0;
+    plan->seq_o_offset = plan->seq_lse_offset = plan->prefix_o_offset = plan->prefix_lse_offset = 0;
     if (plan->skip_tiles > 0) {
         // the prefix pass: columns are the (sequence, head of the group) pairs, 16 per wave, at most
         // kMaxColsMfma per workgroup, further column groups beyond that
@@ -267,7 +265,8 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         if (Pp < 1) Pp = 1;
         plan->Pp = (int32_t)Pp;
         const size_t out_rows = (size_t)s->batch * s->num_q_heads * query_len(s);
-        plan->seq_lse_offset = plan->ws_bytes;
+        plan->seq_o_offset = plan->ws_bytes;
+        plan->seq_lse_offset = plan->seq_o_offset + pad(out_rows * s->head_dim * sizeof(float));
         plan->prefix_o_offset = plan->seq_lse_offset + pad(out_rows * sizeof(float));
         plan->prefix_lse_offset = plan->prefix_o_offset + pad((size_t)plan->Pp * out_rows * s->head_dim * sizeof(float));
         plan->ws_bytes = plan->prefix_lse_offset + pad((size_t)plan->Pp * out_rows * sizeof(float));
@@ -396,6 +395,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.Pp = plan.Pp;
     if (plan.skip_tiles > 0) {
         char* ws = static_cast<char*>(workspace);
+        p.seq_o = reinterpret_cast<float*>(ws + plan.seq_o_offset);
         p.seq_lse = reinterpret_cast<float*>(ws + plan.seq_lse_offset);
         p.prefix_o = reinterpret_cast<float*>(ws + plan.prefix_o_offset);
         p.prefix_lse = reinterpret_cast<float*>(ws + plan.prefix_lse_offset);

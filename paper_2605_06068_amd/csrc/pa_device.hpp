@@ -38,9 +38,10 @@ struct Params {
     // and the same physical blocks; a pass of its own reads them once for all sequences
     int32_t skip_tiles;           // tiles of the shared prefix (0: no shared prefix)
     int32_t Pp;                   // partitions of the prefix tiles
-    float* seq_lse;               // [B, Hq]  log-sum-exp of the rows in `out` that still lack the prefix part
-    float* prefix_o;              // [Pp, B*Hq, D] normalised partial outputs over the prefix
-    float* prefix_lse;            // [Pp, B*Hq]
+    float* seq_o;                 // [B, QH, D] rows the per-sequence pass finished inside one partition: they still lack the prefix part
+    float* seq_lse;               // [B, QH]    their log-sum-exps
+    float* prefix_o;              // [Pp, B*QH, D] normalised partial outputs over the prefix
+    float* prefix_lse;            // [Pp, B*QH]
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

@@ -223,8 +223,7 @@ __global__ __launch_bounds__(64) void merge_rows_kernel(const Params p)
 // taken 256 at a time: thread t looks at piece t (address, log-sum-exp), the workgroup agrees on
 // the maximum and the weights, then wave w sums pieces w, w+4, ... with eight row loads in
 // flight, and the four sums are added through LDS.  `safe_row` is any row that is certainly
-// written (it stands in, with weight 0, for pieces that do not exist).  A piece may be the
-// row in `out` itself: every read has been consumed before the row is stored.
+// written (it stands in, with weight 0, for pieces that do not exist).
 constexpr int kMergeWaves = 4;
 
 template <int D, class Piece>
@@ -302,7 +301,7 @@ __device__ __forceinline__ void combine_pieces(const Params& p, int64_t out_elem
         }
         __syncthreads();  // s_row / s_w / s_red are reused by the next batch
     }
-    // add the four waves' sums; every read of a row in `out` has been consumed by now
+    // add the four waves' sums
 #pragma unroll
     for (int i = 0; i < V; ++i) s_acc[w][lane * V + i] = acc[i];
     __syncthreads();
@@ -352,7 +351,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_many_kernel(const P
 // every piece of that output row:
 //   - the Pp partials of the prefix pass (slot kp of prefix_o / prefix_lse), and
 //   - what the per-sequence pass produced over the rest of the context: nothing (the context ends
-//     with the prefix), or the row already in `out` with its log-sum-exp in seq_lse (the rest lies
+//     with the prefix), or the row in seq_o with its log-sum-exp in seq_lse (the rest lies
 //     inside one partition), or the partials of the partitions that cut it (slots as above).
 template <int D>
 __global__ __launch_bounds__(kMergeWaves * kWave) void merge_prefix_kernel(const Params p)
@@ -390,7 +389,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_prefix_kernel(const
             return true;
         }
         if (inside_one) {
-            src = p.out + row * D;
+            src = p.seq_o + row * D;
             lse = p.seq_lse[row];
             return true;
         }

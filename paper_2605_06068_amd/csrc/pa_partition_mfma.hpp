@@ -312,8 +312,11 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
                     // row with an "empty" log-sum-exp
                     const float inv = l > 0.f ? vs / l : 0.f;
                     const float lse = l > 0.f ? st[ct].m + fast_log2(l) : kNegBig;
-                    if (whole) {
-                        if (skip > 0 && q4 == 0) p.seq_lse[(int64_t)cc.b * p.QH + col_row[ct]] = lse;
+                    if (whole && skip > 0) {  // final but for the prefix part: to the workspace, for the prefix merge
+                        const int64_t row = (int64_t)cc.b * p.QH + col_row[ct];
+                        if (q4 == 0) p.seq_lse[row] = lse;
+                        store_partial_row(p.seq_o + row * D, st[ct], inv, q4);
+                    } else if (whole) {
                         store_final_row(p, ((int64_t)cc.b * p.QH + col_row[ct]) * D, st[ct], inv, q4);
                     } else {
                         const int64_t slot = ((int64_t)2 * k + (cc.b != first_b ? 1 : 0)) * p.QH + col_row[ct];

@@ -40,6 +40,9 @@ CASES = {
     "verification, one wave": lambda: W.make_batch("o4", 703, [600, 2, 90], 8, 2, 128, 16, W.KV_BF16, q_len=4),
     "verification, one wave, two column tiles": lambda: W.make_batch("o7", 706, [600, 2, 90, 33], 8, 2, 128, 16, W.KV_BF16, q_len=7),
     "verification, multi-wave": lambda: W.make_batch("o5", 704, [600, 3, 90, 0], 8, 2, 128, 16, W.KV_BF16, q_len=16),
+    "shared prefix": lambda: W.make_batch("o8", 707, [160, 161, 200, 700, 175], 8, 2, 128, 16, W.KV_BF16, shared_prefix_blocks=10),
+    "shared prefix, multi-token, fp8": lambda: W.make_batch("o9", 708, [180, 164, 200, 700], 8, 2, 128, 16, W.KV_FP8_E4M3, q_len=4,
+                                                            shared_prefix_blocks=10),
     "sliding window": lambda: W.make_batch("o6", 705, [700, 50, 1], 8, 2, 128, 16, W.KV_BF16, window=100),
     "reduced 8B-shaped batch": lambda: W.make_config(2, length_scale=0.25),
 }
