@@ -1,8 +1,9 @@
 // Pieces shared by the two matrix-core partition kernels (pa_partition_mfma.hpp: one wavefront per
-// (partition, KV head), up to 16 columns; pa_partition_mfma_wide.hpp: a workgroup of wavefronts,
-// 16 columns each): the geometry of a tile in LDS, the LDS-DMA load, the cursor over the global
-// tile sequence, and what one wavefront does with one tile of 32 tokens and 16 columns --
-// which blocks and rows to load, scores, online softmax, PV.  D = head_dim is 128 or 64.
+// (partition, KV head), up to 32 columns; pa_partition_mfma_wide.hpp: a workgroup of wavefronts,
+// 16 or 32 columns each): the geometry of a tile in LDS, the LDS-DMA load, the cursor over the
+// global tile sequence, and what one wavefront does with one tile of 32 tokens and one or two
+// tiles of 16 columns -- which blocks and rows to load, scores, online softmax, PV.  D = head_dim
+// is 128 or 64.
 //
 // LDS tile layout: row t (one token, 2 D bytes bf16 / D bytes fp8) at byte t*rowbytes; the 16-byte
 // piece holding dims [8c, 8c+8) (fp8: [16c, 16c+16)) sits at piece position c ^ (t mod pieces).

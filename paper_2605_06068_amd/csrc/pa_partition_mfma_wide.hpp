@@ -1,5 +1,6 @@
-// Partition kernel, matrix-core variant for more than 16 columns per KV head (multi-token
-// verification: q_len * G = 17 .. 128 (query token, query head) pairs).  A workgroup of NW
+// Partition kernel, matrix-core variant for many columns per KV head (multi-token verification,
+// wide groups: up to 128 (query token, query head) pairs per workgroup, further workgroups side by
+// side beyond that).  A workgroup of NW
 // wavefronts serves one (partition, KV head): the waves share ONE ring of K/V tiles in LDS, so
 // the cache is read from HBM once for all columns, and each wave computes its own NCT = 1 or 2
 // tiles of 16 columns (columns 16 NCT w .. 16 NCT (w + 1) - 1) exactly as the single-wave kernel
