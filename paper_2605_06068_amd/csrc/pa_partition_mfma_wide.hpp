@@ -227,56 +227,31 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     for (int t = 0; t < NSTAGE - 1; ++t)
         if (t < ntiles && issue(t)) ++q_age;
 
-    int stage = 0;
-    for (int tile = 0; tile < ntiles; ++tile) {
-        const bool seg_start = tile == 0 || cc.lt == 0;
-        // my loads of this tile have landed once at most the tiles issued after it are in flight; at
-        // a segment start the query rows (issued q_age tiles ago) must have landed as well
-        int later = min(kMaxLater, ntiles - 1 - tile);
-        if (seg_start && q_age < later) later = q_age;
-        wait_loads<PT, kMaxLater>(later);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // my LDS reads of the previous tile have returned
-        __builtin_amdgcn_s_barrier();
-        const int ahead = tile + NSTAGE - 1;
-        if (ahead < ntiles) {
-            int stg = stage + NSTAGE - 1;
-            if (stg >= NSTAGE) stg -= NSTAGE;
-            if (issue(stg)) ++q_age;
+    // what a wave does when tile `tile` (the compute cursor stands on it) begins a segment
+    auto begin_segment = [&](int tile) {
+        seg_first_lt = cc.lt;
+        if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is this workgroup's
+            const int cum = rs.t_lo + tile, end = cum + cc.nt;
+            write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
         }
-        const char* kbuf = smem + stage * kStageBytes;
-        const char* vbuf = kbuf + 2 * kSlabBytes;
-        if (!wave_active) {  // keeps loading and meeting the others at the barrier; nothing to compute
-            advance(cc, p.context_lens, B, sp);
-            stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
-            continue;
-        }
-
-        if (seg_start) {
-            seg_first_lt = cc.lt;
-            if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is this workgroup's
-                const int cum = rs.t_lo + tile, end = cum + cc.nt;
-                write_seq_desc(p.merge_desc, cc.b, end > rs.t_hi ? k + 1 : 0, cum, end, rs.T);
-            }
 #pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) {
-                st[ct].reset();
-                load_query_operand<D>(qslot + ct * 16 * QG::kRow, n, q4, col_ok[ct], qreg[ct]);
-            }
-            // refill the slot with the rows of the next segment of this range, if there is one
-            if (tile + (cc.nt - cc.lt) < ntiles) {
-                int nb = cc.b;
-                do {
-                    ++nb;
-                } while (nb < B - 1 && uniform_load(p.context_lens, nb) <= 0);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the slot has been read
-                issue_q(nb);
-                q_age = 0;
-            }
+        for (int ct = 0; ct < NCT; ++ct) {
+            st[ct].reset();
+            load_query_operand<D>(qslot + ct * 16 * QG::kRow, n, q4, col_ok[ct], qreg[ct]);
         }
-
-        f32x4 s0[NCT], s1[NCT];
-        qk_scores<D, KV, NCT>(kbuf, of, qreg, s0, s1);
-
+        // refill the slot with the rows of the next segment of this range, if there is one
+        if (tile + (cc.nt - cc.lt) < ntiles) {
+            int nb = cc.b;
+            do {
+                ++nb;
+            } while (nb < B - 1 && uniform_load(p.context_lens, nb) <= 0);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the slot has been read
+            issue_q(nb);
+            q_age = 0;
+        }
+    };
+    // softmax, PV and, at the end of a segment, the result of tile `tile` from its scores
+    auto finish_tile = [&](int tile, const char* vbuf, const f32x4 (&s0)[NCT], const f32x4 (&s1)[NCT]) {
         // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (where the causal
         // limits lie) and the tiles where the columns' sliding windows begin need the mask:
         // everywhere else every column sees the whole tile.
@@ -321,6 +296,31 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
                     }
                 }
             }
+        }
+    };
+
+    int stage = 0;
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const bool seg_start = tile == 0 || cc.lt == 0;
+        // my loads of this tile have landed once at most the tiles issued after it are in flight; at
+        // a segment start the query rows (issued q_age tiles ago) must have landed as well
+        int later = min(kMaxLater, ntiles - 1 - tile);
+        if (seg_start && q_age < later) later = q_age;
+        wait_loads<PT, kMaxLater>(later);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // my LDS reads of the previous tile have returned
+        __builtin_amdgcn_s_barrier();
+        const int ahead = tile + NSTAGE - 1;
+        if (ahead < ntiles) {
+            int stg = stage + NSTAGE - 1;
+            if (stg >= NSTAGE) stg -= NSTAGE;
+            if (issue(stg)) ++q_age;
+        }
+        const char* kbuf = smem + stage * kStageBytes;
+        if (wave_active) {  // a wave without columns keeps loading and meeting the others at the barrier
+            if (seg_start) begin_segment(tile);
+            f32x4 s0[NCT], s1[NCT];
+            qk_scores<D, KV, NCT>(kbuf, of, qreg, s0, s1);
+            finish_tile(tile, kbuf + 2 * kSlabBytes, s0, s1);
         }
         advance(cc, p.context_lens, B, sp);
         stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
