@@ -148,7 +148,7 @@ int32_t pa_split_plan(const pa_shape *shape, pa_kv_dtype kv_dtype, const int32_t
 
 /* Bytes of device workspace pa_decode needs for this shape: two partial results (normalised
  * output row + log-sum-exp per query head and query token) per partition, and 16 bytes per
- * sequence that tell the merge kernel whether and where the sequence was cut; with a shared prefix in
+ * sequence plus 4 per partition that tell the merge kernel whether and where a sequence was cut; with a shared prefix in
  * addition one partial result per range of the prefix and one more per output row.  0 when P == 1.  Returns 0 as well for
  * an invalid shape (pa_decode then reports the error). */
 size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);

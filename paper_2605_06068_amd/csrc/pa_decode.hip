@@ -65,6 +65,7 @@ struct Plan {
     int32_t max_ctx;    // resolved max context length
     size_t lse_offset;  // byte offset of the lse array inside the workspace
     size_t desc_offset; // byte offset of the merge descriptors
+    size_t cut_offset;  // byte offset of the list of sequences the partitions' starts cut
     size_t ws_bytes;
     // shared-prefix calls
     int32_t skip_tiles;       // tiles of the shared prefix (0: none)
@@ -245,7 +246,8 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     const auto pad = [](size_t n) { return (n + 255) / 256 * 256; };
     plan->lse_offset = pad(o_bytes);
     plan->desc_offset = plan->lse_offset + pad(rows * sizeof(float));
-    plan->ws_bytes = plan->P == 1 ? 0 : plan->desc_offset + pad((size_t)s->batch * 4 * sizeof(int32_t));
+    plan->cut_offset = plan->desc_offset + pad((size_t)s->batch * 4 * sizeof(int32_t));
+    plan->ws_bytes = plan->P == 1 ? 0 : plan->cut_offset + pad((size_t)plan->P * sizeof(int32_t));
     plan->Pp = 0;
     plan->prefix_waves = plan->prefix_groups = 0;
     plan->seq_o_offset = plan->seq_lse_offset = plan->prefix_o_offset = plan->prefix_lse_offset = 0;
@@ -381,6 +383,9 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.part_o = plan.P > 1 ? static_cast<float*>(workspace) : nullptr;
     p.part_lse = plan.P > 1 ? reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.lse_offset) : nullptr;
     p.merge_desc = plan.P > 1 ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.desc_offset) : nullptr;
+    // batches with at least as many sequences as boundaries: the merge looks its sequences up by boundary
+    p.cut_list = (plan.P > 1 && shape->batch >= plan.P - 1)
+                     ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.cut_offset) : nullptr;
     p.trace_blocks = trace ? trace_blocks : nullptr;
     p.scale_log2 = scale * pa::kLog2e;
     p.B = shape->batch;

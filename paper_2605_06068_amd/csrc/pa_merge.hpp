@@ -36,6 +36,20 @@ __device__ __forceinline__ int nth_cut_sequence(const int32_t* desc, int B, int 
     return -1;
 }
 
+// The sequence merge slot y works on, or -1.  Large batches come with a list of the sequences that
+// the partitions' starts cut (cut_list[k] for boundary k = y + 1): the slot takes the sequence its
+// boundary cuts if that is the first boundary inside it (a sequence cut several times is merged
+// once).  Small batches (one or two 64-lane scans) look for the y-th cut sequence instead.  All
+// 64 lanes must call; the result is wave-uniform.
+__device__ __forceinline__ int slot_sequence(const Params& p, int y, int lane)
+{
+    if (p.cut_list == nullptr) return nth_cut_sequence(p.merge_desc, p.B, y, lane);
+    const int k = y + 1;
+    const int b = uniform_load(p.cut_list, k);
+    if (b < 0) return -1;
+    return uniform_load(p.merge_desc, 4 * (int64_t)b) == k ? b : -1;
+}
+
 template <int D>
 __global__ __launch_bounds__(64) void merge_kernel(const Params p)
 {
@@ -47,7 +61,7 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
     const int P = p.P;
 
     // what the partition kernel left about the sequences: see write_seq_desc
-    const int b = nth_cut_sequence(p.merge_desc, p.B, blockIdx.y, lane);
+    const int b = slot_sequence(p, blockIdx.y, lane);
     if (b < 0) return;  // fewer sequences were cut than the grid has room for
     const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
     const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),
@@ -140,7 +154,7 @@ __global__ __launch_bounds__(64) void merge_rows_kernel(const Params p)
     constexpr int V4 = D / kLanesPerRow / 4;                  // float4s per lane: 2 (head_dim 128) or 1 (64)
     const int lane = threadIdx.x;
     const int P = p.P;
-    const int b = nth_cut_sequence(p.merge_desc, p.B, blockIdx.y, lane);
+    const int b = slot_sequence(p, blockIdx.y, lane);
     if (b < 0) return;  // fewer sequences were cut than the grid has room for
     const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
     const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),
@@ -326,7 +340,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_many_kernel(const P
 {
     const int h = blockIdx.x;
     const int P = p.P;
-    const int b = nth_cut_sequence(p.merge_desc, p.B, blockIdx.y, threadIdx.x & (kWave - 1));
+    const int b = slot_sequence(p, blockIdx.y, threadIdx.x & (kWave - 1));
     if (b < 0) return;  // fewer sequences were cut than the grid has room for (the same for every thread)
     const int j = uniform_load(p.merge_desc, 4 * (int64_t)b);
     const int cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1), end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2),

@@ -111,6 +111,29 @@ __device__ __forceinline__ void advance(Cursor& c, const int32_t* context_lens, 
     c.ft = first_tile(c.L, sp);
 }
 
+// Output rows of empty contexts are zero.  The sequences are dealt out over the partitions (slice k of
+// P); the calling wave looks at its slice 64 sequences at a time and zero-fills, all lanes together,
+// the rows of KV head g's group for every empty one (the wave of KV head 0 also notes that there
+// is nothing to merge).  All 64 lanes must call.
+__device__ __forceinline__ void zero_rows_of_empty_contexts(const Params& p, int k, int g, int B, int Q, int D, int lane)
+{
+    const int per = (B + p.P - 1) / p.P;
+    const int b_end = min(B, (k + 1) * per);
+    for (int b0 = k * per; b0 < b_end; b0 += kWave) {
+        const int b = b0 + lane;
+        unsigned long long empty = __ballot(b < b_end && p.context_lens[b] <= 0);
+        while (empty != 0ull) {
+            const int bb = b0 + __ffsll((long long)empty) - 1;
+            empty &= empty - 1ull;
+            for (int i = 0; i < Q; ++i) {
+                const int64_t row = ((int64_t)bb * p.QH + (int64_t)i * p.Hq + g * p.G) * D;
+                for (int e = 4 * lane; e < p.G * D; e += 4 * kWave) store_out4(p, row + e, 0.f, 0.f, 0.f, 0.f);
+            }
+            if (g == 0 && p.merge_desc != nullptr && lane == 0) write_seq_desc(p.merge_desc, bb, 0, 0, 0, 0);
+        }
+    }
+}
+
 // ---- one tile (two KV blocks) of a sequence: what to load ---------------------------------------
 // Per block of the tile: its physical id and the rows [lo, hi) that hold tokens some query can
 // see.  Every other row (past the context, before the earliest sliding window) may hold anything,

@@ -116,19 +116,10 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     } else {
         rs = find_range(p.context_lens, B, k, p.P, lane, sp);
     }
-    if (!PREFIX && k == 0 && w == 0 && col0 == 0) {  // empty contexts: their output rows are zero
-        for (int b0 = 0; b0 < B; b0 += kWave) {
-            const int b = b0 + lane;
-            if (b < B && p.context_lens[b] <= 0) {
-                for (int i = 0; i < Q; ++i) {
-                    const int64_t row = ((int64_t)b * p.QH + (int64_t)i * p.Hq + g * G) * D;
-                    for (int e = 0; e < G * D; ++e) store_out1(p, row + e, 0.f);
-                }
-                if (g == 0 && p.merge_desc != nullptr) write_seq_desc(p.merge_desc, b, 0, 0, 0, 0);
-            }
-        }
-    }
+    if (!PREFIX && w == 0 && col0 == 0) zero_rows_of_empty_contexts(p, k, g, B, Q, D, lane);
     const bool describes = !PREFIX && g == 0 && w == 0 && col0 == 0 && p.merge_desc != nullptr;  // tells the merge about its sequences
+    if (describes && p.cut_list != nullptr && lane == 0)  // does my range start inside a sequence, and which
+        p.cut_list[k] = (rs.t_lo < rs.t_hi && rs.t_lo > rs.cum) ? rs.b : -1;
     if (rs.t_lo >= rs.t_hi) return;  // the same for every wave of the workgroup
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;

@@ -132,12 +132,30 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
         }
         return r;
     }
-    r.T = __builtin_amdgcn_readfirstlane(total_tiles(context_lens, B, lane, sp));
+    // First pass: the total, and on the way the running total at the end of every group of 16 chunks
+    // (1024 sequences), kept by lane `group` (a batch has at most 64 groups).  Second pass: only the
+    // group that holds tile t_lo is searched chunk by chunk.
+    constexpr int kGroupChunks = 16;
+    int sum = 0, running = 0, group_end = 0;
+    const int nchunks = (B + kWave - 1) / kWave;
+    for (int c = 0; c < nchunks; ++c) {
+        const int b = c * kWave + lane;
+        sum += b < B ? tiles_of(context_lens[b], sp) : 0;
+        if ((c & (kGroupChunks - 1)) == kGroupChunks - 1 || c == nchunks - 1) {
+            running += wave_sum(sum);
+            sum = 0;
+            if (lane == c / kGroupChunks) group_end = running;
+        }
+    }
+    r.T = __builtin_amdgcn_readfirstlane(running);
     r.t_lo = part_begin(k, r.T, P);
     r.t_hi = part_begin(k + 1, r.T, P);
     if (r.t_lo >= r.t_hi) return r;
-    int carry = 0;
-    for (int b0 = 0; b0 < B; b0 += kWave) {
+    const int ngroups = (nchunks + kGroupChunks - 1) / kGroupChunks;
+    const unsigned long long in_group = __ballot(lane < ngroups && group_end > r.t_lo);
+    const int group = __ffsll((long long)in_group) - 1;  // exists: t_lo < T
+    int carry = group > 0 ? __shfl(group_end, group - 1, kWave) : 0;
+    for (int b0 = group * kGroupChunks * kWave; b0 < B; b0 += kWave) {
         const int b = b0 + lane;
         const int L = b < B ? context_lens[b] : 0;
         const int n = tiles_of(L, sp);

@@ -268,3 +268,23 @@ def test_profile_entry_reports_kernel_times(pa):
     dev = pa.DeviceBatch(b)
     part_ms, merge_ms = pa.pa_decode_profile(*dev.args(), shape=dev.shape, workspace=dev.workspace, steps=5)
     assert part_ms > 0 and merge_ms >= 0
+
+
+@pytest.mark.parametrize("B,hi,Hq,Hkv", [(5000, 40, 8, 2), (20000, 9, 4, 1), (3000, 300, 32, 8)])
+def test_thousands_of_sequences(pa, oracle, B, hi, Hq, Hkv):
+    """Batches far larger than a wave: the search for a partition's first sequence goes through groups
+    of 1024 sequences, the zero rows of empty contexts are dealt out over all partitions, and the
+    merge finds its sequences by boundary.  The oracle checks a seeded sample of rows, every empty
+    context must give exact zeros."""
+    rng = np.random.default_rng(B)
+    lens = rng.integers(0, hi, size=B)
+    lens[rng.random(B) < 0.1] = 0
+    b = W.make_batch("thousands", 800 + B % 97, lens.tolist(), Hq, Hkv, 128, 16, W.KV_BF16)
+    for P in (0, 37):
+        got, dev = run_gpu(pa, b, num_partitions=P)
+        assert np.isfinite(got).all()
+        assert np.all(got[lens == 0] == 0)
+        rows = [(int(s), int(rng.integers(0, Hq))) for s in rng.integers(0, B, size=300)]
+        want = oracle.decode_batch(b, rows=rows)["out"]
+        sel = np.stack([got[r] for r in rows])
+        assert_parity(sel[:, None, :], want[:, None, :], b.kv_dtype, f"B={B} P={P}")
