@@ -372,28 +372,30 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_prefix_kernel(const
 {
     const int h = blockIdx.x;
     const int b = blockIdx.y;
-    const int lane = threadIdx.x & (kWave - 1);
     const Span sp{p.skip_tiles, 0};
     const int P = p.P;
     const int64_t rows = (int64_t)p.B * p.QH;
     const int64_t row = (int64_t)b * p.QH + h;
 
-    // the sequence's own tiles (those after the prefix) inside the global tile sequence (every wave computes this)
-    const int T = total_tiles(p.context_lens, p.B, lane, sp);
-    int before = 0;
-    for (int b0 = 0; b0 < b; b0 += kWave) {
-        const int bb = b0 + lane;
-        before += bb < b ? tiles_of(p.context_lens[bb], sp) : 0;
-    }
-    const int cum = wave_sum(before);
-    const int nb = tiles_of(p.context_lens[b], sp);
-    int k_first = 0, nrest = 0;
+    // The sequence's own tiles (those after the prefix): none (the context ends with the prefix), or
+    // what the per-sequence pass noted about them (write_seq_desc: j = 0, they lie inside one
+    // partition and the row waits in seq_o; else j is the first boundary inside them, cum and end
+    // their place in the global sequence of own tiles).  With a single partition nothing is noted
+    // and nothing is cut.
+    const int nb = tiles_of(uniform_load(p.context_lens, b), sp);
+    int k_first = 0, nrest = 0, cum = 0, T = 0;
     bool inside_one = false;
     if (nb > 0) {
-        k_first = part_of(cum, T, P);
-        const int k_last = part_of(cum + nb - 1, T, P);
-        inside_one = k_first == k_last;
-        nrest = inside_one ? 1 : k_last - k_first + 1;
+        const int j = p.merge_desc != nullptr ? uniform_load(p.merge_desc, 4 * (int64_t)b) : 0;
+        inside_one = j == 0;
+        nrest = 1;
+        if (!inside_one) {
+            cum = uniform_load(p.merge_desc, 4 * (int64_t)b + 1);
+            const int end_b = uniform_load(p.merge_desc, 4 * (int64_t)b + 2);
+            T = uniform_load(p.merge_desc, 4 * (int64_t)b + 3);
+            k_first = j - 1;
+            nrest = part_of(end_b - 1, T, P) - k_first + 1;
+        }
     }
     // prefix range 0 of this row is always written and finite
     combine_pieces<D>(p, row * D, p.Pp + nrest, p.prefix_o + row * D, [&](int s, const float*& src, float& lse) {
