@@ -138,14 +138,16 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     constexpr int kGroupChunks = 16;
     int sum = 0, running = 0, group_end = 0;
     const int nchunks = (B + kWave - 1) / kWave;
-    for (int c = 0; c < nchunks; ++c) {
-        const int b = c * kWave + lane;
-        sum += b < B ? tiles_of(context_lens[b], sp) : 0;
-        if ((c & (kGroupChunks - 1)) == kGroupChunks - 1 || c == nchunks - 1) {
-            running += wave_sum(sum);
-            sum = 0;
-            if (lane == c / kGroupChunks) group_end = running;
+    for (int c0 = 0; c0 < nchunks; c0 += kGroupChunks) {
+        const int c1 = min(c0 + kGroupChunks, nchunks);
+#pragma unroll 4
+        for (int c = c0; c < c1; ++c) {  // independent loads: several in flight
+            const int b = c * kWave + lane;
+            sum += b < B ? tiles_of(context_lens[b], sp) : 0;
         }
+        running += wave_sum(sum);
+        sum = 0;
+        if (lane == c0 / kGroupChunks) group_end = running;
     }
     r.T = __builtin_amdgcn_readfirstlane(running);
     r.t_lo = part_begin(k, r.T, P);
