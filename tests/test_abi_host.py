@@ -247,3 +247,25 @@ def test_head_dim_64_takes_every_kind_of_call(extra, kv):
     s = shape(head_dim=64, **extra)
     assert pa.pa_num_partitions(s, kv) >= 1
     assert pa.pa_kernel_variant(s, kv) in ("mfma", "mfma-wide")
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""        # no result line for a run that did not happen
+
+
+def test_missing_library_is_an_error_not_a_fallback(tmp_path, monkeypatch):
+    """With no loadable library the binding raises: there is no other path to fall back to."""
+    bogus = tmp_path / "libpa_decode.so"
+    bogus.write_bytes(b"not a shared object")
+    monkeypatch.setattr(pa, "_lib", None)
+    monkeypatch.setattr(pa, "LIB_PATH", str(bogus))
+    with pytest.raises(OSError):
+        pa.lib()
+    with pytest.raises(OSError):
+        pa.pa_num_partitions(shape(), pa.PA_KV_BF16)
