@@ -292,6 +292,16 @@ __device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets
     }
 }
 
+// Do the softmax weights enter the PV product with their rounding remainder (two bf16 numbers per
+// weight) or as one bf16 number?  The remainder is kept where it is free: bf16 KV in a wave with one
+// 16-column tile, which waits for memory either way (plain decode above all).  It is dropped where
+// the second matrix instruction per operand costs time: fp8 KV (the weights keep 8 significant bits
+// against the 4 of the values they multiply; 70B-head-shaped batch 365 -> 343 us), waves with two
+// column tiles and the multi-wave kernel (16 query tokens on long contexts 450 -> 407 us, the
+// shared-prefix pass 53 -> 48 us per step).  The error this leaves is at most 2^-9 max|v| and in
+// practice a few 1e-3, inside the 1e-2 the method is held to.
+constexpr bool p_has_low_part(int kv, int nct, bool multi_wave) { return kv == KV_BF16 && nct == 1 && !multi_wave; }
+
 // Online softmax state of one column (replicated over the four lanes that hold its tokens) and
 // the unnormalised output accumulators out^T[dim, column].
 template <int D>
@@ -311,10 +321,11 @@ struct ColumnState {
 // Online softmax step (log2 domain) on the tile's scores.  The lane's tokens are t0 + {0..3} and
 // t0 + 16 + {0..3}; with MASKED the column sees only tokens low <= t < lim (the end of the context,
 // the causal limit of a multi-token call, the start of a sliding window); without it the whole tile.
-// Leaves the P^T operand as a bf16 pair (high part + rounding remainder: 16 significant bits, so
-// the weights lose nothing that matters against the fp32 accumulation); the PV product uses the
-// remainder only for bf16 KV.
-template <bool MASKED, int D>
+// Leaves the P^T operand in bf16.  With P_LO it is a pair, high part + rounding remainder (16
+// significant bits: the weights lose nothing that matters against the fp32 accumulation) and the PV
+// product costs two matrix instructions per operand; without, the weights enter at bf16 precision
+// (relative rounding error <= 2^-9 each, unbiased) and pb_lo is left alone.  See p_has_low_part().
+template <bool MASKED, int D, bool P_LO>
 __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1, float qs, int t0, int lim, int low,
                                                ColumnState<D>& st, bf16x8& pb, bf16x8& pb_lo)
 {
@@ -346,13 +357,13 @@ __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1,
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         pb[r] = (__bf16)x[r];
-        pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
+        if (P_LO) pb_lo[r] = (__bf16)(x[r] - (float)pb[r]);
     }
 }
 
 // out^T[dim, column] += V^T . P^T for NCT tiles of 16 columns; the V^T operand is read (and, fp8,
 // converted) once for all of them
-template <int D, int KV, int NCT>
+template <int D, int KV, int NCT, bool P_LO>
 __device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOffsets<D, KV>& of, const bf16x8 (&pb)[NCT],
                                               const bf16x8 (&pb_lo)[NCT], ColumnState<D> (&st)[NCT])
 {
@@ -371,8 +382,7 @@ __device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOff
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) {
             st[ct].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[ct], st[ct].acc[dt], 0, 0, 0);
-            // fp8 KV: the weights stay at bf16 precision (8 bits against the 4 of the values they multiply)
-            if (KV == KV_BF16)
+            if (P_LO)
                 st[ct].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb_lo[ct], st[ct].acc[dt], 0, 0, 0);
         }
     }

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "ring depth");
     static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16 || CPAD == 32, "padded column count");
     constexpr int NCT = CPAD > 16 ? CPAD / 16 : 1;  // MFMA column tiles
+    constexpr bool P_LO = p_has_low_part(KV, NCT, false);
     using Geo = KvGeom<D, KV>;
     using QG = QGeom<D>;
     constexpr int kSlabBytes = Geo::kSlab;
@@ -280,9 +281,9 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             const int lim = cc.L - col_back[ct];
             const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
             if (unmasked)
-                online_softmax<false>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+                online_softmax<false, D, P_LO>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
             else
-                online_softmax<true>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+                online_softmax<true, D, P_LO>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
         }
 
         // V of this tile landed (query rows just issued are newer and may stay in flight)
@@ -290,7 +291,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             wait_tile<kQLoads, kDmaPerTile, NSTAGE - 1>(later);
         else
             wait_tile<0, kDmaPerTile, NSTAGE - 1>(later);
-        pv_accumulate<D, KV, NCT>(vbuf, of, pb, pb_lo, st);
+        pv_accumulate<D, KV, NCT, P_LO>(vbuf, of, pb, pb_lo, st);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {

@@ -70,6 +70,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     static_assert(NW == 2 || NW == 4 || NW == 8, "waves per workgroup");
     static_assert(NCT == 1 || NCT == 2, "MFMA column tiles per wave");
     constexpr int kWaveCols = 16 * NCT;  // columns one wave computes
+    constexpr bool P_LO = p_has_low_part(KV, NCT, true);
     static_assert(NSTAGE >= 3, "the ring holds the tile in use, the one being refilled and at least one in flight");
     using Geo = KvGeom<D, KV>;
     using QG = QGeom<D>;
@@ -256,12 +257,12 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
             const int lim = cc.L - col_back[ct];
             const int low = p.window > 0 ? lim - p.window : INT32_MIN;  // first token the column's window holds
             if (unmasked)
-                online_softmax<false>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+                online_softmax<false, D, P_LO>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
             else
-                online_softmax<true>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
+                online_softmax<true, D, P_LO>(s0[ct], s1[ct], qs, t0, lim, low, st[ct], pb[ct], pb_lo[ct]);
         }
 
-        pv_accumulate<D, KV, NCT>(vbuf, of, pb, pb_lo, st);
+        pv_accumulate<D, KV, NCT, P_LO>(vbuf, of, pb, pb_lo, st);
 
         // ---- segment end: finish the row sums, normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {

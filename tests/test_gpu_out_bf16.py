@@ -61,9 +61,12 @@ def test_bf16_output_is_the_rounded_float32_output(pa, oracle, name, P):
     want = oracle.decode_batch(b)["out"]
     flat = lambda a: a.reshape(a.shape[0], -1, a.shape[-1])
     assert np.isfinite(got).all()
-    # half a bf16 ulp of the value on top of what the float32 result of the same path may be off by
-    # (bf16 KV: next to nothing; fp8 KV: its softmax weights enter the PV product at bf16 precision)
-    slack = 1e-5 if b.kv_dtype == W.KV_BF16 else 1e-2
+    # half a bf16 ulp of the value on top of what the float32 result of the same path may be off by:
+    # next to nothing where the softmax weights enter the PV product with their rounding remainder
+    # (bf16 KV, up to 16 columns, no shared prefix), the path's own bar where they enter as one bf16 number
+    columns = b.q_len * (b.num_q_heads // b.num_kv_heads)
+    full_weights = b.kv_dtype == W.KV_BF16 and columns <= 16 and b.shared_prefix_blocks == 0
+    slack = 1e-5 if full_weights else 1e-2
     assert np.all(np.abs(got.astype(np.float64) - want) <= np.abs(want) / 256 + slack)
     err = errors(flat(got), flat(want))
     assert err[1] <= BF16_REL_L2
