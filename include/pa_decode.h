@@ -168,6 +168,11 @@ size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
  *   stream           hipStream_t
  *
  * The result is deterministic run to run (no floating-point atomics).
+ * Arithmetic: scores, softmax and accumulation in float32.  The softmax weights enter the PV
+ * product with 16 significant bits for PA_KV_BF16 calls with q_len * G <= 16 and no shared
+ * prefix (result within ~1e-5 of the exact one for values of unit size), with 8 (one bf16
+ * number, relative rounding error <= 2^-9 per weight) for every other call: result within
+ * 2^-9 * max|v| of the exact one for the dequantised values.
  */
 pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                     const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,
