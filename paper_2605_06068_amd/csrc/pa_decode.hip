@@ -83,9 +83,9 @@ int shared_tiles(const pa_shape* s) { return s->shared_prefix_blocks / 2; }
 // columns of the score matrix per KV head: (query token, query head of the group) pairs
 int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
 
-// The kernels cover head_dim 64 and 128 and up to 128 columns (query tokens x heads of a group)
-// (narrow groups are padded inside the 16-column tile: the kernel is bound by the KV traffic, and
-// runs at the same speed for 1 column as for 16).
+// Padded column count of the one-wave kernel for `cols` (query tokens x heads of a group) columns.
+// Narrow groups are padded inside the 16-column tile: the kernel is bound by the KV traffic, and
+// runs at the same speed for 1 column as for 16; 17..32 columns are two such tiles.
 int mfma_col_pad(int cols) { return cols <= 4 ? 4 : (cols <= 8 ? 8 : (cols <= 16 ? 16 : 32)); }
 
 // Shape of a workgroup of the multi-wave kernel: waves, and MFMA column tiles (16 columns) per
