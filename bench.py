@@ -156,13 +156,21 @@ def main():
     merge_ms /= reps * n_pools
 
     gbps = kv_bytes / (ms_per_step * 1e-3) / 1e9
+    n_layers = 80 if batch.num_q_heads >= 64 else 32  # 70B-shaped heads, else 8B-shaped
+    tokens_read = kv_bytes / (batch.num_kv_heads * batch.head_dim * 2 * batch.kv_elem_bytes)  # tokens whose K and V the step reads
     part_gbps = kv_bytes / (part_ms * 1e-3) / 1e9
     result = {
         "metric": METRIC,
         "value": round(gbps, 2),
         "unit": "GB/s",
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
-        "tokens_per_s": round(batch.batch / (ms_per_step * 1e-3), 1),
+        "tokens_per_s": round(batch.batch / (ms_per_step * 1e-3), 1),  # attention-layer tokens/s: sequences per step / step time
+        # the same divided over the layers of a model of this head shape: an upper bound from attention alone
+        "model_equivalent_tokens_per_s": {"n_layers": n_layers, "value": round(batch.batch / (n_layers * ms_per_step * 1e-3), 1),
+                                          "note": "attention only, no other layer counted"},
+        # 2 flop per multiply-add, q.K and P.V, every query row against every token read: far below any matrix peak
+        "attention_tflops": round(4.0 * batch.head_dim * batch.num_q_heads * args.q_len * tokens_read
+                                  / (ms_per_step * 1e-3) / 1e12, 2),
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
