@@ -47,7 +47,7 @@ _lib = None
 
 def lib() -> ctypes.CDLL:
     """Open the in-tree library.  It is built by ``paper_2605_06068_amd.build.build()`` (hipcc);
-    when no build exists yet this builds it once.  Raises if that is impossible."""
+    when the library has not been built yet, it is compiled once here.  Raises if that is impossible."""
     global _lib
     if _lib is not None:
         return _lib
