@@ -270,12 +270,12 @@ def test_profile_entry_reports_kernel_times(pa):
     assert part_ms > 0 and merge_ms >= 0
 
 
-@pytest.mark.parametrize("B,hi,Hq,Hkv", [(5000, 40, 8, 2), (20000, 9, 4, 1), (3000, 300, 32, 8)])
+@pytest.mark.parametrize("B,hi,Hq,Hkv", [(5000, 40, 8, 2), (20000, 9, 4, 1), (3000, 300, 32, 8), (65535, 4, 8, 2)])
 def test_thousands_of_sequences(pa, oracle, B, hi, Hq, Hkv):
     """Batches far larger than a wave: the search for a partition's first sequence goes through groups
     of 1024 sequences, the zero rows of empty contexts are dealt out over all partitions, and the
     merge finds its sequences by boundary.  The oracle checks a seeded sample of rows, every empty
-    context must give exact zeros."""
+    context must give exact zeros.  The last case is the largest batch the interface takes."""
     rng = np.random.default_rng(B)
     lens = rng.integers(0, hi, size=B)
     lens[rng.random(B) < 0.1] = 0
