@@ -288,3 +288,15 @@ def test_thousands_of_sequences(pa, oracle, B, hi, Hq, Hkv):
         want = oracle.decode_batch(b, rows=rows)["out"]
         sel = np.stack([got[r] for r in rows])
         assert_parity(sel[:, None, :], want[:, None, :], b.kv_dtype, f"B={B} P={P}")
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_one_very_long_context_beside_short_ones(pa, oracle, kv):
+    """300,000 tokens in one sequence (18,750 table entries), cut by nearly every partition, next to
+    a 17-token and a 100,000-token one; the oracle checks every row."""
+    lens = [300_000, 17, 100_000]
+    b = W.make_batch("long-one", 812, lens, 8, 2, 128, 16, kv)
+    got, dev = run_gpu(pa, b)
+    want = oracle.decode_batch(b)["out"]
+    assert_parity(got, want, kv, "very long context")
+    assert pa.pa_num_partitions(dev.shape, dev.kv_dtype) > 100
