@@ -269,3 +269,18 @@ def test_missing_library_is_an_error_not_a_fallback(tmp_path, monkeypatch):
         pa.lib()
     with pytest.raises(OSError):
         pa.pa_num_partitions(shape(), pa.PA_KV_BF16)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 and as C++11, with nothing else included."""
+    import shutil
+    import subprocess
+
+    if shutil.which("gcc") is None or shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "pa_decode.h"\nint main(void) { pa_shape s; (void)s; return (int)sizeof(s) == 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", str(src)], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", "-x", "c++", str(src)],
+                   check=True)
