@@ -52,13 +52,19 @@ def parse_args():
 
 def recorded_traffic(workload_name: str):
     """HBM bytes per launch of the partition kernel, from the committed counter summary
-    (profiles/partition_<workload>.txt: FETCH_SIZE and WRITE_SIZE, scaled by what the same
+    (profiles/partition_<workload>.txt, partition_wide_<workload>.txt or prefix_<workload>.txt, the
+    workload named as in this run's config: FETCH_SIZE and WRITE_SIZE, scaled by what the same
     counters read for a copy of known size).  None when there is no summary for this workload or
     the kernel sources changed since the counters were taken."""
     from paper_2605_06068_amd import build as pa_build
 
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"partition_{workload_name}.txt")
-    if not os.path.exists(path):
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles")
+    path = None
+    for prefix in ("partition", "partition_wide", "prefix"):  # one-wave kernel, multi-wave kernel, shared-prefix pass
+        cand = os.path.join(here, f"{prefix}_{workload_name}.txt")
+        if os.path.exists(cand):
+            path = cand
+    if path is None:
         return None
     kv = {}
     with open(path) as fh:
@@ -66,7 +72,7 @@ def recorded_traffic(workload_name: str):
             if ":" in line and not line.startswith("#"):
                 k, v = line.split(":", 1)
                 kv[k.strip()] = v.strip()
-    if kv.get("kernel_source_sha256") != pa_build.source_digest():
+    if kv.get("kernel_source_sha256") != pa_build.source_digest() or kv.get("workload") != workload_name:
         return None
     try:
         return int(float(kv["traffic_bytes_per_launch"]))
@@ -156,6 +162,7 @@ def main():
     merge_ms /= reps * n_pools
 
     gbps = kv_bytes / (ms_per_step * 1e-3) / 1e9
+    workload = batch.name + (f"_qlen{args.q_len}" if args.q_len > 1 else "") + (f"_window{args.window}" if args.window > 0 else "")
     n_layers = 80 if batch.num_q_heads >= 64 else 32  # 70B-shaped heads, else 8B-shaped
     tokens_read = kv_bytes / (batch.num_kv_heads * batch.head_dim * 2 * batch.kv_elem_bytes)  # tokens whose K and V the step reads
     part_gbps = kv_bytes / (part_ms * 1e-3) / 1e9
@@ -182,8 +189,7 @@ def main():
         "dtype": "bf16" if batch.kv_dtype == W.KV_BF16 else "fp8_e4m3",
         "data": "synthetic",
         "config": {
-            "workload": batch.name + (f"_qlen{args.q_len}" if args.q_len > 1 else "")
-            + (f"_window{args.window}" if args.window > 0 else ""),
+            "workload": workload,
             "q_len": args.q_len, "window": args.window,
             "batch": batch.batch, "num_q_heads": batch.num_q_heads,
             "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "block_size": batch.block_size,
@@ -194,7 +200,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "kernel": "partition", "achieved": round(part_gbps, 2), "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": round(part_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(batch.name),
+            "unit": "GB/s", "frac": round(part_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(workload),
             "partition_ms": round(part_ms, 5), "merge_ms": round(merge_ms, 5),
         },
     }

@@ -284,3 +284,19 @@ def test_header_is_plain_c(tmp_path):
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", str(src)], check=True)
     subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", "-x", "c++", str(src)],
                    check=True)
+
+
+def test_bench_reads_counters_only_for_the_workload_it_ran():
+    """The recorded HBM traffic belongs to one kernel on one workload: a run with other query
+    lengths, windows or head shapes must not pick up the plain run's figure."""
+    import sys
+
+    sys.path.insert(0, ROOT)
+    import bench
+
+    base = "llama3_8b_b64_ctx512-4096_bf16"
+    assert bench.recorded_traffic(base + "_qlen7") is None
+    assert bench.recorded_traffic(base + "_window5") is None
+    assert bench.recorded_traffic("no_such_workload") is None
+    got = bench.recorded_traffic(base)
+    assert got is None or got > 577_638_400  # when the summary is current: at least the KV bytes of that batch
