@@ -3,7 +3,12 @@
  *
  * TEST INFRASTRUCTURE, not a product path: only the tests, the smoke check and the
  * benchmark's CPU-baseline leg may build or call this file.  It shares no code with
- * the HIP library and knows nothing about tiles, splits or online softmax.
+ * the HIP library.  The attention functions know nothing about tiles, splits or online
+ * softmax.  Next to them sit the helpers that the indexing checks compare the kernels with: the
+ * block-table walk, the check of a table against the pool, and the split plan.  The paper
+ * defines no split, so that last helper restates the definition the product publishes in its
+ * header (tiles of 32 tokens in batch order, cut into P balanced ranges) by brute force; its
+ * pins are property checks (balanced, monotone, tile-aligned), not a second copy of the formula.
  *
  * What it computes is the plain definition of grouped-query attention for one new
  * query token per sequence (the paper's Appendix A, Scenario A, describes the model
@@ -326,6 +331,62 @@ int32_t pa_oracle_window_blocks(const int32_t *block_tables, const int32_t *cont
     for (int32_t j = jb; j <= je && j - jb < cap; ++j)
         ids[j - jb] = block_tables[(int64_t)b * MB + j];
     return je - jb + 1;
+}
+
+/*
+ * What a caller of the paged attention step promises about its block tables and lengths, checked
+ * entry by entry in batch order, then block order (the paged KV cache of the paper's Appendix A,
+ * Scenario A, addresses every token through such a table):
+ *   - 0 <= L_b <= max_ctx, and with a shared prefix of prefix_blocks blocks (only whole pairs of
+ *     blocks count: 2 * (prefix_blocks / 2)) also L_b >= prefix tokens + Q - 1          (kind 1)
+ *   - every block that holds a token some query can see (all of them, or with reach =
+ *     window + Q - 1 > 0 those from the block of token max(0, L_b - reach) on) has an id in
+ *     [0, NB)                                                                             (kind 2)
+ *   - inside the shared prefix the id equals the one in row 0 of the table                (kind 3)
+ * A sequence whose length is refused has none of its blocks looked at.  Returns the number of
+ * offending entries; first[0..3] receive {kind, b, j, value} of the first one in that order
+ * (j = -1 and value = L_b for a length), or {0, -1, -1, 0} when there is none.
+ */
+int64_t pa_oracle_check_tables(const int32_t *block_tables, const int32_t *context_lens, int32_t B, int32_t MB,
+                               int32_t BS, int32_t NB, int32_t max_ctx, int32_t reach, int32_t prefix_blocks,
+                               int32_t Q, int32_t *first)
+{
+    int64_t bad = 0;
+    int32_t shared = 2 * (prefix_blocks / 2);
+    first[0] = 0;
+    first[1] = -1;
+    first[2] = -1;
+    first[3] = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t L = context_lens[b];
+        int length_ok = L >= 0 && L <= max_ctx && !(shared > 0 && L < shared * BS + Q - 1);
+        if (!length_ok) {
+            if (bad++ == 0) {
+                first[0] = 1;
+                first[1] = b;
+                first[2] = -1;
+                first[3] = L;
+            }
+            continue;
+        }
+        int32_t t_first = (reach > 0 && L > reach) ? L - reach : 0;
+        for (int32_t t = t_first - t_first % BS; t < L; t += BS) {
+            int32_t j = t / BS;
+            int32_t id = block_tables[(int64_t)b * MB + j];
+            int kind = 0;
+            if (id < 0 || id >= NB)
+                kind = 2;
+            else if (j < shared && id != block_tables[j])
+                kind = 3;
+            if (kind != 0 && bad++ == 0) {
+                first[0] = kind;
+                first[1] = b;
+                first[2] = j;
+                first[3] = id;
+            }
+        }
+    }
+    return bad;
 }
 
 /*

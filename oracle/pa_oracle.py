@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.pa_oracle_e4m3_encode.argtypes = [ctypes.c_float]
         L.pa_oracle_kv_append.restype = ctypes.c_int
         L.pa_oracle_kv_append.argtypes = [p, p, p, p, p, p, ctypes.c_int, p, p, i32, i32, i32, i32, i32, i32, i32]
+        L.pa_oracle_check_tables.restype = i64
+        L.pa_oracle_check_tables.argtypes = [p, p, i32, i32, i32, i32, i32, i32, i32, i32, p]
         L.pa_oracle_num_threads.restype = ctypes.c_int
         L.pa_oracle_num_threads.argtypes = []
         _lib = L
@@ -234,6 +236,20 @@ def window_blocks(block_tables: np.ndarray, context_lens: np.ndarray, block_size
     n = lib().pa_oracle_window_blocks(_ptr(block_tables), _ptr(context_lens), MB, block_size, b, int(reach),
                                       ctypes.byref(first), _ptr(ids), MB)
     return int(first.value), ids[:n].copy()
+
+
+def check_tables(block_tables: np.ndarray, context_lens: np.ndarray, block_size: int, num_blocks: int,
+                 max_context_len: int, reach: int = 0, shared_prefix_blocks: int = 0, q_len: int = 1):
+    """Check a block table and its lengths against the pool: returns (number of offending entries,
+    (kind, b, j, value) of the first in batch order then block order); kind 0 = none, 1 = length,
+    2 = block id outside the pool, 3 = shared-prefix entry that differs from row 0."""
+    block_tables = _c(block_tables, np.int32)
+    context_lens = _c(context_lens, np.int32)
+    first = np.zeros(4, dtype=np.int32)
+    n = lib().pa_oracle_check_tables(_ptr(block_tables), _ptr(context_lens), len(context_lens), block_tables.shape[1],
+                                     int(block_size), int(num_blocks), int(max_context_len), int(reach),
+                                     int(shared_prefix_blocks), int(q_len), _ptr(first))
+    return int(n), tuple(int(x) for x in first)
 
 
 def e4m3_encode(x: float) -> int:

@@ -46,6 +46,38 @@ def core_pins(oracle):
         for i in range(3):
             for h in range(4):
                 assert np.array_equal(out[s, i, h], W.bf16_bits_to_f32(v_new[s, i, h // 2]))
+    table_check_pins(oracle)
+
+
+def table_check_pins(oracle):
+    """The table check against cases small enough to read off by hand (expected values are literals)."""
+    t = np.array([[3, 1, -1, -1],      # L = 20: blocks 0, 1 are looked at, the -1s are not
+                  [0, 2, 4, 5],        # L = 64: all four
+                  [7, 7, 7, 7]],       # L = 0: nothing is looked at, whatever the row holds
+                 dtype=np.int32)
+    lens = np.array([20, 64, 0], dtype=np.int32)
+    assert oracle.check_tables(t, lens, 16, 6, 64) == (0, (0, -1, -1, 0))
+    assert oracle.check_tables(t, lens, 16, 5, 64) == (1, (2, 1, 3, 5))          # id 5 is outside a pool of 5
+    assert oracle.check_tables(t, lens, 16, 4, 64) == (2, (2, 1, 2, 4))          # ids 4 and 5; first in block order
+    assert oracle.check_tables(t, lens, 16, 6, 63) == (1, (1, 1, -1, 64))        # a length above the bound
+    assert oracle.check_tables(t, lens, 16, 4, 63) == (1, (1, 1, -1, 64))        # ... whose blocks are then not looked at
+    lens2 = np.array([33, 64, -2], dtype=np.int32)                               # L = 33 reaches the -1 in block 2
+    assert oracle.check_tables(t, lens2, 16, 6, 64) == (2, (2, 0, 2, -1))        # and the negative length counts too
+    # sliding window: reach 16 on L = 64 looks at blocks 3 only (token 48 on); on L = 20 at blocks 0 and 1 (token 4 on)
+    t3 = t.copy()
+    t3[1, :3] = 99
+    assert oracle.check_tables(t3, lens, 16, 6, 64, reach=16) == (0, (0, -1, -1, 0))
+    assert oracle.check_tables(t3, lens, 16, 6, 64, reach=17) == (1, (2, 1, 2, 99))
+    # shared prefix of 2 blocks: rows must repeat row 0 there, and every length must cover it
+    tp = np.array([[3, 1, 2], [3, 1, 0], [3, 4, 5]], dtype=np.int32)
+    lp = np.array([40, 33, 48], dtype=np.int32)
+    assert oracle.check_tables(tp, lp, 16, 6, 48, shared_prefix_blocks=2) == (1, (3, 2, 1, 4))
+    assert oracle.check_tables(tp, lp, 16, 6, 48, shared_prefix_blocks=3) == (1, (3, 2, 1, 4))   # whole pairs only
+    lp[1] = 31
+    assert oracle.check_tables(tp, lp, 16, 6, 48, shared_prefix_blocks=2) == (2, (1, 1, -1, 31))
+    lp[1] = 34
+    assert oracle.check_tables(tp, lp, 16, 6, 48, shared_prefix_blocks=2, q_len=4)[1] == (1, 1, -1, 34)  # 32 + 4 - 1 = 35
+    assert oracle.check_tables(tp, lp, 16, 6, 48, shared_prefix_blocks=2, q_len=3)[1] == (3, 2, 1, 4)
 
 
 def main(so_path):
@@ -54,7 +86,7 @@ def main(so_path):
     good = pa_oracle.lib()
     other = ctypes.CDLL(so_path)
     for fn in ("pa_oracle_decode", "pa_oracle_verify", "pa_oracle_window", "pa_oracle_e4m3_table",
-               "pa_oracle_kv_append"):
+               "pa_oracle_kv_append", "pa_oracle_check_tables"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     pa_oracle._lib = other

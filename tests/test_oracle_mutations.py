@@ -45,6 +45,12 @@ MUTATIONS = {
                                                    "int32_t t = context_lens[b] - 1 - i;"),
     "append: token and head axes of the new rows swapped": ("int64_t src = (((int64_t)b * Q + i) * Hkv + g) * D + d;",
                                                             "int64_t src = (((int64_t)b * Hkv + g) * Q + i) * D + d;"),
+    "table check: id equal to the pool size accepted": ("if (id < 0 || id >= NB)", "if (id < 0 || id > NB)"),
+    "table check: window start rounded up to the next block": ("for (int32_t t = t_first - t_first % BS; t < L; t += BS) {",
+                                                               "for (int32_t t = t_first + (BS - t_first % BS) % BS; t < L; t += BS) {"),
+    "table check: blocks of a refused length still looked at": ("                first[3] = L;\n            }\n            continue;",
+                                                                "                first[3] = L;\n            }"),
+    "table check: an odd prefix block counted as shared": ("int32_t shared = 2 * (prefix_blocks / 2);", "int32_t shared = prefix_blocks;"),
 }
 
 

@@ -14,6 +14,7 @@ import numpy as np
 import pytest
 
 from paper_2605_06068_amd import workloads as W
+from tests.oracle_core_pins import table_check_pins
 from tests.dense_reference import dense_attention, dense_window_attention, e4m3_to_f64, torch_sdpa, widen_bf16
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -505,6 +506,32 @@ def test_visited_blocks_follow_the_table(oracle):
     b = W.make_config(1)
     assert oracle.visited_blocks(b.block_tables, b.context_lens, 16, 0).tolist() == b.block_tables[0, :3].tolist()
     assert oracle.visited_blocks(b.block_tables, b.context_lens, 16, 1).tolist() == b.block_tables[1, :7].tolist()
+
+
+def test_check_tables_hand_cases(oracle):
+    table_check_pins(oracle)
+
+
+def test_check_tables_finds_planted_faults(oracle):
+    """A clean generated table passes; one entry spoiled at a place the test chooses is reported at
+    exactly that place; entries the attention never looks at may hold anything."""
+    rng = np.random.default_rng(11)
+    b = W.make_config(4, length_scale=1 / 8)
+    t, lens, NB = b.block_tables, b.context_lens, b.num_blocks
+    top = int(lens.max())
+    assert oracle.check_tables(t, lens, 16, NB, top) == (0, (0, -1, -1, 0))
+    for bad in (-1, NB, 2 ** 30, -2 ** 31):
+        s = int(rng.integers(0, b.batch))
+        j = int(rng.integers(0, (int(lens[s]) + 15) // 16))
+        spoiled = t.copy()
+        spoiled[s, j] = bad
+        assert oracle.check_tables(spoiled, lens, 16, NB, top) == (1, (2, s, j, bad))
+        spoiled[s, (int(lens[s]) + 15) // 16:] = bad   # behind the context: never looked at
+        assert oracle.check_tables(spoiled, lens, 16, NB, top)[0] == 1
+    two = t.copy()
+    two[5, 0] = NB
+    two[2, 0] = -5
+    assert oracle.check_tables(two, lens, 16, NB, top) == (2, (2, 2, 0, -5))
 
 
 def test_block_partition_is_a_balanced_contiguous_cut(oracle):
