@@ -14,14 +14,21 @@
  * Conventions for every entry point
  *   - All tensor arguments are DEVICE pointers owned by the caller, contiguous in the layouts
  *     below and 16-byte aligned.  The shape struct and the split-plan arrays are HOST memory.
- *   - The library allocates no device memory, keeps no state between calls, never reads device
- *     memory on the host, and (except pa_decode_profile) never synchronises: work is enqueued on
- *     the given HIP stream (hipStream_t passed as void*, NULL = the default stream) and the call
- *     returns at once.  Calls that share a workspace must be ordered by the caller.
+ *   - The library allocates no device memory, never reads device memory on the host, and (except
+ *     pa_decode_profile) never synchronises: work is enqueued on the given HIP stream (hipStream_t
+ *     passed as void*, NULL = the default stream) and the call returns at once.  Calls that share
+ *     a workspace must be ordered by the caller.  Between calls it keeps nothing about the data;
+ *     what it does keep, per process, is the compute-unit count of the device that was current at
+ *     the first call (the number of partitions, hence the workspace size and the cut points,
+ *     follow from it: a process is assumed to drive GPUs of one kind).
  *   - Errors are return codes (pa_status).  Everything the host can check (null pointers, shape,
  *     alignment, workspace size) is rejected BEFORE any launch; the contents of block_tables and
- *     context_lens are trusted: ids of valid tokens must lie in [0, num_blocks) and
- *     0 <= context_lens[b] <= max_context_len.
+ *     context_lens are trusted by pa_decode and pa_kv_append: ids of tokens a query can see must
+ *     lie in [0, num_blocks) and 0 <= context_lens[b] <= max_context_len.  pa_check_tables checks
+ *     exactly that on the device without following any id, and pa_decode_trace refuses to follow
+ *     an id outside the pool.
+ *   - A launch failure is detected with hipGetLastError() after the launches of a call: that
+ *     clears, and may report, an error left by another HIP call of the same host thread.
  *   - Table entries past ceil(context_lens[b] / block_size), token slots past context_lens[b] in
  *     a sequence's last block, and blocks no sequence owns are never dereferenced / never
  *     influence the result (they may hold garbage ids and NaN patterns).
@@ -205,20 +212,56 @@ pa_status pa_kv_append(const void *k_new, const void *v_new, void *k_cache, void
                        const float *k_scale, const float *v_scale, const pa_shape *shape, void *stream);
 
 /*
- * Same computation with the production indexing code instrumented (slow; for tests).  In
- * addition to out it records, for checking the block-table walk and the split boundaries bit
- * for bit:
+ * The debug path of the boundary: the same computation with the production indexing code
+ * instrumented and every block id held against the pool before it becomes an address (slow; for
+ * tests and for finding a bad table).  In addition to out it records, for checking the
+ * block-table walk and the split boundaries bit for bit:
  *   visited_blocks [batch, num_kv_heads, max_blocks_per_seq, 3] int32 device: for logical block j
- *                  of sequence b and KV head g, the physical id the kernel used for its K loads
+ *                  of sequence b and KV head g, the id the table gave the kernel for its K loads
  *                  ([..,0]) and for its V loads ([..,1]) and the partition that processed it
  *                  ([..,2]).  Entries of blocks the kernel never touched keep the caller's initial
  *                  contents.
- * Shapes with a shared prefix are PA_ERR_UNSUPPORTED here.
+ * An id outside [0, shape.num_blocks) is recorded as it stands and NOT followed: block 0 is read
+ * in its place, the call completes normally, and `out` is then meaningless for that sequence.
+ * With a shared prefix the prefix pass reads the prefix blocks through row 0 of block_tables for
+ * the whole batch: their records appear under sequence 0 only, with -2 - r in place of the
+ * partition, r being the range of the prefix tiles as in pa_split_plan.
  */
 pa_status pa_decode_trace(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                           const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,
                           const float *k_scale, const float *v_scale, const pa_shape *shape, void *workspace,
                           size_t workspace_bytes, void *stream, int32_t *visited_blocks);
+
+/* What pa_check_tables found (report[0]) */
+typedef enum pa_tables_status {
+    PA_TABLES_OK = 0,
+    PA_TABLES_BAD_LENGTH = 1,      /* context_lens[b] < 0, > max_context_len, or shorter than a shared prefix allows */
+    PA_TABLES_BAD_BLOCK_ID = 2,    /* an id outside [0, num_blocks) where a query can see a token */
+    PA_TABLES_PREFIX_MISMATCH = 3  /* an entry of the shared prefix that differs from row 0 */
+} pa_tables_status;
+
+/*
+ * Checks, on the device and without following a single id, what pa_decode trusts about a paged
+ * KV cache's tables (the paper's serving stack addresses every cached token through such a block
+ * table: Appendix A, Scenario A), for the call `shape` describes:
+ *   - 0 <= context_lens[b] <= max_context_len (the resolved bound), and with a shared prefix
+ *     context_lens[b] >= prefix tokens + q_len - 1;
+ *   - for every sequence whose length passed, every block that holds a token some query of the
+ *     call can see (all blocks up to the context's last; with a sliding window those from the
+ *     block of token max(0, context_lens[b] - window - q_len + 1) on) has an id in [0, num_blocks);
+ *   - inside a shared prefix (whole pairs of blocks) every row repeats row 0.
+ * Entries behind a context, and blocks a sliding window has left behind, may hold anything.
+ *
+ *   block_tables, context_lens   device, layouts above; only these two are read
+ *   report   device int32[8], 16-byte aligned, written by this call: [0] a pa_tables_status,
+ *            [1] sequence b, [2] logical block j (-1: the length itself) and [3] the offending value
+ *            of the FIRST offending entry in batch order, then block order ([1] = [2] = -1 and
+ *            [3] = 0 when there is none), [4] the number of offending entries; [5..7] scratch.
+ * Three small launches on `stream`; no workspace, no synchronisation (the caller reads `report`
+ * after synchronising the stream); can be captured into a HIP graph.
+ */
+pa_status pa_check_tables(const int32_t *block_tables, const int32_t *context_lens, const pa_shape *shape,
+                          int32_t *report, void *stream);
 
 /*
  * Measurement helper: runs pa_decode `steps` times on `stream` with HIP events around each
@@ -235,6 +278,10 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
  * (partition, KV head), up to 32 query rows (Q * G) per KV head (16 for fp8 at head_dim 128); "mfma-wide":
  * a workgroup of 2, 4 or 8 wavefronts, up to 128); NULL for an invalid or unsupported shape.  Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
+
+/* SHA-256 (hex) over the library's sources as the build recorded it, "" when the build recorded
+ * none: lets a loader refuse a library that was not built from the sources beside it.  Static storage. */
+const char *pa_source_digest(void);
 
 /* Human-readable name of a status code.  Static storage. */
 const char *pa_status_string(pa_status status);

@@ -27,7 +27,7 @@ PA_OUT_F32 = 0
 PA_OUT_BF16 = 1
 
 EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa_decode",
-           "pa_kv_append", "pa_decode_trace", "pa_decode_profile", "pa_kernel_variant", "pa_status_string")
+           "pa_kv_append", "pa_decode_trace", "pa_check_tables", "pa_decode_profile", "pa_kernel_variant", "pa_source_digest", "pa_status_string")
 
 
 class pa_shape(ctypes.Structure):
@@ -46,14 +46,15 @@ _lib = None
 
 
 def lib() -> ctypes.CDLL:
-    """Open the in-tree library.  It is built by ``paper_2605_06068_amd.build.build()`` (hipcc);
-    when the library has not been built yet, it is compiled once here.  Raises if that is impossible."""
+    """Open the in-tree library.  It is built by ``paper_2605_06068_amd.build.build()`` (hipcc).  A
+    library that is missing, or that was not built from the sources beside it (its
+    pa_source_digest() differs from theirs), is compiled here first; raises if that is impossible."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        from . import build as _build
+    from . import build as _build
 
+    if _build.built_digest() != _build.source_digest():
         _build.build()
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
@@ -74,8 +75,12 @@ def lib() -> ctypes.CDLL:
     L.pa_decode_profile.argtypes = common + [i32, fp, fp]
     L.pa_kv_append.restype = ctypes.c_int
     L.pa_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, shp, vp]
+    L.pa_check_tables.restype = ctypes.c_int
+    L.pa_check_tables.argtypes = [vp, vp, shp, vp, vp]
     L.pa_kernel_variant.restype = ctypes.c_char_p
     L.pa_kernel_variant.argtypes = [shp, ctypes.c_int]
+    L.pa_source_digest.restype = ctypes.c_char_p
+    L.pa_source_digest.argtypes = []
     L.pa_status_string.restype = ctypes.c_char_p
     L.pa_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -180,6 +185,20 @@ def pa_decode_trace(q, k_cache, v_cache, block_tables, context_lens, scale, kv_d
                                _dev_ptr(visited_blocks, "visited_blocks"))
     if st != PA_OK:
         raise PaError(st, "pa_decode_trace")
+
+
+PA_TABLES_OK = 0
+PA_TABLES_BAD_LENGTH = 1
+PA_TABLES_BAD_BLOCK_ID = 2
+PA_TABLES_PREFIX_MISMATCH = 3
+
+
+def pa_check_tables(block_tables, context_lens, *, shape: pa_shape, report, stream=None) -> None:
+    """Enqueue the device-side check of the tables and lengths; ``report`` is a device int32[8]."""
+    st = lib().pa_check_tables(_dev_ptr(block_tables, "block_tables"), _dev_ptr(context_lens, "context_lens"),
+                               ctypes.byref(shape), _dev_ptr(report, "report"), _stream_ptr(stream))
+    if st != PA_OK:
+        raise PaError(st, "pa_check_tables")
 
 
 def pa_decode_profile(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale=None,

@@ -8,6 +8,7 @@
 #include <type_traits>
 #include <vector>
 
+#include "pa_check_tables.hpp"
 #include "pa_device.hpp"
 #include "pa_kv_append.hpp"
 #include "pa_merge.hpp"
@@ -322,15 +323,25 @@ void launch_partition(const Params& p, bool one_wave, bool trace, dim3 grid, hip
 }
 
 // the pass over the prefix all sequences share
+template <int D, int NW, int KV>
+void launch_prefix_nw(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    constexpr int NSTAGE = wide_stages(D, KV, WideShape{NW, 1});
+    if (trace)
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, 1, NSTAGE, KV, true, true>), grid, dim3(NW * 64), 0, st, p);
+    else
+        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, 1, NSTAGE, KV, false, true>), grid, dim3(NW * 64), 0, st, p);
+}
+
 template <int D, int KV>
-void launch_prefix(const Params& p, int nw, dim3 grid, hipStream_t st)
+void launch_prefix(const Params& p, int nw, bool trace, dim3 grid, hipStream_t st)
 {
     if (nw == 2)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 2, 1, wide_stages(D, KV, WideShape{2, 1}), KV, false, true>), grid, dim3(128), 0, st, p);
+        launch_prefix_nw<D, 2, KV>(p, trace, grid, st);
     else if (nw == 4)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 4, 1, wide_stages(D, KV, WideShape{4, 1}), KV, false, true>), grid, dim3(256), 0, st, p);
+        launch_prefix_nw<D, 4, KV>(p, trace, grid, st);
     else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, 8, 1, wide_stages(D, KV, WideShape{8, 1}), KV, false, true>), grid, dim3(512), 0, st, p);
+        launch_prefix_nw<D, 8, KV>(p, trace, grid, st);
 }
 
 // calls f with head_dim and the KV type as compile-time constants
@@ -363,7 +374,6 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         return PA_ERR_INVALID_ARG;
     if (!(scale == scale) || scale * 0.f != 0.f) return PA_ERR_INVALID_ARG;  // NaN or infinite
     if (trace && !trace_blocks) return PA_ERR_INVALID_ARG;
-    if (trace && plan.skip_tiles > 0) return PA_ERR_UNSUPPORTED;  // no instrumented prefix pass
     if (plan.ws_bytes > 0) {
         if (!workspace || !aligned(workspace, 256)) return PA_ERR_INVALID_ARG;
         if (workspace_bytes < plan.ws_bytes) return PA_ERR_WORKSPACE_TOO_SMALL;
@@ -393,6 +403,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     p.Hkv = shape->num_kv_heads;
     p.G = shape->num_q_heads / shape->num_kv_heads;
     p.MB = shape->max_blocks_per_seq;
+    p.num_blocks = shape->num_blocks;
     p.Q = query_len(shape);
     p.QH = p.Q * p.Hq;
     p.P = plan.P;
@@ -415,7 +426,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         constexpr int D = decltype(d)::value, KV = decltype(kvt)::value;
         if (plan.skip_tiles > 0) {
             const dim3 pgrid((uint32_t)plan.Pp * (uint32_t)p.Hkv * (uint32_t)plan.prefix_groups);
-            launch_prefix<D, KV>(p, plan.prefix_waves, pgrid, hs);
+            launch_prefix<D, KV>(p, plan.prefix_waves, trace, pgrid, hs);
             if (hipGetLastError() != hipSuccess) { launched = false; return; }
         }
         const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv * (uint32_t)column_groups(shape));
@@ -602,10 +613,46 @@ pa_status pa_kv_append(const void* k_new, const void* v_new, void* k_cache, void
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }
 
+pa_status pa_check_tables(const int32_t* block_tables, const int32_t* context_lens, const pa_shape* shape,
+                          int32_t* report, void* stream)
+{
+    const pa_status st = check_shape(shape, PA_KV_BF16);  // nothing here depends on the KV type
+    if (st != PA_OK) return st;
+    if (!block_tables || !context_lens || !report) return PA_ERR_INVALID_ARG;
+    if (!aligned(block_tables, 4) || !aligned(context_lens, 4) || !aligned(report, 16)) return PA_ERR_INVALID_ARG;
+    pa::CheckParams c{};
+    c.block_tables = block_tables;
+    c.context_lens = context_lens;
+    c.report = report;
+    c.B = shape->batch;
+    c.MB = shape->max_blocks_per_seq;
+    c.num_blocks = shape->num_blocks;
+    c.max_ctx = shape->max_context_len > 0 ? shape->max_context_len : shape->max_blocks_per_seq * shape->block_size;
+    c.reach = shape->window > 0 ? shape->window + query_len(shape) - 1 : 0;
+    c.shared_blocks = 2 * shared_tiles(shape);
+    c.min_len = shared_tiles(shape) > 0 ? shared_tiles(shape) * pa::kTileTokens + query_len(shape) - 1 : 0;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(pa::check_tables_init, dim3(1), dim3(64), 0, hs, report);
+    if (shape->batch > 0) {
+        hipLaunchKernelGGL(pa::check_tables_scan, dim3((uint32_t)shape->batch), dim3(pa::kCheckThreads), 0, hs, c);
+        hipLaunchKernelGGL(pa::check_tables_finish, dim3(1), dim3(64), 0, hs, c);
+    }
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
 const char* pa_kernel_variant(const pa_shape* shape, pa_kv_dtype kv_dtype)
 {
     if (check_shape(shape, kv_dtype) != PA_OK) return nullptr;
     return one_wave(shape, kv_dtype) ? "mfma" : "mfma-wide";
+}
+
+const char* pa_source_digest(void)
+{
+#ifdef PA_SOURCE_DIGEST
+    return PA_SOURCE_DIGEST;
+#else
+    return "";
+#endif
 }
 
 const char* pa_status_string(pa_status status)

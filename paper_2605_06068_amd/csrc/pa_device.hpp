@@ -30,6 +30,7 @@ struct Params {
     int32_t* trace_blocks;        // [B, Hkv, MB, 3] or null
     float scale_log2;             // softmax scale * log2(e)
     int32_t B, Hq, Hkv, G, MB;
+    int32_t num_blocks;           // blocks in the pool: instrumented runs hold every id against it
     int32_t Q;                    // query tokens per sequence (1 = plain decode)
     int32_t QH;                   // Q * Hq: output rows per sequence (q, out and the partials are [.., Q, Hq, D])
     int32_t P;                    // number of partitions of the global tile sequence

@@ -69,7 +69,7 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi)
 }
 
 // 16-byte-per-lane load from global memory straight into LDS.  LDS destination is
-// lds_addr + lane*16 (wave-uniform lds_addr goes through M0); the global source is
+// lds_addr + lane*16 (wave-uniform lds_addr travels in M0); the global source is
 // base (wave-uniform) + voff (per lane).  Completion is tracked by vmcnt.
 // STREAM marks the load non-temporal: the KV cache is read once per call and is far larger than
 // the L2, so its lines should not displace what is re-read (block tables, lengths, query rows,
@@ -77,12 +77,12 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi)
 template <bool STREAM>
 __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const void* base)
 {
+    // M0 is an operand the compiler sets (and so knows about); the wait state a write of M0 needs
+    // before an instruction that reads it is inside the statement, where the compiler cannot see
     if constexpr (STREAM)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
-                     :: "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+        asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" :: "v"(voff), "s"(base), "{m0}"(lds_addr) : "memory");
     else
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :: "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+        asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(voff), "s"(base), "{m0}"(lds_addr) : "memory");
 }
 
 template <int N>
@@ -178,12 +178,34 @@ __device__ __forceinline__ TileBlocks tile_blocks(const int32_t* block_tables, i
     return t;
 }
 
-// instrumented runs: which physical block was loaded for which logical block, and by which partition
-__device__ __forceinline__ void trace_tile_blocks(int32_t* trace, const TileBlocks& t, int b, int g, int k, int Hkv, int MB)
+// Instrumented runs only.  Before any id becomes an address it is held against the pool: an id
+// outside [0, num_blocks) is kept as it stands for the record (`raw`) and block 0 is read in its
+// place, so a table with a bad entry at a valid position shows up in the trace instead of as a
+// memory fault.  All lanes must call (the ids are wave-uniform).
+struct RawIds {
+    int id[2];
+};
+
+__device__ __forceinline__ RawIds check_tile_blocks(TileBlocks& t, int num_blocks)
 {
-    int32_t* v = trace + (((int64_t)b * Hkv + g) * MB + t.j0) * 3;
-    if (!t.first_gone) { v[0] = t.phys[0]; v[1] = t.phys[0]; v[2] = k; }
-    if (t.second) { v[3] = t.phys[1]; v[4] = t.phys[1]; v[5] = k; }
+    RawIds raw{{t.phys[0], t.phys[1]}};
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+        if ((unsigned)t.phys[sub] >= (unsigned)num_blocks) t.phys[sub] = 0;
+    return raw;
+}
+
+// ... and the record: for logical block j0 + sub of (sequence b, KV head g), slot `which` (0: the
+// id the K loads of that block were addressed with, 1: the V loads) and, with the K loads, the
+// partition `k` that did it.  Blocks the tile does not read (gone from a sliding window, past the
+// context) leave no record.  One lane calls.
+__device__ __forceinline__ void trace_block_use(int32_t* trace, const TileBlocks& t, const RawIds& raw, int sub, int which,
+                                                int b, int g, int k, int Hkv, int MB)
+{
+    if (sub == 0 ? t.first_gone : !t.second) return;
+    int32_t* v = trace + (((int64_t)b * Hkv + g) * MB + t.j0 + sub) * 3;
+    v[which] = raw.id[sub];
+    if (which == 0) v[2] = k;
 }
 
 // this lane's global byte offset for LDS-DMA instruction r of a slab (rows r*kRowsPerDma ..)

@@ -23,8 +23,9 @@
 // so "at most N operations outstanding" implies every load older than the newest N has landed,
 // whatever else (stores, extra loads) is in flight: other traffic only makes a wait stricter.
 // Everything else the loop needs from memory comes through the scalar cache (block ids,
-// context lengths), which the vector-memory counter does not see.  The inline asm writes M0
-// (the LDS-DMA destination register); nothing else in these kernels uses M0.
+// context lengths), which the vector-memory counter does not see.  The LDS-DMA destination
+// travels in M0, which the inline asm takes as an input operand, so the compiler sets it and
+// knows that it did.
 #pragma once
 #include "pa_device.hpp"
 #include "pa_mfma_tile.hpp"
@@ -174,12 +175,14 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     auto issue = [&](int i, int stage) {
         // ring of slots: a new segment starts, send its query rows ahead of its first tile
         if (!ONE_SLOT && (i == 0 || ic.lt == 0)) issue_q(ic.b);
-        const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
-        if (TRACE && lane == 0) trace_tile_blocks(p.trace_blocks, tb, ic.b, g, k, p.Hkv, p.MB);
+        TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
+        RawIds raw{};
+        if (TRACE) raw = check_tile_blocks(tb, p.num_blocks);
         const uint32_t ldst = lds0 + stage * kStageBytes;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const char* kb = kc + tb.phys[sub] * head_stride;
+            if (TRACE && lane == 0) trace_block_use(p.trace_blocks, tb, raw, sub, 0, ic.b, g, k, p.Hkv, p.MB);
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r)
                 dma16<true>(ldst + sub * kSlabBytes + r * 1024,
@@ -188,6 +191,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const char* vb = vc + tb.phys[sub] * head_stride;
+            if (TRACE && lane == 0) trace_block_use(p.trace_blocks, tb, raw, sub, 1, ic.b, g, k, p.Hkv, p.MB);
 #pragma unroll
             for (int r = 0; r < Geo::kDmaPerSlab; ++r)
                 dma16<true>(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024,

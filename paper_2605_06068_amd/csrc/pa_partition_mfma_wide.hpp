@@ -89,7 +89,6 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    static_assert(!(PREFIX && TRACE), "the prefix pass has no instrumented variant");
     // partition index fastest, as in the single-wave kernel; then the KV head, then (prefix pass
     // with more than 16*NW columns) the column group
     const int nparts = PREFIX ? p.Pp : p.P;
@@ -187,8 +186,19 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     };
     // returns whether this wave put loads in flight
     auto issue = [&](int stage) {
-        const TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
-        if (TRACE && w == 0 && lane == 0 && col0 == 0) trace_tile_blocks(p.trace_blocks, tb, ic.b, g, k, p.Hkv, p.MB);
+        TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
+        if (TRACE) {
+            const RawIds raw = check_tile_blocks(tb, p.num_blocks);
+            // the waves of a workgroup load different slabs of the tile from the same two ids: each loading
+            // wave records the (block, K or V) pairs of its own instructions, for the first column group.
+            // The prefix pass reads row 0 of the table for the whole batch and records its range as -2 - k.
+            if (loader && lane == 0 && col0 == 0) {
+#pragma unroll
+                for (int j = 0; j < PT; ++j)
+                    trace_block_use(p.trace_blocks, tb, raw, my_slab[j] & 1, my_slab[j] >> 1, ic.b, g, PREFIX ? -2 - k : k,
+                                    p.Hkv, p.MB);
+            }
+        }
         const uint32_t ldst = lds0 + stage * kStageBytes;
         if (loader) {
 #pragma unroll

@@ -155,14 +155,6 @@ def test_shared_prefix_plan_and_workspace():
     # one shared block is less than a tile: the call is the plain one
     s1 = shape(batch=B, shared_prefix_blocks=1)
     assert pa.pa_decode_workspace_size(s1, pa.PA_KV_BF16) == pa.pa_decode_workspace_size(shape(batch=B), pa.PA_KV_BF16)
-    # the instrumented entry point has no prefix pass
-    s = shape(batch=B, shared_prefix_blocks=prefix_blocks)
-    vp = ctypes.c_void_p
-    need = pa.pa_decode_workspace_size(s, pa.PA_KV_BF16)
-    st = pa.lib().pa_decode_trace(vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000), vp(0x5000), ctypes.c_float(0.1), 0,
-                                  vp(0x6000), None, None, ctypes.byref(s), vp(0x10000), ctypes.c_size_t(need), None,
-                                  vp(0x7000))
-    assert st == pa.PA_ERR_UNSUPPORTED
 
 
 def test_split_plan_rejects_lengths_above_the_bound():
@@ -300,3 +292,35 @@ def test_bench_reads_counters_only_for_the_workload_it_ran():
     assert bench.recorded_traffic("no_such_workload") is None
     got = bench.recorded_traffic(base)
     assert got is None or got > 577_638_400  # when the summary is current: at least the KV bytes of that batch
+
+
+def test_check_tables_rejects_bad_arguments_before_any_launch():
+    vp = ctypes.c_void_p
+    s = shape()
+    L = pa.lib()
+    assert L.pa_check_tables(None, vp(0x5000), ctypes.byref(s), vp(0x6000), None) == pa.PA_ERR_INVALID_ARG
+    assert L.pa_check_tables(vp(0x4000), None, ctypes.byref(s), vp(0x6000), None) == pa.PA_ERR_INVALID_ARG
+    assert L.pa_check_tables(vp(0x4000), vp(0x5000), ctypes.byref(s), None, None) == pa.PA_ERR_INVALID_ARG
+    assert L.pa_check_tables(vp(0x4000), vp(0x5000), ctypes.byref(s), vp(0x6004), None) == pa.PA_ERR_INVALID_ARG
+    assert L.pa_check_tables(vp(0x4000), vp(0x5000), None, vp(0x6000), None) == pa.PA_ERR_INVALID_ARG
+    assert L.pa_check_tables(vp(0x4000), vp(0x5000), ctypes.byref(shape(num_blocks=0)), vp(0x6000), None) == pa.PA_ERR_INVALID_ARG
+    assert L.pa_check_tables(vp(0x4000), vp(0x5000), ctypes.byref(shape(block_size=8)), vp(0x6000), None) == pa.PA_ERR_UNSUPPORTED
+
+
+def test_built_library_carries_the_digest_of_the_sources_beside_it():
+    from paper_2605_06068_amd import build
+
+    pa.lib()
+    assert build.built_digest() == build.source_digest()
+    assert pa.lib().pa_source_digest().decode() == build.source_digest()
+
+
+def test_device_code_has_no_packed_fp32_arithmetic():
+    """The device pass is compiled with the packed-fp32 target feature switched off; the generated
+    gfx950 assembly of every kernel must hold none of those instructions (the same sources compiled
+    without the switch do hold them, so the switch reaches the device back end)."""
+    from paper_2605_06068_amd import build
+
+    asm = build.device_asm()
+    assert asm.count("global_load_lds_dwordx4") > 100  # it is the kernels' assembly
+    assert re.findall(r"\bv_pk_(?:add|mul|fma)_f32\b", asm) == []
