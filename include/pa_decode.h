@@ -187,6 +187,26 @@ pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, con
                     size_t workspace_bytes, void *stream);
 
 /*
+ * pa_decode for callers that cannot allocate device memory or hold a workspace of their own: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  The same step
+ * with the same arguments minus the workspace: the partials and merge notes live in a static
+ * device array of PA_STATIC_SCRATCH_BYTES inside the library (one copy per GPU the library runs
+ * on, held until the process ends), whose address is looked up once per device, at the first call
+ * made with that device current.  The call itself allocates nothing and synchronises nothing.
+ *   - A shape whose pa_decode_workspace_size() exceeds PA_STATIC_SCRATCH_BYTES is refused with
+ *     PA_ERR_WORKSPACE_TOO_SMALL before any launch (16 MiB hold the one-token step of every
+ *     workload this library was measured on; multi-token calls on wide models need pa_decode).
+ *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ *     host threads) race; order them.  Nothing in the array needs clearing between calls: a call
+ *     reads back only what it wrote itself.
+ *   - The result is bit-identical to pa_decode's for the same arguments.
+ */
+#define PA_STATIC_SCRATCH_BYTES (16u << 20)
+pa_status pa_decode_static(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                           const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,
+                           const float *k_scale, const float *v_scale, const pa_shape *shape, void *stream);
+
+/*
  * The write that precedes the decode step in a serving loop (the paper's scenarios keep the
  * KV cache paged and append to it token by token: Appendix A, Scenarios A and C): stores the key
  * and value rows of the token generated in this step into the cache, at logical position

@@ -27,7 +27,7 @@ PA_OUT_F32 = 0
 PA_OUT_BF16 = 1
 
 EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa_decode",
-           "pa_kv_append", "pa_decode_trace", "pa_check_tables", "pa_decode_profile", "pa_kernel_variant", "pa_source_digest", "pa_status_string")
+           "pa_decode_static", "pa_kv_append", "pa_decode_trace", "pa_check_tables", "pa_decode_profile", "pa_kernel_variant", "pa_source_digest", "pa_status_string")
 
 
 class pa_shape(ctypes.Structure):
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     common = [vp, vp, vp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, shp, vp, ctypes.c_size_t, vp]
     L.pa_decode.restype = ctypes.c_int
     L.pa_decode.argtypes = common
+    L.pa_decode_static.restype = ctypes.c_int
+    L.pa_decode_static.argtypes = common[:11] + [vp]
     L.pa_decode_trace.restype = ctypes.c_int
     L.pa_decode_trace.argtypes = common + [vp]
     L.pa_decode_profile.restype = ctypes.c_int
@@ -165,6 +167,19 @@ def pa_decode(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, 
                                        v_scale, shape, workspace, stream))
     if st != PA_OK:
         raise PaError(st, "pa_decode")
+
+
+PA_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def pa_decode_static(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale=None, v_scale=None,
+                     *, shape: pa_shape, stream=None) -> None:
+    """The same step with the library's static scratch array as the workspace (nothing to allocate)."""
+    a = _common_args(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
+                     None, stream)
+    st = lib().pa_decode_static(*a[:11], a[13])
+    if st != PA_OK:
+        raise PaError(st, "pa_decode_static")
 
 
 def pa_kv_append(k_new, v_new, k_cache, v_cache, block_tables, context_lens, kv_dtype, k_scale=None, v_scale=None, *,

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 #include <vector>
 
@@ -15,6 +16,13 @@
 #include "pa_partition_mfma.hpp"
 #include "pa_partition_mfma_wide.hpp"
 #include "pa_plan.hpp"
+
+// Scratch memory of pa_decode_static, the entry point for callers that cannot allocate: one array
+// per GPU the library runs on, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels get the device address that call returns.
+#define PA_STATIC_SCRATCH_BYTES_IMPL (16u << 20)
+static_assert(PA_STATIC_SCRATCH_BYTES_IMPL == PA_STATIC_SCRATCH_BYTES, "as the header states");
+static __device__ __align__(256) unsigned char scratch[PA_STATIC_SCRATCH_BYTES_IMPL];
 
 namespace {
 
@@ -457,6 +465,29 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
     return PA_OK;
 }
 
+// Device address of `scratch` on the current device: looked up once per device, with that device
+// current (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];
+
+pa_status static_scratch(void** ptr)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return PA_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return PA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -520,6 +551,23 @@ pa_status pa_decode(const void* q, const void* k_cache, const void* v_cache, con
 {
     return run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape,
                workspace, workspace_bytes, stream, nullptr, false, nullptr);
+}
+
+pa_status pa_decode_static(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
+                           const int32_t* context_lens, float scale, pa_kv_dtype kv_dtype, void* out,
+                           const float* k_scale, const float* v_scale, const pa_shape* shape, void* stream)
+{
+    Plan plan;
+    const pa_status st = make_plan(shape, kv_dtype, &plan);
+    if (st != PA_OK) return st;
+    if (plan.ws_bytes > PA_STATIC_SCRATCH_BYTES) return PA_ERR_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    if (plan.ws_bytes > 0) {
+        const pa_status ss = static_scratch(&ws);
+        if (ss != PA_OK) return ss;
+    }
+    return run(q, k_cache, v_cache, block_tables, context_lens, scale, kv_dtype, out, k_scale, v_scale, shape, ws,
+               plan.ws_bytes > 0 ? PA_STATIC_SCRATCH_BYTES : 0, stream, nullptr, false, nullptr);
 }
 
 pa_status pa_decode_trace(const void* q, const void* k_cache, const void* v_cache, const int32_t* block_tables,
