@@ -512,6 +512,18 @@ int pa_oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, void *k_ca
     return 0;
 }
 
+/* How many threads the row loops may use from now on (the benchmark's one-thread leg); the
+ * arithmetic of a row does not depend on it. */
+void pa_oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1)
+        omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int pa_oracle_num_threads(void)
 {
     int n = 1;

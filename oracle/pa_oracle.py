@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.pa_oracle_kv_append.argtypes = [p, p, p, p, p, p, ctypes.c_int, p, p, i32, i32, i32, i32, i32, i32, i32]
         L.pa_oracle_check_tables.restype = i64
         L.pa_oracle_check_tables.argtypes = [p, p, i32, i32, i32, i32, i32, i32, i32, i32, p]
+        L.pa_oracle_set_num_threads.restype = None
+        L.pa_oracle_set_num_threads.argtypes = [ctypes.c_int]
         L.pa_oracle_num_threads.restype = ctypes.c_int
         L.pa_oracle_num_threads.argtypes = []
         _lib = L
@@ -281,6 +283,11 @@ def kv_append(k_new: np.ndarray, v_new: np.ndarray, k_cache: np.ndarray, v_cache
                                    block_tables.shape[1], NB)
     if rc != 0:
         raise RuntimeError(f"pa_oracle_kv_append failed with code {rc}")
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the oracle's row loops use from now on."""
+    lib().pa_oracle_set_num_threads(int(n))
 
 
 def num_threads() -> int:
