@@ -122,6 +122,8 @@ typedef struct pa_shape {
                                    rounded to nearest even */
     int32_t window;             /* 0 = every query sees its whole past; W > 0 = sliding window: the query at
                                    position t sees tokens t-W+1 .. t only (see pa_decode) */
+    int32_t precise_weights;    /* 0 = the library chooses how many bits of the softmax weights enter the PV
+                                   product (see "Arithmetic" at pa_decode); 1 = 16 significant bits on every path */
 } pa_shape;
 
 /*
@@ -175,11 +177,19 @@ size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
  *   stream           hipStream_t
  *
  * The result is deterministic run to run (no floating-point atomics).
- * Arithmetic: scores, softmax and accumulation in float32.  The softmax weights enter the PV
- * product with 16 significant bits for PA_KV_BF16 calls with q_len * G <= 16 and no shared
- * prefix (result within ~1e-5 of the exact one for values of unit size), with 8 (one bf16
- * number, relative rounding error <= 2^-9 per weight) for every other call: result within
- * 2^-9 * max|v| of the exact one for the dequantised values.
+ * Arithmetic: scores, softmax and accumulation in float32; the softmax weights are the operand of a
+ * bf16 matrix product with the values.  With shape.precise_weights = 0 they enter it with 16
+ * significant bits (a bf16 number plus its rounding remainder) for PA_KV_BF16 calls with
+ * q_len * G <= 16 and no shared prefix: result within ~1e-5 of the exact one for values of unit
+ * size; and with 8 bits (one bf16 number, relative rounding error <= 2^-9 per weight, unbiased) for
+ * every other call (fp8 KV, more than 16 columns, a shared prefix): result within 2^-9 * max|v| of
+ * the exact one for the dequantised values, a few 1e-3 in practice for values of unit size, and
+ * proportionally more for larger ones.  With shape.precise_weights = 1 every call uses 16 bits
+ * (result within ~1e-5 * max|v|) at the price of one more matrix instruction per operand: nothing
+ * for plain bf16 decode, 5-25 % more time for the calls listed above.  The paper's accuracy
+ * gates compare generated text with a reference implementation's (Appendix A, Scenario B: greedy
+ * outputs must match); a caller held to such a gate, or one whose values are not of unit size,
+ * sets it.
  */
 pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                     const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,

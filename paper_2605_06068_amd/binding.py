@@ -33,7 +33,7 @@ EXPORTS = ("pa_num_partitions", "pa_split_plan", "pa_decode_workspace_size", "pa
 class pa_shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_blocks",
-        "max_context_len", "num_partitions", "q_len", "shared_prefix_blocks", "out_dtype", "window")]
+        "max_context_len", "num_partitions", "q_len", "shared_prefix_blocks", "out_dtype", "window", "precise_weights")]
 
 
 class PaError(RuntimeError):
@@ -95,12 +95,13 @@ def status_string(status: int) -> str:
 
 def make_shape(batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_blocks,
                max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0,
-               out_dtype=PA_OUT_F32) -> pa_shape:
+               out_dtype=PA_OUT_F32, precise_weights=0) -> pa_shape:
     return pa_shape(batch=int(batch), num_q_heads=int(num_q_heads), num_kv_heads=int(num_kv_heads),
                     head_dim=int(head_dim), block_size=int(block_size), max_blocks_per_seq=int(max_blocks_per_seq),
                     num_blocks=int(num_blocks), max_context_len=int(max_context_len),
                     num_partitions=int(num_partitions), q_len=int(q_len),
-                    shared_prefix_blocks=int(shared_prefix_blocks), out_dtype=int(out_dtype), window=int(window))
+                    shared_prefix_blocks=int(shared_prefix_blocks), out_dtype=int(out_dtype), window=int(window),
+                    precise_weights=int(precise_weights))
 
 
 def _neg_is_error(v: int, where: str) -> int:
@@ -235,7 +236,7 @@ def pa_decode_profile(q, k_cache, v_cache, block_tables, context_lens, scale, kv
 class DeviceBatch:
     def __init__(self, batch, device="cuda:0", max_context_len: Optional[int] = None, num_partitions: int = 0,
                  shared_prefix_blocks: Optional[int] = None, window: Optional[int] = None,
-                 out_dtype: int = PA_OUT_F32):
+                 out_dtype: int = PA_OUT_F32, precise_weights: int = 0):
         import numpy as np
         import torch
 
@@ -267,7 +268,8 @@ class DeviceBatch:
                                 batch.max_blocks_per_seq, batch.num_blocks, max_context_len, num_partitions, q_len,
                                 int(getattr(batch, "shared_prefix_blocks", 0)) if shared_prefix_blocks is None
                                 else shared_prefix_blocks,
-                                int(getattr(batch, "window", 0)) if window is None else window, out_dtype)
+                                int(getattr(batch, "window", 0)) if window is None else window, out_dtype,
+                                precise_weights)
         nbytes = pa_decode_workspace_size(self.shape, self.kv_dtype)
         # NaN-filled so that a read of an entry this call did not write shows up in the output
         self.workspace = None if nbytes == 0 else torch.full((nbytes // 4,), float("nan"), dtype=torch.float32,

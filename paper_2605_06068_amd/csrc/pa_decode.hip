@@ -199,7 +199,7 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (kv != PA_KV_BF16 && kv != PA_KV_FP8_E4M3) return PA_ERR_INVALID_ARG;
     if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->head_dim <= 0 || s->block_size <= 0 ||
         s->max_blocks_per_seq <= 0 || s->num_blocks <= 0 || s->max_context_len < 0 || s->num_partitions < 0 ||
-        s->q_len < 0 || s->shared_prefix_blocks < 0 || s->window < 0 ||
+        s->q_len < 0 || s->shared_prefix_blocks < 0 || s->window < 0 || (s->precise_weights != 0 && s->precise_weights != 1) ||
         (s->out_dtype != PA_OUT_F32 && s->out_dtype != PA_OUT_BF16))
         return PA_ERR_INVALID_ARG;
     if (s->shared_prefix_blocks > s->max_blocks_per_seq) return PA_ERR_INVALID_ARG;
@@ -211,6 +211,7 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (columns(s) > kMaxCols) return PA_ERR_UNSUPPORTED;
     if (s->num_partitions > kMaxPartitions) return PA_ERR_UNSUPPORTED;
     if (s->batch > kMaxBatch) return PA_ERR_UNSUPPORTED;  // the merge kernels index sequences by blockIdx.y
+    if (s->num_kv_heads > 65536) return PA_ERR_UNSUPPORTED;  // bytes between physical blocks fit 32 bits
     if (shared_tiles(s) > 0) {
         // the per-sequence pass runs on the one-wave kernel (up to 32 columns), the prefix pass on the multi-wave one
         if (s->batch < 1 || columns(s) > 32) return PA_ERR_UNSUPPORTED;
@@ -288,68 +289,76 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// Does shape.precise_weights change the kernel?  Only where the default drops the low part.
+constexpr bool precise_matters(int kv, int nct, bool multi_wave) { return !pa::p_has_low_part(kv, nct, multi_wave); }
+
 template <int D, int CPAD, int KV>
-void launch_mfma(const Params& p, bool trace, dim3 grid, hipStream_t st)
+void launch_mfma(const Params& p, bool trace, bool precise, dim3 grid, hipStream_t st)
 {
     constexpr int NSTAGE = mfma_stages(D, KV);
-    if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, true>), grid, dim3(64), 0, st, p);
-    else
-        hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, false>), grid, dim3(64), 0, st, p);
+    constexpr bool kMatters = precise_matters(KV, CPAD > 16 ? 2 : 1, false);
+    if (kMatters && precise) {
+        if (trace)
+            hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, true, kMatters>), grid, dim3(64), 0, st, p);
+        else
+            hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, false, kMatters>), grid, dim3(64), 0, st, p);
+    } else {
+        if (trace)
+            hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, true, false>), grid, dim3(64), 0, st, p);
+        else
+            hipLaunchKernelGGL((pa::partition_mfma_kernel<D, NSTAGE, CPAD, KV, false, false>), grid, dim3(64), 0, st, p);
+    }
 }
 
-template <int D, int NW, int NCT, int KV>
-void launch_wide(const Params& p, bool trace, dim3 grid, hipStream_t st)
+template <int D, int NW, int NCT, int KV, bool PREFIX>
+void launch_wide(const Params& p, bool trace, bool precise, dim3 grid, hipStream_t st)
 {
     constexpr int NSTAGE = wide_stages(D, KV, WideShape{NW, NCT});
-    if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, true, false>), grid, dim3(NW * 64), 0, st, p);
-    else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, false, false>), grid, dim3(NW * 64), 0, st, p);
+    if (precise) {
+        if (trace)
+            hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, true, PREFIX, true>), grid, dim3(NW * 64), 0, st, p);
+        else
+            hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, false, PREFIX, true>), grid, dim3(NW * 64), 0, st, p);
+    } else {
+        if (trace)
+            hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, true, PREFIX, false>), grid, dim3(NW * 64), 0, st, p);
+        else
+            hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, false, PREFIX, false>), grid, dim3(NW * 64), 0, st, p);
+    }
 }
 
 // the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2 or 4 waves above
 template <int D, int KV>
-void launch_partition(const Params& p, bool one_wave, bool trace, dim3 grid, hipStream_t st)
+void launch_partition(const Params& p, bool one_wave, bool trace, bool precise, dim3 grid, hipStream_t st)
 {
     const int cols = p.Q * p.G;
     if (cols <= 4)
-        launch_mfma<D, 4, KV>(p, trace, grid, st);
+        launch_mfma<D, 4, KV>(p, trace, precise, grid, st);
     else if (cols <= 8)
-        launch_mfma<D, 8, KV>(p, trace, grid, st);
+        launch_mfma<D, 8, KV>(p, trace, precise, grid, st);
     else if (cols <= 16)
-        launch_mfma<D, 16, KV>(p, trace, grid, st);
+        launch_mfma<D, 16, KV>(p, trace, precise, grid, st);
     else if (one_wave)
-        launch_mfma<D, 32, KV>(p, trace, grid, st);
+        launch_mfma<D, 32, KV>(p, trace, precise, grid, st);
     else if (cols <= 32)
-        launch_wide<D, 2, 1, KV>(p, trace, grid, st);
+        launch_wide<D, 2, 1, KV, false>(p, trace, precise, grid, st);
     else if (cols <= 64)
-        launch_wide<D, 4, 1, KV>(p, trace, grid, st);
+        launch_wide<D, 4, 1, KV, false>(p, trace, precise, grid, st);
     else
-        launch_wide<D, 4, 2, KV>(p, trace, grid, st);
+        launch_wide<D, 4, 2, KV, false>(p, trace, precise, grid, st);
     static_assert(wide_shape(32, false).nw == 2 && wide_shape(64, false).nw == 4 && wide_shape(128, false).nct == 2, "as launched");
 }
 
 // the pass over the prefix all sequences share
-template <int D, int NW, int KV>
-void launch_prefix_nw(const Params& p, bool trace, dim3 grid, hipStream_t st)
-{
-    constexpr int NSTAGE = wide_stages(D, KV, WideShape{NW, 1});
-    if (trace)
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, 1, NSTAGE, KV, true, true>), grid, dim3(NW * 64), 0, st, p);
-    else
-        hipLaunchKernelGGL((pa::partition_mfma_wide_kernel<D, NW, 1, NSTAGE, KV, false, true>), grid, dim3(NW * 64), 0, st, p);
-}
-
 template <int D, int KV>
-void launch_prefix(const Params& p, int nw, bool trace, dim3 grid, hipStream_t st)
+void launch_prefix(const Params& p, int nw, bool trace, bool precise, dim3 grid, hipStream_t st)
 {
     if (nw == 2)
-        launch_prefix_nw<D, 2, KV>(p, trace, grid, st);
+        launch_wide<D, 2, 1, KV, true>(p, trace, precise, grid, st);
     else if (nw == 4)
-        launch_prefix_nw<D, 4, KV>(p, trace, grid, st);
+        launch_wide<D, 4, 1, KV, true>(p, trace, precise, grid, st);
     else
-        launch_prefix_nw<D, 8, KV>(p, trace, grid, st);
+        launch_wide<D, 8, 1, KV, true>(p, trace, precise, grid, st);
 }
 
 // calls f with head_dim and the KV type as compile-time constants
@@ -426,6 +435,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         p.prefix_lse = reinterpret_cast<float*>(ws + plan.prefix_lse_offset);
     }
 
+    const bool precise = shape->precise_weights != 0;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (ev && hipEventRecord(ev->before, hs) != hipSuccess) return PA_ERR_HIP;
 
@@ -434,11 +444,11 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
         constexpr int D = decltype(d)::value, KV = decltype(kvt)::value;
         if (plan.skip_tiles > 0) {
             const dim3 pgrid((uint32_t)plan.Pp * (uint32_t)p.Hkv * (uint32_t)plan.prefix_groups);
-            launch_prefix<D, KV>(p, plan.prefix_waves, trace, pgrid, hs);
+            launch_prefix<D, KV>(p, plan.prefix_waves, trace, precise, pgrid, hs);
             if (hipGetLastError() != hipSuccess) { launched = false; return; }
         }
         const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv * (uint32_t)column_groups(shape));
-        launch_partition<D, KV>(p, plan.one_wave, trace, grid, hs);
+        launch_partition<D, KV>(p, plan.one_wave, trace, precise, grid, hs);
         if (hipGetLastError() != hipSuccess) { launched = false; return; }
         if (ev && hipEventRecord(ev->between, hs) != hipSuccess) { launched = false; return; }
 

@@ -178,6 +178,33 @@ __device__ __forceinline__ TileBlocks tile_blocks(const int32_t* block_tables, i
     return t;
 }
 
+// A tile whose 32 rows are all visible (it ends inside the context and starts inside every
+// window) needs none of the above: two table entries, two slab addresses.
+__device__ __forceinline__ bool interior_tile(const Cursor& c, int reach)
+{
+    const int first = 2 * (c.lt + c.ft) * kBlockSize;
+    return first + kTileTokens <= c.L && (reach == 0 || first >= c.L - reach);
+}
+
+// The two block ids of such a tile, asked for one tile ahead: the issue side requests the ids of
+// the tile it will load NEXT as soon as it has sent the loads of the current one, so the scalar
+// loads travel while the wave computes and the next round of LDS-DMA loads starts without a
+// round trip to the table.  Returns whether id0 / id1 now hold the ids of the tile `c` stands on;
+// false when that tile is not interior (or there is none): the general path then reads its ids
+// itself.  (Plain scalars, not a struct: everything here has to stay in scalar registers.)
+__device__ __forceinline__ bool ask_next_ids(const int32_t* block_tables, int MB, const Cursor& c, int B, int reach, int& id0,
+                                             int& id1)
+{
+    const bool valid = c.b < B && c.lt < c.nt && interior_tile(c, reach);
+    if (valid) {
+        const int32_t* table = block_tables + (int64_t)c.b * MB;
+        const int j0 = 2 * (c.lt + c.ft);
+        id0 = uniform_load(table, j0);
+        id1 = uniform_load(table, j0 + 1);
+    }
+    return valid;
+}
+
 // Instrumented runs only.  Before any id becomes an address it is held against the pool: an id
 // outside [0, num_blocks) is kept as it stands for the record (`raw`) and block 0 is read in its
 // place, so a table with a bad entry at a valid position shows up in the trace instead of as a
@@ -315,66 +342,111 @@ __device__ __forceinline__ void qk_scores(const char* kbuf, const OperandOffsets
 }
 
 // Do the softmax weights enter the PV product with their rounding remainder (two bf16 numbers per
-// weight) or as one bf16 number?  The remainder is kept where it is free: bf16 KV in a wave with one
-// 16-column tile, which waits for memory either way (plain decode above all).  It is dropped where
-// the second matrix instruction per operand costs time: fp8 KV (the weights keep 8 significant bits
-// against the 4 of the values they multiply; 70B-head-shaped batch 365 -> 343 us), waves with two
-// column tiles and the multi-wave kernel (16 query tokens on long contexts 450 -> 407 us, the
-// shared-prefix pass 53 -> 48 us per step).  The error this leaves is at most 2^-9 max|v| and in
-// practice a few 1e-3, inside the 1e-2 the method is held to.
+// weight) or as one bf16 number?  By default the remainder is kept where it is free: bf16 KV in a
+// wave with one 16-column tile, which waits for memory either way (plain decode above all).  It is
+// dropped where the second matrix instruction per operand costs time: fp8 KV (the weights keep 8
+// significant bits against the 4 of the values they multiply; 70B-head-shaped batch 365 -> 343 us),
+// waves with two column tiles and the multi-wave kernel (16 query tokens on long contexts
+// 450 -> 407 us, the shared-prefix pass 53 -> 48 us per step).  The error this leaves is at most
+// 2^-9 max|v| and in practice a few 1e-3 for values of unit size.  A caller that needs more (values
+// of larger magnitude, an accuracy gate on generated text) sets pa_shape.precise_weights, which
+// keeps the remainder on every path (the kernels' PRECISE parameter).
 constexpr bool p_has_low_part(int kv, int nct, bool multi_wave) { return kv == KV_BF16 && nct == 1 && !multi_wave; }
 
 // Online softmax state of one column (replicated over the four lanes that hold its tokens) and
-// the unnormalised output accumulators out^T[dim, column].
+// the unnormalised output accumulators out^T[dim, column].  The running sum of the weights is an
+// accumulator of the matrix pipe as well: the PV step multiplies the weights by a row of ones
+// next to the value rows, so the sum costs no vector instructions, needs no reduction over the
+// four lanes at the end (every element of lacc is the column's total), and is the sum of exactly
+// the rounded weights that multiplied the values.
 template <int D>
 struct ColumnState {
-    float m, lsum;
+    float m;
+    f32x4 lacc;
     f32x4 acc[D / 16];
 
-    __device__ __forceinline__ void reset()
+    // once, before a wave's first tile
+    __device__ __forceinline__ void clear()
     {
         m = kNegBig;
-        lsum = 0.f;
+        lacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+
+    // A new segment begins.  Only the maximum is reset: the column's first visible score will find
+    // m == kNegBig and wipe the accumulators with a rescale factor of zero (online_softmax), so no
+    // accumulator is written here, on a path every tile's control flow would have to merge with.
+    // Until then they hold the (finite) left-overs of the previous segment: seen() says whether
+    // the column has anything of its own.
+    __device__ __forceinline__ void reset() { m = kNegBig; }
+
+    __device__ __forceinline__ bool seen() const { return m > kNegBig; }
+    __device__ __forceinline__ float weight_sum() const { return lacc[0]; }
 };
+
+// The running maximum is raised only when a score exceeds it by more than this (log2 domain):
+// weights then reach 2^6 at most, which float32 sums and bf16 operands hold as well as values
+// below 1, and the cross-lane maximum, the rescale factor and the rescaling of the accumulators
+// leave the common path (after a sequence's first tiles the maximum rarely moves that far).
+constexpr float kLazyMax = 6.f;
 
 // Online softmax step (log2 domain) on the tile's scores.  The lane's tokens are t0 + {0..3} and
 // t0 + 16 + {0..3}; with MASKED the column sees only tokens low <= t < lim (the end of the context,
 // the causal limit of a multi-token call, the start of a sliding window); without it the whole tile.
-// Leaves the P^T operand in bf16.  With P_LO it is a pair, high part + rounding remainder (16
-// significant bits: the weights lose nothing that matters against the fp32 accumulation) and the PV
-// product costs two matrix instructions per operand; without, the weights enter at bf16 precision
-// (relative rounding error <= 2^-9 each, unbiased) and pb_lo is left alone.  See p_has_low_part().
+// qs (softmax scale * log2 e, times the K scale for fp8) is folded into the exponent:
+// weight = 2^(s * qs - m).  Leaves the P^T operand in bf16.  With P_LO it is a pair, high part +
+// rounding remainder (16 significant bits: the weights lose nothing that matters against the fp32
+// accumulation) and the PV product costs two matrix instructions per operand; without, the weights
+// enter at bf16 precision (relative rounding error <= 2^-9 each, unbiased) and pb_lo is left alone.
+// See p_has_low_part().
 template <bool MASKED, int D, bool P_LO>
 __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1, float qs, int t0, int lim, int low,
                                                ColumnState<D>& st, bf16x8& pb, bf16x8& pb_lo)
 {
-    float x[8];
+    // Two ways to the same exponents.  PRODUCTS: every score is scaled first and the maximum is taken
+    // over the products, so the largest one meets itself in the subtraction and its weight is exactly
+    // 1 (a context of one token returns its value row bit for bit even when the weights carry their
+    // low part); used where instructions are free (P_LO) and on masked tiles.  Otherwise the maximum
+    // is taken over the raw scores and scale and subtraction are one fused multiply-add per score.
+    constexpr bool PRODUCTS = MASKED || P_LO;
+    float v[8];
     bool ok[8];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
+        v[r] = s0[r];
+        v[4 + r] = s1[r];
         ok[r] = !MASKED || (t0 + r < lim && t0 + r >= low);
         ok[4 + r] = !MASKED || (t0 + kBlockSize + r < lim && t0 + kBlockSize + r >= low);
-        x[r] = ok[r] ? s0[r] * qs : kNegBig;
-        x[4 + r] = ok[4 + r] ? s1[r] * qs : kNegBig;
     }
-    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mx = rows_max(mx);
-    const float m_new = fmaxf(st.m, mx);
-    const float alpha = fast_exp2(st.m - m_new);
-    float ps = 0.f;
+    // the largest exponent among this lane's visible tokens
+    float mx;
+    if (PRODUCTS) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        x[r] = ok[r] ? fast_exp2(x[r] - m_new) : 0.f;  // a column may see nothing of a tile
-        ps += x[r];
+        for (int r = 0; r < 8; ++r) v[r] = ok[r] ? v[r] * qs : kNegBig;
+        mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+    } else if (qs >= 0.f) {  // the same for every lane
+        mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))) * qs;
+    } else {
+        mx = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7]))) * qs;
     }
-    st.lsum = st.lsum * alpha + ps;
-    st.m = m_new;
-    if (__any(alpha != 1.f)) {
+    if (__any(mx > st.m + kLazyMax)) {
+        const float m_new = fmaxf(st.m, rows_max(mx));
+        // nothing seen so far: the accumulators hold the previous segment's values, drop them
+        const float alpha = st.seen() ? fast_exp2(st.m - m_new) : 0.f;
+        st.m = m_new;
+        st.lacc *= alpha;
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) st.acc[dt] *= alpha;
+    }
+    const float neg_m = -st.m;
+    float x[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        if (PRODUCTS)
+            x[r] = ok[r] ? fast_exp2(v[r] - st.m) : 0.f;  // a column may see nothing of a tile
+        else
+            x[r] = fast_exp2(fmaf(v[r], qs, neg_m));
     }
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -384,12 +456,20 @@ __device__ __forceinline__ void online_softmax(const f32x4& s0, const f32x4& s1,
 }
 
 // out^T[dim, column] += V^T . P^T for NCT tiles of 16 columns; the V^T operand is read (and, fp8,
-// converted) once for all of them
+// converted) once for all of them.  A row of ones joins the value rows: its product is the sum of
+// the column's weights (ColumnState::lacc).
 template <int D, int KV, int NCT, bool P_LO>
 __device__ __forceinline__ void pv_accumulate(const char* vbuf, const OperandOffsets<D, KV>& of, const bf16x8 (&pb)[NCT],
                                               const bf16x8 (&pb_lo)[NCT], ColumnState<D> (&st)[NCT])
 {
     constexpr int kSlabBytes = KvGeom<D, KV>::kSlab;
+    const __bf16 one = (__bf16)1.0f;
+    const bf16x8 ones{one, one, one, one, one, one, one, one};
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        st[ct].lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[ct], st[ct].lacc, 0, 0, 0);
+        if (P_LO) st[ct].lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb_lo[ct], st[ct].lacc, 0, 0, 0);
+    }
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
         bf16x8 va;

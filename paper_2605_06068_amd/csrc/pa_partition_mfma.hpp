@@ -71,13 +71,14 @@ __device__ __forceinline__ void wait_tile(int later_tiles)
     }
 }
 
-template <int D, int NSTAGE, int CPAD, int KV, bool TRACE>
+// PRECISE: the softmax weights keep their low part on every path (see p_has_low_part).
+template <int D, int NSTAGE, int CPAD, int KV, bool TRACE, bool PRECISE>
 __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
 {
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "ring depth");
     static_assert(CPAD == 4 || CPAD == 8 || CPAD == 16 || CPAD == 32, "padded column count");
     constexpr int NCT = CPAD > 16 ? CPAD / 16 : 1;  // MFMA column tiles
-    constexpr bool P_LO = p_has_low_part(KV, NCT, false);
+    constexpr bool P_LO = PRECISE || p_has_low_part(KV, NCT, false);
     using Geo = KvGeom<D, KV>;
     using QG = QGeom<D>;
     constexpr int kSlabBytes = Geo::kSlab;
@@ -162,42 +163,63 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     const char* qslots = smem + NSTAGE * kStageBytes;
 
     const int64_t head_stride = (int64_t)p.Hkv * kSlabBytes;  // bytes between physical blocks
+    const uint32_t head_stride32 = (uint32_t)p.Hkv * (uint32_t)kSlabBytes;  // the same; the host keeps it below 2^32
     const char* kc = static_cast<const char*>(p.k_cache) + (int64_t)g * kSlabBytes;
     const char* vc = static_cast<const char*>(p.v_cache) + (int64_t)g * kSlabBytes;
 
     int q_issue = 0;  // query slot the issue side fills next
-    auto issue_q = [&](int b) {
+    auto issue_q = [&](int b) __attribute__((always_inline)) {
         const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)b * p.QH + g * G) * QG::kRow;
 #pragma unroll
         for (int r = 0; r < kQLoads; ++r) dma16<false>(ldsq + q_issue * kQSlot + r * 1024, qdma_off[r], qb);
         if (!ONE_SLOT) q_issue = (q_issue + 1 == NSTAGE) ? 0 : q_issue + 1;
     };
-    auto issue = [&](int i, int stage) {
+    int nx_id0 = 0, nx_id1 = 0;  // ids of the tile `ic` stands on ...
+    bool nx_valid = false;       // ... if they were asked for ahead
+    auto issue = [&](int i, int stage) __attribute__((always_inline)) {
         // ring of slots: a new segment starts, send its query rows ahead of its first tile
         if (!ONE_SLOT && (i == 0 || ic.lt == 0)) issue_q(ic.b);
-        TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
-        RawIds raw{};
-        if (TRACE) raw = check_tile_blocks(tb, p.num_blocks);
         const uint32_t ldst = lds0 + stage * kStageBytes;
+        if (!TRACE && nx_valid) {
+            // interior tile, ids already here: every row is visible
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const char* kb = kc + tb.phys[sub] * head_stride;
-            if (TRACE && lane == 0) trace_block_use(p.trace_blocks, tb, raw, sub, 0, ic.b, g, k, p.Hkv, p.MB);
+            for (int sub = 0; sub < 2; ++sub) {
+                const char* kb = kc + (uint64_t)(uint32_t)(sub ? nx_id1 : nx_id0) * head_stride32;
 #pragma unroll
-            for (int r = 0; r < Geo::kDmaPerSlab; ++r)
-                dma16<true>(ldst + sub * kSlabBytes + r * 1024,
-                      live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), kb);
-        }
+                for (int r = 0; r < Geo::kDmaPerSlab; ++r) dma16<true>(ldst + sub * kSlabBytes + r * 1024, dma_off[r], kb);
+            }
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const char* vb = vc + tb.phys[sub] * head_stride;
-            if (TRACE && lane == 0) trace_block_use(p.trace_blocks, tb, raw, sub, 1, ic.b, g, k, p.Hkv, p.MB);
+            for (int sub = 0; sub < 2; ++sub) {
+                const char* vb = vc + (uint64_t)(uint32_t)(sub ? nx_id1 : nx_id0) * head_stride32;
 #pragma unroll
-            for (int r = 0; r < Geo::kDmaPerSlab; ++r)
-                dma16<true>(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024,
-                      live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), vb);
+                for (int r = 0; r < Geo::kDmaPerSlab; ++r)
+                    dma16<true>(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024, dma_off[r], vb);
+            }
+        } else {
+            TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
+            RawIds raw{};
+            if (TRACE) raw = check_tile_blocks(tb, p.num_blocks);
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const char* kb = kc + tb.phys[sub] * head_stride;
+                if (TRACE && lane == 0) trace_block_use(p.trace_blocks, tb, raw, sub, 0, ic.b, g, k, p.Hkv, p.MB);
+#pragma unroll
+                for (int r = 0; r < Geo::kDmaPerSlab; ++r)
+                    dma16<true>(ldst + sub * kSlabBytes + r * 1024,
+                          live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), kb);
+            }
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const char* vb = vc + tb.phys[sub] * head_stride;
+                if (TRACE && lane == 0) trace_block_use(p.trace_blocks, tb, raw, sub, 1, ic.b, g, k, p.Hkv, p.MB);
+#pragma unroll
+                for (int r = 0; r < Geo::kDmaPerSlab; ++r)
+                    dma16<true>(ldst + 2 * kSlabBytes + sub * kSlabBytes + r * 1024,
+                          live_or_stand_in<D, KV>(dma_off[r], dma_row[r], tb.lo[sub], tb.hi[sub]), vb);
+            }
         }
         advance(ic, p.context_lens, B, sp);
+        nx_valid = ask_next_ids(p.block_tables, p.MB, ic, B, reach, nx_id0, nx_id1);
     };
 
     // ---- online softmax state: lane = column n, tokens 4*q4+{0..3} of each block
@@ -205,7 +227,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
     ColumnState<D> st[NCT];
 #pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) st[ct].reset();
+    for (int ct = 0; ct < NCT; ++ct) st[ct].clear();
     bf16x8 qreg[NCT][D / 32];
     int q_comp = 0;       // query slot of the segment being computed
     int seg_first_lt = 0;
@@ -244,7 +266,8 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
         else
             wait_tile<kDmaPerTile / 2, kDmaPerTile, NSTAGE - 1>(later);
         bool refilled = false;  // one slot: query rows of the next segment were issued in this iteration
-        if (tile == 0 || cc.lt == 0) {  // segment start
+        const bool seg_start = tile == 0 || cc.lt == 0;
+        if (seg_start) {
             seg_first_lt = cc.lt;
             if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is mine
                 const int cum = rs.t_lo + tile, end = cum + cc.nt;
@@ -297,17 +320,18 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
             wait_tile<0, kDmaPerTile, NSTAGE - 1>(later);
         pv_accumulate<D, KV, NCT, P_LO>(vbuf, of, pb, pb_lo, st);
 
-        // ---- segment end: finish the row sums, normalise, write
+        // ---- segment end: normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
             const bool whole = seg_first_lt == 0 && cc.lt == cc.nt - 1;  // the entire sequence: final result
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
-                const float l = rows_sum(st[ct].lsum);
+                const float l = st[ct].weight_sum();
                 if (col_ok[ct]) {
                     // a column that saw no token (its query sits before this segment) leaves a zero
                     // row with an "empty" log-sum-exp
-                    const float inv = l > 0.f ? vs / l : 0.f;
-                    const float lse = l > 0.f ? st[ct].m + fast_log2(l) : kNegBig;
+                    const bool seen = st[ct].seen();
+                    const float inv = seen ? vs / l : 0.f;
+                    const float lse = seen ? st[ct].m + fast_log2(l) : kNegBig;
                     if (whole && skip > 0) {  // final but for the prefix part: to the workspace, for the prefix merge
                         const int64_t row = (int64_t)cc.b * p.QH + col_row[ct];
                         if (q4 == 0) p.seq_lse[row] = lse;

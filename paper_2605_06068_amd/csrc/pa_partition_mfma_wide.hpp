@@ -64,13 +64,13 @@ __device__ __forceinline__ void wait_loads(int tiles)
 // caps the register budget at 256, which makes the compiler keep the MFMA accumulators in ordinary
 // VGPRs: with more it parks them in AGPRs and moves all 32 to VGPRs and back in every tile around
 // the rarely taken rescale branch.
-template <int D, int NW, int NCT, int NSTAGE, int KV, bool TRACE, bool PREFIX>
+template <int D, int NW, int NCT, int NSTAGE, int KV, bool TRACE, bool PREFIX, bool PRECISE>
 __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_kernel(const Params p)
 {
     static_assert(NW == 2 || NW == 4 || NW == 8, "waves per workgroup");
     static_assert(NCT == 1 || NCT == 2, "MFMA column tiles per wave");
     constexpr int kWaveCols = 16 * NCT;  // columns one wave computes
-    constexpr bool P_LO = p_has_low_part(KV, NCT, true);
+    constexpr bool P_LO = PRECISE || p_has_low_part(KV, NCT, true);
     static_assert(NSTAGE >= 3, "the ring holds the tile in use, the one being refilled and at least one in flight");
     using Geo = KvGeom<D, KV>;
     using QG = QGeom<D>;
@@ -176,41 +176,57 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     const char* qslot = smem + NSTAGE * kStageBytes + w * kQSlotBytes;
 
     const int64_t head_stride = (int64_t)p.Hkv * kSlabBytes;
+    const uint32_t head_stride32 = (uint32_t)p.Hkv * (uint32_t)kSlabBytes;  // the same; the host keeps it below 2^32
     const char* kc = static_cast<const char*>(p.k_cache) + (int64_t)g * kSlabBytes;
     const char* vc = static_cast<const char*>(p.v_cache) + (int64_t)g * kSlabBytes;
 
-    auto issue_q = [&](int b) {
+    auto issue_q = [&](int b) __attribute__((always_inline)) {
         const char* qb = reinterpret_cast<const char*>(p.q) + ((int64_t)b * (Q * p.Hq) + g * G) * QG::kRow;
 #pragma unroll
         for (int r = 0; r < kQLoads; ++r) dma16<false>(ldsq + r * 1024, qdma_off[r], qb);
     };
     // returns whether this wave put loads in flight
-    auto issue = [&](int stage) {
-        TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
-        if (TRACE) {
-            const RawIds raw = check_tile_blocks(tb, p.num_blocks);
-            // the waves of a workgroup load different slabs of the tile from the same two ids: each loading
-            // wave records the (block, K or V) pairs of its own instructions, for the first column group.
-            // The prefix pass reads row 0 of the table for the whole batch and records its range as -2 - k.
-            if (loader && lane == 0 && col0 == 0) {
-#pragma unroll
-                for (int j = 0; j < PT; ++j)
-                    trace_block_use(p.trace_blocks, tb, raw, my_slab[j] & 1, my_slab[j] >> 1, ic.b, g, PREFIX ? -2 - k : k,
-                                    p.Hkv, p.MB);
-            }
-        }
+    int nx_id0 = 0, nx_id1 = 0;  // ids of the tile `ic` stands on ...
+    bool nx_valid = false;       // ... if they were asked for ahead
+    auto issue = [&](int stage) __attribute__((always_inline)) {
         const uint32_t ldst = lds0 + stage * kStageBytes;
-        if (loader) {
+        if (!TRACE && nx_valid) {
+            // interior tile, ids already here: every row is visible
+            if (loader) {
 #pragma unroll
-            for (int j = 0; j < PT; ++j) {
-                const int sub = my_slab[j] & 1;
-                const char* base = (my_slab[j] >> 1 ? vc : kc) + (sub ? tb.phys[1] : tb.phys[0]) * head_stride;
-                dma16<!PREFIX>(ldst + my_dst[j],  // the prefix pass measured 3 % faster with ordinary loads
-                      live_or_stand_in<D, KV>(my_off[j], my_tok[j], sub ? tb.lo[1] : tb.lo[0], sub ? tb.hi[1] : tb.hi[0]),
-                      base);
+                for (int j = 0; j < PT; ++j) {
+                    const uint32_t id = (uint32_t)((my_slab[j] & 1) ? nx_id1 : nx_id0);
+                    const char* base = (my_slab[j] >> 1 ? vc : kc) + (uint64_t)id * head_stride32;
+                    dma16<!PREFIX>(ldst + my_dst[j], my_off[j], base);  // the prefix pass measured 3 % faster with ordinary loads
+                }
+            }
+        } else {
+            TileBlocks tb = tile_blocks(p.block_tables, p.MB, ic, reach);
+            if (TRACE) {
+                const RawIds raw = check_tile_blocks(tb, p.num_blocks);
+                // the waves of a workgroup load different slabs of the tile from the same two ids: each loading
+                // wave records the (block, K or V) pairs of its own instructions, for the first column group.
+                // The prefix pass reads row 0 of the table for the whole batch and records its range as -2 - k.
+                if (loader && lane == 0 && col0 == 0) {
+#pragma unroll
+                    for (int j = 0; j < PT; ++j)
+                        trace_block_use(p.trace_blocks, tb, raw, my_slab[j] & 1, my_slab[j] >> 1, ic.b, g, PREFIX ? -2 - k : k,
+                                        p.Hkv, p.MB);
+                }
+            }
+            if (loader) {
+#pragma unroll
+                for (int j = 0; j < PT; ++j) {
+                    const int sub = my_slab[j] & 1;
+                    const char* base = (my_slab[j] >> 1 ? vc : kc) + (sub ? tb.phys[1] : tb.phys[0]) * head_stride;
+                    dma16<!PREFIX>(ldst + my_dst[j],
+                          live_or_stand_in<D, KV>(my_off[j], my_tok[j], sub ? tb.lo[1] : tb.lo[0], sub ? tb.hi[1] : tb.hi[0]),
+                          base);
+                }
             }
         }
         advance(ic, p.context_lens, B, sp);
+        nx_valid = ask_next_ids(p.block_tables, p.MB, ic, B, reach, nx_id0, nx_id1);
         return loader;
     };
 
@@ -218,7 +234,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
     ColumnState<D> st[NCT];
 #pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) st[ct].reset();
+    for (int ct = 0; ct < NCT; ++ct) st[ct].clear();
     bf16x8 qreg[NCT][D / 32];
     int seg_first_lt = 0;
 
@@ -230,7 +246,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         if (t < ntiles && issue(t)) ++q_age;
 
     // what a wave does when tile `tile` (the compute cursor stands on it) begins a segment
-    auto begin_segment = [&](int tile) {
+    auto begin_segment = [&](int tile) __attribute__((always_inline)) {
         seg_first_lt = cc.lt;
         if (describes && cc.lt == 0 && lane == 0) {  // the sequence's first tile is this workgroup's
             const int cum = rs.t_lo + tile, end = cum + cc.nt;
@@ -253,7 +269,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
         }
     };
     // softmax, PV and, at the end of a segment, the result of tile `tile` from its scores
-    auto finish_tile = [&](int tile, const char* vbuf, const f32x4 (&s0)[NCT], const f32x4 (&s1)[NCT]) {
+    auto finish_tile = [&](int tile, const char* vbuf, const f32x4 (&s0)[NCT], const f32x4 (&s1)[NCT]) __attribute__((always_inline)) {
         // The column sees tokens low <= t < lim.  Only the last tiles of a sequence (where the causal
         // limits lie) and the tiles where the columns' sliding windows begin need the mask:
         // everywhere else every column sees the whole tile.
@@ -274,17 +290,18 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
 
         pv_accumulate<D, KV, NCT, P_LO>(vbuf, of, pb, pb_lo, st);
 
-        // ---- segment end: finish the row sums, normalise, write
+        // ---- segment end: normalise, write
         if (cc.lt == cc.nt - 1 || tile == ntiles - 1) {
             const bool whole = seg_first_lt == 0 && cc.lt == cc.nt - 1;
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
-                const float l = rows_sum(st[ct].lsum);
+                const float l = st[ct].weight_sum();
                 if (col_ok[ct]) {
                     // a column that saw no token (its query sits before this segment) leaves a zero row
                     // with an "empty" log-sum-exp
-                    const float inv = l > 0.f ? vs / l : 0.f;
-                    const float lse = l > 0.f ? st[ct].m + fast_log2(l) : kNegBig;
+                    const bool seen = st[ct].seen();
+                    const float inv = seen ? vs / l : 0.f;
+                    const float lse = seen ? st[ct].m + fast_log2(l) : kNegBig;
                     if (PREFIX) {
                         const int64_t slot = (int64_t)k * ((int64_t)p.B * p.QH) + col_row[ct];
                         if (q4 == 0) p.prefix_lse[slot] = lse;

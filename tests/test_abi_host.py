@@ -15,7 +15,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def shape(**kw):
     base = dict(batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
-                num_blocks=1024, max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0, out_dtype=0)
+                num_blocks=1024, max_context_len=0, num_partitions=0, q_len=0, shared_prefix_blocks=0, window=0, out_dtype=0,
+                precise_weights=0)
     base.update(kw)
     return pa.make_shape(**base)
 
@@ -188,6 +189,8 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
     (dict(out_dtype=2), pa.PA_ERR_INVALID_ARG),
     (dict(out_dtype=-1), pa.PA_ERR_INVALID_ARG),
+    (dict(precise_weights=2), pa.PA_ERR_INVALID_ARG),
+    (dict(num_kv_heads=2 ** 17, num_q_heads=2 ** 17), pa.PA_ERR_UNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected(bad, code):
     s = shape(**bad)
@@ -287,11 +290,12 @@ def test_bench_reads_counters_only_for_the_workload_it_ran():
     import bench
 
     base = "llama3_8b_b64_ctx512-4096_bf16"
-    assert bench.recorded_traffic(base + "_qlen7") is None
-    assert bench.recorded_traffic(base + "_window5") is None
-    assert bench.recorded_traffic("no_such_workload") is None
-    got = bench.recorded_traffic(base)
+    assert bench.recorded_traffic(base + "_qlen7")[0] is None
+    assert bench.recorded_traffic(base + "_window5")[0] is None
+    assert bench.recorded_traffic("no_such_workload")[0] is None
+    got, where = bench.recorded_traffic(base)
     assert got is None or got > 577_638_400  # when the summary is current: at least the KV bytes of that batch
+    assert isinstance(where, str) and where  # ... and the line always says where the figure comes from, or why there is none
 
 
 def test_check_tables_rejects_bad_arguments_before_any_launch():
