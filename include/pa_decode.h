@@ -60,7 +60,7 @@
  * are read once for the whole batch, with the (sequence, head) pairs as matrix columns, instead
  * of once per sequence; the rest of every context is processed per sequence as usual and a merge
  * kernel joins the two by their log-sum-exps.  The promise is not checked on the device: block
- * ids of the prefix are taken from row 0 of block_tables.  Supported for Q * G <= 32; in a
+ * ids of the prefix are taken from row 0 of block_tables.  Supported for Q * G <= 128; in a
  * multi-token call every query token must lie after the prefix (context_lens[b] >= prefix tokens
  * + Q - 1).
  *

@@ -176,7 +176,6 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
 {
     const int cols = columns(s);
     if (cols <= 16) return true;
-    if (shared_tiles(s) > 0) return true;  // only the one-wave kernel leaves a prefix out of its plan (groups of up to 32)
     if (cols > max_cols_one_wave(s->head_dim, (int)kv)) return false;
     const int64_t P = s->num_partitions > 0 ? s->num_partitions
                                             : (int64_t)compute_units() * one_wave_per_cu(s, kv) / s->num_kv_heads;
@@ -213,8 +212,8 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
     if (s->batch > kMaxBatch) return PA_ERR_UNSUPPORTED;  // the merge kernels index sequences by blockIdx.y
     if (s->num_kv_heads > 65536) return PA_ERR_UNSUPPORTED;  // bytes between physical blocks fit 32 bits
     if (shared_tiles(s) > 0) {
-        // the per-sequence pass runs on the one-wave kernel (up to 32 columns), the prefix pass on the multi-wave one
-        if (s->batch < 1 || columns(s) > 32) return PA_ERR_UNSUPPORTED;
+        // the per-sequence pass takes one workgroup's columns, the prefix pass any number
+        if (s->batch < 1 || columns(s) > kMaxColsMfma) return PA_ERR_UNSUPPORTED;
         // every query token lies after the prefix
         if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens + query_len(s) - 1) return PA_ERR_INVALID_ARG;
     }

@@ -102,9 +102,12 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     const int n = lane & 15;
     const int q4 = lane >> 4;
 
-    // sliding window (never together with a shared prefix): see the single-wave kernel
+    // sliding window (never together with a shared prefix): see the single-wave kernel.  In the
+    // per-sequence pass of a shared-prefix call the first skip tiles of every sequence belong to the
+    // prefix pass, and no row this pass writes is final (the prefix merge adds the prefix part).
     const int reach = (!PREFIX && p.window > 0) ? p.window + Q - 1 : 0;
-    const Span sp{0, reach};
+    const int skip = PREFIX ? 0 : p.skip_tiles;
+    const Span sp{skip, reach};
     RangeStart rs;
     if (PREFIX) {
         rs.T = p.skip_tiles;
@@ -116,7 +119,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     } else {
         rs = find_range(p.context_lens, B, k, p.P, lane, sp);
     }
-    if (!PREFIX && w == 0 && col0 == 0) zero_rows_of_empty_contexts(p, k, g, B, Q, D, lane);
+    if (!PREFIX && skip == 0 && w == 0 && col0 == 0) zero_rows_of_empty_contexts(p, k, g, B, Q, D, lane);  // (behind a shared prefix no context is empty)
     const bool describes = !PREFIX && g == 0 && w == 0 && col0 == 0 && p.merge_desc != nullptr;  // tells the merge about its sequences
     if (describes && p.cut_list != nullptr && lane == 0)  // does my range start inside a sequence, and which
         p.cut_list[k] = (rs.t_lo < rs.t_hi && rs.t_lo > rs.cum) ? rs.b : -1;
@@ -262,7 +265,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
             int nb = cc.b;
             do {
                 ++nb;
-            } while (nb < B - 1 && uniform_load(p.context_lens, nb) <= 0);
+            } while (nb < B - 1 && tiles_of(uniform_load(p.context_lens, nb), sp) == 0);  // (none of its own behind a shared prefix counts as empty)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the slot has been read
             issue_q(nb);
             q_age = 0;
@@ -306,6 +309,10 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
                         const int64_t slot = (int64_t)k * ((int64_t)p.B * p.QH) + col_row[ct];
                         if (q4 == 0) p.prefix_lse[slot] = lse;
                         store_partial_row(p.prefix_o + slot * D, st[ct], inv, q4);
+                    } else if (whole && skip > 0) {  // final but for the prefix part: to the workspace, for the prefix merge
+                        const int64_t row = (int64_t)cc.b * p.QH + col_row[ct];
+                        if (q4 == 0) p.seq_lse[row] = lse;
+                        store_partial_row(p.seq_o + row * D, st[ct], inv, q4);
                     } else if (whole) {
                         store_final_row(p, ((int64_t)cc.b * p.QH + col_row[ct]) * D, st[ct], inv, q4);
                     } else {

@@ -182,9 +182,9 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(shared_prefix_blocks=-2), pa.PA_ERR_INVALID_ARG),
     (dict(shared_prefix_blocks=257), pa.PA_ERR_INVALID_ARG),              # more than a table row holds
     (dict(shared_prefix_blocks=8, max_context_len=100), pa.PA_ERR_INVALID_ARG),  # contexts shorter than the prefix
-    (dict(shared_prefix_blocks=8, q_len=16), pa.PA_ERR_UNSUPPORTED),             # more than 32 columns
+    (dict(shared_prefix_blocks=8, q_len=33), pa.PA_ERR_UNSUPPORTED),             # more than 128 columns
     (dict(shared_prefix_blocks=8, q_len=4, max_context_len=130), pa.PA_ERR_INVALID_ARG),  # a query token inside the prefix
-    (dict(shared_prefix_blocks=8, num_q_heads=8 * 40), pa.PA_ERR_UNSUPPORTED),  # groups wider than 32
+    (dict(shared_prefix_blocks=8, num_q_heads=8 * 129), pa.PA_ERR_UNSUPPORTED),  # groups wider than 128
     (dict(window=-1), pa.PA_ERR_INVALID_ARG),
     (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
     (dict(out_dtype=2), pa.PA_ERR_INVALID_ARG),

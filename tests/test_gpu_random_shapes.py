@@ -43,7 +43,7 @@ def draw_case(seed):
         G = int(rng.choice([1, 2, 4, 8, 16, 32]))
         prefix_blocks = int(rng.choice([1, 2, 3, 4, 7, 8, 21, 40]))
         if kind == "prefix-verify":
-            Q = int(rng.integers(2, 1 + max(2, 32 // G))) if G <= 16 else 1
+            Q = int(rng.integers(2, 1 + max(2, 128 // G)))  # up to 128 columns per KV head behind a shared prefix
     B = int(rng.choice([1, 2, 3, 5, 8, 17, 40]))
     style = rng.choice(["short", "mixed", "long"])
     hi = {"short": 70, "mixed": 600, "long": 1500}[style]
