@@ -210,12 +210,12 @@ __device__ __forceinline__ bool ask_next_ids(const int32_t* block_tables, int MB
 // place, so a table with a bad entry at a valid position shows up in the trace instead of as a
 // memory fault.  All lanes must call (the ids are wave-uniform).
 struct RawIds {
-    int id[2];
+    int id0, id1;  // (plain scalars: an array indexed at run time would live in scratch memory)
 };
 
 __device__ __forceinline__ RawIds check_tile_blocks(TileBlocks& t, int num_blocks)
 {
-    RawIds raw{{t.phys[0], t.phys[1]}};
+    const RawIds raw{t.phys[0], t.phys[1]};
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
         if ((unsigned)t.phys[sub] >= (unsigned)num_blocks) t.phys[sub] = 0;
@@ -231,7 +231,7 @@ __device__ __forceinline__ void trace_block_use(int32_t* trace, const TileBlocks
 {
     if (sub == 0 ? t.first_gone : !t.second) return;
     int32_t* v = trace + (((int64_t)b * Hkv + g) * MB + t.j0 + sub) * 3;
-    v[which] = raw.id[sub];
+    v[which] = sub ? raw.id1 : raw.id0;
     if (which == 0) v[2] = k;
 }
 

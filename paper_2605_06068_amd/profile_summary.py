@@ -15,6 +15,9 @@ and reduces their CSV output to a text file of `key: value` lines (bench.py read
 WRITE_SIZE (KiB per dispatch) are scaled by what the same counters read, in the same run, for the
 largest device-to-device copy of a KV pool, whose size is known.  Raw profiler output goes to a
 scratch directory under gpurun_out/ and is deleted afterwards.
+
+Two more modes need no GPU:  --resources OUT.txt  tabulates registers, LDS and scratch of every kernel
+from the compiler's remarks;  --index FOLDER  writes FOLDER/INDEX.md from the summaries in it.
 """
 from __future__ import annotations
 
@@ -81,8 +84,94 @@ def short(name):
     return name.replace("void ", "").replace("(pa::Params)", "").replace("(pa::CheckParams)", "")
 
 
+def write_resources(out_path):
+    """Registers, LDS and scratch of every kernel as the compiler reports them (no GPU needed)."""
+    import re
+
+    sys.path.insert(0, ROOT)
+    from paper_2605_06068_amd import build as pa_build
+
+    cmd = [pa_build.hipcc(), pa_build.ARCH, *pa_build.COMMON_FLAGS, *pa_build.DEVICE_ONLY_FLAGS, "--cuda-device-only",
+           "-Rpass-analysis=kernel-resource-usage", f"-I{pa_build.INCLUDE}", f"-I{pa_build.CSRC}", "-S", "-o", os.devnull,
+           *pa_build.sources()]
+    text = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, check=True).stdout.decode()
+    rows, cur = [], None
+    for line in text.splitlines():
+        m = re.search(r"remark:\s+(.*?): (.*?) \[-Rpass", line)
+        if not m:
+            continue
+        k, v = m.group(1).strip(), m.group(2).strip()
+        if k == "Function Name":
+            cur = {"name": v}
+            rows.append(cur)
+        elif cur is not None:
+            cur[k] = v
+    names = subprocess.run(["c++filt"] + [r["name"] for r in rows], stdout=subprocess.PIPE, check=True).stdout.decode().splitlines()
+    table = []
+    for r, n in zip(rows, names):
+        n = re.sub(r"\(.*\)$", "", n.replace("void pa::", "")).strip()
+        table.append((n, r["TotalSGPRs"], r["VGPRs"], r["AGPRs"], r["ScratchSize [bytes/lane]"],
+                      r["SGPRs Spill"] + "/" + r["VGPRs Spill"], r["LDS Size [bytes/block]"], r["Occupancy [waves/SIMD]"]))
+    scratch_free = all(t[4] == "0" and t[5].endswith("/0") for t in table)
+    w = max(len(t[0]) for t in table)
+    fmt = "%-*s %5s %5s %5s %7s %7s %7s %4s\n"
+    with open(out_path, "w") as fh:
+        fh.write("# Register, LDS and scratch use of every kernel of the library, as the compiler reports it (gfx950).\n"
+                 "# Command (from the repository root; no GPU needed):\n"
+                 f"#   python3 -m paper_2605_06068_amd.profile_summary --resources {os.path.relpath(out_path, ROOT)}\n"
+                 "# which compiles the device code with -Rpass-analysis=kernel-resource-usage and tabulates the remarks: TotalSGPRs, VGPRs,\n"
+                 "# AGPRs, ScratchSize [bytes/lane], spills (SGPR/VGPR), LDS Size [bytes/block], and the occupancy the compiler derives\n"
+                 "# from registers and LDS (waves/SIMD).\n"
+                 "# Template arguments: partition_mfma_kernel<D, NSTAGE, CPAD, KV(0 bf16, 1 fp8), TRACE, PRECISE>;\n"
+                 "#                     partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, TRACE, PREFIX, PRECISE>.\n"
+                 + ("# No kernel uses scratch memory or spills a vector register.  The scalar registers counted under spills live in\n"
+                    "# lanes of a vector register (v_writelane / v_readlane), not in memory.\n" if scratch_free else
+                    "# SOME KERNELS USE SCRATCH MEMORY OR SPILL VECTOR REGISTERS: see the scratch and spills columns.\n"))
+        fh.write(f"kernel_source_sha256: {pa_build.source_digest()}\n")
+        fh.write(fmt % (w, "kernel", "sgpr", "vgpr", "agpr", "scratch", "spills", "lds", "occ"))
+        for t in sorted(table):
+            fh.write(fmt % ((w,) + t))
+    print(f"{out_path}: {len(table)} kernels, scratch-free: {scratch_free}")
+
+
+def write_index(folder):
+    """INDEX.md: one line per summary in `folder`."""
+    rows = []
+    for f in sorted(os.listdir(folder)):
+        if not f.endswith(".txt") or f.startswith("kernel_resources"):
+            continue
+        kv = {}
+        with open(os.path.join(folder, f)) as fh:
+            for line in fh:
+                if ":" in line and not line.startswith("#"):
+                    k, v = line.split(":", 1)
+                    kv[k.strip()] = v.strip()
+        if "partition_avg_ns" not in kv:
+            continue
+        counters = "yes" if any(k.startswith("partition_SQ_") for k in kv) else ""
+        rows.append(f"| `{f}` | `{kv.get('partition_kernel', '?')}` | {float(kv['partition_avg_ns']) / 1e3:.1f} µs | "
+                    f"{100 * float(kv['partition_frac_of_8000_GBps']):.1f} % | {float(kv['all_kernels_avg_ns_per_step']) / 1e3:.1f} µs | "
+                    f"{kv.get('traffic_over_algorithmic', '-')} | {counters} |")
+    with open(os.path.join(folder, "INDEX.md"), "w") as fh:
+        fh.write("# rocprofv3 summaries in this folder\n\n"
+                 "One file per kernel and workload, written by `python3 -m paper_2605_06068_amd.profile_summary` (each file names its\n"
+                 "full command, which runs `bench.py` of this repository under rocprofv3, and the hash of the kernel sources the figures\n"
+                 "belong to). Durations are rocprofv3 averages per launch; the fraction is algorithmic KV bytes / duration / 8000 GB/s;\n"
+                 "traffic is measured HBM bytes (FETCH_SIZE + WRITE_SIZE, calibrated on a copy of known size) over algorithmic KV bytes;\n"
+                 "files marked under *counters* also hold the issue / LDS / occupancy / cache counters of their kernels.\n"
+                 "`kernel_resources_gfx950.txt` lists registers, LDS and scratch of every kernel as the compiler reports them.\n"
+                 "This index: `python3 -m paper_2605_06068_amd.profile_summary --index profiles`.\n\n"
+                 "| file | dominant kernel | its time | of HBM peak | all kernels of a step | traffic / algorithmic | counters |\n"
+                 "|---|---|---|---|---|---|---|\n" + "\n".join(rows) + "\n")
+    print(f"{folder}/INDEX.md: {len(rows)} summaries")
+
+
 def main():
     argv = sys.argv[1:]
+    if len(argv) == 2 and argv[0] == "--resources":
+        return write_resources(os.path.abspath(argv[1]))
+    if len(argv) == 2 and argv[0] == "--index":
+        return write_index(os.path.abspath(argv[1]))
     bench_args = []
     if "--" in argv:
         i = argv.index("--")

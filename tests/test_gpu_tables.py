@@ -293,3 +293,38 @@ def test_prefix_pass_trace_on_the_prompt_cache_workload(pa, oracle):
     want = oracle.decode_batch(b, rows=rows)["out"]
     sel = np.stack([got[s, h] for s, h in rows])
     assert_parity(sel[:, None, :], want[:, None, :], b.kv_dtype, "prompt-cache workload, instrumented")
+
+
+def test_table_check_in_a_hip_graph(pa, oracle):
+    """The check is three launches and no memset, so a serving loop can capture it beside its decode
+    step: captured once, replayed over tables that change between replays (clean, spoiled, clean,
+    spoiled elsewhere), every replay compared with the oracle's check and with the eager call."""
+    import torch
+
+    b = W.make_config(2, length_scale=0.25)
+    s = shape_of(pa, b)
+    t = torch.from_numpy(b.block_tables).cuda()
+    l = torch.from_numpy(b.context_lens).cuda()
+    report = torch.full((8,), 777, dtype=torch.int32, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pa.pa_check_tables(t, l, shape=s, report=report)  # warm-up outside capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            pa.pa_check_tables(t, l, shape=s, report=report)
+    torch.cuda.synchronize()
+    for i, spoil in enumerate([None, (5, 3, -1), None, (40, 0, b.num_blocks), (2, 1, 2 ** 30)]):
+        tables = b.block_tables.copy()
+        if spoil is not None:
+            tables[spoil[0], spoil[1]] = spoil[2]
+        t.copy_(torch.from_numpy(tables))
+        report.fill_(777)
+        graph.replay()
+        torch.cuda.synchronize()
+        r = report.cpu().numpy()
+        got = (int(r[4]), tuple(int(x) for x in r[:4]))
+        print(f"[case] table check, graph replay {i}: {got}", flush=True)
+        assert got == oracle_check(oracle, tables, b.context_lens, s) == gpu_check(pa, tables, b.context_lens, s)
+        _ = (torch.randn(1 << 16, device="cuda") * 2).sum().item()  # unrelated eager work between replays

@@ -79,3 +79,44 @@ def test_static_scratch_refuses_what_does_not_fit(pa):
     with pytest.raises(pa.PaError) as e:
         pa.pa_decode_static(None, *small.args()[1:], shape=small.shape)
     assert e.value.status == pa.PA_ERR_INVALID_ARG
+
+
+def test_static_scratch_call_replayed_from_a_hip_graph(pa, oracle):
+    """What the entry point is for: a caller under graph capture.  After one eager call on the
+    device (which looks the array's address up), the call is captured once and replayed with q
+    updated in place; every replay is checked against the oracle and against pa_decode run eagerly
+    on the same inputs, with unrelated eager work and synchronisations between the replays."""
+    import torch
+
+    rng = np.random.default_rng(21)
+    b = W.make_config(2, length_scale=0.25, poison=False)
+    dev = pa.DeviceBatch(b)
+    out_eager = torch.empty_like(dev.out)
+
+    def enqueue():
+        pa.pa_decode_static(*dev.args(), shape=dev.shape)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue()  # warm-up outside capture: the first call on a device resolves the array's address
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for i in range(4):
+        q_new = W.f32_to_bf16_bits((rng.standard_normal(b.q.shape) * 0.5).astype(np.float32))
+        b.q = q_new
+        dev.q.copy_(torch.from_numpy(q_new.view(np.int16)))
+        dev.out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dev.out.cpu().numpy().copy()
+        want = oracle.decode_batch(b)["out"]
+        assert_parity(got, want, b.kv_dtype, f"static scratch, graph replay {i}")
+        pa.pa_decode(dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens, dev.scale, dev.kv_dtype,
+                     out_eager, dev.k_scale, dev.v_scale, shape=dev.shape, workspace=dev.workspace)
+        torch.cuda.synchronize()
+        assert np.array_equal(out_eager.cpu().numpy(), got)
+        _ = (torch.randn(1 << 16, device="cuda") * 2).sum().item()  # unrelated eager work between replays
