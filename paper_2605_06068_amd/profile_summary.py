@@ -40,7 +40,8 @@ COUNTER_SETS = [
      "SQ_INSTS_SALU", "SQ_INSTS_VMEM"],
     ["SQ_BUSY_CYCLES", "SQ_WAVE_CYCLES", "SQ_ACTIVE_INST_VALU", "SQ_ACTIVE_INST_LDS", "SQ_VALU_MFMA_BUSY_CYCLES",
      "SQ_WAIT_INST_ANY", "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_ANY"],
-    ["SQ_WAVES", "SQ_BUSY_CU_CYCLES", "SQ_INSTS_SMEM", "SQ_INSTS_VALU_CVT", "SQ_INSTS_VALU_TRANS_F32", "SQ_ACTIVE_INST_SCA"],
+    ["SQ_WAVES", "SQ_BUSY_CU_CYCLES", "SQ_INSTS_SMEM", "SQ_INSTS_VALU_CVT", "SQ_INSTS_VALU_TRANS_F32", "SQ_ACTIVE_INST_SCA",
+     "SQ_VALU_MFMA_COEXEC_CYCLES"],
     ["SQC_DCACHE_REQ", "SQC_DCACHE_HITS", "SQC_DCACHE_MISSES", "SQC_TC_DATA_READ_REQ"],
     ["TCC_HIT_sum", "TCC_MISS_sum", "TCC_REQ_sum"],
 ]
@@ -281,6 +282,7 @@ def main():
                 # cycles and SQ_VALU_MFMA_BUSY_CYCLES in cycles, both summed over the 1024 SIMDs
                 ("valu_pipe_issuing_share_of_kernel_time_per_simd", ratio("SQ_ACTIVE_INST_VALU", "SQ_BUSY_CYCLES", "{:.4f}", 4.0 * 32 / 1024)),
                 ("matrix_pipe_busy_share_of_kernel_time_per_simd", ratio("SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CYCLES", "{:.4f}", 32.0 / 1024)),
+                ("matrix_pipe_busy_cycles_with_a_vector_instruction_issuing_share", ratio("SQ_VALU_MFMA_COEXEC_CYCLES", "SQ_VALU_MFMA_BUSY_CYCLES")),
                 ("resident_waves_per_simd_while_busy", ratio("SQ_WAVE_CYCLES", "SQ_BUSY_CYCLES", "{:.2f}", 4.0 * 32 / 1024)),
                 ("wave_cycles_waiting_on_any_instruction_share", ratio("SQ_WAIT_INST_ANY", "SQ_WAVE_CYCLES")),
                 ("wave_cycles_waiting_on_lds_share", ratio("SQ_WAIT_INST_LDS", "SQ_WAVE_CYCLES")),
