@@ -14,6 +14,7 @@
 #include "pa_kv_append.hpp"
 #include "pa_merge.hpp"
 #include "pa_partition_mfma.hpp"
+#include "pa_partition_mfma_staged.hpp"
 #include "pa_partition_mfma_wide.hpp"
 #include "pa_plan.hpp"
 
@@ -71,6 +72,7 @@ constexpr int kMergeRowsFrom = 128;
 struct Plan {
     int32_t P;          // partitions of the global tile sequence
     bool one_wave;      // the per-sequence pass runs on the one-wave kernel
+    bool staged;        // ... on the stage-split kernel
     int32_t max_ctx;    // resolved max context length
     size_t lse_offset;  // byte offset of the lse array inside the workspace
     size_t desc_offset; // byte offset of the merge descriptors
@@ -185,10 +187,30 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
 // workgroups of up to 128 columns a call needs side by side (more than one: the cache is read once per group)
 int column_groups(const pa_shape* s) { return (columns(s) + kMaxColsMfma - 1) / kMaxColsMfma; }
 
+// Above 32 columns at head_dim 128 the per-sequence pass runs on the stage-split kernel (eight
+// waves: four compute scores and weights, four the PV product of the tile before), unless the
+// weights are to keep their low part, which its hand-over buffers have no room for.  bf16 KV with
+// more than 64 columns stays on the multi-wave kernel: only one stage-split workgroup would fit a
+// compute unit's LDS (8B-shaped batch, 32 query tokens: 197 against 169 us per step).
+bool staged(const pa_shape* s, pa_kv_dtype kv)
+{
+    if (one_wave(s, kv) || columns(s) <= 32 || s->head_dim != 128 || s->precise_weights != 0) return false;
+    return kv == PA_KV_FP8_E4M3 || columns(s) <= 64;
+}
+
+// column tiles per wave of that kernel, and its resident workgroups per compute unit
+int staged_nct(const pa_shape* s) { return columns(s) > 64 ? 2 : 1; }
+int staged_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
+{
+    const int fit = kLdsPerCu / pa::staged_lds_bytes(s->head_dim, staged_nct(s), (int)kv);
+    return fit < 2 ? fit : 2;
+}
+
 // waves (one-wave kernel) or workgroups (multi-wave kernel) resident per compute unit
 int groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
 {
     const int cols = columns(s) < kMaxColsMfma ? columns(s) : kMaxColsMfma;
+    if (staged(s, kv)) return staged_groups_per_cu(s, kv);
     return one_wave(s, kv) ? one_wave_per_cu(s, kv) : wide_groups_per_cu(s->head_dim, (int)kv, wide_shape(cols, false));
 }
 
@@ -236,6 +258,7 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
     plan->max_ctx = s->max_context_len > 0 ? s->max_context_len : s->max_blocks_per_seq * s->block_size;
     plan->skip_tiles = shared_tiles(s);
     plan->one_wave = one_wave(s, kv);
+    plan->staged = staged(s, kv);
     if (s->num_partitions > 0) {
         plan->P = s->num_partitions;
     } else {
@@ -326,11 +349,30 @@ void launch_wide(const Params& p, bool trace, bool precise, dim3 grid, hipStream
     }
 }
 
-// the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2 or 4 waves above
+template <int D, int NCT, int KV>
+void launch_staged(const Params& p, bool trace, dim3 grid, hipStream_t st)
+{
+    if constexpr (D == 128) {
+        if (trace)
+            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NCT, KV, true>), grid, dim3(pa::kStagedWaves * 64), 0, st, p);
+        else
+            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NCT, KV, false>), grid, dim3(pa::kStagedWaves * 64), 0, st, p);
+    }
+}
+
+// the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2 or 4 waves
+// or the stage-split workgroup of 8 above
 template <int D, int KV>
-void launch_partition(const Params& p, bool one_wave, bool trace, bool precise, dim3 grid, hipStream_t st)
+void launch_partition(const Params& p, bool one_wave, bool staged, bool trace, bool precise, dim3 grid, hipStream_t st)
 {
     const int cols = p.Q * p.G;
+    if (staged) {
+        if (cols <= 64)
+            launch_staged<D, 1, KV>(p, trace, grid, st);
+        else if constexpr (KV == pa::KV_FP8)
+            launch_staged<D, 2, KV>(p, trace, grid, st);
+        return;
+    }
     if (cols <= 4)
         launch_mfma<D, 4, KV>(p, trace, precise, grid, st);
     else if (cols <= 8)
@@ -447,7 +489,7 @@ pa_status run(const void* q, const void* k_cache, const void* v_cache, const int
             if (hipGetLastError() != hipSuccess) { launched = false; return; }
         }
         const dim3 grid((uint32_t)plan.P * (uint32_t)p.Hkv * (uint32_t)column_groups(shape));
-        launch_partition<D, KV>(p, plan.one_wave, trace, precise, grid, hs);
+        launch_partition<D, KV>(p, plan.one_wave, plan.staged, trace, precise, grid, hs);
         if (hipGetLastError() != hipSuccess) { launched = false; return; }
         if (ev && hipEventRecord(ev->between, hs) != hipSuccess) { launched = false; return; }
 
@@ -700,7 +742,7 @@ pa_status pa_check_tables(const int32_t* block_tables, const int32_t* context_le
 const char* pa_kernel_variant(const pa_shape* shape, pa_kv_dtype kv_dtype)
 {
     if (check_shape(shape, kv_dtype) != PA_OK) return nullptr;
-    return one_wave(shape, kv_dtype) ? "mfma" : "mfma-wide";
+    return one_wave(shape, kv_dtype) ? "mfma" : (staged(shape, kv_dtype) ? "mfma-staged" : "mfma-wide");
 }
 
 const char* pa_source_digest(void)

@@ -79,10 +79,15 @@ def test_workspace_size_covers_partials():
 
 def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     one = shape(num_partitions=16)
-    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_BF16) == "mfma-wide"  # 128 columns per KV head
+    # 128 columns per KV head: the stage-split workgroup at head_dim 128, unless the weights keep their low part
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_FP8_E4M3) == "mfma-staged"
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_BF16) == "mfma-wide"  # bf16: up to 64 columns
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=8), pa.PA_KV_BF16) == "mfma-staged"
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16, precise_weights=1), pa.PA_KV_BF16) == "mfma-wide"
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16, head_dim=64), pa.PA_KV_BF16) == "mfma-wide"
     for Q in (2, 4, 16):
         win = shape(num_partitions=16, q_len=Q)
-        assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == ("mfma" if Q * 4 <= 32 else "mfma-wide")  # 512 tiles, 16 partitions
+        assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == ("mfma" if Q * 4 <= 32 else "mfma-staged")  # 512 tiles, 16 partitions
         need = 2 * 16 * Q * 32 * (128 + 1) * 4 + 4 * 16 + 16 * 4
         assert need <= pa.pa_decode_workspace_size(win, pa.PA_KV_BF16) <= need + 4 * 256
         lens = [100, 4096, 1, 33]

@@ -180,13 +180,15 @@ def test_multi_token_calls_over_a_shared_prefix(pa, oracle, kv, D, Q, Hq, Hkv, B
 @pytest.mark.parametrize("B,prefix_blocks", [(3, 8), (20, 64), (7, 5)])
 def test_wide_multi_token_calls_over_a_shared_prefix(pa, oracle, kv, Q, Hq, Hkv, D, B, prefix_blocks):
     """33 .. 128 columns per KV head behind a shared prefix: the per-sequence pass runs on the
-    multi-wave kernel, which leaves the prefix tiles out of its plan as the one-wave kernel does."""
+    multi-wave kernels (stage-split at head_dim 128), which leave the prefix tiles out of their plan as the
+    one-wave kernel does."""
     lens = [L + Q - 1 for L in suffix_lens(prefix_blocks, B, B + Q)]
     b = W.make_batch("prefix-verify-wide", 580 + 7 * B + Hq + Q, lens, Hq, Hkv, D, 16, kv, q_len=Q,
                      shared_prefix_blocks=prefix_blocks)
     print(f"[case] wide prefix verify Q={Q} Hq={Hq} Hkv={Hkv} D={D} B={B} prefix={prefix_blocks} kv={kv}", flush=True)
     got, dev = run_gpu(pa, b)
-    assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-wide"
+    staged = D == 128 and (kv == W.KV_FP8_E4M3 or Q * (Hq // Hkv) <= 64)
+    assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == ("mfma-staged" if staged else "mfma-wide")
     want = oracle.decode_batch(b)["out"]
     flat = lambda a: a.reshape(a.shape[0], -1, a.shape[-1])
     assert_parity(flat(got), flat(want), kv, "shared prefix, wide multi-token")
@@ -201,7 +203,7 @@ def test_prompt_cache_workload_with_16_token_verification(pa, oracle):
     of 16 proposed tokens each, 4 query heads per KV head (64 columns); the oracle computes sampled rows."""
     b = W.make_config(6, q_len=16)
     got, dev = run_gpu(pa, b)
-    assert np.isfinite(got).all() and pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-wide"
+    assert np.isfinite(got).all() and pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-staged"
     rng = np.random.default_rng(66)
     rows = [(s, int(rng.integers(0, 16)), int(rng.integers(0, b.num_q_heads))) for s in range(b.batch)] + \
            [(0, 0, 0), (b.batch - 1, 15, b.num_q_heads - 1)]
