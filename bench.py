@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 METRIC = "paged decode attention achieved HBM GB/s (% of peak) + decode tokens/s, 1 GPU"
 
 # (workload, q_len, window): what `others` reports beside the headline
-OTHER_WORKLOADS = [(3, 1, 0), (4, 1, 0), (5, 1, 0), (6, 1, 0), (2, 16, 0), (2, 1, 1024)]
+OTHER_WORKLOADS = [(3, 1, 0), (4, 1, 0), (5, 1, 0), (6, 1, 0), (2, 16, 0), (5, 16, 0), (2, 1, 1024)]
 
 
 def parse_args():
@@ -62,8 +62,8 @@ def parse_args():
 
 def recorded_traffic(workload_name: str):
     """(HBM bytes per launch of the partition kernel, where that figure is recorded): from the
-    committed counter summary (profiles/partition_<workload>.txt, partition_wide_<workload>.txt or
-    prefix_<workload>.txt, the workload named as in this run's config: FETCH_SIZE and WRITE_SIZE,
+    committed counter summary (profiles/partition_<workload>.txt, partition_wide_<workload>.txt,
+    partition_staged_<workload>.txt or prefix_<workload>.txt, the workload named as in this run's config: FETCH_SIZE and WRITE_SIZE,
     scaled by what the same counters read for a copy of known size).  (None, why) when there is no
     summary for this workload or the kernel sources changed since the counters were taken.  The
     counters are never collected inside a timed run."""
@@ -71,7 +71,8 @@ def recorded_traffic(workload_name: str):
 
     here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles")
     path = None
-    for prefix in ("partition", "partition_wide", "prefix"):  # one-wave kernel, multi-wave kernel, shared-prefix pass
+    # one-wave kernel, multi-wave kernel, stage-split kernel, shared-prefix pass
+    for prefix in ("partition", "partition_wide", "partition_staged", "prefix"):
         cand = os.path.join(here, f"{prefix}_{workload_name}.txt")
         if os.path.exists(cand):
             path = cand

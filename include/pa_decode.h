@@ -306,7 +306,10 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
 
 /* Name of the partition kernel variant pa_decode picks for this shape ("mfma": one wavefront per
  * (partition, KV head), up to 32 query rows (Q * G) per KV head (16 for fp8 at head_dim 128); "mfma-wide":
- * a workgroup of 2, 4 or 8 wavefronts, up to 128); NULL for an invalid or unsupported shape.  Static storage. */
+ * a workgroup of 2, 4 or 8 wavefronts, up to 128; "mfma-staged": a workgroup of 8 wavefronts, four computing
+ * scores and softmax weights and four the product with V, for 33 .. 128 query rows at head_dim 128 -- fp8 KV,
+ * or bf16 KV up to 64 rows -- unless shape.precise_weights is set); NULL for an invalid or unsupported shape.
+ * Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 
 /* SHA-256 (hex) over the library's sources as the build recorded it, "" when the build recorded

@@ -1,0 +1,108 @@
+"""GPU parity of the stage-split partition kernel (33 .. 128 columns per KV head at head_dim 128:
+score waves and value waves, fp8 scores on the fp8 matrix instruction with the query rows split in
+two) against the float64 CPU oracle: query rows of wide dynamic range, and context lengths that
+put the ends of its runs of plain steps on every side of a tile boundary."""
+import numpy as np
+import pytest
+
+from paper_2605_06068_amd import workloads as W
+from tests.parity import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pa():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2605_06068_amd import binding
+
+    binding.lib()
+    return binding
+
+
+def run_gpu(pa, batch, **kw):
+    import torch
+
+    dev = pa.DeviceBatch(batch, **kw)
+    out = dev.decode()
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), dev
+
+
+def flat(a):
+    return a.reshape(a.shape[0], -1, a.shape[-1])
+
+
+def rescale_queries(batch, rng, lo_exp, hi_exp):
+    """Every query element times a power of two of its own (exact in bf16), and a few special rows:
+    all zeros, one spike among tiny elements, one constant magnitude."""
+    q = W.bf16_bits_to_f32(batch.q).astype(np.float32)
+    q *= np.exp2(rng.integers(lo_exp, hi_exp + 1, size=q.shape)).astype(np.float32)
+    rows = q.reshape(-1, q.shape[-1])
+    rows[0] = 0.0
+    rows[1] = np.float32(2.0 ** -10) * np.sign(rows[1])
+    rows[1, 7] = 96.0
+    rows[2] = np.float32(0.5) * np.where(rows[2] >= 0, 1, -1)
+    batch.q = W.f32_to_bf16_bits(q).reshape(batch.q.shape)
+    assert np.array_equal(W.bf16_bits_to_f32(batch.q), q), "powers of two keep bf16 numbers exact"
+
+
+# (Q, Hq, Hkv): 64 columns (one column tile per wave) and 96 / 128 (two)
+SHAPES = [(16, 4, 1), (16, 8, 1), (12, 16, 2), (8, 16, 1)]
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Q,Hq,Hkv", SHAPES)
+@pytest.mark.parametrize("lo_exp,hi_exp", [(-12, 0), (-3, 3), (-20, -8)])
+def test_query_rows_of_wide_dynamic_range(pa, oracle, kv, Q, Hq, Hkv, lo_exp, hi_exp):
+    """fp8 KV: the kernel splits every query row into two e4m3 operands after scaling it by a power of
+    two of the row's own; elements many binades below the row's largest, zero rows and rows that are
+    one spike must come through (bf16 KV runs the same cases on the bf16 path)."""
+    rng = np.random.default_rng(9000 + 31 * Q + Hq + hi_exp)
+    lens = [int(x) for x in rng.integers(Q, 700, size=5)] + [Q, 33 + Q, 1024]
+    b = W.make_batch("staged-dynamic-range", 9100 + Q + Hq + hi_exp - lo_exp, lens, Hq, Hkv, 128, 16, kv, q_len=Q)
+    rescale_queries(b, rng, lo_exp, hi_exp)
+    print(f"[case] dynamic range 2^{lo_exp}..2^{hi_exp} Q={Q} Hq={Hq} Hkv={Hkv} kv={kv}", flush=True)
+    got, dev = run_gpu(pa, b)
+    cols = Q * (Hq // Hkv)
+    staged = kv == W.KV_FP8_E4M3 or cols <= 64
+    assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == ("mfma-staged" if staged else "mfma-wide")
+    want = oracle.decode_batch(b)["out"]
+    err = assert_parity(flat(got), flat(want), kv, "query rows of wide dynamic range")
+    print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(16, 4, 1), (16, 8, 1)])
+@pytest.mark.parametrize("P", [0, 1, 3, 7])
+def test_lengths_around_the_ends_of_runs(pa, oracle, kv, Q, Hq, Hkv, P):
+    """A run of plain steps ends before the first tile that needs a causal mask and before a sequence's
+    last tile; lengths that put L and L - Q + 1 just below, on and just above multiples of 32, with range
+    starts in the middle of sequences (odd partition counts)."""
+    lens = []
+    for base in (64, 96, 128, 160, 1024):
+        for d in (-1, 0, 1):
+            lens += [base + d, base + Q - 1 + d]
+    lens += [Q, Q + 1, 31 + Q, 2048]
+    b = W.make_batch("staged-run-ends", 9300 + Q + Hq, lens, Hq, Hkv, 128, 16, kv, q_len=Q)
+    print(f"[case] run ends Q={Q} Hq={Hq} Hkv={Hkv} kv={kv} P={P}", flush=True)
+    got, dev = run_gpu(pa, b, num_partitions=P)
+    cols = Q * (Hq // Hkv)
+    if kv == W.KV_FP8_E4M3 or cols <= 64:
+        assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-staged"
+    want = oracle.decode_batch(b)["out"]
+    err = assert_parity(flat(got), flat(want), kv, "lengths around the ends of runs")
+    print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e} P={pa.pa_num_partitions(dev.shape, dev.kv_dtype)}", flush=True)
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+def test_negative_softmax_scale(pa, oracle, kv):
+    """A negative scale turns the search for the largest exponent into one for the smallest raw score."""
+    b = W.make_batch("staged-negative-scale", 9400, [100, 257, 40, 16, 512], 8, 1, 128, 16, kv, q_len=8)
+    b.scale = np.float32(-b.scale)
+    got, dev = run_gpu(pa, b)
+    assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-staged"
+    want = oracle.decode_batch(b)["out"]
+    assert_parity(flat(got), flat(want), kv, "negative scale")
