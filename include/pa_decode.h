@@ -306,9 +306,10 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
 
 /* Name of the partition kernel variant pa_decode picks for this shape ("mfma": one wavefront per
  * (partition, KV head), up to 32 query rows (Q * G) per KV head (16 for fp8 at head_dim 128); "mfma-wide":
- * a workgroup of 2, 4 or 8 wavefronts, up to 128; "mfma-staged": a workgroup of 8 wavefronts, four computing
- * scores and softmax weights and four the product with V, for 33 .. 128 query rows at head_dim 128 -- fp8 KV,
- * or bf16 KV up to 64 rows -- unless shape.precise_weights is set); NULL for an invalid or unsupported shape.
+ * a workgroup of 2, 4 or 8 wavefronts, up to 128; "mfma-staged": a workgroup of 4 or 8 wavefronts, half of
+ * them computing scores and softmax weights and half the product with V, at head_dim 128 for 17 .. 128 query
+ * rows with fp8 KV and 33 .. 64 with bf16 KV, unless shape.precise_weights is set); NULL for an invalid or
+ * unsupported shape.
  * Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 

@@ -187,23 +187,28 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
 // workgroups of up to 128 columns a call needs side by side (more than one: the cache is read once per group)
 int column_groups(const pa_shape* s) { return (columns(s) + kMaxColsMfma - 1) / kMaxColsMfma; }
 
-// Above 32 columns at head_dim 128 the per-sequence pass runs on the stage-split kernel (eight
-// waves: four compute scores and weights, four the PV product of the tile before), unless the
-// weights are to keep their low part, which its hand-over buffers have no room for.  bf16 KV with
-// more than 64 columns stays on the multi-wave kernel: only one stage-split workgroup would fit a
-// compute unit's LDS (8B-shaped batch, 32 query tokens: 197 against 169 us per step).
+// At head_dim 128 the per-sequence pass of calls the one-wave kernel does not take runs on the
+// stage-split kernel (score waves and value waves: four and four above 32 columns, two and two
+// up to 32): fp8 KV from 17 columns, bf16 KV from 33 to 64 -- unless the weights are to keep their
+// low part, which its hand-over buffers have no room for.  bf16 KV with more than 64 columns stays
+// on the multi-wave kernel: only one stage-split workgroup would fit a compute unit's LDS
+// (8B-shaped batch, 32 query tokens: 197 against 169 us per step).
 bool staged(const pa_shape* s, pa_kv_dtype kv)
 {
-    if (one_wave(s, kv) || columns(s) <= 32 || s->head_dim != 128 || s->precise_weights != 0) return false;
-    return kv == PA_KV_FP8_E4M3 || columns(s) <= 64;
+    if (one_wave(s, kv) || s->head_dim != 128 || s->precise_weights != 0) return false;
+    if (kv == PA_KV_FP8_E4M3) return columns(s) > 16;
+    return columns(s) > 32 && columns(s) <= 64;
 }
 
-// column tiles per wave of that kernel, and its resident workgroups per compute unit
+// score waves per workgroup and column tiles per wave of that kernel, and its resident workgroups
+// per compute unit (sixteen waves, LDS permitting)
+int staged_ns(const pa_shape* s) { return columns(s) <= 32 ? 2 : 4; }
 int staged_nct(const pa_shape* s) { return columns(s) > 64 ? 2 : 1; }
 int staged_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
 {
-    const int fit = kLdsPerCu / pa::staged_lds_bytes(s->head_dim, staged_nct(s), (int)kv);
-    return fit < 2 ? fit : 2;
+    const int fit = kLdsPerCu / pa::staged_lds_bytes(s->head_dim, staged_ns(s), staged_nct(s), (int)kv);
+    const int want = 16 / (2 * staged_ns(s));
+    return fit < want ? fit : want;
 }
 
 // waves (one-wave kernel) or workgroups (multi-wave kernel) resident per compute unit
@@ -349,14 +354,14 @@ void launch_wide(const Params& p, bool trace, bool precise, dim3 grid, hipStream
     }
 }
 
-template <int D, int NCT, int KV>
+template <int D, int NS, int NCT, int KV>
 void launch_staged(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
     if constexpr (D == 128) {
         if (trace)
-            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NCT, KV, true>), grid, dim3(pa::kStagedWaves * 64), 0, st, p);
+            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NS, NCT, KV, true>), grid, dim3(2 * NS * 64), 0, st, p);
         else
-            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NCT, KV, false>), grid, dim3(pa::kStagedWaves * 64), 0, st, p);
+            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NS, NCT, KV, false>), grid, dim3(2 * NS * 64), 0, st, p);
     }
 }
 
@@ -367,10 +372,13 @@ void launch_partition(const Params& p, bool one_wave, bool staged, bool trace, b
 {
     const int cols = p.Q * p.G;
     if (staged) {
-        if (cols <= 64)
-            launch_staged<D, 1, KV>(p, trace, grid, st);
-        else if constexpr (KV == pa::KV_FP8)
-            launch_staged<D, 2, KV>(p, trace, grid, st);
+        if (cols <= 32) {
+            if constexpr (KV == pa::KV_FP8) launch_staged<D, 2, 1, KV>(p, trace, grid, st);
+        } else if (cols <= 64) {
+            launch_staged<D, 4, 1, KV>(p, trace, grid, st);
+        } else {
+            if constexpr (KV == pa::KV_FP8) launch_staged<D, 4, 2, KV>(p, trace, grid, st);
+        }
         return;
     }
     if (cols <= 4)

@@ -1,17 +1,17 @@
-// Partition kernel, matrix-core variant for 33 .. 128 columns per KV head in which the waves of a
+// Partition kernel, matrix-core variant for 17 .. 128 columns per KV head in which the waves of a
 // workgroup split a tile's work by STAGE as well as by column (head_dim 128).
 //
 // The multi-wave kernel of pa_partition_mfma_wide.hpp gives every wave the whole chain of a tile
 // -- K reads, scores, softmax, V reads, PV -- for its own columns, holds the query operand AND the
 // output accumulators in every wave, and so fits two waves per SIMD, which do not cover each
-// other's dependent waits.  Here a workgroup has eight waves: waves 0..3 ("score waves") hold the
-// query operand and compute scores and softmax weights of tile i, waves 4..7 ("value waves") hold
-// the accumulators and add the PV product of tile i-1, at the same time.  Wave w and wave w + 4
-// serve the same NCT = 1 or 2 tiles of 16 columns.  The weights travel through LDS (one 16-byte
-// write and read per lane and column tile, in the register layout both matrix products use, so
-// nothing is shuffled), together with each column's running maximum and rescale factor.  Every
-// wave needs half the registers, four waves fit a SIMD, and a tile's chain is cut in two halves
-// that overlap.
+// other's dependent waits.  Here a workgroup has 2 NS waves (NS = 4, or 2 for up to 32 columns):
+// waves 0 .. NS-1 ("score waves") hold the query operand and compute scores and softmax weights of
+// tile i, waves NS .. 2 NS - 1 ("value waves") hold the accumulators and add the PV product of
+// tile i-1, at the same time.  Wave w and wave w + NS serve the same NCT = 1 or 2 tiles of 16
+// columns.  The weights travel through LDS (one 16-byte write and read per lane and column tile,
+// in the register layout both matrix products use, so nothing is shuffled), together with each
+// column's running maximum and rescale factor.  Every wave needs half the registers, four waves
+// fit a SIMD, and a tile's chain is cut in two halves that overlap.
 //
 // Per step i = 0 .. ntiles (one more than there are tiles: the value waves run one behind), every
 // wave of the workgroup meets at ONE barrier:
@@ -35,7 +35,8 @@
 // arithmetic of the general step (a "run", see the score waves' loop): with sixteen waves per
 // compute unit every scalar instruction per step and wave counts.  Measured, 70B-head-shaped fp8
 // batch, 16 query tokens = 128 columns: 850-900 us on the multi-wave kernel, 800 us split by
-// stage, 735 us with the fp8 score instruction, 685-730 us with runs.
+// stage, 735 us with the fp8 score instruction, 685-730 us with runs; 4 query tokens = 32 columns
+// (two score and two value waves): 453 -> 369 us per step.
 #pragma once
 #include <type_traits>
 
@@ -46,18 +47,17 @@
 
 namespace pa {
 
-constexpr int kStagedScoreWaves = 4;                    // and as many value waves
-constexpr int kStagedWaves = 2 * kStagedScoreWaves;
+// ns = score waves of a workgroup (and as many value waves): 4, or 2 for up to 32 columns
 constexpr int kStagedRing = 3;                           // half-stages (K or V blocks of one tile) per ring
 
 constexpr int staged_half_bytes(int d, int kv) { return mfma_stage_bytes(d, kv) / 2; }
-constexpr int staged_weight_bytes(int nct) { return kStagedScoreWaves * nct * 1024; }          // one tile's weights
-constexpr int staged_column_bytes(int nct) { return kStagedScoreWaves * nct * 16 * 8; }        // one tile's {alpha, m}
+constexpr int staged_weight_bytes(int ns, int nct) { return ns * nct * 1024; }          // one tile's weights
+constexpr int staged_column_bytes(int ns, int nct) { return ns * nct * 16 * 8; }        // one tile's {alpha, m}
 
-constexpr int staged_lds_bytes(int d, int nct, int kv)
+constexpr int staged_lds_bytes(int d, int ns, int nct, int kv)
 {
-    return 2 * kStagedRing * staged_half_bytes(d, kv) + kStagedScoreWaves * wide_q_slot_bytes(d, nct) +
-           2 * staged_weight_bytes(nct) + 2 * staged_column_bytes(nct);
+    return 2 * kStagedRing * staged_half_bytes(d, kv) + ns * wide_q_slot_bytes(d, nct) + 2 * staged_weight_bytes(ns, nct) +
+           2 * staged_column_bytes(ns, nct);
 }
 
 // The softmax step of online_softmax() for a wave that does not hold the accumulators: the same
@@ -185,12 +185,12 @@ __device__ __forceinline__ void qk_scores_fp8(const char* kbuf, const uint32_t (
 
 // Two workgroups per compute unit: four waves per SIMD (the second launch bound), 128 registers
 // each; the instrumented variants, whose records need a few more, settle for half of that.
-template <int D, int NCT, int KV, bool TRACE>
-__global__ __launch_bounds__(kStagedWaves * 64, TRACE ? 2 : 4) void partition_mfma_staged_kernel(const Params p)
+template <int D, int NS, int NCT, int KV, bool TRACE>
+__global__ __launch_bounds__(2 * NS * 64, TRACE ? 2 : 4) void partition_mfma_staged_kernel(const Params p)
 {
-    static_assert(D == 128, "eight waves share a tile's loads evenly at head_dim 128 only");
+    static_assert(D == 128, "the waves share a tile's loads evenly at head_dim 128 only");
+    static_assert(NS == 2 || NS == 4, "score waves per workgroup");
     static_assert(NCT == 1 || NCT == 2, "MFMA column tiles per wave");
-    constexpr int NS = kStagedScoreWaves;
     constexpr int kWaveCols = 16 * NCT;
     using Geo = KvGeom<D, KV>;
     using QG = QGeom<D>;
@@ -203,10 +203,10 @@ __global__ __launch_bounds__(kStagedWaves * 64, TRACE ? 2 : 4) void partition_mf
     constexpr int kQLoads = kQSlotBytes / 1024;
     constexpr int kQBase = 2 * kStagedRing * kHalf;
     constexpr int kWBase = kQBase + NS * kQSlotBytes;
-    constexpr int kCBase = kWBase + 2 * staged_weight_bytes(NCT);
-    static_assert(staged_lds_bytes(D, NCT, KV) == kCBase + 2 * staged_column_bytes(NCT), "layout");
-    static_assert(staged_lds_bytes(D, NCT, KV) <= 160 * 1024, "LDS of one compute unit");
-    __shared__ __attribute__((aligned(1024))) char smem[staged_lds_bytes(D, NCT, KV)];
+    constexpr int kCBase = kWBase + 2 * staged_weight_bytes(NS, NCT);
+    static_assert(staged_lds_bytes(D, NS, NCT, KV) == kCBase + 2 * staged_column_bytes(NS, NCT), "layout");
+    static_assert(staged_lds_bytes(D, NS, NCT, KV) <= 160 * 1024, "LDS of one compute unit");
+    __shared__ __attribute__((aligned(1024))) char smem[staged_lds_bytes(D, NS, NCT, KV)];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -364,9 +364,9 @@ __global__ __launch_bounds__(kStagedWaves * 64, TRACE ? 2 : 4) void partition_mf
             }
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
-                *reinterpret_cast<bf16x8*>(wbuf + par * staged_weight_bytes(NCT) + ct * 1024) = pb[ct];
+                *reinterpret_cast<bf16x8*>(wbuf + par * staged_weight_bytes(NS, NCT) + ct * 1024) = pb[ct];
                 if (q4 == 0)
-                    *reinterpret_cast<float2*>(cbuf + par * staged_column_bytes(NCT) + ct * 128) = make_float2(alpha[ct], m[ct]);
+                    *reinterpret_cast<float2*>(cbuf + par * staged_column_bytes(NS, NCT) + ct * 128) = make_float2(alpha[ct], m[ct]);
             }
         };
 
@@ -487,8 +487,8 @@ __global__ __launch_bounds__(kStagedWaves * 64, TRACE ? 2 : 4) void partition_mf
             bf16x8 pb[NCT], pb_lo[NCT];
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
-                pb[ct] = *reinterpret_cast<const bf16x8*>(wbuf + par * staged_weight_bytes(NCT) + ct * 1024);
-                const float2 am = *reinterpret_cast<const float2*>(cbuf + par * staged_column_bytes(NCT) + ct * 128);
+                pb[ct] = *reinterpret_cast<const bf16x8*>(wbuf + par * staged_weight_bytes(NS, NCT) + ct * 1024);
+                const float2 am = *reinterpret_cast<const float2*>(cbuf + par * staged_column_bytes(NS, NCT) + ct * 128);
                 if (__any(am.x != 1.f)) {
                     st[ct].lacc *= am.x;
 #pragma unroll

@@ -105,7 +105,7 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     assert pa.pa_kernel_variant(shape(**big), pa.PA_KV_FP8_E4M3) == "mfma"
     assert pa.pa_kernel_variant(shape(**dict(big, batch=4)), pa.PA_KV_FP8_E4M3) == "mfma-wide"
     assert pa.pa_kernel_variant(shape(**dict(big, batch=4, num_partitions=8)), pa.PA_KV_FP8_E4M3) == "mfma"
-    assert pa.pa_kernel_variant(shape(**dict(big, head_dim=128)), pa.PA_KV_FP8_E4M3) == "mfma-wide"  # fp8 at head_dim 128
+    assert pa.pa_kernel_variant(shape(**dict(big, head_dim=128)), pa.PA_KV_FP8_E4M3) == "mfma-staged"  # fp8 at head_dim 128: two score and two value waves
     assert pa.pa_kernel_variant(shape(**dict(big, head_dim=128)), pa.PA_KV_BF16) == "mfma"
     assert pa.pa_kernel_variant(shape(num_q_heads=24, head_dim=64, q_len=16), pa.PA_KV_FP8_E4M3) == "mfma-wide"  # 48
 

@@ -1,4 +1,4 @@
-"""GPU parity of the stage-split partition kernel (33 .. 128 columns per KV head at head_dim 128:
+"""GPU parity of the stage-split partition kernel (17 .. 128 columns per KV head at head_dim 128:
 score waves and value waves, fp8 scores on the fp8 matrix instruction with the query rows split in
 two) against the float64 CPU oracle: query rows of wide dynamic range, and context lengths that
 put the ends of its runs of plain steps on every side of a tile boundary."""
@@ -49,8 +49,8 @@ def rescale_queries(batch, rng, lo_exp, hi_exp):
     assert np.array_equal(W.bf16_bits_to_f32(batch.q), q), "powers of two keep bf16 numbers exact"
 
 
-# (Q, Hq, Hkv): 64 columns (one column tile per wave) and 96 / 128 (two)
-SHAPES = [(16, 4, 1), (16, 8, 1), (12, 16, 2), (8, 16, 1)]
+# (Q, Hq, Hkv): 64 columns (one column tile per wave), 96 / 128 (two), 24 / 32 (fp8: two score and two value waves)
+SHAPES = [(16, 4, 1), (16, 8, 1), (12, 16, 2), (8, 16, 1), (4, 8, 1), (3, 16, 2), (2, 9, 1)]
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
@@ -67,15 +67,18 @@ def test_query_rows_of_wide_dynamic_range(pa, oracle, kv, Q, Hq, Hkv, lo_exp, hi
     print(f"[case] dynamic range 2^{lo_exp}..2^{hi_exp} Q={Q} Hq={Hq} Hkv={Hkv} kv={kv}", flush=True)
     got, dev = run_gpu(pa, b)
     cols = Q * (Hq // Hkv)
-    staged = kv == W.KV_FP8_E4M3 or cols <= 64
-    assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == ("mfma-staged" if staged else "mfma-wide")
+    if cols > 32:
+        staged = kv == W.KV_FP8_E4M3 or cols <= 64
+        assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == ("mfma-staged" if staged else "mfma-wide")
+    elif kv == W.KV_FP8_E4M3:
+        assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-staged"
     want = oracle.decode_batch(b)["out"]
     err = assert_parity(flat(got), flat(want), kv, "query rows of wide dynamic range")
     print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e}", flush=True)
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
-@pytest.mark.parametrize("Q,Hq,Hkv", [(16, 4, 1), (16, 8, 1)])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(16, 4, 1), (16, 8, 1), (4, 8, 1)])
 @pytest.mark.parametrize("P", [0, 1, 3, 7])
 def test_lengths_around_the_ends_of_runs(pa, oracle, kv, Q, Hq, Hkv, P):
     """A run of plain steps ends before the first tile that needs a causal mask and before a sequence's
@@ -90,7 +93,7 @@ def test_lengths_around_the_ends_of_runs(pa, oracle, kv, Q, Hq, Hkv, P):
     print(f"[case] run ends Q={Q} Hq={Hq} Hkv={Hkv} kv={kv} P={P}", flush=True)
     got, dev = run_gpu(pa, b, num_partitions=P)
     cols = Q * (Hq // Hkv)
-    if kv == W.KV_FP8_E4M3 or cols <= 64:
+    if kv == W.KV_FP8_E4M3 or 32 < cols <= 64:
         assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-staged"
     want = oracle.decode_batch(b)["out"]
     err = assert_parity(flat(got), flat(want), kv, "lengths around the ends of runs")
