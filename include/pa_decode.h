@@ -189,7 +189,11 @@ size_t pa_decode_workspace_size(const pa_shape *shape, pa_kv_dtype kv_dtype);
  * for plain bf16 decode, 5-25 % more time for the calls listed above.  The paper's accuracy
  * gates compare generated text with a reference implementation's (Appendix A, Scenario B: greedy
  * outputs must match); a caller held to such a gate, or one whose values are not of unit size,
- * sets it.
+ * sets it.  Range of the scores: the 8-bit paths fold the scale into the exponent (one fused
+ * multiply-add per score), which leaves every exponent off by up to 2^-24 |score * scale|: nothing
+ * for scores of ordinary size (below 2^-12 up to 2^12), a loss of accuracy beyond, and overflowing
+ * weights (a non-finite result) from about 2^26.  The 16-bit paths scale first and subtract the
+ * maximum from the products: the largest weight is exactly 1 whatever the size of the scores.
  */
 pa_status pa_decode(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                     const int32_t *context_lens, float scale, pa_kv_dtype kv_dtype, void *out,

@@ -47,12 +47,13 @@
 
 namespace pa {
 
-// ns = score waves of a workgroup (and as many value waves): 4, or 2 for up to 32 columns
-constexpr int kStagedRing = 3;                           // half-stages (K or V blocks of one tile) per ring
+constexpr int kStagedRing = 3;  // half-stages (the K or the V blocks of one tile) per ring
 
+// LDS of a workgroup with ns score waves (and as many value waves) of nct column tiles each: the two
+// rings, the score waves' query-row slots, and two sets of hand-over buffers
 constexpr int staged_half_bytes(int d, int kv) { return mfma_stage_bytes(d, kv) / 2; }
-constexpr int staged_weight_bytes(int ns, int nct) { return ns * nct * 1024; }          // one tile's weights
-constexpr int staged_column_bytes(int ns, int nct) { return ns * nct * 16 * 8; }        // one tile's {alpha, m}
+constexpr int staged_weight_bytes(int ns, int nct) { return ns * nct * 1024; }    // one tile's weights
+constexpr int staged_column_bytes(int ns, int nct) { return ns * nct * 16 * 8; }  // one tile's {alpha, m}
 
 constexpr int staged_lds_bytes(int d, int ns, int nct, int kv)
 {
@@ -139,8 +140,9 @@ __device__ __forceinline__ float split_query_fp8(const char* slot, int n, int q4
 #pragma unroll
     for (int e = 0; e < 32; ++e) amax = fmaxf(amax, fabsf(x[e]));
     amax = rows_max(amax);  // over the four lanes that hold the row
-    // amax = f 2^ex with f in [0.5, 1): x 2^(8 - ex) has its largest element in [128, 256)
-    const int ex = amax > 0.f ? __builtin_amdgcn_frexp_expf(amax) : 8;
+    // amax = f 2^ex with f in [0.5, 1): x 2^(8 - ex) has its largest element in [128, 256).  (Rows whose
+    // largest element lies below 2^-100 keep the factor of 2^-100: the powers of two stay finite.)
+    const int ex = amax > 0.f ? max(__builtin_amdgcn_frexp_expf(amax), -100) : 8;
     const float up = __builtin_amdgcn_ldexpf(1.f, 8 - ex), down = __builtin_amdgcn_ldexpf(1.f, ex - 8);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {

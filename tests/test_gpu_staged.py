@@ -109,3 +109,22 @@ def test_negative_softmax_scale(pa, oracle, kv):
     assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == "mfma-staged"
     want = oracle.decode_batch(b)["out"]
     assert_parity(flat(got), flat(want), kv, "negative scale")
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(16, 4, 1), (4, 8, 1)])
+def test_query_rows_at_the_ends_of_the_bf16_range(pa, oracle, kv, Q, Hq, Hkv):
+    """Rows of magnitude 2^-118 (all scores vanish: the output is the mean of the visible values) and
+    2^8 (scores of a few thousand: one token takes nearly all the weight) beside ordinary ones: the
+    per-row power of two of the fp8 split stays finite at the low end, and the exponents keep their
+    accuracy at the upper end of what the 8-bit paths are specified for."""
+    b = W.make_batch("staged-range-ends", 9500 + Q, [200, 77, 512, 33 + Q], Hq, Hkv, 128, 16, kv, q_len=Q)
+    q = W.bf16_bits_to_f32(b.q).astype(np.float32)
+    rows = q.reshape(-1, q.shape[-1])
+    rows[0::5] *= np.float32(2.0 ** -118)
+    rows[1::5] *= np.float32(2.0 ** 8)
+    b.q = W.f32_to_bf16_bits(q).reshape(b.q.shape)
+    got, dev = run_gpu(pa, b)
+    assert np.isfinite(got).all()
+    want = oracle.decode_batch(b)["out"]
+    assert_parity(flat(got), flat(want), kv, "query rows at the ends of the bf16 range")
