@@ -312,8 +312,8 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
  * (partition, KV head), up to 32 query rows (Q * G) per KV head (16 for fp8 at head_dim 128); "mfma-wide":
  * a workgroup of 2, 4 or 8 wavefronts, up to 128; "mfma-staged": a workgroup of 4 or 8 wavefronts, half of
  * them computing scores and softmax weights and half the product with V, at head_dim 128 for 17 .. 128 query
- * rows with fp8 KV and 33 .. 64 with bf16 KV, unless shape.precise_weights is set); NULL for an invalid or
- * unsupported shape.
+ * rows with fp8 KV and 17 .. 64 with bf16 KV (17 .. 32 bf16 rows with long runs of tiles per partition stay
+ * on "mfma"), unless shape.precise_weights is set); NULL for an invalid or unsupported shape.
  * Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 

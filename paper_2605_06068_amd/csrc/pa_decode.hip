@@ -63,7 +63,13 @@ constexpr int kMaxPartitions = 65535;
 constexpr int kMaxBatch = 65535;
 constexpr int kMinTilesOneWave = 2;  // tiles a partition should at least have: one-wave kernels
 constexpr int kMinTilesWide = 4;     // multi-wave kernel
-constexpr int kMinTilesTwoColumnTiles = 16;  // tiles per partition from which one wave takes two column tiles
+// tiles per partition from which one wave takes two column tiles: where the alternative is the
+// two-wave multi-wave workgroup (head_dim 64), and where it is the stage-split workgroup of two
+// score and two value waves (head_dim 128, bf16), which stays ahead for longer (one sequence, 64
+// query / 8 KV heads, 4 tokens: 64k tokens = 16 tiles per partition 59.7 against 53.9 us; at 36
+// tiles per partition, 8B-shaped batch, the two tie; at 156, long-context batch, 365.9 against 372.6)
+constexpr int kMinTilesTwoColumnTiles = 16;
+constexpr int kMinTilesTwoColumnTilesStaged = 48;
 constexpr int kMergeManyPerSeq = 8;  // partitions per sequence from which the multi-wave merge kernel is used
 // output rows per sequence from which a merge wave takes four rows (8B-shaped batch: 32 rows 6.7
 // against 7.0 us, 128 rows 9.2 against 8.5 us, 256 rows 12.8 against 11.1 us, 512 rows 16.9 against 12.3 us)
@@ -181,7 +187,8 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
     if (cols > max_cols_one_wave(s->head_dim, (int)kv)) return false;
     const int64_t P = s->num_partitions > 0 ? s->num_partitions
                                             : (int64_t)compute_units() * one_wave_per_cu(s, kv) / s->num_kv_heads;
-    return tile_bound(s) >= kMinTilesTwoColumnTiles * (P < 1 ? 1 : P);
+    const int min_tiles = s->head_dim == 128 && s->precise_weights == 0 ? kMinTilesTwoColumnTilesStaged : kMinTilesTwoColumnTiles;
+    return tile_bound(s) >= min_tiles * (P < 1 ? 1 : P);
 }
 
 // workgroups of up to 128 columns a call needs side by side (more than one: the cache is read once per group)
@@ -189,15 +196,14 @@ int column_groups(const pa_shape* s) { return (columns(s) + kMaxColsMfma - 1) / 
 
 // At head_dim 128 the per-sequence pass of calls the one-wave kernel does not take runs on the
 // stage-split kernel (score waves and value waves: four and four above 32 columns, two and two
-// up to 32): fp8 KV from 17 columns, bf16 KV from 33 to 64 -- unless the weights are to keep their
-// low part, which its hand-over buffers have no room for.  bf16 KV with more than 64 columns stays
-// on the multi-wave kernel: only one stage-split workgroup would fit a compute unit's LDS
-// (8B-shaped batch, 32 query tokens: 197 against 169 us per step).
+// up to 32), from 17 columns on -- unless the weights are to keep their low part, which its
+// hand-over buffers have no room for.  bf16 KV with more than 64 columns stays on the multi-wave
+// kernel: only one stage-split workgroup would fit a compute unit's LDS (8B-shaped batch, 32
+// query tokens: 197 against 169 us per step).
 bool staged(const pa_shape* s, pa_kv_dtype kv)
 {
-    if (one_wave(s, kv) || s->head_dim != 128 || s->precise_weights != 0) return false;
-    if (kv == PA_KV_FP8_E4M3) return columns(s) > 16;
-    return columns(s) > 32 && columns(s) <= 64;
+    if (one_wave(s, kv) || s->head_dim != 128 || s->precise_weights != 0 || columns(s) <= 16) return false;
+    return kv == PA_KV_FP8_E4M3 || columns(s) <= 64;
 }
 
 // score waves per workgroup and column tiles per wave of that kernel, and its resident workgroups
@@ -373,7 +379,7 @@ void launch_partition(const Params& p, bool one_wave, bool staged, bool trace, b
     const int cols = p.Q * p.G;
     if (staged) {
         if (cols <= 32) {
-            if constexpr (KV == pa::KV_FP8) launch_staged<D, 2, 1, KV>(p, trace, grid, st);
+            launch_staged<D, 2, 1, KV>(p, trace, grid, st);
         } else if (cols <= 64) {
             launch_staged<D, 4, 1, KV>(p, trace, grid, st);
         } else {

@@ -185,10 +185,17 @@ __device__ __forceinline__ void qk_scores_fp8(const char* kbuf, const uint32_t (
     }
 }
 
-// Two workgroups per compute unit: four waves per SIMD (the second launch bound), 128 registers
-// each; the instrumented variants, whose records need a few more, settle for half of that.
+// Waves per SIMD the register budget is cut for (the second launch bound): as many as the LDS lets
+// a compute unit hold, four at most (128 registers each); the instrumented variants, whose records
+// need a few more, settle for two.
+constexpr int staged_waves_per_simd(int d, int ns, int nct, int kv, bool trace)
+{
+    const int by_lds = (160 * 1024 / staged_lds_bytes(d, ns, nct, kv)) * 2 * ns / 4;
+    return trace || by_lds < 4 ? (by_lds < 2 ? by_lds : 2) : 4;
+}
+
 template <int D, int NS, int NCT, int KV, bool TRACE>
-__global__ __launch_bounds__(2 * NS * 64, TRACE ? 2 : 4) void partition_mfma_staged_kernel(const Params p)
+__global__ __launch_bounds__(2 * NS * 64, staged_waves_per_simd(D, NS, NCT, KV, TRACE)) void partition_mfma_staged_kernel(const Params p)
 {
     static_assert(D == 128, "the waves share a tile's loads evenly at head_dim 128 only");
     static_assert(NS == 2 || NS == 4, "score waves per workgroup");
