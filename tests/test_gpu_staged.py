@@ -128,3 +128,49 @@ def test_query_rows_at_the_ends_of_the_bf16_range(pa, oracle, kv, Q, Hq, Hkv):
     assert np.isfinite(got).all()
     want = oracle.decode_batch(b)["out"]
     assert_parity(flat(got), flat(want), kv, "query rows at the ends of the bf16 range")
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(4, 8, 1), (16, 4, 1), (16, 8, 1)])
+def test_verification_call_in_a_hip_graph(pa, oracle, kv, Q, Hq, Hkv):
+    """A multi-token call captured once and replayed with queries and lengths updated in place: every
+    replay equals the eager call on the same state bit for bit and the oracle within tolerance, with
+    host work and synchronisations between the replays."""
+    import torch
+
+    rng = np.random.default_rng(9600 + Q + Hq)
+    full = np.array([700, 40 + Q, 1030, 333, 96 + Q], dtype=np.int32)
+    b = W.make_batch("staged-graph", 9600 + Q, full.tolist(), Hq, Hkv, 128, 16, kv, poison=False, q_len=Q)
+    dev = pa.DeviceBatch(b, max_context_len=int(full.max()))
+    out_eager = torch.empty_like(dev.out)
+
+    def enqueue(out):
+        pa.pa_decode(dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens, dev.scale, dev.kv_dtype, out,
+                     dev.k_scale, dev.v_scale, shape=dev.shape, workspace=dev.workspace)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue(dev.out)  # warm-up outside capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue(dev.out)
+    torch.cuda.synchronize()
+
+    for i in range(4):
+        b.context_lens = np.maximum(full - rng.integers(0, 40, size=full.shape), Q).astype(np.int32)
+        q_new = W.f32_to_bf16_bits(rng.standard_normal(b.q.shape).astype(np.float32)).reshape(b.q.shape)
+        b.q = q_new
+        dev.q.copy_(torch.from_numpy(q_new.view(np.int16)))
+        dev.context_lens.copy_(torch.from_numpy(b.context_lens))
+        dev.out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dev.out.cpu().numpy()
+        want = oracle.decode_batch(b)["out"]
+        assert_parity(flat(got), flat(want), kv, f"graph replay {i}")
+        enqueue(out_eager)
+        torch.cuda.synchronize()
+        assert np.array_equal(out_eager.cpu().numpy(), got)
+        _ = (torch.randn(1 << 16, device="cuda") * 2).sum().item()  # unrelated eager work between replays
