@@ -485,6 +485,11 @@ __global__ __launch_bounds__(2 * NS * 64, staged_waves_per_simd(D, NS, NCT, KV, 
         __builtin_amdgcn_s_barrier();
     } else {
         // ================================ value waves ================================
+        // The value waves issue ahead of the score waves they share a SIMD with: their step is mostly
+        // matrix instructions, which then start as soon as their operands are there and run while the
+        // score waves' vector instructions fill the issue slots in between (fp8 KV, 32 / 64 / 128
+        // columns: 365 -> 352, 529 -> 515, 717 -> 694 us per step; bf16 KV unchanged).
+        __builtin_amdgcn_s_setprio(1);
         const float vs = KV == KV_FP8 ? p.v_scale[g] : 1.f;
         ColumnState<D> st[NCT];
 #pragma unroll
