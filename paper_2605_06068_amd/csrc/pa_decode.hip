@@ -195,8 +195,8 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
 int column_groups(const pa_shape* s) { return (columns(s) + kMaxColsMfma - 1) / kMaxColsMfma; }
 
 // At head_dim 128 the per-sequence pass of calls the one-wave kernel does not take runs on the
-// stage-split kernel (score waves and value waves: four and four above 32 columns, two and two
-// up to 32), from 17 columns on -- unless the weights are to keep their low part, which its
+// stage-split kernel (score waves and value waves: two and two up to 64 columns, with two column
+// tiles each above 32; four and four with two tiles each above 64), from 17 columns on -- unless the weights are to keep their low part, which its
 // hand-over buffers have no room for.  bf16 KV with more than 64 columns stays on the multi-wave
 // kernel: only one stage-split workgroup would fit a compute unit's LDS (8B-shaped batch, 32
 // query tokens: 197 against 169 us per step).
@@ -208,8 +208,12 @@ bool staged(const pa_shape* s, pa_kv_dtype kv)
 
 // score waves per workgroup and column tiles per wave of that kernel, and its resident workgroups
 // per compute unit (sixteen waves, LDS permitting)
-int staged_ns(const pa_shape* s) { return columns(s) <= 32 ? 2 : 4; }
-int staged_nct(const pa_shape* s) { return columns(s) > 64 ? 2 : 1; }
+// (64 columns as two waves of two tiles, three workgroups per compute unit, against four waves of one
+// tile, two workgroups: every K and V operand read and fp8 conversion serves two tiles.  fp8 KV:
+// 70B-head-shaped batch, 8 tokens 521.5 -> 469.6 us per step, ragged batch, 16 tokens 330.5 -> 302.3;
+// bf16 KV: long-context batch, 16 tokens 398.1 -> 388.2, 8B-shaped 133.7 -> 132.3)
+int staged_ns(const pa_shape* s) { return columns(s) <= 64 ? 2 : 4; }
+int staged_nct(const pa_shape* s) { return columns(s) > 32 ? 2 : 1; }
 int staged_groups_per_cu(const pa_shape* s, pa_kv_dtype kv)
 {
     const int fit = kLdsPerCu / pa::staged_lds_bytes(s->head_dim, staged_ns(s), staged_nct(s), (int)kv);
@@ -381,7 +385,7 @@ void launch_partition(const Params& p, bool one_wave, bool staged, bool trace, b
         if (cols <= 32) {
             launch_staged<D, 2, 1, KV>(p, trace, grid, st);
         } else if (cols <= 64) {
-            launch_staged<D, 4, 1, KV>(p, trace, grid, st);
+            launch_staged<D, 2, 2, KV>(p, trace, grid, st);
         } else {
             if constexpr (KV == pa::KV_FP8) launch_staged<D, 4, 2, KV>(p, trace, grid, st);
         }

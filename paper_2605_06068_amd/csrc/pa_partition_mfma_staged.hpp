@@ -4,7 +4,7 @@
 // The multi-wave kernel of pa_partition_mfma_wide.hpp gives every wave the whole chain of a tile
 // -- K reads, scores, softmax, V reads, PV -- for its own columns, holds the query operand AND the
 // output accumulators in every wave, and so fits two waves per SIMD, which do not cover each
-// other's dependent waits.  Here a workgroup has 2 NS waves (NS = 4, or 2 for up to 32 columns):
+// other's dependent waits.  Here a workgroup has 2 NS waves (NS = 2 up to 64 columns, 4 above):
 // waves 0 .. NS-1 ("score waves") hold the query operand and compute scores and softmax weights of
 // tile i, waves NS .. 2 NS - 1 ("value waves") hold the accumulators and add the PV product of
 // tile i-1, at the same time.  Wave w and wave w + NS serve the same NCT = 1 or 2 tiles of 16
@@ -191,7 +191,8 @@ __device__ __forceinline__ void qk_scores_fp8(const char* kbuf, const uint32_t (
 constexpr int staged_waves_per_simd(int d, int ns, int nct, int kv, bool trace)
 {
     const int by_lds = (160 * 1024 / staged_lds_bytes(d, ns, nct, kv)) * 2 * ns / 4;
-    return trace || by_lds < 4 ? (by_lds < 2 ? by_lds : 2) : 4;
+    const int most = trace ? 2 : 4;
+    return by_lds < most ? by_lds : most;
 }
 
 template <int D, int NS, int NCT, int KV, bool TRACE>
