@@ -63,6 +63,10 @@ constexpr int kMaxPartitions = 65535;
 constexpr int kMaxBatch = 65535;
 constexpr int kMinTilesOneWave = 2;  // tiles a partition should at least have: one-wave kernels
 constexpr int kMinTilesWide = 4;     // multi-wave kernel
+// stage-split kernel, while that leaves a workgroup for every compute unit (one request, 64 query / 8 KV
+// heads, fp8 KV, 4 tokens: 16k tokens 28.6 -> 22.5 us with 32 instead of 128 partitions, 64k tokens
+// 43.6 -> 40.4 us with 64; batches have more tiles than that either way)
+constexpr int kMinTilesStaged = 32;
 // tiles per partition from which one wave takes two column tiles: where the alternative is the
 // two-wave multi-wave workgroup (head_dim 64), and where it is the stage-split workgroup of two
 // score and two value waves (head_dim 128, bf16), which stays ahead for longer (one sequence, 64
@@ -283,7 +287,15 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         // small calls: a partition should have a few tiles to amortise its start-up, and every extra
         // partition is one more piece per row for the merge (measured on single-sequence calls)
         const int min_tiles = plan->one_wave ? kMinTilesOneWave : kMinTilesWide;
-        if (P > tile_bound(s) / min_tiles) P = tile_bound(s) / min_tiles;
+        int64_t most = tile_bound(s) / min_tiles;
+        if (plan->staged) {
+            // the stage-split workgroups (up to four per compute unit) want longer runs of tiles, as long
+            // as every compute unit still gets a workgroup
+            const int64_t one_per_cu = (int64_t)compute_units() / ((int64_t)s->num_kv_heads * column_groups(s));
+            const int64_t longer = tile_bound(s) / kMinTilesStaged;
+            most = longer >= one_per_cu ? longer : (one_per_cu < most ? one_per_cu : most);
+        }
+        if (P > most) P = most;
         if (P > kMaxPartitions) P = kMaxPartitions;
         if (P < 1) P = 1;
         plan->P = (int32_t)P;
