@@ -62,6 +62,9 @@ constexpr int kDefaultCus = 256;   // MI355X; used when no device can be queried
 constexpr int kMaxPartitions = 65535;
 constexpr int kMaxBatch = 65535;
 constexpr int kMinTilesOneWave = 2;  // tiles a partition should at least have: one-wave kernels
+// ... and should have while that leaves every compute unit a wave (one request of 8k tokens, 32 / 64 query
+// and 8 KV heads, 1 and 2 tokens: 15.8 / 16.6 / 16.8 / 19.4 us with 128 partitions, 14.4 / 14.7 / 14.8 / 16.2 with 64)
+constexpr int kWantTilesOneWave = 4;
 constexpr int kMinTilesWide = 4;     // multi-wave kernel
 // stage-split kernel, while that leaves a workgroup for every compute unit (one request, 64 query / 8 KV
 // heads, fp8 KV, 4 tokens: 16k tokens 28.6 -> 22.5 us with 32 instead of 128 partitions, 64k tokens
@@ -288,11 +291,12 @@ pa_status make_plan(const pa_shape* s, pa_kv_dtype kv, Plan* plan)
         // partition is one more piece per row for the merge (measured on single-sequence calls)
         const int min_tiles = plan->one_wave ? kMinTilesOneWave : kMinTilesWide;
         int64_t most = tile_bound(s) / min_tiles;
-        if (plan->staged) {
-            // the stage-split workgroups (up to four per compute unit) want longer runs of tiles, as long
-            // as every compute unit still gets a workgroup
+        // ... and longer runs of tiles than that are better still, as long as every compute unit keeps a
+        // wave (or workgroup): the stage-split workgroups, up to four per compute unit, most of all
+        const int want_tiles = plan->staged ? kMinTilesStaged : (plan->one_wave ? kWantTilesOneWave : min_tiles);
+        if (want_tiles > min_tiles) {
             const int64_t one_per_cu = (int64_t)compute_units() / ((int64_t)s->num_kv_heads * column_groups(s));
-            const int64_t longer = tile_bound(s) / kMinTilesStaged;
+            const int64_t longer = tile_bound(s) / want_tiles;
             most = longer >= one_per_cu ? longer : (one_per_cu < most ? one_per_cu : most);
         }
         if (P > most) P = most;
