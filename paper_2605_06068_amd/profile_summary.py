@@ -125,7 +125,7 @@ def write_resources(out_path):
                  "# from registers and LDS (waves/SIMD).\n"
                  "# Template arguments: partition_mfma_kernel<D, NSTAGE, CPAD, KV(0 bf16, 1 fp8), TRACE, PRECISE>;\n"
                  "#                     partition_mfma_wide_kernel<D, NW, NCT, NSTAGE, KV, TRACE, PREFIX, PRECISE>;\n"
-                 "#                     partition_mfma_staged_kernel<D, NCT, KV, TRACE>.\n"
+                 "#                     partition_mfma_staged_kernel<D, NS, NCT, KV, TRACE>.\n"
                  + ("# No kernel uses scratch memory or spills a vector register.  The scalar registers counted under spills live in\n"
                     "# lanes of a vector register (v_writelane / v_readlane), not in memory.\n" if scratch_free else
                     "# SOME KERNELS USE SCRATCH MEMORY OR SPILL VECTOR REGISTERS: see the scratch and spills columns.\n"))
