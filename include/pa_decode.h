@@ -70,7 +70,9 @@
  * position (context_lens[b] - 1 for plain decode, context_lens[b] - Q + i for query token i of a
  * multi-token call).  Blocks that lie entirely before the earliest window of a sequence
  * (before token context_lens[b] - Q - W + 1) are never dereferenced: their table entries may be
- * stale.  Not supported together with a shared prefix.
+ * stale.  Together with a shared prefix the promise is accepted and goes unused (no prefix pass, none
+ * of its conditions): every sequence reads its own last W + Q - 1 tokens, whichever blocks hold them,
+ * and no block before them.
  *
  * Supported: batch <= 65535; head_dim in {64, 128}; block_size == 16; num_q_heads a multiple of num_kv_heads with
  * Q * G <= 512; PA_KV_FP8_E4M3 is the OCP e4m3 format (bias 7, no
@@ -311,9 +313,10 @@ pa_status pa_decode_profile(const void *q, const void *k_cache, const void *v_ca
 /* Name of the partition kernel variant pa_decode picks for this shape ("mfma": one wavefront per
  * (partition, KV head), up to 32 query rows (Q * G) per KV head (16 for fp8 at head_dim 128); "mfma-wide":
  * a workgroup of 2, 4 or 8 wavefronts, up to 128; "mfma-staged": a workgroup of 4 or 8 wavefronts, half of
- * them computing scores and softmax weights and half the product with V, at head_dim 128 for 17 .. 128 query
- * rows with fp8 KV and 17 .. 64 with bf16 KV (17 .. 32 bf16 rows with long runs of tiles per partition stay
- * on "mfma"), unless shape.precise_weights is set); NULL for an invalid or unsupported shape.
+ * them computing scores and softmax weights and half the product with V, for the query-row counts above
+ * "mfma"'s: up to 64, and up to 128 with fp8 KV at head_dim 128 and with bf16 KV at head_dim 64 (17 .. 32
+ * rows with long runs of tiles per partition stay on "mfma"), unless shape.precise_weights is set); NULL for
+ * an invalid or unsupported shape.
  * Static storage. */
 const char *pa_kernel_variant(const pa_shape *shape, pa_kv_dtype kv_dtype);
 

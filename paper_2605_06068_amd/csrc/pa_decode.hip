@@ -101,8 +101,10 @@ struct Plan {
 
 int query_len(const pa_shape* s) { return s->q_len > 0 ? s->q_len : 1; }
 
-// tiles (pairs of blocks) at the head of every block table that the whole batch shares
-int shared_tiles(const pa_shape* s) { return s->shared_prefix_blocks / 2; }
+// tiles (pairs of blocks) at the head of every block table that the whole batch shares and the prefix
+// pass reads once.  Under a sliding window the promise goes unused: every sequence reads its own last
+// window + Q - 1 tokens and nothing before them, so there is nothing left to share.
+int shared_tiles(const pa_shape* s) { return s->window > 0 ? 0 : s->shared_prefix_blocks / 2; }
 
 // columns of the score matrix per KV head: (query token, query head of the group) pairs
 int columns(const pa_shape* s) { return query_len(s) * (s->num_q_heads / s->num_kv_heads); }
@@ -209,8 +211,10 @@ int column_groups(const pa_shape* s) { return (columns(s) + kMaxColsMfma - 1) / 
 // query tokens: 197 against 169 us per step).
 bool staged(const pa_shape* s, pa_kv_dtype kv)
 {
-    if (one_wave(s, kv) || s->head_dim != 128 || s->precise_weights != 0 || columns(s) <= 16) return false;
-    return kv == PA_KV_FP8_E4M3 || columns(s) <= 64;
+    if (one_wave(s, kv) || s->precise_weights != 0 || columns(s) <= 16) return false;
+    if (columns(s) <= 64) return true;
+    // four and four waves with two column tiles each: where a tile's loads divide over them and two workgroups fit
+    return s->head_dim == 128 ? kv == PA_KV_FP8_E4M3 : kv == PA_KV_BF16;
 }
 
 // score waves per workgroup and column tiles per wave of that kernel, and its resident workgroups
@@ -261,8 +265,6 @@ pa_status check_shape(const pa_shape* s, pa_kv_dtype kv)
         // every query token lies after the prefix
         if (s->max_context_len > 0 && s->max_context_len < shared_tiles(s) * pa::kTileTokens + query_len(s) - 1) return PA_ERR_INVALID_ARG;
     }
-    // sliding windows: not together with a shared prefix
-    if (s->window > 0 && shared_tiles(s) > 0) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->window + kMaxQueryLen > INT32_MAX / 2) return PA_ERR_UNSUPPORTED;
     if ((int64_t)s->max_blocks_per_seq * s->block_size > INT32_MAX) return PA_ERR_UNSUPPORTED;
     // the global tile index and the launch grid are 32-bit
@@ -383,12 +385,10 @@ void launch_wide(const Params& p, bool trace, bool precise, dim3 grid, hipStream
 template <int D, int NS, int NCT, int KV>
 void launch_staged(const Params& p, bool trace, dim3 grid, hipStream_t st)
 {
-    if constexpr (D == 128) {
-        if (trace)
-            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NS, NCT, KV, true>), grid, dim3(2 * NS * 64), 0, st, p);
-        else
-            hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NS, NCT, KV, false>), grid, dim3(2 * NS * 64), 0, st, p);
-    }
+    if (trace)
+        hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NS, NCT, KV, true>), grid, dim3(2 * NS * 64), 0, st, p);
+    else
+        hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NS, NCT, KV, false>), grid, dim3(2 * NS * 64), 0, st, p);
 }
 
 // the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2 or 4 waves
@@ -403,7 +403,7 @@ void launch_partition(const Params& p, bool one_wave, bool staged, bool trace, b
         } else if (cols <= 64) {
             launch_staged<D, 2, 2, KV>(p, trace, grid, st);
         } else {
-            if constexpr (KV == pa::KV_FP8) launch_staged<D, 4, 2, KV>(p, trace, grid, st);
+            if constexpr ((D == 128) == (KV == pa::KV_FP8)) launch_staged<D, 4, 2, KV>(p, trace, grid, st);
         }
         return;
     }

@@ -1,5 +1,5 @@
 // Partition kernel, matrix-core variant for 17 .. 128 columns per KV head in which the waves of a
-// workgroup split a tile's work by STAGE as well as by column (head_dim 128).
+// workgroup split a tile's work by STAGE as well as by column.
 //
 // The multi-wave kernel of pa_partition_mfma_wide.hpp gives every wave the whole chain of a tile
 // -- K reads, scores, softmax, V reads, PV -- for its own columns, holds the query operand AND the
@@ -28,15 +28,20 @@
 //
 // Layouts, swizzle, block and row selection, the arithmetic of softmax and PV, the wait-count
 // discipline and the handling of query rows are those of the other two kernels
-// (pa_mfma_tile.hpp, pa_partition_mfma.hpp).  fp8 KV differs in one step: the scores come from
-// the fp8 matrix instruction (qk_scores_fp8 below), not from K converted to bf16.
+// (pa_mfma_tile.hpp, pa_partition_mfma.hpp).  fp8 KV at head_dim 128 differs in one step: the
+// scores come from the fp8 matrix instruction (qk_scores_fp8 below), not from K converted to bf16.
+// Every wave of a role takes an equal share of a tile's 1 KB load instructions, which is what
+// bounds NS: a tile of K (or V) is 8 of them with bf16 at head_dim 128, 4 with fp8 at 128 or bf16
+// at 64, 2 with fp8 at head_dim 64 (so no four score waves there).
 //
 // Most steps lie in the middle of a sequence, and for those the loops below skip the cursor
 // arithmetic of the general step (a "run", see the score waves' loop): with sixteen waves per
 // compute unit every scalar instruction per step and wave counts.  Measured, 70B-head-shaped fp8
 // batch, 16 query tokens = 128 columns: 850-900 us on the multi-wave kernel, 800 us split by
 // stage, 735 us with the fp8 score instruction, 685-730 us with runs; 4 query tokens = 32 columns
-// (two score and two value waves): 453 -> 369 us per step.
+// (two score and two value waves): 453 -> 369 us per step.  head_dim 64, 8B-shaped batch, 16 query
+// tokens: 64 bf16 columns 71.8 -> 66.3 us, 128 bf16 columns 99.3 -> 95.8, 64 fp8 columns 63.7 -> 59.5
+// against the multi-wave kernel; long contexts, 64 fp8 columns: 208.7 -> 172.3 us.
 #pragma once
 #include <type_traits>
 
@@ -68,6 +73,33 @@ constexpr int staged_lds_bytes(int d, int ns, int nct, int kv)
 // `qs` is the wave-uniform scale (its sign picks the extreme to look for), `qsl` the scale this
 // lane's column multiplies by: qs times a positive factor of the column's own (1 unless the query
 // rows were rescaled, see split_query_fp8).
+// The two halves of softmax_weights<false> for a caller that has matrix instructions to issue in
+// between: the running maximum (and alpha) first, the weights second.
+__device__ __forceinline__ void softmax_maximum(const f32x4& s0, const f32x4& s1, float qs, float qsl, float& m, float& alpha)
+{
+    float mx;
+    if (qs >= 0.f)  // the same for every lane
+        mx = max8_f32(s0, s1) * qsl;
+    else
+        mx = min8_f32(s0, s1) * qsl;
+    alpha = 1.f;
+    if (__any(mx > m + kLazyMax)) {
+        const float m_new = fmaxf(m, rows_max(mx));
+        alpha = m > kNegBig ? fast_exp2(m - m_new) : 0.f;
+        m = m_new;
+    }
+}
+
+__device__ __forceinline__ void softmax_exponentials(const f32x4& s0, const f32x4& s1, float qsl, float m, bf16x8& pb)
+{
+    const float neg_m = -m;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        pb[r] = (__bf16)fast_exp2(fmaf(s0[r], qsl, neg_m));
+        pb[4 + r] = (__bf16)fast_exp2(fmaf(s1[r], qsl, neg_m));
+    }
+}
+
 template <bool MASKED>
 __device__ __forceinline__ void softmax_weights(const f32x4& s0, const f32x4& s1, float qs, float qsl, int t0, int lim, int low,
                                                 float& m, float& alpha, bf16x8& pb)
@@ -87,9 +119,9 @@ __device__ __forceinline__ void softmax_weights(const f32x4& s0, const f32x4& s1
         for (int r = 0; r < 8; ++r) v[r] = ok[r] ? v[r] * qsl : kNegBig;
         mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
     } else if (qs >= 0.f) {  // the same for every lane
-        mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))) * qsl;
+        mx = max8_f32(s0, s1) * qsl;
     } else {
-        mx = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7]))) * qsl;
+        mx = min8_f32(s0, s1) * qsl;
     }
     alpha = 1.f;
     if (__any(mx > m + kLazyMax)) {
@@ -185,6 +217,26 @@ __device__ __forceinline__ void qk_scores_fp8(const char* kbuf, const uint32_t (
     }
 }
 
+// ... the same in two steps, for interleaving: the K operand of a tile, then one column tile's scores
+__device__ __forceinline__ void read_k_fp8(const char* kbuf, const uint32_t (&kread)[2], i32x8 (&a)[2])
+{
+    constexpr int kSlabBytes = KvGeom<128, KV_FP8>::kSlab;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+        const uint4 p0 = *reinterpret_cast<const uint4*>(kbuf + sub * kSlabBytes + kread[0]);
+        const uint4 p1 = *reinterpret_cast<const uint4*>(kbuf + sub * kSlabBytes + kread[1]);
+        a[sub] = i32x8{(int)p0.x, (int)p0.y, (int)p0.z, (int)p0.w, (int)p1.x, (int)p1.y, (int)p1.z, (int)p1.w};
+    }
+}
+__device__ __forceinline__ void qk_scores_fp8_one(const i32x8 (&a)[2], const i32x8& qhi, const i32x8& qlo, f32x4& s0, f32x4& s1)
+{
+    const f32x4 zero{0.f, 0.f, 0.f, 0.f};
+    s0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[0], qhi, zero, 0, 0, 0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[1], qhi, zero, 0, 0, 0, 0, 0, 0);
+    s0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[0], qlo, s0, 0, 0, 0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[1], qlo, s1, 0, 0, 0, 0, 0, 0);
+}
+
 // Waves per SIMD the register budget is cut for (the second launch bound): as many as the LDS lets
 // a compute unit hold, four at most (128 registers each); the instrumented variants, whose records
 // need a few more, settle for two.
@@ -198,7 +250,8 @@ constexpr int staged_waves_per_simd(int d, int ns, int nct, int kv, bool trace)
 template <int D, int NS, int NCT, int KV, bool TRACE>
 __global__ __launch_bounds__(2 * NS * 64, staged_waves_per_simd(D, NS, NCT, KV, TRACE)) void partition_mfma_staged_kernel(const Params p)
 {
-    static_assert(D == 128, "the waves share a tile's loads evenly at head_dim 128 only");
+    static_assert(D == 128 || D == 64, "head_dim");
+    constexpr bool QK_F8 = KV == KV_FP8 && D == 128;  // scores on the fp8 matrix instruction (whose depth is 128)
     static_assert(NS == 2 || NS == 4, "score waves per workgroup");
     static_assert(NCT == 1 || NCT == 2, "MFMA column tiles per wave");
     constexpr int kWaveCols = 16 * NCT;
@@ -352,14 +405,42 @@ __global__ __launch_bounds__(2 * NS * 64, staged_waves_per_simd(D, NS, NCT, KV, 
         // the whole tile (all but the last tiles of a sequence and the tiles where sliding windows begin)
         auto score_tile = [&](int stage, int par, bool unmasked) __attribute__((always_inline)) {
             f32x4 s0[NCT], s1[NCT];
-            if constexpr (KV == KV_FP8)
-                qk_scores_fp8<NCT>(smem + stage * kHalf, kread8, qhi, qlo, s0, s1);
-            else
-                qk_scores<D, KV, NCT>(smem + stage * kHalf, of, qreg, s0, s1);
-            const int tile_first = (cc.lt + cc.ft) * kTileTokens;
             float alpha[NCT];
             bf16x8 pb[NCT];
-            if (unmasked) {
+            if constexpr (QK_F8 && NCT == 2) {
+                if (unmasked) {
+                    // the second column tile's matrix instructions run while the first one's exponentials issue
+                    i32x8 a[2];
+                    read_k_fp8(smem + stage * kHalf, kread8, a);
+                    qk_scores_fp8_one(a, qhi[0], qlo[0], s0[0], s1[0]);
+                    softmax_maximum(s0[0], s1[0], qs, qsl[0], m[0], alpha[0]);
+                    qk_scores_fp8_one(a, qhi[1], qlo[1], s0[1], s1[1]);
+                    softmax_exponentials(s0[0], s1[0], qsl[0], m[0], pb[0]);
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
+                        __builtin_amdgcn_sched_group_barrier(0x002 | 0x400, 5, 0);  // five vector / transcendental ones
+                    }
+                    {  // keeps the first tile's weights on this side of the second tile's branch
+                        typedef int i32x4 __attribute__((ext_vector_type(4)));
+                        i32x4 w = __builtin_bit_cast(i32x4, pb[0]);
+                        asm volatile("" : "+v"(w));
+                        pb[0] = __builtin_bit_cast(bf16x8, w);
+                    }
+                    softmax_maximum(s0[1], s1[1], qs, qsl[1], m[1], alpha[1]);
+                    softmax_exponentials(s0[1], s1[1], qsl[1], m[1], pb[1]);
+                } else {
+                    qk_scores_fp8<NCT>(smem + stage * kHalf, kread8, qhi, qlo, s0, s1);
+                }
+            } else if constexpr (QK_F8) {
+                qk_scores_fp8<NCT>(smem + stage * kHalf, kread8, qhi, qlo, s0, s1);
+            } else {
+                qk_scores<D, KV, NCT>(smem + stage * kHalf, of, qreg, s0, s1);
+            }
+            const int tile_first = (cc.lt + cc.ft) * kTileTokens;
+            if (QK_F8 && NCT == 2 && unmasked) {
+                // done above
+            } else if (unmasked) {
 #pragma unroll
                 for (int ct = 0; ct < NCT; ++ct)
                     softmax_weights<false>(s0[ct], s1[ct], qs, qsl[ct], 0, 0, 0, m[ct], alpha[ct], pb[ct]);
@@ -433,7 +514,7 @@ __global__ __launch_bounds__(2 * NS * 64, staged_waves_per_simd(D, NS, NCT, KV, 
 #pragma unroll
                     for (int ct = 0; ct < NCT; ++ct) {
                         m[ct] = kNegBig;
-                        if constexpr (KV == KV_FP8) {
+                        if constexpr (QK_F8) {
                             qsl[ct] = qs * split_query_fp8(qslot + ct * 16 * QG::kRow, n, q4, col_ok[ct], qhi[ct], qlo[ct]);
                         } else {
                             qsl[ct] = qs;

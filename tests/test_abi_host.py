@@ -84,7 +84,10 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16), pa.PA_KV_BF16) == "mfma-wide"  # bf16: up to 64 columns
     assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=8), pa.PA_KV_BF16) == "mfma-staged"
     assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16, precise_weights=1), pa.PA_KV_BF16) == "mfma-wide"
-    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16, head_dim=64), pa.PA_KV_BF16) == "mfma-wide"
+    # head_dim 64: bf16 up to 128 columns (its tiles are half as large), fp8 up to 64
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16, head_dim=64), pa.PA_KV_BF16) == "mfma-staged"
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=16, head_dim=64), pa.PA_KV_FP8_E4M3) == "mfma-wide"
+    assert pa.pa_kernel_variant(shape(num_q_heads=64, q_len=8, head_dim=64), pa.PA_KV_FP8_E4M3) == "mfma-staged"
     for Q in (2, 4, 16):
         win = shape(num_partitions=16, q_len=Q)
         assert pa.pa_kernel_variant(win, pa.PA_KV_BF16) == ("mfma" if Q * 4 <= 32 else "mfma-staged")  # 512 tiles, 16 partitions
@@ -100,14 +103,14 @@ def test_query_window_scales_the_workspace_and_leaves_the_plan_alone():
     assert pa.pa_kernel_variant(shape(num_q_heads=8), pa.PA_KV_BF16) == "mfma"
     assert pa.pa_kernel_variant(shape(num_q_heads=16, head_dim=64), pa.PA_KV_BF16) == "mfma"
     # 17 .. 32 columns: two column tiles in one wave when every partition has a long run of tiles (here: at
-    # most 128 tiles per sequence and 256 partitions of the full device), else the two-wave workgroup
+    # most 128 tiles per sequence and 256 partitions of the full device), else two score and two value waves
     big = dict(batch=64, num_q_heads=16, head_dim=64, q_len=16)
     assert pa.pa_kernel_variant(shape(**big), pa.PA_KV_FP8_E4M3) == "mfma"
-    assert pa.pa_kernel_variant(shape(**dict(big, batch=4)), pa.PA_KV_FP8_E4M3) == "mfma-wide"
+    assert pa.pa_kernel_variant(shape(**dict(big, batch=4)), pa.PA_KV_FP8_E4M3) == "mfma-staged"
     assert pa.pa_kernel_variant(shape(**dict(big, batch=4, num_partitions=8)), pa.PA_KV_FP8_E4M3) == "mfma"
     assert pa.pa_kernel_variant(shape(**dict(big, head_dim=128)), pa.PA_KV_FP8_E4M3) == "mfma-staged"  # fp8 at head_dim 128: two score and two value waves
     assert pa.pa_kernel_variant(shape(**dict(big, head_dim=128)), pa.PA_KV_BF16) == "mfma"
-    assert pa.pa_kernel_variant(shape(num_q_heads=24, head_dim=64, q_len=16), pa.PA_KV_FP8_E4M3) == "mfma-wide"  # 48
+    assert pa.pa_kernel_variant(shape(num_q_heads=24, head_dim=64, q_len=16), pa.PA_KV_FP8_E4M3) == "mfma-staged"  # 48
 
 
 @pytest.mark.parametrize("Q,window", [(1, 1), (1, 16), (1, 100), (4, 33), (16, 5), (1, 10 ** 6)])
@@ -161,6 +164,18 @@ def test_shared_prefix_plan_and_workspace():
     # one shared block is less than a tile: the call is the plain one
     s1 = shape(batch=B, shared_prefix_blocks=1)
     assert pa.pa_decode_workspace_size(s1, pa.PA_KV_BF16) == pa.pa_decode_workspace_size(shape(batch=B), pa.PA_KV_BF16)
+    # under a sliding window the promise goes unused: plan, partitions and workspace of the windowed call
+    # without it, and none of its conditions (a context may end inside the prefix, any column count)
+    for extra in (dict(), dict(q_len=4), dict(q_len=64)):
+        sw = shape(batch=B, window=100, shared_prefix_blocks=prefix_blocks, **extra)
+        s0 = shape(batch=B, window=100, **extra)
+        for kv in (pa.PA_KV_BF16, pa.PA_KV_FP8_E4M3):
+            assert pa.pa_num_partitions(sw, kv) == pa.pa_num_partitions(s0, kv)
+            assert pa.pa_decode_workspace_size(sw, kv) == pa.pa_decode_workspace_size(s0, kv)
+            assert pa.pa_kernel_variant(sw, kv) == pa.pa_kernel_variant(s0, kv)
+        Tw, planw = pa.pa_split_plan(sw, pa.PA_KV_BF16, [144, 100, 400, 1000])
+        T0, plan0 = pa.pa_split_plan(s0, pa.PA_KV_BF16, [144, 100, 400, 1000])
+        assert Tw == T0 and np.array_equal(planw, plan0) and np.all(planw > -2)
 
 
 def test_split_plan_rejects_lengths_above_the_bound():
@@ -191,7 +206,6 @@ def test_split_plan_rejects_lengths_above_the_bound():
     (dict(shared_prefix_blocks=8, q_len=4, max_context_len=130), pa.PA_ERR_INVALID_ARG),  # a query token inside the prefix
     (dict(shared_prefix_blocks=8, num_q_heads=8 * 129), pa.PA_ERR_UNSUPPORTED),  # groups wider than 128
     (dict(window=-1), pa.PA_ERR_INVALID_ARG),
-    (dict(window=64, shared_prefix_blocks=8), pa.PA_ERR_UNSUPPORTED),
     (dict(out_dtype=2), pa.PA_ERR_INVALID_ARG),
     (dict(out_dtype=-1), pa.PA_ERR_INVALID_ARG),
     (dict(precise_weights=2), pa.PA_ERR_INVALID_ARG),
@@ -246,7 +260,7 @@ def test_binding_refuses_host_tensors():
 def test_head_dim_64_takes_every_kind_of_call(extra, kv):
     s = shape(head_dim=64, **extra)
     assert pa.pa_num_partitions(s, kv) >= 1
-    assert pa.pa_kernel_variant(s, kv) in ("mfma", "mfma-wide")
+    assert pa.pa_kernel_variant(s, kv) in ("mfma", "mfma-wide", "mfma-staged")
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -187,7 +187,7 @@ def test_wide_multi_token_calls_over_a_shared_prefix(pa, oracle, kv, Q, Hq, Hkv,
                      shared_prefix_blocks=prefix_blocks)
     print(f"[case] wide prefix verify Q={Q} Hq={Hq} Hkv={Hkv} D={D} B={B} prefix={prefix_blocks} kv={kv}", flush=True)
     got, dev = run_gpu(pa, b)
-    staged = D == 128 and (kv == W.KV_FP8_E4M3 or Q * (Hq // Hkv) <= 64)
+    staged = Q * (Hq // Hkv) <= 64 or (D == 128) == (kv == W.KV_FP8_E4M3)
     assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == ("mfma-staged" if staged else "mfma-wide")
     want = oracle.decode_batch(b)["out"]
     flat = lambda a: a.reshape(a.shape[0], -1, a.shape[-1])
@@ -211,3 +211,25 @@ def test_prompt_cache_workload_with_16_token_verification(pa, oracle):
     sel = np.stack([got[s, i, h] for s, i, h in rows])
     err = assert_parity(sel[:, None, :], want[:, None, :], b.kv_dtype, "prompt-cache workload, 16-token verification")
     print(f"        {len(rows)} sampled rows max_abs={err[0]:.3e} worst row rel_l2={err[1]:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Q,Hq,Hkv,D", [(1, 8, 2, 128), (4, 8, 2, 128), (16, 4, 1, 128), (3, 16, 2, 64), (16, 8, 1, 64)])
+@pytest.mark.parametrize("window", [1, 33, 200, 1000])
+def test_sliding_window_over_a_shared_prefix(pa, oracle, kv, Q, Hq, Hkv, D, window):
+    """A window and the promise of a shared prefix in one call: the promise goes unused, every sequence
+    reads its own last window + Q - 1 tokens (inside the prefix for some sequences, behind it for others)
+    and no block before them: the batch's evicted prefix blocks are poisoned and their table entries,
+    row 0's included, are -1."""
+    prefix_blocks = 24
+    lens = [L + Q - 1 for L in suffix_lens(prefix_blocks, 18, 60 + Q)]
+    b = W.make_batch("prefix-window", 640 + Q + Hq + window, lens, Hq, Hkv, D, 16, kv, q_len=Q,
+                     shared_prefix_blocks=prefix_blocks, window=window)
+    assert (b.block_tables[:, :prefix_blocks] == -1).any(axis=1).all() == (window + Q - 1 <= prefix_blocks * 16 - 16)
+    flat = lambda a: a.reshape(a.shape[0], -1, a.shape[-1])
+    for P in (0, 3):
+        print(f"[case] window over a shared prefix Q={Q} Hq={Hq} Hkv={Hkv} D={D} W={window} kv={kv} P={P}", flush=True)
+        got, dev = run_gpu(pa, b, num_partitions=P)
+        assert dev.shape.window == window and dev.shape.shared_prefix_blocks == prefix_blocks
+        want = oracle.decode_batch(b)["out"]
+        assert_parity(flat(got), flat(want), kv, "window over a shared prefix")
