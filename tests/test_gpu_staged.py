@@ -1,5 +1,5 @@
-"""GPU parity of the stage-split partition kernel (17 .. 128 columns per KV head at head_dim 128:
-score waves and value waves, fp8 scores on the fp8 matrix instruction with the query rows split in
+"""GPU parity of the stage-split partition kernel (17 .. 128 columns per KV head: score waves and
+value waves; at head_dim 128 fp8 scores on the fp8 matrix instruction with the query rows split in
 two) against the float64 CPU oracle: query rows of wide dynamic range, and context lengths that
 put the ends of its runs of plain steps on every side of a tile boundary."""
 import numpy as np
@@ -98,6 +98,30 @@ def test_lengths_around_the_ends_of_runs(pa, oracle, kv, Q, Hq, Hkv, P):
     want = oracle.decode_batch(b)["out"]
     err = assert_parity(flat(got), flat(want), kv, "lengths around the ends of runs")
     print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e} P={pa.pa_num_partitions(dev.shape, dev.kv_dtype)}", flush=True)
+
+
+@pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
+@pytest.mark.parametrize("Q,Hq,Hkv", [(16, 4, 1), (16, 8, 1), (5, 8, 1), (12, 16, 2)])
+@pytest.mark.parametrize("P", [0, 3])
+def test_head_dim_64(pa, oracle, kv, Q, Hq, Hkv, P):
+    """head_dim 64: a tile has half the load instructions, so four score waves exist for bf16 KV only
+    (128 fp8 columns stay on the multi-wave kernel), and fp8 scores go through K converted to bf16."""
+    lens = []
+    for base in (64, 96, 160, 1024):
+        for d in (-1, 0, 1):
+            lens += [base + d, base + Q - 1 + d]
+    lens += [Q, 31 + Q, 2048, 700]
+    b = W.make_batch("staged-d64", 9700 + Q + Hq, lens, Hq, Hkv, 64, 16, kv, q_len=Q)
+    rescale_queries(b, np.random.default_rng(9700 + Q), -6, 2)
+    print(f"[case] head_dim 64 Q={Q} Hq={Hq} Hkv={Hkv} kv={kv} P={P}", flush=True)
+    got, dev = run_gpu(pa, b, num_partitions=P)
+    cols = Q * (Hq // Hkv)
+    if cols > 32:
+        staged = cols <= 64 or kv == W.KV_BF16
+        assert pa.pa_kernel_variant(dev.shape, dev.kv_dtype) == ("mfma-staged" if staged else "mfma-wide")
+    want = oracle.decode_batch(b)["out"]
+    err = assert_parity(flat(got), flat(want), kv, "head_dim 64")
+    print(f"        max_abs={err[0]:.3e} rel_l2={err[1]:.3e} {pa.pa_kernel_variant(dev.shape, dev.kv_dtype)}", flush=True)
 
 
 @pytest.mark.parametrize("kv", [W.KV_BF16, W.KV_FP8_E4M3])
