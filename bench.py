@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 METRIC = "paged decode attention achieved HBM GB/s (% of peak) + decode tokens/s, 1 GPU"
 
 # (workload, q_len, window): what `others` reports beside the headline
-OTHER_WORKLOADS = [(3, 1, 0), (4, 1, 0), (5, 1, 0), (6, 1, 0), (2, 16, 0), (5, 4, 0), (5, 16, 0), (2, 1, 1024)]
+OTHER_WORKLOADS = [(3, 1, 0), (4, 1, 0), (5, 1, 0), (6, 1, 0), (2, 16, 0), (5, 4, 0), (5, 8, 0), (5, 16, 0), (2, 1, 1024)]
 
 
 def parse_args():
