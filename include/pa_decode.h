@@ -286,7 +286,9 @@ typedef enum pa_tables_status {
  *     call can see (all blocks up to the context's last; with a sliding window those from the
  *     block of token max(0, context_lens[b] - window - q_len + 1) on) has an id in [0, num_blocks);
  *   - inside a shared prefix (whole pairs of blocks) every row repeats row 0.
- * Entries behind a context, and blocks a sliding window has left behind, may hold anything.
+ * Entries behind a context, and blocks a sliding window has left behind, may hold anything.  A shared
+ * prefix declared together with a sliding window goes unused by pa_decode and is not checked here
+ * (neither the lengths against it nor the rows against row 0).
  *
  *   block_tables, context_lens   device, layouts above; only these two are read
  *   report   device int32[8], 16-byte aligned, written by this call: [0] a pa_tables_status,
