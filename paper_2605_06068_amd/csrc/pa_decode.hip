@@ -203,12 +203,13 @@ bool one_wave(const pa_shape* s, pa_kv_dtype kv)
 // workgroups of up to 128 columns a call needs side by side (more than one: the cache is read once per group)
 int column_groups(const pa_shape* s) { return (columns(s) + kMaxColsMfma - 1) / kMaxColsMfma; }
 
-// At head_dim 128 the per-sequence pass of calls the one-wave kernel does not take runs on the
-// stage-split kernel (score waves and value waves: two and two up to 64 columns, with two column
-// tiles each above 32; four and four with two tiles each above 64), from 17 columns on -- unless the weights are to keep their low part, which its
-// hand-over buffers have no room for.  bf16 KV with more than 64 columns stays on the multi-wave
-// kernel: only one stage-split workgroup would fit a compute unit's LDS (8B-shaped batch, 32
-// query tokens: 197 against 169 us per step).
+// The per-sequence pass of calls the one-wave kernel does not take runs on the stage-split kernel
+// (score waves and value waves: two and two up to 64 columns, with two column tiles each above 32;
+// four and four with two tiles each above 64), from 17 columns on -- unless the weights are to keep
+// their low part, which its hand-over buffers have no room for.  Above 64 columns two cases stay on
+// the multi-wave kernel: bf16 KV at head_dim 128, where only one stage-split workgroup would fit a
+// compute unit's LDS (8B-shaped batch, 32 query tokens: 197 against 169 us per step), and fp8 KV
+// at head_dim 64, whose tiles have two load instructions for four waves to share.
 bool staged(const pa_shape* s, pa_kv_dtype kv)
 {
     if (one_wave(s, kv) || s->precise_weights != 0 || columns(s) <= 16) return false;
@@ -391,8 +392,8 @@ void launch_staged(const Params& p, bool trace, dim3 grid, hipStream_t st)
         hipLaunchKernelGGL((pa::partition_mfma_staged_kernel<D, NS, NCT, KV, false>), grid, dim3(2 * NS * 64), 0, st, p);
 }
 
-// the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns, a workgroup of 2 or 4 waves
-// or the stage-split workgroup of 8 above
+// the per-sequence pass: one wave per (partition, KV head) up to 16 or 32 columns; above, the stage-split
+// workgroup of 4 or 8 waves or the multi-wave workgroup of 2, 4 or 8
 template <int D, int KV>
 void launch_partition(const Params& p, bool one_wave, bool staged, bool trace, bool precise, dim3 grid, hipStream_t st)
 {
