@@ -26,7 +26,7 @@ struct Params {
     float* part_o;                // [2P, Hq, D] normalised partial outputs (null when P == 1)
     float* part_lse;              // [2P, Hq]    log2-domain log-sum-exp of each partial
     int32_t* merge_desc;          // [B, 4] what the merge kernel needs to know per sequence (null when P == 1)
-    int32_t* cut_list;            // [P] the sequence inside which partition k starts, or -1 (null: the merge scans merge_desc instead)
+    int32_t* cut_list;            // [P] the sequence inside which partition k starts (empty partitions included), or -1 (null: the merge scans merge_desc instead)
     int32_t* trace_blocks;        // [B, Hkv, MB, 3] or null
     float scale_log2;             // softmax scale * log2(e)
     int32_t B, Hq, Hkv, G, MB;

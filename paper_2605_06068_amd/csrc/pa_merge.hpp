@@ -39,7 +39,8 @@ __device__ __forceinline__ int nth_cut_sequence(const int32_t* desc, int B, int 
 // The sequence merge slot y works on, or -1.  Large batches come with a list of the sequences that
 // the partitions' starts cut (cut_list[k] for boundary k = y + 1): the slot takes the sequence its
 // boundary cuts if that is the first boundary inside it (a sequence cut several times is merged
-// once).  Small batches (one or two 64-lane scans) look for the y-th cut sequence instead.  All
+// once; an empty partition that lies between two tiles of a sequence counts as a boundary there, or
+// a sequence whose first boundary it is would be merged by nobody).  Small batches (one or two 64-lane scans) look for the y-th cut sequence instead.  All
 // 64 lanes must call; the result is wave-uniform.
 __device__ __forceinline__ int slot_sequence(const Params& p, int y, int lane)
 {

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(64) void partition_mfma_kernel(const Params p)
     if (skip == 0) zero_rows_of_empty_contexts(p, k, g, B, Q, D, lane);  // (behind a shared prefix no context is empty)
     const bool describes = g == 0 && p.merge_desc != nullptr;  // this wave tells the merge about its sequences
     if (describes && p.cut_list != nullptr && lane == 0)  // does my range start inside a sequence, and which
-        p.cut_list[k] = (rs.t_lo < rs.t_hi && rs.t_lo > rs.cum) ? rs.b : -1;
+        p.cut_list[k] = (rs.t_lo < rs.T && rs.t_lo > rs.cum) ? rs.b : -1;
     if (rs.t_lo >= rs.t_hi) return;
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;

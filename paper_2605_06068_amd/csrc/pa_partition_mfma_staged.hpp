@@ -292,7 +292,7 @@ __global__ __launch_bounds__(2 * NS * 64, staged_waves_per_simd(D, NS, NCT, KV, 
     if (skip == 0 && w == 0 && col0 == 0) zero_rows_of_empty_contexts(p, k, g, B, Q, D, lane);
     const bool describes = g == 0 && w == 0 && col0 == 0 && p.merge_desc != nullptr;
     if (describes && p.cut_list != nullptr && lane == 0)
-        p.cut_list[k] = (rs.t_lo < rs.t_hi && rs.t_lo > rs.cum) ? rs.b : -1;
+        p.cut_list[k] = (rs.t_lo < rs.T && rs.t_lo > rs.cum) ? rs.b : -1;
     if (rs.t_lo >= rs.t_hi) return;  // the same for every wave of the workgroup
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;

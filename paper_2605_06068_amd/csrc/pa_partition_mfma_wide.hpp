@@ -122,7 +122,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void partition_mfma_wide_
     if (!PREFIX && skip == 0 && w == 0 && col0 == 0) zero_rows_of_empty_contexts(p, k, g, B, Q, D, lane);  // (behind a shared prefix no context is empty)
     const bool describes = !PREFIX && g == 0 && w == 0 && col0 == 0 && p.merge_desc != nullptr;  // tells the merge about its sequences
     if (describes && p.cut_list != nullptr && lane == 0)  // does my range start inside a sequence, and which
-        p.cut_list[k] = (rs.t_lo < rs.t_hi && rs.t_lo > rs.cum) ? rs.b : -1;
+        p.cut_list[k] = (rs.t_lo < rs.T && rs.t_lo > rs.cum) ? rs.b : -1;
     if (rs.t_lo >= rs.t_hi) return;  // the same for every wave of the workgroup
     const int ntiles = rs.t_hi - rs.t_lo;
     const int first_b = rs.b;

@@ -103,8 +103,10 @@ __device__ __forceinline__ void locate_tile(const int32_t* context_lens, int B, 
 }
 
 // Where partition k of P starts: total tile count T, the partition's global tile range
-// [t_lo, t_hi), and for a non-empty range the sequence b that holds tile t_lo, the number of
-// tiles before b and b's context length.  All 64 lanes must call; results are wave-uniform.
+// [t_lo, t_hi), and whenever t_lo < T (every non-empty range, and the empty ones that lie between
+// two tiles: there are some as soon as the call has fewer tiles than partitions) the sequence b
+// that holds tile t_lo, the number of tiles before b and b's context length.  All 64 lanes must
+// call; results are wave-uniform.
 // A batch of up to 64 sequences needs a single load of the context lengths.
 struct RangeStart {
     int T, t_lo, t_hi, b, cum, L;
@@ -123,7 +125,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
         r.T = __builtin_amdgcn_readlane(incl, kWave - 1);
         r.t_lo = part_begin(k, r.T, P);
         r.t_hi = part_begin(k + 1, r.T, P);
-        if (r.t_lo < r.t_hi) {
+        if (r.t_lo < r.T) {
             const unsigned long long hit = __ballot(incl > r.t_lo);
             const int l = __ffsll((long long)hit) - 1;
             r.b = l;
@@ -152,7 +154,7 @@ __device__ __forceinline__ RangeStart find_range(const int32_t* context_lens, in
     r.T = __builtin_amdgcn_readfirstlane(running);
     r.t_lo = part_begin(k, r.T, P);
     r.t_hi = part_begin(k + 1, r.T, P);
-    if (r.t_lo >= r.t_hi) return r;
+    if (r.t_lo >= r.T) return r;
     const int ngroups = (nchunks + kGroupChunks - 1) / kGroupChunks;
     const unsigned long long in_group = __ballot(lane < ngroups && group_end > r.t_lo);
     const int group = __ffsll((long long)in_group) - 1;  // exists: t_lo < T
