@@ -58,7 +58,19 @@ def draw_case(seed):
                 lens=[int(x) for x in lens], P=P, out_bf16=out_bf16)
 
 
-@pytest.mark.parametrize("seed", range(400))
+def seeds():
+    """400 seeds by default; PA_EXTRA_SEEDS=first:last adds a range of further ones (a longer run by hand)."""
+    import os
+
+    extra = os.environ.get("PA_EXTRA_SEEDS", "")
+    more = []
+    if extra:
+        first, last = (int(x) for x in extra.split(":"))
+        more = list(range(first, last))
+    return list(range(400)) + more
+
+
+@pytest.mark.parametrize("seed", seeds())
 def test_random_call(pa, oracle, seed):
     import torch
 
