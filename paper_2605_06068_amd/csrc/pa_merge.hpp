@@ -82,7 +82,12 @@ __global__ __launch_bounds__(64) void merge_kernel(const Params p)
             slot = 2 * kk + ((kk == j - 1 && lo != cum) ? 1 : 0);
         }
         const unsigned long long vmask = __ballot(valid);
-        if (vmask == 0ull) break;
+        if (vmask == 0ull) {
+            // 64 partitions without a piece: behind the sequence, or empty partitions inside it (a call
+            // with far fewer tiles than partitions spreads a sequence's pieces that far apart)
+            if (part_begin(base, T, P) >= end_b) break;
+            continue;
+        }
         const float lse = valid ? p.part_lse[(int64_t)slot * p.QH + h] : kNegBig;
         float cm = lse;
 #pragma unroll
